@@ -1,0 +1,155 @@
+"""ctypes access to the CPU oracle (oracle/dagsched_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the benchmark's
+CPU-baseline leg.  The product package never imports this module.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+import threading
+from typing import Optional, Tuple
+
+import numpy as np
+
+_DIR = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_DIR, "dagsched_oracle.c")
+_LIB = os.path.join(_DIR, "libdagsched_oracle.so")
+
+OK, EINVAL, ECYCLE, EOVERFLOW, ENOMEM = 0, -1, -2, -3, -4
+FLAG_CYCLIC, FLAG_BAD_PLACEMENT, FLAG_BAD_RANK = 1, 2, 4
+CAND_MAJOR, CAND_MINOR = 0, 1
+
+_lib = None
+
+
+def build() -> str:
+    """gcc -> oracle/libdagsched_oracle.so (always recompiles)."""
+    tmp = _LIB + ".tmp"
+    proc = subprocess.run(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-Wall", "-Wextra", _SRC, "-o", tmp],
+                          stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if proc.returncode != 0:
+        raise RuntimeError("oracle build failed:\n" + proc.stdout)
+    os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+            build()
+        lib = ctypes.CDLL(_LIB)
+        vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+        lib.dagsched_oracle_check_problem.restype = ctypes.c_int
+        lib.dagsched_oracle_check_problem.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp]
+        lib.dagsched_oracle_evaluate.restype = ctypes.c_int
+        lib.dagsched_oracle_evaluate.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, i32, i64, vp, vp, i64, i64,
+                                                 vp, vp, vp, vp]
+        lib.dagsched_oracle_schedule.restype = ctypes.c_int
+        lib.dagsched_oracle_schedule.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        _lib = lib
+    return _lib
+
+
+def _c(a, dt):
+    return np.ascontiguousarray(a, dtype=dt)
+
+
+def _ptr(a):
+    return a.ctypes.data if a.size else None
+
+
+class Problem:
+    """The candidate-independent part: DAG CSR, durations, comm matrix, memory deltas."""
+
+    def __init__(self, n_devices, row_ptr, col_idx, dur, comm, mem_delta):
+        self.P = int(n_devices)
+        self.row_ptr = _c(row_ptr, np.int32)
+        self.col_idx = _c(col_idx, np.int32)
+        self.dur = _c(dur, np.int32)
+        self.comm = _c(comm, np.int32).reshape(-1)
+        self.mem_delta = _c(mem_delta, np.int64)
+        self.N = len(self.row_ptr) - 1
+        self.E = len(self.col_idx)
+
+    @classmethod
+    def of(cls, w) -> "Problem":
+        return cls(w.n_devices, w.row_ptr, w.col_idx, w.dur, w.comm, w.mem_delta)
+
+    def _head(self):
+        return (self.N, self.E, self.P, _ptr(self.row_ptr), _ptr(self.col_idx), _ptr(self.dur),
+                _ptr(self.comm), _ptr(self.mem_delta))
+
+    def check(self) -> int:
+        return _load().dagsched_oracle_check_problem(*self._head())
+
+    def evaluate(self, placement, rank, layout: int = CAND_MAJOR, threads: int = 1
+                 ) -> Tuple[np.ndarray, np.ndarray, np.ndarray, np.ndarray]:
+        """-> (makespan int32 [C], bubble int64 [C], peak_mem int64 [C,P] or [P,C], flags int32 [C]).
+
+        ``threads`` > 1 only fans contiguous candidate chunks out over Python threads (the C call
+        releases the GIL); every chunk runs the same serial routine.
+        """
+        placement = _c(placement, np.int32)
+        rank = _c(rank, np.int32)
+        if layout == CAND_MAJOR:
+            C = placement.shape[0]
+            assert placement.shape == (C, self.N) and rank.shape == (C, self.N)
+            peak = np.empty((C, self.P), dtype=np.int64)
+        else:
+            C = placement.shape[1]
+            assert placement.shape == (self.N, C) and rank.shape == (self.N, C)
+            peak = np.empty((self.P, C), dtype=np.int64)
+        makespan = np.empty(C, dtype=np.int32)
+        bubble = np.empty(C, dtype=np.int64)
+        flags = np.empty(C, dtype=np.int32)
+        lib = _load()
+        rcs = []
+
+        def run(first, count):
+            rcs.append(lib.dagsched_oracle_evaluate(*self._head(), layout, C, _ptr(placement), _ptr(rank),
+                                                    first, count, _ptr(makespan), _ptr(bubble), _ptr(peak),
+                                                    _ptr(flags)))
+
+        threads = max(1, min(int(threads), C if C else 1))
+        if threads == 1:
+            run(0, C)
+        else:
+            bounds = np.linspace(0, C, threads + 1).astype(np.int64)
+            ts = [threading.Thread(target=run, args=(int(bounds[i]), int(bounds[i + 1] - bounds[i])))
+                  for i in range(threads)]
+            for t in ts:
+                t.start()
+            for t in ts:
+                t.join()
+        for rc in rcs:
+            if rc != OK:
+                raise OracleError(rc)
+        return makespan, bubble, peak, flags
+
+    def schedule(self, placement, rank):
+        """One candidate -> (flag, start, end, m_minus, m_plus); arrays valid when flag == 0."""
+        placement = _c(placement, np.int32).reshape(-1)
+        rank = _c(rank, np.int32).reshape(-1)
+        assert placement.shape == (self.N,) and rank.shape == (self.N,)
+        out = [np.zeros(self.N, dtype=np.int64) for _ in range(4)]
+        rc = _load().dagsched_oracle_schedule(*self._head(), _ptr(placement), _ptr(rank), *[_ptr(o) for o in out])
+        if rc < 0:
+            raise OracleError(rc)
+        return (rc, *out)
+
+
+class OracleError(RuntimeError):
+    def __init__(self, code: int):
+        super().__init__("oracle returned %d" % code)
+        self.code = code
+
+
+def evaluate_workload(w, layout: int = CAND_MAJOR, threads: int = 1):
+    """Convenience: evaluate every candidate of a workload object (candidate-major arrays)."""
+    prob = Problem.of(w)
+    if layout == CAND_MAJOR:
+        return prob.evaluate(w.placement, w.rank, layout, threads)
+    return prob.evaluate(np.ascontiguousarray(w.placement.T), np.ascontiguousarray(w.rank.T), layout, threads)

@@ -1,0 +1,300 @@
+/*
+ * CPU oracle for batched evaluation of candidate operator schedules.
+ *
+ * TEST INFRASTRUCTURE ONLY.  Plain, serial, slow and meant to be checked against the paper by
+ * eye.  It shares no code with the HIP library and must never be called from the product path;
+ * only the tests, the smoke check and the benchmark's CPU-baseline leg load it.
+ *
+ * What it computes (Sec. III of arxiv 2503.09357).  A candidate fixes every binary of the MIP:
+ * the allocation x (eq. (6)) as placement[i], and the per-machine total orders y (eqs. (7)-(8))
+ * together with the immediate-precedence variables u (used by eqs. (17)-(18)) as dense ranks:
+ * on machine j the ranks are exactly 0..n_j-1.  With the binaries fixed, eqs. (2), (3), (5), (7)
+ * and (11)-(13) are difference constraints  s_v >= e_u + const  on the disjunctive graph
+ * (operator DAG edges B plus one chain edge between consecutive operations of a machine), and
+ * the optimum of eq. (1) is the longest path: the earliest-start schedule
+ *
+ *     s_v = max( 0,                                   all machines free at t = 0 (assumption 1)
+ *                e_u               (u,v) chain edge,  one op per machine at a time (eq. (7))
+ *                e_u + delta(u,v)  (u,v) in B  )      eqs. (13),(11),(12): c >= e_u, d >= c + D^c, s_v >= d
+ *     e_v = s_v + D^o_v                               eq. (3), non-preemptive (assumption 3)
+ *
+ * with delta(u,v) = comm[placement[u]][placement[v]] when the two machines differ and 0 when they
+ * coincide (machine-dimension form of D^c, footnote of Sec. III; co-located operations exchange
+ * no message).  Results per candidate:
+ *
+ *     makespan  z = max_v e_v                                           eqs. (1)-(2)
+ *     bubble      = P * z - sum_v D^o_v    idle time of all P machines inside [0, z]
+ *     peak_mem[j] = max(0, max_k sum_{t<k} A_{list_j[t]})               eqs. (17)-(19): m+ = m- + A,
+ *                   the level after an operation is the level before the next one on that machine;
+ *                   the level starts at 0 and 0 takes part in the maximum
+ *     flags       = 2 BAD_PLACEMENT | 4 BAD_RANK | 1 CYCLIC | 0 (exactly one value, tested in that
+ *                   order); flagged candidates return -1 in every other output.
+ *
+ * A candidate is CYCLIC when DAG edges and chain edges together contain a directed cycle
+ * (eqs. (5), (7), (8) cannot hold together).  The test is structural (Kahn's algorithm pops
+ * fewer than N nodes), so zero-duration cycles are found as well.
+ *
+ * Algorithm: Kahn topological order on the combined graph, one candidate at a time.
+ *
+ * Pins (tests/test_oracle_*.py): 1F1B and GPipe closed forms, P = 1, one machine per node,
+ * alternating path, critical-path and load lower bounds, an independent unit-time-step simulator,
+ * brute-force enumeration of all linear extensions on tiny DAGs, the constraint system itself
+ * (eqs. (2),(3),(7),(11)-(13),(17)-(19)) with tightness, scaling / relabelling / time-reversal
+ * invariances, constructed cycles and malformed candidates.
+ * Parity unpinned: the DualPipe bubble values and the random-graph speed-up of Sec. V (the
+ * instances and the schedules found there are not published).
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { OR_OK = 0, OR_EINVAL = -1, OR_ECYCLE = -2, OR_EOVERFLOW = -3, OR_ENOMEM = -4 };
+enum { FLAG_CYCLIC = 1, FLAG_BAD_PLACEMENT = 2, FLAG_BAD_RANK = 4 };
+enum { LAYOUT_CAND_MAJOR = 0, LAYOUT_CAND_MINOR = 1 };
+
+/*
+ * Checks on the problem itself (not on a candidate):
+ *   EINVAL     sizes out of range, CSR not monotone, index out of range, self-loop, negative
+ *              duration, negative off-diagonal comm entry
+ *   ECYCLE     the operator graph is not a DAG (Sec. III requires one)
+ *   EOVERFLOW  sum(dur) + (N-1) * max off-diagonal comm > INT32_MAX: a path visits every node at
+ *              most once and pays at most one delay per edge, so below this bound int32 times
+ *              are exact
+ */
+int dagsched_oracle_check_problem(int32_t N, int32_t E, int32_t P, const int32_t *row_ptr,
+                                  const int32_t *col_idx, const int32_t *dur, const int32_t *comm,
+                                  const int64_t *mem_delta) {
+  if (N < 1 || E < 0 || P < 1 || P > 64) return OR_EINVAL;
+  if (!row_ptr || !dur || !comm || !mem_delta || (E > 0 && !col_idx)) return OR_EINVAL;
+  if (row_ptr[0] != 0 || row_ptr[N] != E) return OR_EINVAL;
+  for (int32_t u = 0; u < N; ++u)
+    if (row_ptr[u + 1] < row_ptr[u]) return OR_EINVAL;
+  for (int32_t u = 0; u < N; ++u)
+    for (int32_t k = row_ptr[u]; k < row_ptr[u + 1]; ++k)
+      if (col_idx[k] < 0 || col_idx[k] >= N || col_idx[k] == u) return OR_EINVAL;
+  int64_t sum_dur = 0, max_comm = 0;
+  for (int32_t v = 0; v < N; ++v) {
+    if (dur[v] < 0) return OR_EINVAL;
+    sum_dur += dur[v];
+  }
+  for (int32_t a = 0; a < P; ++a)
+    for (int32_t b = 0; b < P; ++b) {
+      if (a == b) continue;
+      if (comm[a * P + b] < 0) return OR_EINVAL;
+      if (comm[a * P + b] > max_comm) max_comm = comm[a * P + b];
+    }
+  /* the DAG must be acyclic: Kahn on B alone */
+  int32_t *indeg = (int32_t *)calloc((size_t)N, sizeof(int32_t));
+  int32_t *queue = (int32_t *)malloc((size_t)N * sizeof(int32_t));
+  if (!indeg || !queue) { free(indeg); free(queue); return OR_ENOMEM; }
+  for (int32_t k = 0; k < E; ++k) indeg[col_idx[k]]++;
+  int32_t head = 0, tail = 0;
+  for (int32_t v = 0; v < N; ++v) if (indeg[v] == 0) queue[tail++] = v;
+  while (head < tail) {
+    int32_t u = queue[head++];
+    for (int32_t k = row_ptr[u]; k < row_ptr[u + 1]; ++k)
+      if (--indeg[col_idx[k]] == 0) queue[tail++] = col_idx[k];
+  }
+  free(indeg); free(queue);
+  if (tail != N) return OR_ECYCLE;
+  if (sum_dur + (int64_t)(N - 1) * max_comm > (int64_t)INT32_MAX) return OR_EOVERFLOW;
+  return OR_OK;
+}
+
+typedef struct {
+  int32_t *cnt;     /* [P]   n_j                                   */
+  int32_t *off;     /* [P+1] start of machine j in list            */
+  int32_t *list;    /* [N]   list[off[j] + r] = node of rank r     */
+  int32_t *indeg;   /* [N]   remaining predecessors (DAG + chain)  */
+  int32_t *indeg_b; /* [N]   DAG in-degree (with multiplicity)     */
+  int32_t *queue;   /* [N]                                         */
+  int64_t *ready;   /* [N]   lower bound on s_v collected so far   */
+  int64_t *start;   /* [N]                                         */
+  int64_t *end;     /* [N]                                         */
+} scratch_t;
+
+static void scratch_free(scratch_t *w) {
+  free(w->cnt); free(w->off); free(w->list); free(w->indeg); free(w->indeg_b);
+  free(w->queue); free(w->ready); free(w->start); free(w->end);
+}
+
+static int scratch_alloc(scratch_t *w, int32_t N, int32_t P) {
+  memset(w, 0, sizeof(*w));
+  w->cnt = (int32_t *)malloc((size_t)P * sizeof(int32_t));
+  w->off = (int32_t *)malloc((size_t)(P + 1) * sizeof(int32_t));
+  w->list = (int32_t *)malloc((size_t)N * sizeof(int32_t));
+  w->indeg = (int32_t *)malloc((size_t)N * sizeof(int32_t));
+  w->indeg_b = (int32_t *)calloc((size_t)N, sizeof(int32_t));
+  w->queue = (int32_t *)malloc((size_t)N * sizeof(int32_t));
+  w->ready = (int64_t *)malloc((size_t)N * sizeof(int64_t));
+  w->start = (int64_t *)malloc((size_t)N * sizeof(int64_t));
+  w->end = (int64_t *)malloc((size_t)N * sizeof(int64_t));
+  if (!w->cnt || !w->off || !w->list || !w->indeg || !w->indeg_b || !w->queue || !w->ready ||
+      !w->start || !w->end) {
+    scratch_free(w);
+    return OR_ENOMEM;
+  }
+  return OR_OK;
+}
+
+/*
+ * One candidate.  pl[v*stride], rk[v*stride] are placement and rank of node v.
+ * Returns the flag; on flag 0 fills *makespan, *bubble, peak[j*peak_stride] and leaves
+ * start/end times of every node in w->start / w->end.
+ */
+static int32_t evaluate_one(int32_t N, int32_t P, const int32_t *row_ptr, const int32_t *col_idx,
+                            const int32_t *dur, const int32_t *comm, const int64_t *mem_delta,
+                            const int32_t *pl, const int32_t *rk, int64_t stride, scratch_t *w,
+                            int32_t *makespan, int64_t *bubble, int64_t *peak, int64_t peak_stride) {
+  /* 1. placement in range (eq. (6): exactly one machine of J) */
+  for (int32_t v = 0; v < N; ++v) {
+    int32_t j = pl[v * stride];
+    if (j < 0 || j >= P) return FLAG_BAD_PLACEMENT;
+  }
+  /* 2. ranks dense per machine: a total order on each machine (eqs. (7)-(8)) */
+  for (int32_t j = 0; j < P; ++j) w->cnt[j] = 0;
+  for (int32_t v = 0; v < N; ++v) w->cnt[pl[v * stride]]++;
+  w->off[0] = 0;
+  for (int32_t j = 0; j < P; ++j) w->off[j + 1] = w->off[j] + w->cnt[j];
+  for (int32_t i = 0; i < N; ++i) w->list[i] = -1;
+  for (int32_t v = 0; v < N; ++v) {
+    int32_t j = pl[v * stride], r = rk[v * stride];
+    if (r < 0 || r >= w->cnt[j]) return FLAG_BAD_RANK;
+    if (w->list[w->off[j] + r] != -1) return FLAG_BAD_RANK;
+    w->list[w->off[j] + r] = v;
+  }
+  /* 3. Kahn on the combined graph: DAG edges B plus chain edges list_j[k] -> list_j[k+1] */
+  for (int32_t v = 0; v < N; ++v) {
+    w->indeg[v] = w->indeg_b[v] + (rk[v * stride] > 0 ? 1 : 0);
+    w->ready[v] = 0;                                   /* s_v >= 0 */
+  }
+  int32_t head = 0, tail = 0;
+  for (int32_t v = 0; v < N; ++v) if (w->indeg[v] == 0) w->queue[tail++] = v;
+  while (head < tail) {
+    int32_t v = w->queue[head++];
+    int32_t jv = pl[v * stride];
+    int64_t s = w->ready[v];
+    int64_t e = s + dur[v];                            /* eq. (3) */
+    w->start[v] = s;
+    w->end[v] = e;
+    for (int32_t k = row_ptr[v]; k < row_ptr[v + 1]; ++k) {      /* data-dependent successors */
+      int32_t x = col_idx[k];
+      int32_t jx = pl[x * stride];
+      int64_t delay = (jx != jv) ? comm[jv * P + jx] : 0;        /* eqs. (11)-(13) */
+      if (e + delay > w->ready[x]) w->ready[x] = e + delay;
+      if (--w->indeg[x] == 0) w->queue[tail++] = x;
+    }
+    int32_t r = rk[v * stride];
+    if (r + 1 < w->cnt[jv]) {                                    /* next op on the same machine, eq. (7) */
+      int32_t x = w->list[w->off[jv] + r + 1];
+      if (e > w->ready[x]) w->ready[x] = e;
+      if (--w->indeg[x] == 0) w->queue[tail++] = x;
+    }
+  }
+  if (tail < N) return FLAG_CYCLIC;
+  /* 4. reductions */
+  int64_t z = 0, sum_dur = 0;
+  for (int32_t v = 0; v < N; ++v) {
+    if (w->end[v] > z) z = w->end[v];                  /* eq. (2) */
+    sum_dur += dur[v];
+  }
+  *makespan = (int32_t)z;
+  *bubble = (int64_t)P * z - sum_dur;
+  for (int32_t j = 0; j < P; ++j) {
+    int64_t level = 0, top = 0;                        /* eqs. (17)-(19) along the chain */
+    for (int32_t k = 0; k < w->cnt[j]; ++k) {
+      level += mem_delta[w->list[w->off[j] + k]];
+      if (level > top) top = level;
+    }
+    peak[j * peak_stride] = top;
+  }
+  return 0;
+}
+
+/*
+ * Evaluate candidates [first, first + count) of a batch of n_cand candidates.
+ * layout 0: placement[c*N + v], peak_mem[c*P + j];  layout 1: placement[v*n_cand + c], peak_mem[j*n_cand + c].
+ * All pointers are host memory; outputs are indexed by the absolute candidate number.
+ */
+int dagsched_oracle_evaluate(int32_t N, int32_t E, int32_t P, const int32_t *row_ptr,
+                             const int32_t *col_idx, const int32_t *dur, const int32_t *comm,
+                             const int64_t *mem_delta, int32_t layout, int64_t n_cand,
+                             const int32_t *placement, const int32_t *rank, int64_t first,
+                             int64_t count, int32_t *makespan, int64_t *bubble, int64_t *peak_mem,
+                             int32_t *flags) {
+  int rc = dagsched_oracle_check_problem(N, E, P, row_ptr, col_idx, dur, comm, mem_delta);
+  if (rc != OR_OK) return rc;
+  if (layout != LAYOUT_CAND_MAJOR && layout != LAYOUT_CAND_MINOR) return OR_EINVAL;
+  if (n_cand < 0 || first < 0 || count < 0 || first + count > n_cand) return OR_EINVAL;
+  if (count == 0) return OR_OK;
+  if (!placement || !rank || !makespan || !bubble || !peak_mem || !flags) return OR_EINVAL;
+  scratch_t w;
+  rc = scratch_alloc(&w, N, P);
+  if (rc != OR_OK) return rc;
+  for (int32_t k = 0; k < E; ++k) w.indeg_b[col_idx[k]]++;
+  for (int64_t c = first; c < first + count; ++c) {
+    const int32_t *pl, *rk;
+    int64_t stride, peak_stride;
+    int64_t *peak;
+    if (layout == LAYOUT_CAND_MAJOR) {
+      pl = placement + c * N; rk = rank + c * N; stride = 1;
+      peak = peak_mem + c * P; peak_stride = 1;
+    } else {
+      pl = placement + c; rk = rank + c; stride = n_cand;
+      peak = peak_mem + c; peak_stride = n_cand;
+    }
+    int32_t z = -1;
+    int64_t b = -1;
+    int32_t f = evaluate_one(N, P, row_ptr, col_idx, dur, comm, mem_delta, pl, rk, stride, &w, &z,
+                             &b, peak, peak_stride);
+    flags[c] = f;
+    if (f != 0) {
+      z = -1; b = -1;
+      for (int32_t j = 0; j < P; ++j) peak[j * peak_stride] = -1;
+    }
+    makespan[c] = z;
+    bubble[c] = b;
+  }
+  scratch_free(&w);
+  return OR_OK;
+}
+
+/*
+ * The full earliest-start schedule of ONE candidate (placement[N], rank[N]), for the constraint
+ * checker: start/end times (eqs. (2),(3)) and memory level before/after every operation
+ * (m-, m+ of eqs. (16)-(19), base level 0).  Returns the problem code (<0) or the flag (>= 0);
+ * the arrays are filled only when the result is 0.
+ */
+int dagsched_oracle_schedule(int32_t N, int32_t E, int32_t P, const int32_t *row_ptr,
+                             const int32_t *col_idx, const int32_t *dur, const int32_t *comm,
+                             const int64_t *mem_delta, const int32_t *placement, const int32_t *rank,
+                             int64_t *start, int64_t *end, int64_t *m_minus, int64_t *m_plus) {
+  int rc = dagsched_oracle_check_problem(N, E, P, row_ptr, col_idx, dur, comm, mem_delta);
+  if (rc != OR_OK) return rc;
+  if (!placement || !rank || !start || !end || !m_minus || !m_plus) return OR_EINVAL;
+  scratch_t w;
+  rc = scratch_alloc(&w, N, P);
+  if (rc != OR_OK) return rc;
+  for (int32_t k = 0; k < E; ++k) w.indeg_b[col_idx[k]]++;
+  int64_t *peak = (int64_t *)malloc((size_t)P * sizeof(int64_t));
+  if (!peak) { scratch_free(&w); return OR_ENOMEM; }
+  int32_t z;
+  int64_t b;
+  int32_t f = evaluate_one(N, P, row_ptr, col_idx, dur, comm, mem_delta, placement, rank, 1, &w, &z,
+                           &b, peak, 1);
+  if (f == 0) {
+    for (int32_t v = 0; v < N; ++v) { start[v] = w.start[v]; end[v] = w.end[v]; }
+    for (int32_t j = 0; j < P; ++j) {
+      int64_t level = 0;
+      for (int32_t k = 0; k < w.cnt[j]; ++k) {
+        int32_t v = w.list[w.off[j] + k];
+        m_minus[v] = level;
+        level += mem_delta[v];                         /* eq. (19) */
+        m_plus[v] = level;
+      }
+    }
+  }
+  free(peak);
+  scratch_free(&w);
+  return f;
+}

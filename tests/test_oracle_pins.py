@@ -1,0 +1,442 @@
+"""Pins for the CPU oracle: closed forms, special cases, lower bounds, an independent simulator,
+brute force, the constraint system, invariances, cycles and malformed candidates.
+
+Nothing here touches the HIP library.  Each test states what fixes the expected value.
+"""
+from __future__ import annotations
+
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2503_09357_amd import workloads as W
+
+import checkers as K
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+def _eval(w, layout=oracle.CAND_MAJOR):
+    return oracle.evaluate_workload(w, layout)
+
+
+def _problem(P, row_ptr, col_idx, dur, comm, mem):
+    return oracle.Problem(P, row_ptr, col_idx, dur, comm, mem)
+
+
+# --------------------------------------------------------------------------- hand-worked fixture
+
+def _read_golden(name):
+    out = {}
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            key, *vals = line.split()
+            out[key] = [int(x) for x in vals]
+    return out
+
+
+def test_hand_worked_diamond():
+    """tests/golden/hand_diamond.txt: worked by hand from eqs. (2),(3),(7),(11)-(13),(17)-(19)."""
+    g = _read_golden("hand_diamond.txt")
+    n, P = g["n_nodes"][0], g["n_devices"][0]
+    e = g["edges"]
+    row_ptr, col_idx = W.csr_from_edges(n, e[0::2], e[1::2])
+    prob = _problem(P, row_ptr, col_idx, g["dur"], np.array(g["comm"]).reshape(P, P), g["mem_delta"])
+    z, b, pk, f = prob.evaluate(np.array([g["placement"]]), np.array([g["rank"]]))
+    assert f[0] == 0 and z[0] == g["makespan"][0] and b[0] == g["bubble"][0]
+    assert pk[0].tolist() == g["peak_mem"]
+    flag, s, en, mm, mp = prob.schedule(g["placement"], g["rank"])
+    assert flag == 0 and s.tolist() == g["start"] and en.tolist() == g["end"]
+
+
+# --------------------------------------------------------------------------- P1 / P2 closed forms
+
+@pytest.mark.parametrize("p,m,tf,tb", [(4, 8, 2, 4), (2, 2, 1, 1), (3, 7, 5, 2), (8, 8, 1, 2), (6, 13, 3, 7), (1, 5, 2, 3)])
+def test_1f1b_closed_form(p, m, tf, tb):
+    """Uniform 1F1B without channel delay: z = (m+p-1)(tf+tb), bubble fraction (p-1)/(m+p-1),
+    in-flight activations on stage s peak at min(m, p-s)."""
+    w = W.uniform_pipeline(p, m, tf, tb, 0, "1f1b")
+    z, b, pk, f = _eval(w)
+    assert f[0] == 0
+    assert z[0] == (m + p - 1) * (tf + tb)
+    assert b[0] == p * (p - 1) * (tf + tb)
+    assert b[0] * (m + p - 1) == (p - 1) * p * z[0]          # bubble / (p z) = (p-1)/(m+p-1)
+    assert pk[0].tolist() == [min(m, p - s) for s in range(p)]
+
+
+@pytest.mark.parametrize("p,m,tf,tb,lam", [(4, 8, 2, 4, 0), (4, 8, 2, 4, 3), (2, 5, 1, 1, 7), (5, 3, 4, 2, 1), (3, 1, 2, 2, 2)])
+def test_gpipe_closed_form(p, m, tf, tb, lam):
+    """All forwards then all backwards with a uniform channel delay lam between stages:
+    fill (p-1)(tf+lam), m forwards + m backwards on the last stage, drain (p-1)(lam+tb);
+    every stage holds all m activations at its peak."""
+    w = W.uniform_pipeline(p, m, tf, tb, lam, "gpipe")
+    z, b, pk, f = _eval(w)
+    assert f[0] == 0
+    assert z[0] == (m + p - 1) * (tf + tb) + 2 * (p - 1) * lam
+    assert b[0] == p * z[0] - p * m * (tf + tb)
+    assert pk[0].tolist() == [m] * p
+
+
+# --------------------------------------------------------------------------- P3 single machine
+
+def test_single_machine():
+    """P = 1: one operation at a time means z = sum of durations and no idle time for any order
+    that respects the DAG; an order that violates a DAG edge is cyclic."""
+    rng = np.random.default_rng(3)
+    for _ in range(20):
+        n = int(rng.integers(2, 30))
+        row_ptr, col_idx = W.random_dag(rng, n, 3)
+        dur = rng.integers(0, 9, n).astype(np.int32)
+        mem = rng.integers(-5, 6, n).astype(np.int64)
+        prob = _problem(1, row_ptr, col_idx, dur, np.array([[0]]), mem)
+        pl, rk = W.list_schedules(row_ptr, col_idx, 1, 8, int(rng.integers(1 << 30)))
+        z, b, pk, f = prob.evaluate(pl, rk)
+        assert (f == 0).all() and (z == dur.sum()).all() and (b == 0).all()
+        if len(col_idx):
+            u = int(np.nonzero(np.diff(row_ptr))[0][0])
+            v = int(col_idx[row_ptr[u]])
+            bad = rk[0].copy()
+            bad[u], bad[v] = bad[v], bad[u]                   # v now runs before its producer u
+            z, b, pk, f = prob.evaluate(pl[:1], bad[None])
+            assert f[0] == oracle.FLAG_CYCLIC and z[0] == -1 and b[0] == -1 and (pk == -1).all()
+
+
+# --------------------------------------------------------------------------- P4 one machine per node
+
+def test_one_machine_per_node_is_critical_path():
+    """No chain edges at all: z is the textbook critical path with the channel delay on every edge."""
+    rng = np.random.default_rng(4)
+    for _ in range(20):
+        n = int(rng.integers(2, 40))
+        row_ptr, col_idx = W.random_dag(rng, n, 3)
+        dur = rng.integers(0, 9, n).astype(np.int32)
+        comm = rng.integers(0, 6, (n, n)).astype(np.int32)
+        prob = _problem(n, row_ptr, col_idx, dur, comm, np.zeros(n, np.int64))
+        pl = rng.permutation(n).astype(np.int32)
+        z, b, pk, f = prob.evaluate(pl[None], np.zeros((1, n), np.int32))
+        assert f[0] == 0
+        assert z[0] == K.critical_path(row_ptr, col_idx, dur, lambda u, v: int(comm[pl[u], pl[v]]))
+
+
+# --------------------------------------------------------------------------- P5 alternating path
+
+def test_path_on_alternating_machines():
+    """Chain 0 -> 1 -> ... on machines 0,1,0,1,...: z = sum dur + every channel delay on the way,
+    each taken in its own direction (the matrix is asymmetric)."""
+    rng = np.random.default_rng(5)
+    n = 11
+    row_ptr, col_idx = W.csr_from_edges(n, list(range(n - 1)), list(range(1, n)))
+    dur = rng.integers(1, 9, n).astype(np.int32)
+    comm = np.array([[0, 3], [10, 0]], dtype=np.int32)
+    pl = (np.arange(n) % 2).astype(np.int32)
+    rk = (np.arange(n) // 2).astype(np.int32)
+    z, b, pk, f = _problem(2, row_ptr, col_idx, dur, comm, np.zeros(n, np.int64)).evaluate(pl[None], rk[None])
+    n01 = sum(1 for i in range(n - 1) if i % 2 == 0)
+    n10 = (n - 1) - n01
+    assert f[0] == 0 and z[0] == dur.sum() + 3 * n01 + 10 * n10
+
+
+# --------------------------------------------------------------------------- P6 lower bounds
+
+@pytest.mark.parametrize("cfg,c", [(1, 256), (2, 256), (3, 32), (4, 16), (5, 4)])
+def test_lower_bounds_on_configs(cfg, c):
+    """Every feasible candidate obeys z >= critical path of the DAG (without and with the
+    candidate's own channel delays) and z >= the heaviest machine load."""
+    w = W.gen_config(cfg, n_cand=c)
+    z, b, pk, f = _eval(w)
+    cp0 = K.critical_path(w.row_ptr, w.col_idx, w.dur)
+    for i in range(c):
+        if f[i] != 0:
+            continue
+        assert z[i] >= cp0
+        load = np.bincount(w.placement[i], weights=w.dur, minlength=w.n_devices).max()
+        assert z[i] >= load
+        assert b[i] == w.n_devices * int(z[i]) - int(w.dur.sum())
+    for i in range(min(c, 3)):
+        if f[i] == 0:
+            pl = w.placement[i]
+            cpd = K.critical_path(w.row_ptr, w.col_idx, w.dur,
+                                  lambda u, v: int(w.comm[pl[u], pl[v]]) if pl[u] != pl[v] else 0)
+            assert z[i] >= cpd
+
+
+# --------------------------------------------------------------------------- P7 unit-time-step simulator
+
+def test_against_tick_simulator_random():
+    """An event-free clock simulation of the machines agrees on z, bubble, peaks, every start time,
+    and stalls exactly on the candidates the oracle calls cyclic."""
+    rng = np.random.default_rng(7)
+    n_cyc = n_ok = 0
+    for trial in range(60):
+        n = int(rng.integers(2, 14))
+        p = int(rng.integers(1, 5))
+        w = W.random_instance(rng, n, p, 6, max_fanin=3, max_dur=4, max_comm=3, frac_arbitrary=0.5, frac_bad=0.0)
+        prob = oracle.Problem.of(w)
+        z, b, pk, f = prob.evaluate(w.placement, w.rank)
+        for c in range(w.n_cand):
+            sim = K.tick_simulate(p, w.row_ptr, w.col_idx, w.dur, w.comm, w.mem_delta, w.placement[c], w.rank[c])
+            if sim is None:
+                assert f[c] == oracle.FLAG_CYCLIC
+                n_cyc += 1
+            else:
+                assert f[c] == 0
+                assert (z[c], b[c], pk[c].tolist()) == (sim[0], sim[1], sim[2])
+                flag, s, e, mm, mp = prob.schedule(w.placement[c], w.rank[c])
+                assert flag == 0 and (s == sim[3]).all() and (e == sim[4]).all()
+                n_ok += 1
+    assert n_cyc > 20 and n_ok > 100
+
+
+def test_against_tick_simulator_config1():
+    w = W.gen_config(1, n_cand=24)
+    z, b, pk, f = _eval(w)
+    for c in range(w.n_cand):
+        sim = K.tick_simulate(w.n_devices, w.row_ptr, w.col_idx, w.dur, w.comm, w.mem_delta, w.placement[c], w.rank[c])
+        assert sim is not None and f[c] == 0
+        assert (z[c], b[c], pk[c].tolist()) == (sim[0], sim[1], sim[2])
+
+
+# --------------------------------------------------------------------------- P8 brute force
+
+def test_brute_force_feasible_set_and_optimum():
+    """For tiny DAGs: the per-machine order tuples the oracle accepts are exactly the projections
+    of the DAG's linear extensions, and the best makespan over all tuples matches the simulator's."""
+    rng = np.random.default_rng(8)
+    for trial in range(25):
+        n = int(rng.integers(3, 8))
+        p = int(rng.integers(1, 4))
+        row_ptr, col_idx = W.random_dag(rng, n, 2)
+        dur = rng.integers(0, 5, n).astype(np.int32)
+        comm = rng.integers(0, 4, (p, p)).astype(np.int32)
+        mem = rng.integers(-3, 4, n).astype(np.int64)
+        pl = rng.integers(0, p, n).astype(np.int32)
+        prob = _problem(p, row_ptr, col_idx, dur, comm, mem)
+        projected = {K.project_extension(p, pl, ext) for ext in K.linear_extensions(row_ptr, col_idx)}
+        tuples, ranks = zip(*K.all_order_tuples(p, pl))
+        ranks = np.stack(ranks)
+        z, b, pk, f = prob.evaluate(np.repeat(pl[None], len(ranks), 0), ranks)
+        accepted = {t for t, fl in zip(tuples, f) if fl == 0}
+        assert accepted == projected
+        assert set(f.tolist()) <= {0, oracle.FLAG_CYCLIC}
+        best_sim = None
+        for t, r in zip(tuples, ranks):
+            sim = K.tick_simulate(p, row_ptr, col_idx, dur, comm, mem, pl, r)
+            if sim is not None:
+                best_sim = sim[0] if best_sim is None else min(best_sim, sim[0])
+        assert best_sim == z[f == 0].min()
+
+
+# --------------------------------------------------------------------------- P9 the constraint system
+
+@pytest.mark.parametrize("cfg,c", [(1, 16), (2, 8), (3, 2)])
+def test_constraints_hold_and_are_tight_configs(cfg, c):
+    w = W.gen_config(cfg, n_cand=c)
+    prob = oracle.Problem.of(w)
+    z, b, pk, f = prob.evaluate(w.placement, w.rank)
+    for i in range(c):
+        flag, s, e, mm, mp = prob.schedule(w.placement[i], w.rank[i])
+        assert flag == f[i]
+        if flag == 0:
+            K.check_constraints(w.n_devices, w.row_ptr, w.col_idx, w.dur, w.comm, w.mem_delta, w.placement[i],
+                                w.rank[i], s, e, mm, mp, int(z[i]))
+            lists = K.device_lists(w.n_devices, w.placement[i], w.rank[i])
+            for j, lst in enumerate(lists):
+                assert pk[i, j] == max([0] + [int(mp[v]) for v in lst])
+
+
+def test_constraints_hold_random():
+    rng = np.random.default_rng(9)
+    for trial in range(40):
+        n = int(rng.integers(2, 40))
+        p = int(rng.integers(1, 7))
+        w = W.random_instance(rng, n, p, 4, frac_arbitrary=0.0, frac_bad=0.0)
+        prob = oracle.Problem.of(w)
+        z, b, pk, f = prob.evaluate(w.placement, w.rank)
+        assert (f == 0).all()
+        for i in range(w.n_cand):
+            flag, s, e, mm, mp = prob.schedule(w.placement[i], w.rank[i])
+            K.check_constraints(p, w.row_ptr, w.col_idx, w.dur, w.comm, w.mem_delta, w.placement[i], w.rank[i],
+                                s, e, mm, mp, int(z[i]))
+
+
+# --------------------------------------------------------------------------- P10 invariances
+
+def _reverse_instance(w):
+    """Time reversal: reverse every DAG edge and every machine order, transpose comm."""
+    src, dst = W.edges_from_csr(w.row_ptr, w.col_idx)
+    row_ptr, col_idx = W.csr_from_edges(w.n_nodes, dst, src)
+    cnt = np.stack([np.bincount(w.placement[c], minlength=w.n_devices) for c in range(w.n_cand)])
+    rank = np.take_along_axis(cnt, w.placement, 1) - 1 - w.rank
+    return W.Workload("rev", w.n_devices, row_ptr, col_idx, w.dur, np.ascontiguousarray(w.comm.T), w.mem_delta,
+                      w.placement, rank.astype(np.int32))
+
+
+def test_invariances():
+    rng = np.random.default_rng(10)
+    for trial in range(30):
+        n = int(rng.integers(2, 50))
+        p = int(rng.integers(1, 7))
+        w = W.random_instance(rng, n, p, 6, frac_arbitrary=0.3, frac_bad=0.0)
+        z, b, pk, f = _eval(w)
+        # scaling durations and delays by k scales z by k and leaves feasibility and memory alone
+        k = int(rng.integers(2, 6))
+        ws = W.Workload("s", p, w.row_ptr, w.col_idx, w.dur * k, w.comm * k, w.mem_delta, w.placement, w.rank)
+        zs, bs, pks, fs = _eval(ws)
+        assert (fs == f).all() and (zs[f == 0] == k * z[f == 0]).all() and (pks == pk).all()
+        assert (bs[f == 0] == k * b[f == 0]).all()
+        # relabelling machines (with the comm matrix permuted alike) only permutes peak_mem
+        perm = rng.permutation(p)
+        inv = np.argsort(perm)
+        wp = W.Workload("p", p, w.row_ptr, w.col_idx, w.dur, w.comm[np.ix_(inv, inv)], w.mem_delta,
+                        perm[w.placement].astype(np.int32), w.rank)
+        zp, bp, pkp, fp = _eval(wp)
+        assert (fp == f).all() and (zp == z).all() and (bp == b).all() and (pkp[:, perm] == pk).all()
+        # time reversal keeps z (a longest path read backwards) and feasibility
+        zr, br, pkr, fr = _eval(_reverse_instance(w))
+        assert (fr == f).all() and (zr == z).all() and (br == b).all()
+        # an extra DAG edge between two operations the chain already orders changes nothing
+        for c in range(w.n_cand):
+            if f[c] != 0:
+                continue
+            lists = K.device_lists(p, w.placement[c], w.rank[c])
+            lst = max(lists, key=len)
+            if len(lst) < 2:
+                continue
+            a = int(rng.integers(0, len(lst) - 1))
+            bb = int(rng.integers(a + 1, len(lst)))
+            src, dst = W.edges_from_csr(w.row_ptr, w.col_idx)
+            rp2, ci2 = W.csr_from_edges(n, np.append(src, lst[a]), np.append(dst, lst[bb]))
+            z2, b2, pk2, f2 = _problem(p, rp2, ci2, w.dur, w.comm, w.mem_delta).evaluate(w.placement[c:c + 1],
+                                                                                          w.rank[c:c + 1])
+            assert f2[0] == 0 and z2[0] == z[c] and (pk2[0] == pk[c]).all()
+
+
+def test_layouts_agree():
+    rng = np.random.default_rng(11)
+    w = W.random_instance(rng, 23, 3, 17)
+    a = _eval(w, oracle.CAND_MAJOR)
+    bq = _eval(w, oracle.CAND_MINOR)
+    assert (a[0] == bq[0]).all() and (a[1] == bq[1]).all() and (a[3] == bq[3]).all()
+    assert (a[2] == bq[2].T).all()
+    t = oracle.evaluate_workload(w, oracle.CAND_MAJOR, threads=4)
+    assert all((x == y).all() for x, y in zip(a, t))
+
+
+# --------------------------------------------------------------------------- P11 constructed cycles
+
+def test_constructed_cycles():
+    """Single-machine cycle (B before its own F) and a two-machine cross deadlock."""
+    w = W.uniform_pipeline(4, 8, 2, 4, 1, "1f1b")
+    ids = w.meta["ids"]
+    rk = w.rank.copy()
+    f_, b_ = ids[("F", 2, 3)], ids[("B", 2, 3)]
+    rk[0, f_], rk[0, b_] = rk[0, b_], rk[0, f_]
+    z, b, pk, f = oracle.Problem.of(w).evaluate(w.placement, rk)
+    assert f[0] == oracle.FLAG_CYCLIC and z[0] == -1 and b[0] == -1 and (pk == -1).all()
+    # a1 -> b2 and b1 -> a2 in the DAG; machine A runs a2 before a1, machine B runs b2 before b1
+    a1, a2, b1, b2 = 0, 1, 2, 3
+    row_ptr, col_idx = W.csr_from_edges(4, [a1, b1], [b2, a2])
+    prob = _problem(2, row_ptr, col_idx, [0, 0, 0, 0], [[0, 0], [0, 0]], [0, 0, 0, 0])   # zero weights on purpose
+    pl = np.array([[0, 0, 1, 1]], np.int32)
+    z, b, pk, f = prob.evaluate(pl, np.array([[1, 0, 1, 0]], np.int32))
+    assert f[0] == oracle.FLAG_CYCLIC
+    z, b, pk, f = prob.evaluate(pl, np.array([[0, 1, 0, 1]], np.int32))
+    assert f[0] == 0 and z[0] == 0 and b[0] == 0
+
+
+def test_config2_marked_cyclic_candidates():
+    w = W.gen_config(2, n_cand=4096)
+    z, b, pk, f = _eval(w)
+    marked = np.zeros(w.n_cand, bool)
+    marked[w.meta["cyclic"]] = True
+    assert marked.sum() > 10
+    assert ((f == oracle.FLAG_CYCLIC) == marked).all()
+    assert (z[marked] == -1).all() and (pk[marked] == -1).all() and (z[~marked] > 0).all()
+
+
+# --------------------------------------------------------------------------- P12 malformed candidates
+
+def test_bad_candidates_flag_precedence():
+    w = W.uniform_pipeline(3, 4, 2, 3, 1, "1f1b")
+    prob = oracle.Problem.of(w)
+    n = w.n_nodes
+
+    def run(pl, rk):
+        z, b, pk, f = prob.evaluate(pl[None], rk[None])
+        if f[0] != 0:
+            assert z[0] == -1 and b[0] == -1 and (pk == -1).all()
+        return int(f[0])
+
+    pl0, rk0 = w.placement[0], w.rank[0]
+    assert run(pl0, rk0) == 0
+    for bad in (-1, -7, 3, 64, 2 ** 31 - 1, -2 ** 31):
+        pl = pl0.copy(); pl[5] = bad
+        assert run(pl, rk0) == oracle.FLAG_BAD_PLACEMENT
+    rk = rk0.copy(); rk[4] = rk[np.nonzero((pl0 == pl0[4]) & (np.arange(n) != 4))[0][0]]
+    assert run(pl0, rk) == oracle.FLAG_BAD_RANK                       # duplicate rank
+    rk = rk0.copy(); rk[4] = -1
+    assert run(pl0, rk) == oracle.FLAG_BAD_RANK                       # negative rank
+    rk = rk0.copy(); rk[np.argmax(rk0 * (pl0 == 1))] += 1
+    assert run(pl0, rk) == oracle.FLAG_BAD_RANK                       # gap at the top
+    rk = rk0.copy(); rk[4] = 2 ** 31 - 1
+    assert run(pl0, rk) == oracle.FLAG_BAD_RANK
+    # bad placement wins over bad rank
+    pl = pl0.copy(); pl[0] = 99
+    rk = rk0.copy(); rk[4] = -1
+    assert run(pl, rk) == oracle.FLAG_BAD_PLACEMENT
+    # bad rank wins over cyclic
+    ids = w.meta["ids"]
+    rk = rk0.copy()
+    f_, b_ = ids[("F", 1, 1)], ids[("B", 1, 1)]
+    rk[f_], rk[b_] = rk[b_], rk[f_]
+    assert run(pl0, rk) == oracle.FLAG_CYCLIC
+    rk[ids[("F", 0, 0)]] = -3
+    assert run(pl0, rk) == oracle.FLAG_BAD_RANK
+    # moving an operation to another machine without re-ranking leaves a gap behind
+    pl = pl0.copy(); pl[ids[("F", 0, 0)]] = 2
+    assert run(pl, rk0) == oracle.FLAG_BAD_RANK
+
+
+def test_problem_checks():
+    rp, ci = W.csr_from_edges(3, [0, 1], [1, 2])
+    ok = dict(dur=[1, 2, 3], comm=[[0, 1], [1, 0]], mem=[0, 0, 0])
+
+    def code(P=2, rp=rp, ci=ci, dur=ok["dur"], comm=ok["comm"], mem=ok["mem"]):
+        return _problem(P, rp, ci, dur, comm, mem).check()
+
+    assert code() == oracle.OK
+    assert code(dur=[1, -2, 3]) == oracle.EINVAL
+    assert code(comm=[[0, -1], [1, 0]]) == oracle.EINVAL
+    assert code(comm=[[-5, 1], [1, -9]]) == oracle.OK                   # the diagonal is never read
+    assert code(P=65, comm=np.zeros((65, 65))) == oracle.EINVAL
+    rp2, ci2 = W.csr_from_edges(3, [0, 1, 2], [1, 2, 0])
+    assert code(rp=rp2, ci=ci2) == oracle.ECYCLE
+    assert code(rp=np.array([0, 1, 2, 2]), ci=np.array([0, 2])) == oracle.EINVAL      # self-loop
+    assert code(rp=np.array([0, 1, 2, 2]), ci=np.array([1, 3])) == oracle.EINVAL      # index out of range
+    assert code(rp=np.array([0, 2, 1, 2]), ci=np.array([1, 2])) == oracle.EINVAL      # not monotone
+    big = 2 ** 31 - 1
+    assert code(dur=[big, 0, 0], comm=[[0, 0], [0, 0]]) == oracle.OK
+    assert code(dur=[big, 1, 0], comm=[[0, 0], [0, 0]]) == oracle.EOVERFLOW
+    assert code(dur=[big - 2, 0, 0], comm=[[0, 1], [0, 0]]) == oracle.OK             # + (N-1)*1 = big
+    assert code(dur=[big - 1, 0, 0], comm=[[0, 1], [0, 0]]) == oracle.EOVERFLOW
+    # duplicate edges are legal and change nothing
+    rp3, ci3 = W.csr_from_edges(3, [0, 0, 1], [1, 1, 2])
+    p3 = _problem(2, rp3, ci3, *[ok[k] for k in ("dur", "comm", "mem")])
+    p1 = _problem(2, rp, ci, *[ok[k] for k in ("dur", "comm", "mem")])
+    pl = np.array([[0, 1, 0]], np.int32); rk = np.array([[0, 0, 1]], np.int32)
+    assert all((a == b).all() for a, b in zip(p3.evaluate(pl, rk), p1.evaluate(pl, rk)))
+
+
+def test_empty_batch_and_isolated_nodes():
+    rp, ci = W.csr_from_edges(3, [], [])
+    prob = _problem(2, rp, ci, [4, 5, 6], [[0, 1], [1, 0]], [1, 2, -3])
+    z, b, pk, f = prob.evaluate(np.zeros((0, 3), np.int32), np.zeros((0, 3), np.int32))
+    assert len(z) == 0
+    z, b, pk, f = prob.evaluate(np.array([[0, 0, 0]]), np.array([[2, 0, 1]]))
+    assert f[0] == 0 and z[0] == 15 and b[0] == 15 and pk[0].tolist() == [2, 0]
+    # order 1, 2, 0 on machine 0: levels 2, -1, 0 -> peak 2; machine 1 is empty: peak 0
