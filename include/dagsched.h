@@ -1,0 +1,151 @@
+/*
+ * dagsched - batched evaluation of candidate operator schedules on one MI355X (gfx950).
+ *
+ * Problem statement (arxiv 2503.09357, Sec. III and its notation table).  An operator DAG
+ * G_m(I, B) with durations D^o_i, a cluster of P machines with a channel-delay matrix (the
+ * machine-dimension form of D^c, footnote of Sec. III) and memory adjustments A_i are fixed.
+ * A *candidate* fixes every binary of the MIP: the allocation x (eq. (6)) as placement[i], and
+ * the per-machine total order y / immediate precedence u (eqs. (7)-(8), (17)-(18)) as a dense
+ * per-machine rank[i] (on machine j the ranks are exactly 0..n_j-1).  With the binaries fixed,
+ * eqs. (2), (3), (5), (7), (11)-(13) are difference constraints on the disjunctive graph (DAG
+ * edges plus one chain edge between consecutive operations of a machine) and the optimum of
+ * eq. (1) is a longest path.  For every candidate the library returns
+ *
+ *   makespan   z = max_i e_i, where s_v = max(0, e_chainpred(v), max_{(u,v) in B} e_u + delta(u,v)),
+ *              e_v = s_v + D^o_v, delta(u,v) = comm[placement[u]][placement[v]] if the machines
+ *              differ, else 0                                    (eqs. (1)-(3), (7), (11)-(13))
+ *   bubble     P * z - sum_i D^o_i  (idle time of all P machines inside [0, z])
+ *   peak_mem   per machine, the maximum over prefixes of its order of the running sum of A_i,
+ *              the empty prefix (level 0) included                (eqs. (17)-(19))
+ *   flags      0, or exactly one of DAGSCHED_FLAG_*; a flagged candidate has makespan = bubble =
+ *              every peak_mem entry = -1.
+ *
+ * All entry points are thread-compatible, not thread-safe per handle: one evaluate at a time per
+ * handle; distinct handles are independent.
+ */
+#ifndef DAGSCHED_H
+#define DAGSCHED_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dagsched dagsched_t; /* opaque, owned by the library */
+
+/* Return codes of create / validate / evaluate. */
+enum {
+  DAGSCHED_OK = 0,
+  DAGSCHED_EINVAL = -1,    /* null pointer, size out of range, malformed CSR, negative dur / comm, bad layout,
+                              n_cand > max_candidates */
+  DAGSCHED_ECYCLE = -2,    /* the operator graph itself is cyclic (Sec. III requires a DAG) */
+  DAGSCHED_EOVERFLOW = -3, /* sum(dur) + (N-1) * max off-diagonal comm > INT32_MAX: int32 times would not be exact */
+  DAGSCHED_ENOMEM = -4,    /* host or device allocation failed */
+  DAGSCHED_EHIP = -5       /* any other HIP runtime failure */
+};
+
+/* Per-candidate flags[c]: exactly one value, tested in this order. */
+enum {
+  DAGSCHED_FLAG_OK = 0,
+  DAGSCHED_FLAG_BAD_PLACEMENT = 2, /* some placement[i] outside [0, P)                    (eq. (6))      */
+  DAGSCHED_FLAG_BAD_RANK = 4,      /* some machine's ranks are not exactly {0..n_j-1}     (eqs. (7)-(8)) */
+  DAGSCHED_FLAG_CYCLIC = 1         /* DAG edges + chain edges contain a directed cycle: eqs. (5), (7), (8)
+                                      cannot hold together.  Structural test, zero-duration cycles included. */
+};
+
+/* Memory layout of placement, rank and peak_mem. */
+enum {
+  DAGSCHED_CAND_MAJOR = 0, /* placement[c*N + i], peak_mem[c*P + j] */
+  DAGSCHED_CAND_MINOR = 1  /* placement[i*C + c], peak_mem[j*C + c]  (C = n_cand of the call) */
+};
+
+/* Limits of this implementation. */
+#define DAGSCHED_MAX_DEVICES 64
+#define DAGSCHED_MAX_NODES 65535
+
+/*
+ * The candidate-independent part of the problem.  Every pointer is HOST memory and is deep-copied
+ * by dagsched_create; the caller may free it as soon as the call returns.
+ */
+typedef struct {
+  int32_t n_nodes;          /* N = |I|, 1 <= N <= DAGSCHED_MAX_NODES                                        */
+  int32_t n_edges;          /* E = |B| >= 0                                                                  */
+  int32_t n_devices;        /* P = |J|, 1 <= P <= DAGSCHED_MAX_DEVICES                                       */
+  const int32_t *row_ptr;   /* [N+1] successor CSR of B: edges u -> col_idx[k], k in [row_ptr[u], row_ptr[u+1]) */
+  const int32_t *col_idx;   /* [E]   duplicates allowed, self-loops rejected                                 */
+  const int32_t *dur;       /* [N]   D^o_i >= 0                                                              */
+  const int32_t *comm;      /* [P*P] comm[src*P + dst] >= 0 off the diagonal; may be asymmetric; the diagonal
+                                     is never read                                                           */
+  const int64_t *mem_delta; /* [N]   A_i, any sign                                                           */
+  int32_t max_candidates;   /* capacity of the per-handle device workspace, >= 1                             */
+  int32_t layout;           /* DAGSCHED_CAND_MAJOR or DAGSCHED_CAND_MINOR                                     */
+  int32_t hip_device;       /* ordinal of the GPU that owns the handle                                       */
+} dagsched_desc_t;
+
+/*
+ * Host-only check of a description (no GPU is touched): sizes, CSR shape, signs, acyclicity of B
+ * (Sec. III: G_m is a DAG) and the int32 exactness bound.  Returns DAGSCHED_OK or the error
+ * dagsched_create would return for the same description.
+ */
+int dagsched_validate(const dagsched_desc_t *desc);
+
+/*
+ * Validate, then upload the problem to desc->hip_device and allocate the workspace for
+ * max_candidates candidates.  On success *out receives the handle; on error *out is untouched.
+ * Synchronous; uses the device's default stream for the upload.
+ */
+int dagsched_create(const dagsched_desc_t *desc, dagsched_t **out);
+
+/*
+ * Evaluate n_cand candidates (0 <= n_cand <= max_candidates).  All six array arguments are DEVICE
+ * pointers on the handle's GPU, owned by the caller and borrowed until the work enqueued on
+ * hip_stream (a hipStream_t, or NULL for the default stream) has completed:
+ *   placement, rank : int32, N * n_cand entries in the handle's layout       (inputs, read only)
+ *   makespan        : int32 [n_cand]
+ *   bubble          : int64 [n_cand]
+ *   peak_mem        : int64, n_cand * P entries in the handle's layout
+ *   flags           : int32 [n_cand]
+ * Asynchronous: enqueues kernels only, performs no host synchronisation and no allocation.
+ * Per-candidate problems are reported through flags, never through the return code.
+ * Implements, per candidate, validation of x and y (eqs. (6)-(8)), the chain edges u, the
+ * max-plus longest path (eqs. (2), (3), (5), (7), (11)-(13)), and the memory levels (eqs. (17)-(19)).
+ */
+int dagsched_evaluate(dagsched_t *h, int32_t n_cand, const int32_t *placement, const int32_t *rank,
+                      int32_t *makespan, int64_t *bubble, int64_t *peak_mem, int32_t *flags,
+                      void *hip_stream);
+
+/* Release the handle and its device memory.  NULL is a no-op.  Synchronises the device first. */
+void dagsched_destroy(dagsched_t *h);
+
+/* Static, human-readable text for a return code; for DAGSCHED_EHIP it includes the last HIP error
+ * recorded by this library on the calling thread. */
+const char *dagsched_strerror(int code);
+
+/*
+ * Introspection for benchmarks and tests: which kernel variant the handle selected and its launch
+ * shape.  Fills the struct and returns DAGSCHED_OK, or DAGSCHED_EINVAL on NULL.
+ */
+typedef struct {
+  int32_t variant;         /* internal kernel variant id */
+  int32_t cand_per_block;  /* candidates evaluated by one workgroup */
+  int32_t block_threads;   /* workgroup size */
+  int32_t lds_bytes;       /* dynamic LDS per workgroup */
+  int32_t state_bits;      /* width of the per-node end-time state (16 or 32) */
+  int32_t reserved[3];
+} dagsched_info_t;
+int dagsched_get_info(const dagsched_t *h, dagsched_info_t *info);
+
+/*
+ * Timing aid: evaluate `reps` times back to back on hip_stream between two HIP events recorded on
+ * that same stream and return the mean milliseconds per evaluate in *ms_per_eval.  Synchronises
+ * hip_stream.  Same pointer contract as dagsched_evaluate.
+ */
+int dagsched_time_evaluate(dagsched_t *h, int32_t n_cand, const int32_t *placement, const int32_t *rank,
+                           int32_t *makespan, int64_t *bubble, int64_t *peak_mem, int32_t *flags,
+                           void *hip_stream, int32_t reps, float *ms_per_eval);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DAGSCHED_H */

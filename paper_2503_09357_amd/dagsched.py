@@ -1,0 +1,202 @@
+"""Thin Python binding of the C-ABI in include/dagsched.h (argument marshalling only).
+
+Every step of the evaluation runs in the HIP kernels of ``libdagsched.so``; PyTorch is used for
+device buffers and streams.  There is no CPU fallback: if the library cannot be loaded, or a
+call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+from typing import Optional, Tuple
+
+import numpy as np
+
+from . import _build
+
+OK, EINVAL, ECYCLE, EOVERFLOW, ENOMEM, EHIP = 0, -1, -2, -3, -4, -5
+FLAG_OK, FLAG_CYCLIC, FLAG_BAD_PLACEMENT, FLAG_BAD_RANK = 0, 1, 2, 4
+CAND_MAJOR, CAND_MINOR = 0, 1
+MAX_DEVICES, MAX_NODES = 64, 65535
+
+EXPORTS = ("dagsched_validate", "dagsched_create", "dagsched_evaluate", "dagsched_destroy",
+           "dagsched_strerror", "dagsched_get_info", "dagsched_time_evaluate")
+
+
+class Desc(ctypes.Structure):
+    _fields_ = [("n_nodes", ctypes.c_int32), ("n_edges", ctypes.c_int32), ("n_devices", ctypes.c_int32),
+                ("row_ptr", ctypes.c_void_p), ("col_idx", ctypes.c_void_p), ("dur", ctypes.c_void_p),
+                ("comm", ctypes.c_void_p), ("mem_delta", ctypes.c_void_p),
+                ("max_candidates", ctypes.c_int32), ("layout", ctypes.c_int32), ("hip_device", ctypes.c_int32)]
+
+
+class Info(ctypes.Structure):
+    _fields_ = [("variant", ctypes.c_int32), ("cand_per_block", ctypes.c_int32), ("block_threads", ctypes.c_int32),
+                ("lds_bytes", ctypes.c_int32), ("state_bits", ctypes.c_int32), ("reserved", ctypes.c_int32 * 3)]
+
+
+class DagschedError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__("dagsched error %d: %s" % (code, text))
+        self.code = code
+
+
+_lib = None
+
+
+def load(import_torch_first: bool = True):
+    """dlopen libdagsched.so (built in-tree).  PyTorch is imported first so that the library binds
+    to the HIP runtime already resident in the process (one runtime, shared streams)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if import_torch_first:
+        import torch  # noqa: F401
+    path = _build.ensure_hip()
+    lib = ctypes.CDLL(path)
+    vp, i32 = ctypes.c_void_p, ctypes.c_int32
+    lib.dagsched_validate.restype = ctypes.c_int
+    lib.dagsched_validate.argtypes = [ctypes.POINTER(Desc)]
+    lib.dagsched_create.restype = ctypes.c_int
+    lib.dagsched_create.argtypes = [ctypes.POINTER(Desc), ctypes.POINTER(vp)]
+    lib.dagsched_evaluate.restype = ctypes.c_int
+    lib.dagsched_evaluate.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp]
+    lib.dagsched_time_evaluate.restype = ctypes.c_int
+    lib.dagsched_time_evaluate.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, i32, ctypes.POINTER(ctypes.c_float)]
+    lib.dagsched_destroy.restype = None
+    lib.dagsched_destroy.argtypes = [vp]
+    lib.dagsched_strerror.restype = ctypes.c_char_p
+    lib.dagsched_strerror.argtypes = [ctypes.c_int]
+    lib.dagsched_get_info.restype = ctypes.c_int
+    lib.dagsched_get_info.argtypes = [vp, ctypes.POINTER(Info)]
+    _lib = lib
+    return lib
+
+
+def strerror(code: int) -> str:
+    return load().dagsched_strerror(code).decode()
+
+
+def _check(code: int):
+    if code != OK:
+        raise DagschedError(code, strerror(code))
+
+
+class _HostProblem:
+    """Keeps the contiguous host arrays alive while a Desc points at them."""
+
+    def __init__(self, n_devices, row_ptr, col_idx, dur, comm, mem_delta, max_candidates, layout, hip_device,
+                 n_nodes=None, n_edges=None):
+        self.row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int32)
+        self.col_idx = np.ascontiguousarray(col_idx, dtype=np.int32)
+        self.dur = np.ascontiguousarray(dur, dtype=np.int32)
+        self.comm = np.ascontiguousarray(comm, dtype=np.int32).reshape(-1)
+        self.mem_delta = np.ascontiguousarray(mem_delta, dtype=np.int64)
+        d = Desc()
+        d.n_nodes = len(self.row_ptr) - 1 if n_nodes is None else n_nodes
+        d.n_edges = len(self.col_idx) if n_edges is None else n_edges
+        d.n_devices = n_devices
+        d.row_ptr = self.row_ptr.ctypes.data if self.row_ptr.size else None
+        d.col_idx = self.col_idx.ctypes.data if self.col_idx.size else None
+        d.dur = self.dur.ctypes.data if self.dur.size else None
+        d.comm = self.comm.ctypes.data if self.comm.size else None
+        d.mem_delta = self.mem_delta.ctypes.data if self.mem_delta.size else None
+        d.max_candidates = max_candidates
+        d.layout = layout
+        d.hip_device = hip_device
+        self.desc = d
+
+
+def validate(n_devices, row_ptr, col_idx, dur, comm, mem_delta, max_candidates=1, layout=CAND_MAJOR,
+             n_nodes=None, n_edges=None) -> int:
+    """Host-only description check; returns the code dagsched_create would return."""
+    hp = _HostProblem(n_devices, row_ptr, col_idx, dur, comm, mem_delta, max_candidates, layout, 0, n_nodes, n_edges)
+    return load(import_torch_first=False).dagsched_validate(ctypes.byref(hp.desc))
+
+
+class Evaluator:
+    """dagsched_create / dagsched_evaluate / dagsched_destroy around torch device tensors."""
+
+    def __init__(self, n_devices, row_ptr, col_idx, dur, comm, mem_delta, max_candidates: int,
+                 layout: int = CAND_MAJOR, hip_device: int = 0):
+        lib = load()
+        hp = _HostProblem(n_devices, row_ptr, col_idx, dur, comm, mem_delta, max_candidates, layout, hip_device)
+        handle = ctypes.c_void_p()
+        _check(lib.dagsched_create(ctypes.byref(hp.desc), ctypes.byref(handle)))
+        self._h = handle
+        self.N, self.P = hp.desc.n_nodes, n_devices
+        self.layout, self.max_candidates, self.hip_device = layout, max_candidates, hip_device
+
+    @classmethod
+    def for_workload(cls, w, max_candidates: Optional[int] = None, layout: int = CAND_MAJOR, hip_device: int = 0):
+        return cls(w.n_devices, w.row_ptr, w.col_idx, w.dur, w.comm, w.mem_delta,
+                   w.n_cand if max_candidates is None else max_candidates, layout, hip_device)
+
+    def info(self) -> dict:
+        i = Info()
+        _check(load().dagsched_get_info(self._h, ctypes.byref(i)))
+        return {k: getattr(i, k) for k in ("variant", "cand_per_block", "block_threads", "lds_bytes", "state_bits")}
+
+    def _n_cand(self, placement, rank) -> int:
+        import torch
+        for t in (placement, rank):
+            if not (t.is_cuda and t.dtype == torch.int32 and t.is_contiguous() and t.dim() == 2):
+                raise ValueError("placement/rank must be contiguous 2-D int32 device tensors")
+        shape = tuple(placement.shape)
+        if tuple(rank.shape) != shape:
+            raise ValueError("placement and rank differ in shape")
+        if self.layout == CAND_MAJOR:
+            if shape[1] != self.N:
+                raise ValueError("candidate-major tensors must be [C, N]")
+            return shape[0]
+        if shape[0] != self.N:
+            raise ValueError("candidate-minor tensors must be [N, C]")
+        return shape[1]
+
+    def alloc_outputs(self, n_cand: int):
+        import torch
+        dev = torch.device("cuda", self.hip_device)
+        pk_shape = (n_cand, self.P) if self.layout == CAND_MAJOR else (self.P, n_cand)
+        return (torch.empty(n_cand, dtype=torch.int32, device=dev), torch.empty(n_cand, dtype=torch.int64, device=dev),
+                torch.empty(pk_shape, dtype=torch.int64, device=dev), torch.empty(n_cand, dtype=torch.int32, device=dev))
+
+    def evaluate(self, placement, rank, out: Optional[Tuple] = None, stream=None):
+        """Enqueue one evaluation on ``stream`` (default: torch's current stream); asynchronous.
+        Returns (makespan int32 [C], bubble int64 [C], peak_mem int64 [C,P] | [P,C], flags int32 [C])."""
+        import torch
+        n_cand = self._n_cand(placement, rank)
+        if out is None:
+            out = self.alloc_outputs(n_cand)
+        z, b, pk, f = out
+        s = torch.cuda.current_stream(self.hip_device) if stream is None else stream
+        _check(load().dagsched_evaluate(self._h, n_cand, placement.data_ptr(), rank.data_ptr(), z.data_ptr(),
+                                        b.data_ptr(), pk.data_ptr(), f.data_ptr(), s.cuda_stream))
+        return out
+
+    def time_evaluate(self, placement, rank, out, reps: int, stream=None) -> float:
+        """Mean milliseconds per evaluation over ``reps`` back-to-back launches (HIP events on the stream)."""
+        import torch
+        n_cand = self._n_cand(placement, rank)
+        z, b, pk, f = out
+        s = torch.cuda.current_stream(self.hip_device) if stream is None else stream
+        ms = ctypes.c_float()
+        _check(load().dagsched_time_evaluate(self._h, n_cand, placement.data_ptr(), rank.data_ptr(), z.data_ptr(),
+                                             b.data_ptr(), pk.data_ptr(), f.data_ptr(), s.cuda_stream, reps,
+                                             ctypes.byref(ms)))
+        return float(ms.value)
+
+    def close(self):
+        if self._h:
+            load().dagsched_destroy(self._h)
+            self._h = None
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

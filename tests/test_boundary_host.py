@@ -1,0 +1,92 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every declared symbol, and its host-side
+description check returns the documented codes (the same codes the oracle's problem check returns)."""
+from __future__ import annotations
+
+import ctypes
+import os
+import re
+
+import numpy as np
+
+import oracle
+from paper_2503_09357_amd import _build, dagsched
+from paper_2503_09357_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "dagsched.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dagsched_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = ctypes.CDLL(_build.ensure_hip())
+    names = _declared_symbols()
+    assert set(names) == set(dagsched.EXPORTS)
+    for name in names:
+        assert getattr(lib, name) is not None
+
+
+def test_strerror_texts():
+    lib = dagsched.load(import_torch_first=False)
+    for code in (0, -1, -2, -3, -4, -5, -99):
+        assert len(lib.dagsched_strerror(code)) > 0
+
+
+def test_validate_codes_match_oracle_problem_check():
+    rp, ci = W.csr_from_edges(3, [0, 1], [1, 2])
+    base = dict(n_devices=2, row_ptr=rp, col_idx=ci, dur=[1, 2, 3], comm=[[0, 1], [1, 0]], mem_delta=[0, 0, 0])
+    big = 2 ** 31 - 1
+    rp_cyc, ci_cyc = W.csr_from_edges(3, [0, 1, 2], [1, 2, 0])
+    cases = [
+        ({}, dagsched.OK),
+        ({"dur": [1, -2, 3]}, dagsched.EINVAL),
+        ({"comm": [[0, -1], [1, 0]]}, dagsched.EINVAL),
+        ({"comm": [[-5, 1], [1, -9]]}, dagsched.OK),
+        ({"row_ptr": rp_cyc, "col_idx": ci_cyc}, dagsched.ECYCLE),
+        ({"row_ptr": np.array([0, 1, 2, 2]), "col_idx": np.array([0, 2])}, dagsched.EINVAL),
+        ({"row_ptr": np.array([0, 1, 2, 2]), "col_idx": np.array([1, 3])}, dagsched.EINVAL),
+        ({"row_ptr": np.array([0, 2, 1, 2]), "col_idx": np.array([1, 2])}, dagsched.EINVAL),
+        ({"dur": [big, 0, 0], "comm": [[0, 0], [0, 0]]}, dagsched.OK),
+        ({"dur": [big, 1, 0], "comm": [[0, 0], [0, 0]]}, dagsched.EOVERFLOW),
+        ({"dur": [big - 2, 0, 0], "comm": [[0, 1], [0, 0]]}, dagsched.OK),
+        ({"dur": [big - 1, 0, 0], "comm": [[0, 1], [0, 0]]}, dagsched.EOVERFLOW),
+    ]
+    for change, want in cases:
+        args = dict(base, **change)
+        assert dagsched.validate(**args) == want, change
+        prob = oracle.Problem(args["n_devices"], args["row_ptr"], args["col_idx"], args["dur"], args["comm"],
+                              args["mem_delta"])
+        assert prob.check() == want, change
+    # arguments only the boundary has
+    assert dagsched.validate(**base, max_candidates=0) == dagsched.EINVAL
+    assert dagsched.validate(**base, layout=7) == dagsched.EINVAL
+    assert dagsched.validate(**dict(base, n_devices=65, comm=np.zeros((65, 65)))) == dagsched.EINVAL
+    assert dagsched.validate(**dict(base, n_devices=0)) == dagsched.EINVAL
+    assert dagsched.load(import_torch_first=False).dagsched_validate(None) == dagsched.EINVAL
+    # null array pointer
+    d = dagsched._HostProblem(2, rp, ci, [1, 2, 3], [[0, 1], [1, 0]], [0, 0, 0], 1, 0, 0)
+    d.desc.dur = None
+    assert dagsched.load(import_torch_first=False).dagsched_validate(ctypes.byref(d.desc)) == dagsched.EINVAL
+
+
+def test_validate_accepts_all_configs():
+    for cfg in (1, 2, 3, 4, 5):
+        w = W.gen_config(cfg, n_cand=1)
+        assert dagsched.validate(w.n_devices, w.row_ptr, w.col_idx, w.dur, w.comm, w.mem_delta) == dagsched.OK
+
+
+def test_generators_are_seeded_and_prefix_consistent():
+    a = W.gen_config(4, n_cand=6)
+    b = W.gen_config(4, n_cand=3)
+    assert (a.placement[:3] == b.placement).all() and (a.rank[:3] == b.rank).all()
+    assert (a.dur == b.dur).all() and (a.col_idx == b.col_idx).all()
+    c = W.gen_config(4, n_cand=3, seed=123)
+    assert not (c.placement == b.placement).all()
+    for cfg, (n, e, p) in {1: (64, 80, 4), 2: (768, 960, 8), 3: (6144, 7040, 16), 4: (11712, 25360, 32)}.items():
+        w = W.gen_config(cfg, n_cand=2)
+        assert (w.n_nodes, w.n_edges, w.n_devices) == (n, e, p)
+    w = W.gen_config(5, n_cand=1)
+    assert w.n_nodes == 50000 and w.n_devices == 64 and 120000 < w.n_edges < 130000
