@@ -50,8 +50,10 @@ enum {
   DAGSCHED_FLAG_OK = 0,
   DAGSCHED_FLAG_BAD_PLACEMENT = 2, /* some placement[i] outside [0, P)                    (eq. (6))      */
   DAGSCHED_FLAG_BAD_RANK = 4,      /* some machine's ranks are not exactly {0..n_j-1}     (eqs. (7)-(8)) */
-  DAGSCHED_FLAG_CYCLIC = 1         /* DAG edges + chain edges contain a directed cycle: eqs. (5), (7), (8)
+  DAGSCHED_FLAG_CYCLIC = 1,        /* DAG edges + chain edges contain a directed cycle: eqs. (5), (7), (8)
                                       cannot hold together.  Structural test, zero-duration cycles included. */
+  DAGSCHED_FLAG_INTERNAL = 8       /* a kernel's bounded wait expired; never expected, the candidate's other
+                                      outputs are -1.  Reported instead of hanging the GPU. */
 };
 
 /* Memory layout of placement, rank and peak_mem. */

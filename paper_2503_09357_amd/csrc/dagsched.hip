@@ -1,4 +1,4 @@
-// dagsched: batched evaluation of candidate operator schedules on gfx950 (MI355X).
+// dagsched: batched evaluation of candidate operator schedules on gfx950 (MI355X) - host side and C-ABI.
 //
 // Per candidate (a placement x and dense per-machine ranks fixing y/u of the MIP in Sec. III of
 // arxiv 2503.09357) the kernels compute the earliest-start schedule on the disjunctive graph
@@ -10,25 +10,33 @@
 // Mapping: one lane per (candidate, machine).  A machine's operations are totally ordered, so in a
 // Kahn round at most one operation per machine becomes ready: lane (c, j) walks machine j's order
 // list of candidate c and polls the end times of the DAG predecessors of its head operation.  All
-// lanes of a candidate sit in one 64-wide wavefront (P <= 64), so "no lane of the candidate advanced
-// in a round" (a ballot) is an exact deadlock test, i.e. a cycle of the combined graph.
+// lanes of a candidate sit in one 64-wide wavefront (P <= 64), so "no lane of the candidate advanced"
+// (a ballot) is an exact deadlock test, i.e. a cycle of the combined graph.
 //
-// No MFMA anywhere: the work is integer max/plus with data-dependent gathers, not a contraction.
+// Two kernels: the ring kernel (kernel_ring.h; 16-bit end times in LDS, relaxer + feeder wavefronts)
+// is the fast path; the general kernel (kernel_general.h; int32 end times) takes what the ring kernel
+// cannot prove or finish.  No MFMA anywhere: integer max/plus with data-dependent gathers is not a
+// contraction.
 
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
+#include <numeric>
 #include <vector>
 
 #include "dagsched.h"
+#include "device_common.h"
+#include "kernel_general.h"
+#include "kernel_ring.h"
+#include "kernel_util.h"
+
+using namespace dagsched_dev;
 
 namespace {
-
-constexpr int kWave = 64;
-constexpr int kFlagCyclicBit = 1, kFlagBadPlacementBit = 2, kFlagBadRankBit = 4;
 
 thread_local char g_hip_error[256] = "";
 
@@ -43,228 +51,42 @@ inline int next_pow2(int x) {
   while (p < x) p <<= 1;
   return p;
 }
-
-// ------------------------------------------------------------------------------------------------
-// device helpers
-
-// Loads/stores that must observe data written earlier in the same kernel by other lanes go to L2
-// (agent scope) so that a stale line in the per-CU vector cache can never be returned.
-__device__ __forceinline__ int32_t ld_agent(const int32_t *p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+inline int ilog2(int x) {
+  int l = 0;
+  while ((1 << l) < x) ++l;
+  return l;
 }
-__device__ __forceinline__ void st_agent(int32_t *p, int32_t v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
+inline uint32_t align_up(uint32_t x, uint32_t a) { return (x + a - 1) / a * a; }
 
-struct GeneralParams {
-  int32_t N, P, Pseg, G, C;
-  int64_t row_stride;          // elements between consecutive candidates in list / end workspaces
-  const int32_t *pred_ptr;     // [N+1] predecessor CSR of B
-  const int32_t *pred_idx;     // [E]
-  const int32_t *dur;          // [N]
-  const int32_t *comm;         // [P*P]
-  const int64_t *mem_delta;    // [N]
-  int64_t sum_dur;
-  const int32_t *placement;    // [C][N] candidate-major
-  const int32_t *rank;         // [C][N]
-  int32_t *ws_list;            // [C][row_stride] order lists, machine after machine
-  int32_t *ws_end;             // [C][row_stride] end times (global-state variant)
-  int32_t *makespan;
-  int64_t *bubble;
-  int64_t *peak_mem;
-  int32_t *flags;
-  int64_t peak_stride_c, peak_stride_j;   // peak_mem[c*peak_stride_c + j*peak_stride_j]
-};
-
-// ------------------------------------------------------------------------------------------------
-// General kernel: any N, any time range (int32 end times), state in LDS when it fits, else in a
-// global workspace.  One wavefront per workgroup, G = 64 / Pseg candidates per wavefront.
-// Edge-granular polling: per round a lane consumes at most one DAG predecessor of its head
-// operation and completes the operation once all of them have ended.
-template <bool LDS_STATE>
-__global__ __launch_bounds__(kWave) void relax_general_kernel(GeneralParams p) {
-  extern __shared__ int32_t smem[];
-  __shared__ int32_t s_cnt[kWave];
-  __shared__ int32_t s_off[kWave];
-  __shared__ int32_t s_flag[kWave];
-
-  const int lane = threadIdx.x;
-  const int N = p.N, P = p.P, Pseg = p.Pseg, G = p.G;
-  const int64_t c0 = (int64_t)blockIdx.x * G;
-  const int ng = (int)min((int64_t)G, (int64_t)p.C - c0);
-  const int g = lane / Pseg, j = lane % Pseg;
-
-  s_cnt[lane] = 0;
-  s_flag[lane] = 0;
-  __syncthreads();
-
-  // a1: placement in range (eq. (6)); count operations per machine; reset the end-time state
-  for (int gg = 0; gg < ng; ++gg) {
-    const int32_t *pl = p.placement + (c0 + gg) * N;
-    int32_t *end_g = LDS_STATE ? (smem + (size_t)gg * N) : (p.ws_end + (c0 + gg) * p.row_stride);
-    for (int v = lane; v < N; v += kWave) {
-      int32_t pi = pl[v];
-      if ((uint32_t)pi >= (uint32_t)P) atomicOr(&s_flag[gg], kFlagBadPlacementBit);
-      else atomicAdd(&s_cnt[gg * Pseg + pi], 1);
-      if (LDS_STATE) end_g[v] = -1; else st_agent(end_g + v, -1);
-    }
-  }
-  __syncthreads();
-  // exclusive prefix over the machines of each candidate: start of machine j inside the list
-  {
-    int my = s_cnt[lane], incl = my;
-    for (int d = 1; d < Pseg; d <<= 1) {
-      int t = __shfl_up(incl, d, Pseg);
-      if (j >= d) incl += t;
-    }
-    s_off[lane] = incl - my;
-  }
-  __syncthreads();
-  // a2: order lists list_j[rank] = operation (the fixed disjunctive arcs u of eqs. (7),(17)-(18))
-  for (int gg = 0; gg < ng; ++gg) {
-    if (s_flag[gg] & kFlagBadPlacementBit) continue;
-    const int32_t *pl = p.placement + (c0 + gg) * N;
-    const int32_t *rk = p.rank + (c0 + gg) * N;
-    int32_t *list = p.ws_list + (c0 + gg) * p.row_stride;
-    for (int v = lane; v < N; v += kWave) {
-      int32_t pi = pl[v], r = rk[v];
-      if ((uint32_t)r >= (uint32_t)s_cnt[gg * Pseg + pi]) atomicOr(&s_flag[gg], kFlagBadRankBit);
-      else st_agent(list + s_off[gg * Pseg + pi] + r, v);
-    }
-  }
-  __threadfence();
-  __syncthreads();
-  // every (machine, rank) slot must be hit exactly once: a slot written twice keeps one writer only
-  for (int gg = 0; gg < ng; ++gg) {
-    if (s_flag[gg]) continue;
-    const int32_t *pl = p.placement + (c0 + gg) * N;
-    const int32_t *rk = p.rank + (c0 + gg) * N;
-    const int32_t *list = p.ws_list + (c0 + gg) * p.row_stride;
-    for (int v = lane; v < N; v += kWave) {
-      if (ld_agent(list + s_off[gg * Pseg + pl[v]] + rk[v]) != v) atomicOr(&s_flag[gg], kFlagBadRankBit);
-    }
-  }
-  __syncthreads();
-
-  // a3/a4/a7: relaxation, lane = (candidate g, machine j)
-  const bool lane_valid = (g < ng) && (j < P);
-  const int64_t c = c0 + g;
-  const int32_t *pl = p.placement + (lane_valid ? c : 0) * N;
-  const int32_t *list = p.ws_list + (lane_valid ? c : 0) * p.row_stride;
-  int32_t *end_g = LDS_STATE ? (smem + (size_t)(lane_valid ? g : 0) * N)
-                             : (p.ws_end + (lane_valid ? c : 0) * p.row_stride);
-  int k = 0, kend = 0;
-  if (lane_valid && s_flag[g] == 0) {
-    k = s_off[lane];
-    kend = k + s_cnt[lane];
-  }
-  bool active = k < kend;
-  int v = 0, pp = 0, pe = 0;
-  if (active) {
-    v = ld_agent(list + k);
-    pp = p.pred_ptr[v];
-    pe = p.pred_ptr[v + 1];
-  }
-  int32_t acc = 0;              // time at which machine j becomes free (end of its previous operation)
-  int64_t level = 0, peak = 0;  // running memory level on machine j and its maximum
-  const uint64_t segmask = ((Pseg == kWave) ? ~0ull : ((1ull << Pseg) - 1ull)) << (g * Pseg);
-  const int64_t max_rounds = (int64_t)N + p.pred_ptr[N] + 4;
-
-  for (int64_t round = 0; round < max_rounds; ++round) {
-    bool progressed = false;
-    if (active) {
-      if (pp < pe) {
-        int u = p.pred_idx[pp];
-        int32_t eu = LDS_STATE ? end_g[u] : ld_agent(end_g + u);
-        if (eu >= 0) {   // predecessor has ended: s_v >= e_u + delta(u, v), eqs. (11)-(13)
-          int pu = pl[u];
-          int32_t d = (pu != j) ? p.comm[pu * P + j] : 0;
-          acc = max(acc, eu + d);
-          ++pp;
-          progressed = true;
-        }
-      }
-      if (pp == pe) {      // all inputs have arrived and the machine is free: run v (eq. (3))
-        int32_t e = acc + p.dur[v];
-        if (LDS_STATE) end_g[v] = e; else st_agent(end_g + v, e);
-        acc = e;
-        level += p.mem_delta[v];      // eq. (19); the next operation starts from this level (eqs. (17)-(18))
-        peak = max(peak, level);
-        ++k;
-        progressed = true;
-        if (k < kend) {
-          v = ld_agent(list + k);
-          pp = p.pred_ptr[v];
-          pe = p.pred_ptr[v + 1];
-        } else {
-          active = false;
-        }
-      }
-    }
-    if (!LDS_STATE) __threadfence();
-    __syncthreads();
-    const uint64_t bal_prog = __ballot(progressed);
-    if (active && (bal_prog & segmask) == 0) {
-      // nothing of this candidate moved although operations remain: the combined graph is cyclic
-      s_flag[g] = kFlagCyclicBit;
-      active = false;
-    }
-    if (__ballot(active) == 0) break;
-  }
-  __syncthreads();
-
-  // a5/a6/a8: reductions and outputs
-  int32_t z = acc;
-  for (int d = 1; d < Pseg; d <<= 1) z = max(z, __shfl_xor(z, d, Pseg));
-  if (lane_valid) {
-    const int bits = s_flag[g];
-    const int flag = (bits & kFlagBadPlacementBit) ? DAGSCHED_FLAG_BAD_PLACEMENT
-                   : (bits & kFlagBadRankBit)      ? DAGSCHED_FLAG_BAD_RANK
-                   : (bits & kFlagCyclicBit)       ? DAGSCHED_FLAG_CYCLIC
-                                                   : DAGSCHED_FLAG_OK;
-    p.peak_mem[c * p.peak_stride_c + j * p.peak_stride_j] = flag ? -1 : peak;
-    if (j == 0) {
-      p.makespan[c] = flag ? -1 : z;
-      p.bubble[c] = flag ? -1 : (int64_t)P * z - p.sum_dur;
-      p.flags[c] = flag;
-    }
-  }
-}
-
-// [rows][cols] int32 -> [cols][rows], 64x64 tiles through LDS (both sides coalesced)
-__global__ __launch_bounds__(256) void transpose_i32_kernel(const int32_t *__restrict__ in, int32_t *__restrict__ out,
-                                                             int64_t rows, int64_t cols) {
-  __shared__ int32_t tile[64][65];
-  const int64_t r0 = (int64_t)blockIdx.y * 64, c0 = (int64_t)blockIdx.x * 64;
-  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-  for (int i = ty; i < 64; i += 4) {
-    int64_t r = r0 + i, cc = c0 + tx;
-    if (r < rows && cc < cols) tile[i][tx] = in[r * cols + cc];
-  }
-  __syncthreads();
-  for (int i = ty; i < 64; i += 4) {
-    int64_t cc = c0 + i, r = r0 + tx;
-    if (r < rows && cc < cols) out[cc * rows + r] = tile[tx][i];
-  }
-}
+enum { kVariantGeneralLds = 1, kVariantGeneralGlobal = 2, kVariantRingExact = 3, kVariantRingOptimistic = 4 };
 
 }  // namespace
 
-// ------------------------------------------------------------------------------------------------
-// host side
-
 struct dagsched {
-  int32_t N = 0, E = 0, P = 0, Pseg = 0, G = 0, max_cand = 0, layout = 0, device = 0;
-  int64_t sum_dur = 0, row_stride = 0;
-  int32_t variant = 0, lds_bytes = 0, state_bits = 32, block_threads = kWave;
+  int32_t N = 0, E = 0, P = 0, Pseg = 0, max_cand = 0, layout = 0, device = 0;
+  int64_t sum_dur = 0;
+  int32_t variant = 0;
+  // general kernel
+  int32_t gen_G = 0, gen_lds = 0;
+  bool gen_lds_state = false;
+  int64_t row_stride = 0;
   int32_t *d_pred_ptr = nullptr, *d_pred_idx = nullptr, *d_dur = nullptr, *d_comm = nullptr;
   int64_t *d_mem = nullptr;
-  int32_t *ws_list = nullptr, *ws_end = nullptr, *ws_tp = nullptr, *ws_tr = nullptr;
+  int32_t *ws_list = nullptr, *ws_end = nullptr;
+  // ring kernel
+  int32_t ring_G = 0, ring_slots = 0, n_rec = 0, time_scale = 1;
+  int64_t list_stride = 0;
+  LdsLayout lds{};
+  uint4 *d_rec = nullptr;
+  int32_t *d_comm_scaled = nullptr;
+  uint16_t *ws_list16 = nullptr;
+  int32_t *d_fb_count = nullptr, *d_fb_list = nullptr;
+  uint32_t spin_cap = 0;
+  // candidate-minor input staging
+  int32_t *ws_tp = nullptr, *ws_tr = nullptr;
 };
 
 namespace {
-
-enum { kVariantGeneralLds = 1, kVariantGeneralGlobal = 2 };
 
 int validate_desc(const dagsched_desc_t *d, std::vector<int32_t> *pred_ptr, std::vector<int32_t> *pred_idx,
                   int64_t *sum_dur_out) {
@@ -329,12 +151,169 @@ bool upload(T **dst, const T *src, size_t n) {
   return hip_ok(hipMemcpy(*dst, src, n * sizeof(T), hipMemcpyHostToDevice), "hipMemcpy");
 }
 
+template <typename T>
+bool dev_alloc(T **dst, size_t n) {
+  return hip_ok(hipMalloc((void **)dst, std::max<size_t>(n, 1) * sizeof(T)), "hipMalloc workspace");
+}
+
 void free_handle(dagsched *h) {
   if (!h) return;
-  void *bufs[] = {h->d_pred_ptr, h->d_pred_idx, h->d_dur, h->d_comm, h->d_mem, h->ws_list, h->ws_end, h->ws_tp, h->ws_tr};
+  void *bufs[] = {h->d_pred_ptr, h->d_pred_idx, h->d_dur, h->d_comm, h->d_mem, h->ws_list, h->ws_end, h->d_rec,
+                  h->d_comm_scaled, h->ws_list16, h->d_fb_count, h->d_fb_list, h->ws_tp, h->ws_tr};
   for (void *b : bufs)
     if (b) (void)hipFree(b);
   delete h;
+}
+
+int env_int(const char *name, int dflt) {
+  const char *s = getenv(name);
+  return (s && *s) ? atoi(s) : dflt;
+}
+
+LdsLayout ring_layout(int N, int P, int Pseg, int G, int ring) {
+  LdsLayout o{};
+  const uint32_t L = (uint32_t)(G * Pseg);
+  uint32_t at = 0;
+  o.s_stride = align_up(2u * (uint32_t)(N + 1), 4);
+  o.pi_stride = align_up((uint32_t)(N + 1), 4);
+  o.o_state = at; at += (uint32_t)G * o.s_stride;
+  o.o_pi = at;    at += (uint32_t)G * o.pi_stride;
+  at = align_up(at, 16);
+  o.o_ring = at;  at += (uint32_t)kOpWords * (uint32_t)ring * L * 4u;
+  o.o_tail = at;  at += L * 4u;
+  at = align_up(at, 8);
+  o.o_peak = at;  at += L * 8u;
+  o.o_cnt = at;   at += L * 4u;
+  o.o_off = at;   at += L * 4u;
+  o.o_flag = at;  at += L * 4u;
+  o.o_abort = at; at += L * 4u;
+  o.o_comm = at;  at += align_up((uint32_t)((P + 1) * P), 4);
+  o.total = align_up(at, 16);
+  return o;
+}
+
+// Decide whether the ring kernel can take this problem and with which shape.
+// Needs: every scaled delay <= 255, at most 65536 overflow records, the scaled lower bound on any
+// makespan (critical path of B, heaviest possible average load) below the 16-bit range, and an LDS
+// footprint that fits a workgroup.
+struct RingPlan {
+  bool ok = false, exact = false;
+  int G = 0, ring = 0;
+  int32_t scale = 1;
+  LdsLayout lds{};
+  std::vector<uint4> rec;
+  std::vector<int32_t> comm_scaled;
+};
+
+RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_ptr, const std::vector<int32_t> &pred_idx,
+                   int64_t sum_dur, int lds_max) {
+  RingPlan plan;
+  const int N = d->n_nodes, P = d->n_devices, Pseg = next_pow2(P);
+  int64_t g = 0, max_comm = 0;
+  for (int v = 0; v < N; ++v) g = std::gcd<int64_t, int64_t>(g, d->dur[v]);
+  for (int a = 0; a < P; ++a)
+    for (int b = 0; b < P; ++b)
+      if (a != b) {
+        g = std::gcd<int64_t, int64_t>(g, d->comm[a * P + b]);
+        max_comm = std::max<int64_t>(max_comm, d->comm[a * P + b]);
+      }
+  if (g == 0) g = 1;                                   // every duration and delay is zero
+  if (max_comm / g > 255) return plan;
+  // longest path of B alone in scaled units (no delays): a lower bound on every makespan
+  std::vector<int64_t> fin(N, -1);
+  {
+    std::vector<int32_t> order;                        // topological order by repeated peeling on pred lists
+    std::vector<int32_t> indeg(N);
+    for (int v = 0; v < N; ++v) indeg[v] = pred_ptr[v + 1] - pred_ptr[v];
+    order.reserve(N);
+    for (int v = 0; v < N; ++v) if (indeg[v] == 0) order.push_back(v);
+    for (size_t i = 0; i < order.size(); ++i) {
+      const int u = order[i];
+      int64_t best = 0;
+      for (int k = pred_ptr[u]; k < pred_ptr[u + 1]; ++k) best = std::max(best, fin[pred_idx[k]]);
+      fin[u] = best + d->dur[u] / g;
+      for (int k = d->row_ptr[u]; k < d->row_ptr[u + 1]; ++k)
+        if (--indeg[d->col_idx[k]] == 0) order.push_back(d->col_idx[k]);
+    }
+  }
+  const int64_t crit = *std::max_element(fin.begin(), fin.end());
+  const int64_t lower = std::max<int64_t>(crit, (sum_dur / g + P - 1) / P);
+  if (lower >= (int64_t)kNotDone16) return plan;       // no candidate could stay inside 16 bits
+  const int64_t upper = sum_dur / g + (int64_t)(N - 1) * (max_comm / g);
+  plan.exact = upper < (int64_t)kNotDone16;
+  plan.scale = (int32_t)g;
+
+  // shared operator records, four predecessors per part
+  const uint32_t dummy = (uint32_t)N;
+  std::vector<uint4> rec(N);
+  std::vector<uint4> extra;
+  for (int v = 0; v < N; ++v) {
+    const int deg = pred_ptr[v + 1] - pred_ptr[v];
+    const int parts = std::max(1, (deg + 3) / 4);
+    for (int part = 0; part < parts; ++part) {
+      uint32_t u[4] = {dummy, dummy, dummy, dummy};
+      for (int i = 0; i < 4; ++i) {
+        const int k = pred_ptr[v] + part * 4 + i;
+        if (k < pred_ptr[v + 1]) u[i] = (uint32_t)pred_idx[k];
+      }
+      const bool more = part + 1 < parts;
+      const uint32_t dur = more ? 0u : (uint32_t)std::min<int64_t>(d->dur[v] / g, kNotDone16);
+      const uint32_t next = more ? (uint32_t)extra.size() + (part == 0 ? 0u : 1u) : 0u;
+      uint4 r = make_uint4(u[0] | (u[1] << 16), u[2] | (u[3] << 16), dur | (more ? 0x80000000u : 0u),
+                           next | ((uint32_t)v << 16));
+      if (part == 0) rec[v] = r; else extra.push_back(r);
+    }
+  }
+  if (extra.size() > 65536) return plan;
+  rec.insert(rec.end(), extra.begin(), extra.end());
+  plan.rec.swap(rec);
+  plan.comm_scaled.resize((size_t)P * P);
+  for (int i = 0; i < P * P; ++i) plan.comm_scaled[i] = (i / P != i % P) ? (int32_t)(d->comm[i] / g) : 0;
+
+  // shape: most candidates resident per CU, then fewer wavefronts, then a deeper ring
+  const int force_g = env_int("DAGSCHED_RING_G", 0), force_ring = env_int("DAGSCHED_RING_SLOTS", 0);
+  int best_score = -1;
+  for (int G = kWave / Pseg; G >= 1; G >>= 1) {
+    if (force_g && G != force_g) continue;
+    for (int ring : {8, 4}) {
+      if (force_ring && ring != force_ring) continue;
+      LdsLayout o = ring_layout(N, P, Pseg, G, ring);
+      if ((int)o.total > lds_max) continue;
+      const int wgs = std::min(8, lds_max / (int)align_up(o.total, 1024));
+      if (wgs < 1) continue;
+      const int score = wgs * G * 64 + G * 2 + (ring == 8 ? 1 : 0);
+      if (score > best_score) { best_score = score; plan.G = G; plan.ring = ring; plan.lds = o; }
+    }
+  }
+  plan.ok = best_score >= 0;
+  return plan;
+}
+
+OutPtrs make_out(const dagsched *h, int32_t n_cand, int32_t *makespan, int64_t *bubble, int64_t *peak_mem,
+                 int32_t *flags) {
+  OutPtrs o;
+  o.makespan = makespan; o.bubble = bubble; o.peak_mem = peak_mem; o.flags = flags;
+  if (h->layout == DAGSCHED_CAND_MAJOR) { o.peak_stride_c = h->P; o.peak_stride_j = 1; }
+  else { o.peak_stride_c = 1; o.peak_stride_j = n_cand; }
+  return o;
+}
+
+void launch_general(dagsched *h, int32_t n_cand, const int32_t *pl, const int32_t *rk, const OutPtrs &out,
+                    const int32_t *cand_list, const int32_t *cand_count, hipStream_t stream) {
+  GeneralParams p;
+  p.N = h->N; p.P = h->P; p.Pseg = h->Pseg; p.G = h->gen_G; p.C = n_cand;
+  p.row_stride = h->row_stride;
+  p.pred_ptr = h->d_pred_ptr; p.pred_idx = h->d_pred_idx; p.dur = h->d_dur; p.comm = h->d_comm; p.mem_delta = h->d_mem;
+  p.sum_dur = h->sum_dur;
+  p.placement = pl; p.rank = rk;
+  p.ws_list = h->ws_list; p.ws_end = h->ws_end;
+  p.cand_list = cand_list; p.cand_count = cand_count;
+  p.out = out;
+  const unsigned blocks = (unsigned)((n_cand + h->gen_G - 1) / h->gen_G);
+  if (h->gen_lds_state)
+    hipLaunchKernelGGL(relax_general_kernel<true>, dim3(blocks), dim3(kWave), (size_t)h->gen_lds, stream, p);
+  else
+    hipLaunchKernelGGL(relax_general_kernel<false>, dim3(blocks), dim3(kWave), 0, stream, p);
 }
 
 int launch_evaluate(dagsched *h, int32_t n_cand, const int32_t *placement, const int32_t *rank, int32_t *makespan,
@@ -348,21 +327,29 @@ int launch_evaluate(dagsched *h, int32_t n_cand, const int32_t *placement, const
     pl = h->ws_tp;
     rk = h->ws_tr;
   }
-  GeneralParams p;
-  p.N = N; p.P = h->P; p.Pseg = h->Pseg; p.G = h->G; p.C = n_cand;
-  p.row_stride = h->row_stride;
-  p.pred_ptr = h->d_pred_ptr; p.pred_idx = h->d_pred_idx; p.dur = h->d_dur; p.comm = h->d_comm; p.mem_delta = h->d_mem;
-  p.sum_dur = h->sum_dur;
-  p.placement = pl; p.rank = rk;
-  p.ws_list = h->ws_list; p.ws_end = h->ws_end;
-  p.makespan = makespan; p.bubble = bubble; p.peak_mem = peak_mem; p.flags = flags;
-  if (h->layout == DAGSCHED_CAND_MAJOR) { p.peak_stride_c = h->P; p.peak_stride_j = 1; }
-  else { p.peak_stride_c = 1; p.peak_stride_j = n_cand; }
-  const unsigned blocks = (unsigned)((n_cand + h->G - 1) / h->G);
-  if (h->variant == kVariantGeneralLds)
-    hipLaunchKernelGGL(relax_general_kernel<true>, dim3(blocks), dim3(kWave), (size_t)h->lds_bytes, stream, p);
-  else
-    hipLaunchKernelGGL(relax_general_kernel<false>, dim3(blocks), dim3(kWave), 0, stream, p);
+  const OutPtrs out = make_out(h, n_cand, makespan, bubble, peak_mem, flags);
+  if (h->variant == kVariantGeneralLds || h->variant == kVariantGeneralGlobal) {
+    launch_general(h, n_cand, pl, rk, out, nullptr, nullptr, stream);
+  } else {
+    const bool optimistic = h->variant == kVariantRingOptimistic;
+    if (optimistic) hipLaunchKernelGGL(reset_counter_kernel, dim3(1), dim3(1), 0, stream, h->d_fb_count);
+    RingParams p;
+    p.N = N; p.P = h->P; p.Pseg = h->Pseg; p.log_pseg = ilog2(h->Pseg); p.G = h->ring_G; p.C = n_cand;
+    p.ring = h->ring_slots; p.log_ring = ilog2(h->ring_slots);
+    p.optimistic = optimistic ? 1 : 0;
+    p.list_stride = h->list_stride;
+    p.rec = h->d_rec; p.comm = h->d_comm_scaled; p.mem_delta = h->d_mem;
+    p.sum_dur = h->sum_dur; p.time_scale = h->time_scale;
+    p.placement = pl; p.rank = rk;
+    p.ws_list = h->ws_list16;
+    p.fb_count = h->d_fb_count; p.fb_list = h->d_fb_list;
+    p.spin_cap = h->spin_cap;
+    p.lds = h->lds;
+    p.out = out;
+    const unsigned blocks = (unsigned)((n_cand + h->ring_G - 1) / h->ring_G);
+    hipLaunchKernelGGL(relax_ring_kernel, dim3(blocks), dim3(2 * kWave), (size_t)h->lds.total, stream, p);
+    if (optimistic) launch_general(h, n_cand, pl, rk, out, h->d_fb_list, h->d_fb_count, stream);
+  }
   if (!hip_ok(hipGetLastError(), "kernel launch")) return DAGSCHED_EHIP;
   return DAGSCHED_OK;
 }
@@ -390,40 +377,58 @@ int dagsched_create(const dagsched_desc_t *desc, dagsched_t **out) {
   if (!hip_ok(hipGetDeviceCount(&n_dev), "hipGetDeviceCount")) return DAGSCHED_EHIP;
   if (desc->hip_device < 0 || desc->hip_device >= n_dev) return DAGSCHED_EINVAL;
   if (!hip_ok(hipSetDevice(desc->hip_device), "hipSetDevice")) return DAGSCHED_EHIP;
+  int lds_max = 0;
+  if (!hip_ok(hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, desc->hip_device),
+              "hipDeviceGetAttribute"))
+    return DAGSCHED_EHIP;
 
   dagsched *h = new (std::nothrow) dagsched();
   if (!h) return DAGSCHED_ENOMEM;
   h->N = desc->n_nodes; h->E = desc->n_edges; h->P = desc->n_devices;
   h->Pseg = next_pow2(h->P);
-  h->G = kWave / h->Pseg;
   h->max_cand = desc->max_candidates; h->layout = desc->layout; h->device = desc->hip_device;
   h->sum_dur = sum_dur;
   h->row_stride = ((int64_t)h->N + 31) / 32 * 32;     // 128-byte rows: no cache line shared by two candidates
+  h->list_stride = ((int64_t)h->N + 63) / 64 * 64;
+  const size_t maxc = (size_t)h->max_cand;
 
-  int lds_max = 0;
-  if (!hip_ok(hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, h->device), "hipDeviceGetAttribute")) {
-    delete h;
-    return DAGSCHED_EHIP;
+  RingPlan plan;
+  if (!env_int("DAGSCHED_FORCE_GENERAL", 0)) plan = plan_ring(desc, pred_ptr, pred_idx, sum_dur, lds_max);
+  const bool need_general = !plan.ok || !plan.exact;
+
+  bool ok = upload(&h->d_mem, desc->mem_delta, (size_t)h->N);
+  if (ok && need_general) {
+    h->gen_G = kWave / h->Pseg;
+    const int64_t lds_need = (int64_t)h->gen_G * h->N * 4;
+    h->gen_lds_state = lds_need + 1024 <= lds_max;
+    h->gen_lds = h->gen_lds_state ? (int32_t)lds_need : 0;
+    ok = upload(&h->d_pred_ptr, pred_ptr.data(), (size_t)h->N + 1) &&
+         upload(&h->d_pred_idx, pred_idx.data(), (size_t)h->E) &&
+         upload(&h->d_dur, desc->dur, (size_t)h->N) &&
+         upload(&h->d_comm, desc->comm, (size_t)h->P * h->P) &&
+         dev_alloc(&h->ws_list, maxc * (size_t)h->row_stride);
+    if (ok && !h->gen_lds_state) ok = dev_alloc(&h->ws_end, maxc * (size_t)h->row_stride);
+    if (ok && h->gen_lds > 48 * 1024)
+      ok = hip_ok(hipFuncSetAttribute((const void *)relax_general_kernel<true>,
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, h->gen_lds), "hipFuncSetAttribute");
+    h->variant = h->gen_lds_state ? kVariantGeneralLds : kVariantGeneralGlobal;
   }
-  const int64_t lds_need = (int64_t)h->G * h->N * 4;
-  if (lds_need + 1024 <= lds_max) { h->variant = kVariantGeneralLds; h->lds_bytes = (int32_t)lds_need; }
-  else { h->variant = kVariantGeneralGlobal; h->lds_bytes = 0; }
-
-  const size_t ws = (size_t)h->max_cand * (size_t)h->row_stride;
-  bool ok = upload(&h->d_pred_ptr, pred_ptr.data(), (size_t)h->N + 1) &&
-            upload(&h->d_pred_idx, pred_idx.data(), (size_t)h->E) &&
-            upload(&h->d_dur, desc->dur, (size_t)h->N) &&
-            upload(&h->d_comm, desc->comm, (size_t)h->P * h->P) &&
-            upload(&h->d_mem, desc->mem_delta, (size_t)h->N) &&
-            hip_ok(hipMalloc((void **)&h->ws_list, ws * sizeof(int32_t)), "hipMalloc workspace");
-  if (ok && h->variant == kVariantGeneralGlobal)
-    ok = hip_ok(hipMalloc((void **)&h->ws_end, ws * sizeof(int32_t)), "hipMalloc workspace");
+  if (ok && plan.ok) {
+    h->variant = plan.exact ? kVariantRingExact : kVariantRingOptimistic;
+    h->ring_G = plan.G; h->ring_slots = plan.ring; h->lds = plan.lds; h->time_scale = plan.scale;
+    h->n_rec = (int32_t)plan.rec.size();
+    const int64_t cap = ((int64_t)h->N + h->E + 1024) * 64;
+    h->spin_cap = (uint32_t)std::min<int64_t>(cap, 0x7FFFFFFF);
+    ok = upload(&h->d_rec, plan.rec.data(), plan.rec.size()) &&
+         upload(&h->d_comm_scaled, plan.comm_scaled.data(), plan.comm_scaled.size()) &&
+         dev_alloc(&h->ws_list16, maxc * (size_t)h->list_stride);
+    if (ok && !plan.exact) ok = dev_alloc(&h->d_fb_count, 1) && dev_alloc(&h->d_fb_list, maxc);
+    if (ok && h->lds.total > 48 * 1024)
+      ok = hip_ok(hipFuncSetAttribute((const void *)relax_ring_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      (int)h->lds.total), "hipFuncSetAttribute");
+  }
   if (ok && h->layout == DAGSCHED_CAND_MINOR)
-    ok = hip_ok(hipMalloc((void **)&h->ws_tp, (size_t)h->max_cand * h->N * sizeof(int32_t)), "hipMalloc workspace") &&
-         hip_ok(hipMalloc((void **)&h->ws_tr, (size_t)h->max_cand * h->N * sizeof(int32_t)), "hipMalloc workspace");
-  if (ok && h->variant == kVariantGeneralLds && h->lds_bytes > 48 * 1024)
-    ok = hip_ok(hipFuncSetAttribute((const void *)relax_general_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    h->lds_bytes), "hipFuncSetAttribute");
+    ok = dev_alloc(&h->ws_tp, maxc * (size_t)h->N) && dev_alloc(&h->ws_tr, maxc * (size_t)h->N);
   if (!ok) {
     const bool oom = strstr(g_hip_error, "memory") != nullptr;
     free_handle(h);
@@ -477,10 +482,13 @@ int dagsched_get_info(const dagsched_t *h, dagsched_info_t *info) {
   if (!h || !info) return DAGSCHED_EINVAL;
   memset(info, 0, sizeof(*info));
   info->variant = h->variant;
-  info->cand_per_block = h->G;
-  info->block_threads = h->block_threads;
-  info->lds_bytes = h->lds_bytes;
-  info->state_bits = h->state_bits;
+  const bool ring = h->variant == kVariantRingExact || h->variant == kVariantRingOptimistic;
+  info->cand_per_block = ring ? h->ring_G : h->gen_G;
+  info->block_threads = ring ? 2 * kWave : kWave;
+  info->lds_bytes = ring ? (int32_t)h->lds.total : h->gen_lds;
+  info->state_bits = ring ? 16 : 32;
+  info->reserved[0] = ring ? h->ring_slots : 0;
+  info->reserved[1] = h->time_scale;
   return DAGSCHED_OK;
 }
 
