@@ -74,7 +74,7 @@ struct dagsched {
   int64_t *d_mem = nullptr;
   int32_t *ws_list = nullptr, *ws_end = nullptr;
   // ring kernel
-  int32_t ring_G = 0, ring_slots = 0, n_rec = 0, time_scale = 1;
+  int32_t ring_G = 0, ring_slots = 0, rec_plane = 0, time_scale = 1;
   int64_t list_stride = 0;
   LdsLayout lds{};
   uint4 *d_rec = nullptr;
@@ -170,23 +170,22 @@ int env_int(const char *name, int dflt) {
   return (s && *s) ? atoi(s) : dflt;
 }
 
-LdsLayout ring_layout(int N, int P, int Pseg, int G, int ring) {
+LdsLayout ring_layout(int N, int P, int G, int ring) {
   LdsLayout o{};
-  const uint32_t L = (uint32_t)(G * Pseg);
   uint32_t at = 0;
-  o.s_stride = align_up(2u * (uint32_t)(N + 1), 4);
+  o.s_stride = align_up(2u * (uint32_t)(N + 1), 4);      // the end-time arrays start at LDS offset 0
   o.pi_stride = align_up((uint32_t)(N + 1), 4);
-  o.o_state = at; at += (uint32_t)G * o.s_stride;
+  at += (uint32_t)G * o.s_stride;
   o.o_pi = at;    at += (uint32_t)G * o.pi_stride;
   at = align_up(at, 16);
-  o.o_ring = at;  at += (uint32_t)kOpWords * (uint32_t)ring * L * 4u;
-  o.o_tail = at;  at += L * 4u;
+  o.o_ring = at;  at += (uint32_t)kOpWords * (uint32_t)ring * kWave * 4u;
+  o.o_tail = at;  at += kWave * 4u;
   at = align_up(at, 8);
-  o.o_peak = at;  at += L * 8u;
-  o.o_cnt = at;   at += L * 4u;
-  o.o_off = at;   at += L * 4u;
-  o.o_flag = at;  at += L * 4u;
-  o.o_abort = at; at += L * 4u;
+  o.o_peak = at;  at += kWave * 8u;
+  o.o_cnt = at;   at += kWave * 4u;
+  o.o_off = at;   at += kWave * 4u;
+  o.o_flag = at;  at += kWave * 4u;
+  o.o_abort = at; at += kWave * 4u;
   o.o_comm = at;  at += align_up((uint32_t)((P + 1) * P), 4);
   o.total = align_up(at, 16);
   return o;
@@ -202,6 +201,7 @@ struct RingPlan {
   int32_t scale = 1;
   LdsLayout lds{};
   std::vector<uint4> rec;
+  int rec_plane = 0;
   std::vector<int32_t> comm_scaled;
 };
 
@@ -243,10 +243,13 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
   plan.exact = upper < (int64_t)kNotDone16;
   plan.scale = (int32_t)g;
 
-  // shared operator records, four predecessors per part
+  // shared operator records, four predecessors per part, part i of node v at [i * plane + v]
   const uint32_t dummy = (uint32_t)N;
-  std::vector<uint4> rec(N);
-  std::vector<uint4> extra;
+  int max_parts = 1;
+  for (int v = 0; v < N; ++v) max_parts = std::max(max_parts, (pred_ptr[v + 1] - pred_ptr[v] + 3) / 4);
+  if (max_parts > 16) return plan;                     // very wide fan-in: leave it to the general kernel
+  const int plane = N;
+  std::vector<uint4> rec((size_t)max_parts * plane, make_uint4(dummy | (dummy << 16), dummy | (dummy << 16), 0, 0));
   for (int v = 0; v < N; ++v) {
     const int deg = pred_ptr[v + 1] - pred_ptr[v];
     const int parts = std::max(1, (deg + 3) / 4);
@@ -258,15 +261,13 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
       }
       const bool more = part + 1 < parts;
       const uint32_t dur = more ? 0u : (uint32_t)std::min<int64_t>(d->dur[v] / g, kNotDone16);
-      const uint32_t next = more ? (uint32_t)extra.size() + (part == 0 ? 0u : 1u) : 0u;
-      uint4 r = make_uint4(u[0] | (u[1] << 16), u[2] | (u[3] << 16), dur | (more ? 0x80000000u : 0u),
-                           next | ((uint32_t)v << 16));
-      if (part == 0) rec[v] = r; else extra.push_back(r);
+      rec[(size_t)part * plane + v] = make_uint4(u[0] | (u[1] << 16), u[2] | (u[3] << 16),
+                                                 dur | (part == 0 ? 0x40000000u : 0u) | (more ? 0x80000000u : 0u),
+                                                 (uint32_t)v << 16);
     }
   }
-  if (extra.size() > 65536) return plan;
-  rec.insert(rec.end(), extra.begin(), extra.end());
   plan.rec.swap(rec);
+  plan.rec_plane = plane;
   plan.comm_scaled.resize((size_t)P * P);
   for (int i = 0; i < P * P; ++i) plan.comm_scaled[i] = (i / P != i % P) ? (int32_t)(d->comm[i] / g) : 0;
 
@@ -277,8 +278,9 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
     if (force_g && G != force_g) continue;
     for (int ring : {8, 4}) {
       if (force_ring && ring != force_ring) continue;
-      LdsLayout o = ring_layout(N, P, Pseg, G, ring);
+      LdsLayout o = ring_layout(N, P, G, ring);
       if ((int)o.total > lds_max) continue;
+      if ((uint64_t)G * (o.s_stride >> 1) > 65536u) continue;   // half-addresses must fit 16 bits
       const int wgs = std::min(8, lds_max / (int)align_up(o.total, 1024));
       if (wgs < 1) continue;
       const int score = wgs * G * 64 + G * 2 + (ring == 8 ? 1 : 0);
@@ -335,10 +337,9 @@ int launch_evaluate(dagsched *h, int32_t n_cand, const int32_t *placement, const
     if (optimistic) hipLaunchKernelGGL(reset_counter_kernel, dim3(1), dim3(1), 0, stream, h->d_fb_count);
     RingParams p;
     p.N = N; p.P = h->P; p.Pseg = h->Pseg; p.log_pseg = ilog2(h->Pseg); p.G = h->ring_G; p.C = n_cand;
-    p.ring = h->ring_slots; p.log_ring = ilog2(h->ring_slots);
     p.optimistic = optimistic ? 1 : 0;
     p.list_stride = h->list_stride;
-    p.rec = h->d_rec; p.comm = h->d_comm_scaled; p.mem_delta = h->d_mem;
+    p.rec = h->d_rec; p.rec_plane = h->rec_plane; p.comm = h->d_comm_scaled; p.mem_delta = h->d_mem;
     p.sum_dur = h->sum_dur; p.time_scale = h->time_scale;
     p.placement = pl; p.rank = rk;
     p.ws_list = h->ws_list16;
@@ -347,7 +348,10 @@ int launch_evaluate(dagsched *h, int32_t n_cand, const int32_t *placement, const
     p.lds = h->lds;
     p.out = out;
     const unsigned blocks = (unsigned)((n_cand + h->ring_G - 1) / h->ring_G);
-    hipLaunchKernelGGL(relax_ring_kernel, dim3(blocks), dim3(2 * kWave), (size_t)h->lds.total, stream, p);
+    if (h->ring_slots == 8)
+      hipLaunchKernelGGL(relax_ring_kernel<8>, dim3(blocks), dim3(kThreads), (size_t)h->lds.total, stream, p);
+    else
+      hipLaunchKernelGGL(relax_ring_kernel<4>, dim3(blocks), dim3(kThreads), (size_t)h->lds.total, stream, p);
     if (optimistic) launch_general(h, n_cand, pl, rk, out, h->d_fb_list, h->d_fb_count, stream);
   }
   if (!hip_ok(hipGetLastError(), "kernel launch")) return DAGSCHED_EHIP;
@@ -416,7 +420,7 @@ int dagsched_create(const dagsched_desc_t *desc, dagsched_t **out) {
   if (ok && plan.ok) {
     h->variant = plan.exact ? kVariantRingExact : kVariantRingOptimistic;
     h->ring_G = plan.G; h->ring_slots = plan.ring; h->lds = plan.lds; h->time_scale = plan.scale;
-    h->n_rec = (int32_t)plan.rec.size();
+    h->rec_plane = plan.rec_plane;
     const int64_t cap = ((int64_t)h->N + h->E + 1024) * 64;
     h->spin_cap = (uint32_t)std::min<int64_t>(cap, 0x7FFFFFFF);
     ok = upload(&h->d_rec, plan.rec.data(), plan.rec.size()) &&
@@ -424,8 +428,10 @@ int dagsched_create(const dagsched_desc_t *desc, dagsched_t **out) {
          dev_alloc(&h->ws_list16, maxc * (size_t)h->list_stride);
     if (ok && !plan.exact) ok = dev_alloc(&h->d_fb_count, 1) && dev_alloc(&h->d_fb_list, maxc);
     if (ok && h->lds.total > 48 * 1024)
-      ok = hip_ok(hipFuncSetAttribute((const void *)relax_ring_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                      (int)h->lds.total), "hipFuncSetAttribute");
+      ok = hip_ok(hipFuncSetAttribute(h->ring_slots == 8 ? (const void *)relax_ring_kernel<8>
+                                                         : (const void *)relax_ring_kernel<4>,
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)h->lds.total),
+                  "hipFuncSetAttribute");
   }
   if (ok && h->layout == DAGSCHED_CAND_MINOR)
     ok = dev_alloc(&h->ws_tp, maxc * (size_t)h->N) && dev_alloc(&h->ws_tr, maxc * (size_t)h->N);
