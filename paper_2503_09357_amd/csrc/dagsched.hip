@@ -74,7 +74,8 @@ struct dagsched {
   int64_t *d_mem = nullptr;
   int32_t *ws_list = nullptr, *ws_end = nullptr;
   // ring kernel
-  int32_t ring_G = 0, ring_slots = 0, rec_plane = 0, time_scale = 1;
+  int32_t ring_G = 0, ring_slots = 0, rec_plane = 0, id_bits = 16, time_scale = 1;
+  uint8_t *d_nparts = nullptr;
   int64_t list_stride = 0;
   LdsLayout lds{};
   uint4 *d_rec = nullptr;
@@ -159,7 +160,7 @@ bool dev_alloc(T **dst, size_t n) {
 void free_handle(dagsched *h) {
   if (!h) return;
   void *bufs[] = {h->d_pred_ptr, h->d_pred_idx, h->d_dur, h->d_comm, h->d_mem, h->ws_list, h->ws_end, h->d_rec,
-                  h->d_comm_scaled, h->ws_list16, h->d_fb_count, h->d_fb_list, h->ws_tp, h->ws_tr};
+                  h->d_comm_scaled, h->d_nparts, h->ws_list16, h->d_fb_count, h->d_fb_list, h->ws_tp, h->ws_tr};
   for (void *b : bufs)
     if (b) (void)hipFree(b);
   delete h;
@@ -173,7 +174,7 @@ int env_int(const char *name, int dflt) {
 LdsLayout ring_layout(int N, int P, int G, int ring) {
   LdsLayout o{};
   uint32_t at = 0;
-  o.s_stride = align_up(2u * (uint32_t)(N + 1), 4);      // the end-time arrays start at LDS offset 0
+  o.s_stride = align_up(2u * (uint32_t)(N + 2), 4);      // N cells + dummy + trash; the arrays start at LDS offset 0
   o.pi_stride = align_up((uint32_t)(N + 1), 4);
   at += (uint32_t)G * o.s_stride;
   o.o_pi = at;    at += (uint32_t)G * o.pi_stride;
@@ -186,7 +187,7 @@ LdsLayout ring_layout(int N, int P, int G, int ring) {
   o.o_off = at;   at += kWave * 4u;
   o.o_flag = at;  at += kWave * 4u;
   o.o_abort = at; at += kWave * 4u;
-  o.o_comm = at;  at += align_up((uint32_t)((P + 1) * P), 4);
+  o.o_comm = at;  at += (uint32_t)(P + 1) * kWave;
   o.total = align_up(at, 16);
   return o;
 }
@@ -201,7 +202,8 @@ struct RingPlan {
   int32_t scale = 1;
   LdsLayout lds{};
   std::vector<uint4> rec;
-  int rec_plane = 0;
+  int rec_plane = 0, id_bits = 16;
+  std::vector<uint8_t> nparts;
   std::vector<int32_t> comm_scaled;
 };
 
@@ -268,6 +270,15 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
   }
   plan.rec.swap(rec);
   plan.rec_plane = plane;
+  // the order-list entries are 16 bits: node id below, (parts - 1) above
+  int part_bits = 0;
+  while ((1 << part_bits) < max_parts) ++part_bits;
+  plan.id_bits = 16 - part_bits;
+  if (N > (1 << plan.id_bits)) return plan;            // ids and part counts do not fit: general kernel
+  if (max_parts > 1) {
+    plan.nparts.resize(N);
+    for (int v = 0; v < N; ++v) plan.nparts[v] = (uint8_t)std::max(1, (pred_ptr[v + 1] - pred_ptr[v] + 3) / 4);
+  }
   plan.comm_scaled.resize((size_t)P * P);
   for (int i = 0; i < P * P; ++i) plan.comm_scaled[i] = (i / P != i % P) ? (int32_t)(d->comm[i] / g) : 0;
 
@@ -339,7 +350,7 @@ int launch_evaluate(dagsched *h, int32_t n_cand, const int32_t *placement, const
     p.N = N; p.P = h->P; p.Pseg = h->Pseg; p.log_pseg = ilog2(h->Pseg); p.G = h->ring_G; p.C = n_cand;
     p.optimistic = optimistic ? 1 : 0;
     p.list_stride = h->list_stride;
-    p.rec = h->d_rec; p.rec_plane = h->rec_plane; p.comm = h->d_comm_scaled; p.mem_delta = h->d_mem;
+    p.rec = h->d_rec; p.rec_plane = h->rec_plane; p.id_bits = h->id_bits; p.nparts = h->d_nparts; p.comm = h->d_comm_scaled; p.mem_delta = h->d_mem;
     p.sum_dur = h->sum_dur; p.time_scale = h->time_scale;
     p.placement = pl; p.rank = rk;
     p.ws_list = h->ws_list16;
@@ -420,11 +431,12 @@ int dagsched_create(const dagsched_desc_t *desc, dagsched_t **out) {
   if (ok && plan.ok) {
     h->variant = plan.exact ? kVariantRingExact : kVariantRingOptimistic;
     h->ring_G = plan.G; h->ring_slots = plan.ring; h->lds = plan.lds; h->time_scale = plan.scale;
-    h->rec_plane = plan.rec_plane;
+    h->rec_plane = plan.rec_plane; h->id_bits = plan.id_bits;
     const int64_t cap = ((int64_t)h->N + h->E + 1024) * 64;
     h->spin_cap = (uint32_t)std::min<int64_t>(cap, 0x7FFFFFFF);
     ok = upload(&h->d_rec, plan.rec.data(), plan.rec.size()) &&
          upload(&h->d_comm_scaled, plan.comm_scaled.data(), plan.comm_scaled.size()) &&
+         (plan.nparts.empty() || upload(&h->d_nparts, plan.nparts.data(), plan.nparts.size())) &&
          dev_alloc(&h->ws_list16, maxc * (size_t)h->list_stride);
     if (ok && !plan.exact) ok = dev_alloc(&h->d_fb_count, 1) && dev_alloc(&h->d_fb_list, maxc);
     if (ok && h->lds.total > 48 * 1024)
@@ -490,7 +502,7 @@ int dagsched_get_info(const dagsched_t *h, dagsched_info_t *info) {
   info->variant = h->variant;
   const bool ring = h->variant == kVariantRingExact || h->variant == kVariantRingOptimistic;
   info->cand_per_block = ring ? h->ring_G : h->gen_G;
-  info->block_threads = ring ? 2 * kWave : kWave;
+  info->block_threads = ring ? kThreads : kWave;
   info->lds_bytes = ring ? (int32_t)h->lds.total : h->gen_lds;
   info->state_bits = ring ? 16 : 32;
   info->reserved[0] = ring ? h->ring_slots : 0;

@@ -51,14 +51,16 @@ typedef DAGSCHED_LDS const uint8_t lds_cu8_t;
 //   w1 = ha(pred2) | ha(pred3) << 16       (end time 0, delay 0)
 //   w2 = delta0 | delta1 << 8 | delta2 << 16 | delta3 << 24
 //   w3 = duration (0 for every part but the last of an operation)
-//   w4 = ha(v) | FINAL << 16 | LAST << 17 | seq << 18         seq = (index of the op in its lane + 1) mod 2^14
+//   w4 = ha(v) | LAST << 17 | seq << 18     seq = (index of the op in its lane + 1) mod 2^14; a part that
+//        does not end its operation names the candidate's trash cell instead of v
 constexpr int kOpWords = 5;
-constexpr uint32_t kOpFinal = 1u << 16;   // completes its operation: add D^o, write the end time
+constexpr uint32_t kOpIdle = 1u << 16;    // relaxer-private: the lane holds no op (never set by the feeder)
 constexpr uint32_t kOpLast = 1u << 17;    // last op of this lane's order list
 constexpr int kOpSeqShift = 18;
 constexpr uint32_t kOpSeqMask = 0x3FFFu;
 constexpr uint32_t kNotDone16 = 0xFFFFu;
-constexpr int kThreads = 2 * kWave;
+constexpr int kFeeders = 2;               // feeder wavefronts; feeder f owns the parts with (seq - 1) % kFeeders == f
+constexpr int kThreads = (2 + kFeeders) * kWave;   // relaxer, feeders, accountant
 
 // One shared record per operation part: up to four DAG predecessors (unused slots name the dummy
 // node N).  Part i of operation v sits at rec[i * rec_plane + v]; only the last part carries the
@@ -75,6 +77,8 @@ struct RingParams {
   int64_t list_stride;                 // uint16 elements per candidate in ws_list
   const uint4 *rec;                    // [parts][rec_plane] shared operator records (times divided by time_scale)
   int32_t rec_plane;                   // records per part plane (>= N)
+  int32_t id_bits;                     // order-list entry = node | (parts - 1) << id_bits
+  const uint8_t *nparts;               // [N] parts per node, or NULL when every node has one part
   const int32_t *comm;                 // [P*P] channel delays divided by time_scale (all <= 255)
   const int64_t *mem_delta;            // [N]
   int64_t sum_dur;                     // in original units
@@ -109,13 +113,15 @@ __global__ __launch_bounds__(kThreads) void relax_ring_kernel(RingParams p) {
   int32_t *offw = (int32_t *)(lds + o.o_off);              // [64] start of the machine inside the list
   int32_t *flagw = (int32_t *)(lds + o.o_flag);            // [64] (G used)
   int32_t *abortw = (int32_t *)(lds + o.o_abort);          // [64] (G used)
-  uint8_t *commb = (uint8_t *)(lds + o.o_comm);            // [(P+1)*P], diagonal and dummy row zero
+  uint8_t *commb = (uint8_t *)(lds + o.o_comm);            // [(P+1)][64], diagonal and dummy row zero
 
   // ---------------------------------------------------------------- ingest (both wavefronts)
   if (tid < kWave) { cntw[tid] = 0; tailw[tid] = 0; flagw[tid] = 0; abortw[tid] = 0; peakw[tid] = 0; }
   for (int i = tid; i < kOpWords * RING * kWave; i += kThreads) ringw[i] = 0;
-  for (int i = tid; i < (P + 1) * P; i += kThreads)
-    commb[i] = (i < P * P && (i / P) != (i % P)) ? (uint8_t)p.comm[i] : (uint8_t)0;
+  for (int i = tid; i < (P + 1) * kWave; i += kThreads) {   // rows of 64 bytes: [source machine][destination]
+    const int a = i >> 6, b = i & 63;
+    commb[i] = (a < P && b < P && a != b) ? (uint8_t)p.comm[a * P + b] : (uint8_t)0;
+  }
   const int bm_words = (N + 31) >> 5;                       // rank bitmap, aliased over the state array
   for (int gg = 0; gg < ng; ++gg) {
     uint32_t *bm = (uint32_t *)(lds + gg * o.s_stride);
@@ -197,7 +203,7 @@ __global__ __launch_bounds__(kThreads) void relax_ring_kernel(RingParams p) {
         const uint32_t pos = (uint32_t)(off_g[pi] + r);
         const uint32_t bit = 1u << (pos & 31);
         if (atomicOr(&bm[pos >> 5], bit) & bit) atomicOr(flag_g, kBitBadRank);
-        else list[pos] = (uint16_t)v;
+        else list[pos] = (uint16_t)(p.nparts ? (uint32_t)v | ((uint32_t)(p.nparts[v] - 1) << p.id_bits) : (uint32_t)v);
       }
     };
     if (vec_ok) {
@@ -229,10 +235,10 @@ __global__ __launch_bounds__(kThreads) void relax_ring_kernel(RingParams p) {
   __threadfence();
   __syncthreads();
   // end-time state: every operation "not ended"; the dummy node N has ended at time 0 on a dummy
-  // machine P whose delays are all zero
+  // machine P whose delays are all zero; cell N+1 is a trash cell for parts that do not end an operation
   for (int gg = 0; gg < ng; ++gg) {
     uint32_t *sw = (uint32_t *)(lds + gg * o.s_stride);
-    for (int i = tid; i < (N + 2) / 2; i += kThreads) {
+    for (int i = tid; i < (N + 3) / 2; i += kThreads) {
       const uint32_t lo = (2 * i < N) ? kNotDone16 : 0u, hi = (2 * i + 1 < N) ? kNotDone16 : 0u;
       sw[i] = lo | (hi << 16);
     }
@@ -259,14 +265,21 @@ __global__ __launch_bounds__(kThreads) void relax_ring_kernel(RingParams p) {
     lds_vi32_t *const abort_p = (lds_vi32_t *)(ldsb + o.o_abort) + g;
     const uint64_t segmask = ((Pseg == kWave) ? ~0ull : ((1ull << Pseg) - 1ull)) << (g * Pseg);
     const uint32_t dummy = sbase_half + (uint32_t)N;
-    bool all_taken = !has_ops, have_cur = false;
-    uint32_t t = 0, want = 1, x_acc = 0;
-    uint32_t cw0 = dummy | (dummy << 16), cw1 = cw0, cw2 = 0, cw3 = 0, cw4 = dummy;
+    constexpr uint32_t kWantNothing = 0xFFFFFFFFu;        // no sequence number matches: the list is exhausted
+    // The loop body is branch-free: "this lane holds no op" is an op that can never run (duration
+    // 0xFFFF, flagged idle) and every trip stores x somewhere (the trash cell unless the op ran).
+    const uint32_t trash = sbase_half + (uint32_t)N + 1u;
+    const uint32_t idle_w4 = trash | kOpIdle;
+    uint32_t t = 0, want = has_ops ? 1u : kWantNothing, x_acc = 0;
+    uint32_t cw0 = dummy | (dummy << 16), cw1 = cw0, cw2 = 0, cw3 = kNotDone16, cw4 = idle_w4;
     uint64_t prog_acc = 0;
     bool expired = true;
     for (uint32_t it = 0; it < p.spin_cap; it += 8) {
 #pragma unroll
       for (int sub = 0; sub < 8; ++sub) {
+        // end times of the current op's predecessors (the critical reads go first)
+        const uint32_t e0 = cells[cw0 & 0xFFFFu], e1 = cells[cw0 >> 16];
+        const uint32_t e2 = cells[cw1 & 0xFFFFu], e3 = cells[cw1 >> 16];
         // next op of this lane, read speculatively every trip (tagged word first)
         lds_byte_t *const sp = ring_lane + ((t & (uint32_t)(RING - 1)) << 8);
         const uint32_t r4 = *(lds_vu32_t *)(sp + 4 * kPlaneBytes);
@@ -274,53 +287,56 @@ __global__ __launch_bounds__(kThreads) void relax_ring_kernel(RingParams p) {
         const uint32_t r1 = *(lds_vu32_t *)(sp + kPlaneBytes);
         const uint32_t r2 = *(lds_vu32_t *)(sp + 2 * kPlaneBytes);
         const uint32_t r3 = *(lds_vu32_t *)(sp + 3 * kPlaneBytes);
-        // end times of the current op's predecessors
-        const uint32_t e0 = cells[cw0 & 0xFFFFu], e1 = cells[cw0 >> 16];
-        const uint32_t e2 = cells[cw1 & 0xFFFFu], e3 = cells[cw1 >> 16];
         uint32_t x = max(max(x_acc, e0 + (cw2 & 0xFFu)), e1 + ((cw2 >> 8) & 0xFFu));
         x = max(max(x, e2 + ((cw2 >> 16) & 0xFFu)), e3 + (cw2 >> 24));
         x += cw3;
-        const bool ready = have_cur && x < kNotDone16;      // every predecessor ended and no 16-bit overflow
-        if (ready) {
-          x_acc = x;                                        // the machine is busy until x (chain edge, eq. (7))
-          if (cw4 & kOpFinal) cells[cw4 & 0xFFFFu] = (uint16_t)x;
-        }
-        const bool take = !all_taken && (ready || !have_cur) && ((r4 >> kOpSeqShift) == want);
+        const bool ready = x < kNotDone16;                  // every predecessor ended, no 16-bit overflow, not idle
+        x_acc = ready ? x : x_acc;                          // the machine is busy until x (chain edge, eq. (7))
+        cells[ready ? (cw4 & 0xFFFFu) : trash] = (uint16_t)x;
+        const bool idle = (cw4 & kOpIdle) != 0;
+        const bool take = (ready || idle) && ((r4 >> kOpSeqShift) == want);
         prog_acc |= __ballot(ready || take);                // an op taken now has not been tested yet
-        have_cur = take || (have_cur && !ready);
-        if (take) {
-          cw0 = r0; cw1 = r1; cw2 = r2; cw3 = r3; cw4 = r4;
-          ++t;
-          want = (t + 1) & kOpSeqMask;
-          *tail_p = t;
-          all_taken = (r4 & kOpLast) != 0;
-        }
+        cw0 = take ? r0 : cw0;
+        cw1 = take ? r1 : cw1;
+        cw2 = take ? r2 : cw2;
+        cw3 = take ? r3 : (ready ? kNotDone16 : cw3);
+        cw4 = take ? (r4 & ~kOpIdle) : (ready ? idle_w4 : cw4);
+        t += take ? 1u : 0u;
+        want = take ? ((r4 & kOpLast) ? kWantNothing : ((t + 1) & kOpSeqMask)) : want;
+        *tail_p = t;
       }
-      const bool fin = all_taken && !have_cur;
+      const bool have_cur = (cw4 & kOpIdle) == 0;
+      const bool fin = (want == kWantNothing) && !have_cur;
       if (__ballot(!fin) == 0) { expired = false; break; }
       const uint64_t hold = __ballot(have_cur || fin);
       if (!fin && (prog_acc & segmask) == 0 && (hold & segmask) == segmask) {
         // every unfinished machine of this candidate holds an op and none could run for a whole
         // window: deadlock, i.e. a cycle of the combined graph (or a 16-bit overflow when optimistic)
         stalled = true;
-        all_taken = true;
-        have_cur = false;
+        want = kWantNothing;
+        cw3 = kNotDone16;
+        cw4 = idle_w4;
         *abort_p = 1;
       }
       prog_acc = 0;
     }
     if (expired) {                                          // bounded wait ran out: report, release the feeder
-      const bool fin = all_taken && !have_cur;
+      const bool fin = (want == kWantNothing) && (cw4 & kOpIdle) != 0;
       if (!fin) { flagw[g] = kBitInternal; *abort_p = 1; }
     }
     acc = (int32_t)x_acc;
-  } else {
-    // ------------------------------------------------------------ feeder
-    // Per lane the op parts of machine j form a stream (parts of one operation are consecutive).  A
-    // three-stage register pipeline rc -> r1 -> r2 holds the next three parts; the part after them is
-    // (re)loaded into a temporary every trip and accepted into r2 one trip later, so a global load
-    // always has a full trip to land.  Two sets of temporaries alternate (the loop is unrolled by
-    // two) so that a freshly loaded register is never copied in the trip that issued it.
+  } else if (wave <= kFeeders) {
+    // ------------------------------------------------------------ feeders
+    // Per lane the op parts of machine j form a stream (the parts of one operation are consecutive;
+    // the order-list entry of a node carries its part count, so the stream is known from the ids
+    // alone).  Feeder f owns every kFeeders-th part.  A part is ADMITTED when its ring slot is free
+    // (fewer than RING parts between it and the relaxer's tail), then moves through a fixed pipeline
+    // without ever stalling:
+    //   trip t    record requested from L2
+    //   trip t+1  placement bytes of its predecessors read from LDS
+    //   trip t+2  channel delays read from LDS, op packed and written to the ring
+    // The loop is unrolled by three so that the pipeline registers rotate by renaming, not by moves.
+    const int f = wave - 1;
     lds_cu8_t *const pib = (lds_cu8_t *)(ldsb + o.o_pi + g * o.pi_stride);
     lds_cu8_t *const commr = (lds_cu8_t *)(ldsb + o.o_comm) + j;
     lds_byte_t *const ring_lane = ldsb + o.o_ring + (uint32_t)lane * 4u;
@@ -328,81 +344,107 @@ __global__ __launch_bounds__(kThreads) void relax_ring_kernel(RingParams p) {
     lds_vi32_t *const abort_p = (lds_vi32_t *)(ldsb + o.o_abort) + g;
     const uint16_t *list = p.ws_list + (c0 + (cand_ok ? g : 0)) * p.list_stride;
     const uint32_t base2 = sbase_half | (sbase_half << 16);
-    const int k0 = has_ops ? offw[ql] : 0;
-    const int kend = has_ops ? k0 + cntw[ql] : 1;
-    bool fin = !has_ops;
-    uint32_t head = 0, tail_seen = 0;
-    int64_t level = 0, peak = 0;
-    constexpr uint32_t kStValid = 1u, kStLastNode = 2u;    // dynamic flags in the low half of rec.w
-    uint4 rc = make_uint4(0, 0, 0, 0), r1 = rc, r2 = rc;
-    int64_t m0 = 0, m1 = 0, m2 = 0;
-    // loader: identity of the part the temporaries are loading
-    int npos = k0;
-    uint32_t nv = has_ops ? (uint32_t)list[k0] : 0u;
-    uint32_t naddr = nv;
-    uint32_t idq1 = (has_ops && k0 + 1 < kend) ? (uint32_t)list[k0 + 1] : 0u;
-    bool stream_end = !has_ops;
-    uint4 tra = p.rec[naddr], trb = tra;
-    int64_t tma = p.mem_delta[nv], tmb = tma;
-    uint32_t tia = has_ops ? (uint32_t)list[min(npos + 2, kend - 1)] : 0u, tib = tia;
-    uint32_t q0 = pib[0], q1 = q0, q2 = q0, q3 = q0;       // placement bytes of rc's predecessors
+    const uint32_t trash = sbase_half + (uint32_t)N + 1u;
+    const uint32_t vbits = (uint32_t)p.id_bits, vmask = (1u << vbits) - 1u;
     const uint32_t n_plane = (uint32_t)p.rec_plane;
+    const int k0 = has_ops ? offw[ql] : 0;
+    const int klast = has_ops ? k0 + cntw[ql] - 1 : 0;      // list position of the lane's last node
+    bool stream_end = !has_ops, pending = false;
+    uint32_t admitted = 0, written = 0;
+    uint32_t aseq = (uint32_t)f;                            // (sequence number - 1) of the next part to admit
+    uint32_t wseq = (uint32_t)f;                            // ... of the next part to write
+    // cursor: the next part to admit is part `part` of node v (np parts) at list position k
+    int k = k0;
+    uint32_t w0 = has_ops ? (uint32_t)list[k0] : 0u;
+    uint32_t v = w0 & vmask, np = (w0 >> vbits) + 1u, part = 0;
+    uint32_t id1 = has_ops ? (uint32_t)list[min(k0 + 1, klast)] : 0u;
+    uint32_t id2 = has_ops ? (uint32_t)list[min(k0 + 2, klast)] : 0u;
+    // move the cursor one part ahead; returns true when it entered the next node
+    auto advance = [&](uint32_t next_id) -> bool {
+      const bool node_done = part + 1 == np;
+      const bool to_next = !stream_end && node_done && (k != klast);
+      const bool step = !stream_end && !node_done;
+      stream_end = stream_end || (node_done && k == klast);
+      part = to_next ? 0u : (step ? part + 1u : part);
+      v = to_next ? (next_id & vmask) : v;
+      np = to_next ? (next_id >> vbits) + 1u : np;
+      k += to_next ? 1 : 0;
+      return to_next;
+    };
+    for (int i = 0; i < f; ++i) {                           // feeder f starts at its first own part
+      const bool crossed = advance(id1);
+      id1 = crossed ? id2 : id1;
+    }
+    struct Entry { uint4 rec; uint32_t q0, q1, q2, q3, fl; };   // fl: 1 valid, 2 last part of the lane
+    Entry E[3];
+#pragma unroll
+    for (int i = 0; i < 3; ++i) { E[i].rec = make_uint4(0, 0, 0, 0); E[i].q0 = E[i].q1 = E[i].q2 = E[i].q3 = 0; E[i].fl = 0; }
 
-    auto trip = [&](uint4 &tr, int64_t &tm, uint32_t &ti, uint4 &tr_new, int64_t &tm_new, uint32_t &ti_new) {
-      bool full = (head - tail_seen) >= (uint32_t)RING;
-      if (!fin && full) {
-        tail_seen = *tail_p;
-        full = (head - tail_seen) >= (uint32_t)RING;
-        if (full && *abort_p) fin = true;
-      }
-      const bool rc_valid = (rc.w & kStValid) != 0;
-      const bool produce = !fin && !full && rc_valid;
-      // channel delays of rc (its placement bytes were read one trip ago); placement bytes of r1
-      const uint32_t d0 = commr[q0 * P], d1 = commr[q1 * P], d2 = commr[q2 * P], d3 = commr[q3 * P];
-      const uint32_t n0 = pib[r1.x & 0xFFFFu], n1 = pib[r1.x >> 16], n2 = pib[r1.y & 0xFFFFu], n3 = pib[r1.y >> 16];
-      if (produce) {
-        const bool more = (rc.z >> 31) != 0;
-        const bool last = !more && (rc.w & kStLastNode);
-        const uint32_t w4 = (sbase_half + (rc.w >> 16)) | (more ? 0u : kOpFinal) | (last ? kOpLast : 0u) |
-                            (((head + 1) & kOpSeqMask) << kOpSeqShift);
-        lds_byte_t *const sp = ring_lane + ((head & (uint32_t)(RING - 1)) << 8);
-        *(lds_vu32_t *)(sp) = rc.x + base2;
-        *(lds_vu32_t *)(sp + kPlaneBytes) = rc.y + base2;
-        *(lds_vu32_t *)(sp + 2 * kPlaneBytes) = d0 | (d1 << 8) | (d2 << 16) | (d3 << 24);
-        *(lds_vu32_t *)(sp + 3 * kPlaneBytes) = rc.z & 0x3FFFFFFFu;
-        *(lds_vu32_t *)(sp + 4 * kPlaneBytes) = w4;
-        ++head;
-        if (rc.z & 0x40000000u) { level += m0; peak = max(peak, level); }   // first part: eq. (19) along the chain
-        if (last) fin = true;
-      }
-      if (!fin && (produce || !rc_valid)) {                 // shift the pipeline, accept the temporary
-        rc = r1; m0 = m1; q0 = n0; q1 = n1; q2 = n2; q3 = n3;
-        r1 = r2; m1 = m2;
-        if (!stream_end) {
-          const bool t_more = (tr.z >> 31) != 0;
-          r2 = make_uint4(tr.x, tr.y, tr.z, (tr.w & 0xFFFF0000u) | kStValid | ((npos == kend - 1) ? kStLastNode : 0u));
-          m2 = tm;
-          if (t_more) {
-            naddr += n_plane;
-          } else if (npos == kend - 1) {
-            stream_end = true;
-          } else {
-            ++npos; nv = idq1; naddr = idq1; idq1 = ti;
+    for (uint32_t it = 0; it < p.spin_cap; it += 3) {
+      if (*abort_p) { stream_end = true; written = admitted; }   // the relaxer gave this candidate up
+      if (__ballot(!(stream_end && written == admitted)) == 0) break;
+#pragma unroll
+      for (int s = 0; s < 3; ++s) {
+        Entry &e0 = E[s];                 // admitted in this trip
+        Entry &e1 = E[(s + 2) % 3];       // admitted one trip ago
+        Entry &e2 = E[(s + 1) % 3];       // admitted two trips ago
+        // (A) channel delays of e2 (its placement bytes were read one trip ago)
+        const uint32_t d0 = commr[e2.q0 << 6], d1 = commr[e2.q1 << 6], d2 = commr[e2.q2 << 6], d3 = commr[e2.q3 << 6];
+        // (1) move the cursor past the part admitted in the previous trip and the other feeders' parts
+        if (pending) {
+#pragma unroll
+          for (int a = 0; a < kFeeders; ++a) {
+            const bool crossed = advance(id1);
+            id1 = crossed ? id2 : id1;
           }
-        } else {
-          r2 = make_uint4(0, 0, 0, 0);
+          aseq += kFeeders;
+        }
+        // (2) ids of the next two nodes (reloaded every trip; consumed one trip later at the earliest)
+        id1 = list[min(k + 1, klast)];
+        id2 = list[min(k + 2, klast)];
+        // (3) admission
+        pending = !stream_end && (aseq - *tail_p) < (uint32_t)RING;
+        e0.fl = pending ? (1u | ((k == klast && part + 1 == np) ? 2u : 0u)) : 0u;
+        e0.rec = p.rec[part * n_plane + v];
+        admitted += pending ? 1u : 0u;
+        // (B) placement bytes of e1's predecessors (its record was requested one trip ago)
+        e1.q0 = pib[e1.rec.x & 0xFFFFu]; e1.q1 = pib[e1.rec.x >> 16];
+        e1.q2 = pib[e1.rec.y & 0xFFFFu]; e1.q3 = pib[e1.rec.y >> 16];
+        // (D) pack e2 and publish it
+        if (e2.fl & 1u) {
+          const bool more = (e2.rec.z >> 31) != 0;
+          const uint32_t w4 = (more ? trash : sbase_half + (e2.rec.w >> 16)) | ((e2.fl & 2u) ? kOpLast : 0u) |
+                              (((wseq + 1) & kOpSeqMask) << kOpSeqShift);
+          lds_byte_t *const sp = ring_lane + ((wseq & (uint32_t)(RING - 1)) << 8);
+          *(lds_vu32_t *)(sp) = e2.rec.x + base2;
+          *(lds_vu32_t *)(sp + kPlaneBytes) = e2.rec.y + base2;
+          *(lds_vu32_t *)(sp + 2 * kPlaneBytes) = d0 | (d1 << 8) | (d2 << 16) | (d3 << 24);
+          *(lds_vu32_t *)(sp + 3 * kPlaneBytes) = e2.rec.z & 0x3FFFFFFFu;
+          *(lds_vu32_t *)(sp + 4 * kPlaneBytes) = w4;
+          wseq += kFeeders;
+          ++written;
         }
       }
-      if (!stream_end) {                                    // (re)load the part after r2
-        tr_new = p.rec[naddr];
-        tm_new = p.mem_delta[nv];
-        ti_new = list[min(npos + 2, kend - 1)];
-      }
-    };
-    for (uint32_t it = 0; it < p.spin_cap; it += 2) {
-      if (__ballot(!fin) == 0) break;
-      trip(tra, tma, tia, trb, tmb, tib);
-      trip(trb, tmb, tib, tra, tma, tia);
+    }
+  } else {
+    // ------------------------------------------------------------ accountant
+    // Peak of the running memory level of machine j (eqs. (17)-(19)): it depends on the order only,
+    // so one wavefront walks the order lists on its own, four operations per trip.
+    const uint16_t *list = p.ws_list + (c0 + (cand_ok ? g : 0)) * p.list_stride;
+    const uint32_t vmask = (1u << p.id_bits) - 1u;
+    const int k0 = has_ops ? offw[ql] : 0;
+    const int kend = has_ops ? k0 + cntw[ql] : 0;
+    int64_t level = 0, peak = 0;
+    for (int k = k0; __ballot(k < kend) != 0; k += 4) {
+      uint32_t id[4];
+      int64_t m[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) id[u] = (k + u < kend) ? ((uint32_t)list[k + u] & vmask) : 0u;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) m[u] = p.mem_delta[id[u]];
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (k + u < kend) { level += m[u]; peak = max(peak, level); }   // eq. (19) along the chain
     }
     if (lane_on) peakw[ql] = peak;
   }
