@@ -74,7 +74,7 @@ struct dagsched {
   int64_t *d_mem = nullptr;
   int32_t *ws_list = nullptr, *ws_end = nullptr;
   // ring kernel
-  int32_t ring_G = 0, ring_slots = 0, rec_plane = 0, id_bits = 16, time_scale = 1;
+  int32_t ring_G = 0, ring_slots = 0, ring_preds = 4, ring_feeders = 1, rec_plane = 0, id_bits = 16, time_scale = 1;
   uint8_t *d_nparts = nullptr;
   int64_t list_stride = 0;
   LdsLayout lds{};
@@ -171,7 +171,7 @@ int env_int(const char *name, int dflt) {
   return (s && *s) ? atoi(s) : dflt;
 }
 
-LdsLayout ring_layout(int N, int P, int G, int ring) {
+LdsLayout ring_layout(int N, int P, int G, int ring, int op_words) {
   LdsLayout o{};
   uint32_t at = 0;
   o.s_stride = align_up(2u * (uint32_t)(N + 2), 4);      // N cells + dummy + trash; the arrays start at LDS offset 0
@@ -179,7 +179,7 @@ LdsLayout ring_layout(int N, int P, int G, int ring) {
   at += (uint32_t)G * o.s_stride;
   o.o_pi = at;    at += (uint32_t)G * o.pi_stride;
   at = align_up(at, 16);
-  o.o_ring = at;  at += (uint32_t)kOpWords * (uint32_t)ring * kWave * 4u;
+  o.o_ring = at;  at += (uint32_t)op_words * (uint32_t)ring * kWave * 4u;
   o.o_tail = at;  at += kWave * 4u;
   at = align_up(at, 8);
   o.o_peak = at;  at += kWave * 8u;
@@ -187,7 +187,7 @@ LdsLayout ring_layout(int N, int P, int G, int ring) {
   o.o_off = at;   at += kWave * 4u;
   o.o_flag = at;  at += kWave * 4u;
   o.o_abort = at; at += kWave * 4u;
-  o.o_comm = at;  at += (uint32_t)(P + 1) * kWave;
+  o.o_comm = at;  at += align_up((uint32_t)(P + 1) * (uint32_t)next_pow2(P), 4);
   o.total = align_up(at, 16);
   return o;
 }
@@ -198,7 +198,7 @@ LdsLayout ring_layout(int N, int P, int G, int ring) {
 // footprint that fits a workgroup.
 struct RingPlan {
   bool ok = false, exact = false;
-  int G = 0, ring = 0;
+  int G = 0, ring = 0, preds = 4, feeders = 1;
   int32_t scale = 1;
   LdsLayout lds{};
   std::vector<uint4> rec;
@@ -245,20 +245,31 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
   plan.exact = upper < (int64_t)kNotDone16;
   plan.scale = (int32_t)g;
 
-  // shared operator records, four predecessors per part, part i of node v at [i * plane + v]
+  // predecessors per op part: three (four-dword ops) unless that needs noticeably more parts than four
+  int64_t parts3 = 0, parts4 = 0;
+  for (int v = 0; v < N; ++v) {
+    const int deg = pred_ptr[v + 1] - pred_ptr[v];
+    parts3 += std::max(1, (deg + 2) / 3);
+    parts4 += std::max(1, (deg + 3) / 4);
+  }
+  const int forced_preds = env_int("DAGSCHED_RING_PREDS", 0);
+  const int PR = forced_preds ? forced_preds : ((parts3 * 50 <= parts4 * 51) ? 3 : 4);
+  if (PR != 3 && PR != 4) return plan;
+  plan.preds = PR;
+  // shared operator records, PR predecessors per part, part i of node v at [i * plane + v]
   const uint32_t dummy = (uint32_t)N;
   int max_parts = 1;
-  for (int v = 0; v < N; ++v) max_parts = std::max(max_parts, (pred_ptr[v + 1] - pred_ptr[v] + 3) / 4);
+  for (int v = 0; v < N; ++v) max_parts = std::max(max_parts, (pred_ptr[v + 1] - pred_ptr[v] + PR - 1) / PR);
   if (max_parts > 16) return plan;                     // very wide fan-in: leave it to the general kernel
   const int plane = N;
   std::vector<uint4> rec((size_t)max_parts * plane, make_uint4(dummy | (dummy << 16), dummy | (dummy << 16), 0, 0));
   for (int v = 0; v < N; ++v) {
     const int deg = pred_ptr[v + 1] - pred_ptr[v];
-    const int parts = std::max(1, (deg + 3) / 4);
+    const int parts = std::max(1, (deg + PR - 1) / PR);
     for (int part = 0; part < parts; ++part) {
       uint32_t u[4] = {dummy, dummy, dummy, dummy};
-      for (int i = 0; i < 4; ++i) {
-        const int k = pred_ptr[v] + part * 4 + i;
+      for (int i = 0; i < PR; ++i) {
+        const int k = pred_ptr[v] + part * PR + i;
         if (k < pred_ptr[v + 1]) u[i] = (uint32_t)pred_idx[k];
       }
       const bool more = part + 1 < parts;
@@ -277,29 +288,43 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
   if (N > (1 << plan.id_bits)) return plan;            // ids and part counts do not fit: general kernel
   if (max_parts > 1) {
     plan.nparts.resize(N);
-    for (int v = 0; v < N; ++v) plan.nparts[v] = (uint8_t)std::max(1, (pred_ptr[v + 1] - pred_ptr[v] + 3) / 4);
+    for (int v = 0; v < N; ++v) plan.nparts[v] = (uint8_t)std::max(1, (pred_ptr[v + 1] - pred_ptr[v] + PR - 1) / PR);
   }
   plan.comm_scaled.resize((size_t)P * P);
   for (int i = 0; i < P * P; ++i) plan.comm_scaled[i] = (i / P != i % P) ? (int32_t)(d->comm[i] / g) : 0;
 
-  // shape: most candidates resident per CU, then fewer wavefronts, then a deeper ring
+  // shape: most candidates resident per CU, then fewer wavefronts, then a deeper ring; a second
+  // feeder wavefront when the CU would otherwise hold few wavefronts (LDS-bound configurations)
   const int force_g = env_int("DAGSCHED_RING_G", 0), force_ring = env_int("DAGSCHED_RING_SLOTS", 0);
-  int best_score = -1;
+  const int force_feeders = env_int("DAGSCHED_RING_FEEDERS", 0);
+  const int op_words = PR == 4 ? 5 : 4;
+  int best_score = -1, best_wgs = 0;
   for (int G = kWave / Pseg; G >= 1; G >>= 1) {
     if (force_g && G != force_g) continue;
     for (int ring : {8, 4}) {
       if (force_ring && ring != force_ring) continue;
-      LdsLayout o = ring_layout(N, P, G, ring);
+      LdsLayout o = ring_layout(N, P, G, ring, op_words);
       if ((int)o.total > lds_max) continue;
       if ((uint64_t)G * (o.s_stride >> 1) > 65536u) continue;   // half-addresses must fit 16 bits
-      const int wgs = std::min(8, lds_max / (int)align_up(o.total, 1024));
+      const int wgs = std::min(8, lds_max / (int)align_up(o.total, 512));
       if (wgs < 1) continue;
       const int score = wgs * G * 64 + G * 2 + (ring == 8 ? 1 : 0);
-      if (score > best_score) { best_score = score; plan.G = G; plan.ring = ring; plan.lds = o; }
+      if (score > best_score) { best_score = score; best_wgs = wgs; plan.G = G; plan.ring = ring; plan.lds = o; }
     }
   }
+  plan.feeders = force_feeders ? force_feeders : (best_wgs * 4 <= 12 ? 2 : 1);
+  if (plan.feeders != 1 && plan.feeders != 2) return plan;
   plan.ok = best_score >= 0;
   return plan;
+}
+
+using RingKernel = void (*)(RingParams);
+RingKernel ring_kernel_for(const dagsched *h) {
+  const int r8 = h->ring_slots == 8, p4 = h->ring_preds == 4, f2 = h->ring_feeders == 2;
+  static const RingKernel table[2][2][2] = {
+      {{relax_ring_kernel<4, 3, 1>, relax_ring_kernel<4, 3, 2>}, {relax_ring_kernel<4, 4, 1>, relax_ring_kernel<4, 4, 2>}},
+      {{relax_ring_kernel<8, 3, 1>, relax_ring_kernel<8, 3, 2>}, {relax_ring_kernel<8, 4, 1>, relax_ring_kernel<8, 4, 2>}}};
+  return table[r8][p4][f2];
 }
 
 OutPtrs make_out(const dagsched *h, int32_t n_cand, int32_t *makespan, int64_t *bubble, int64_t *peak_mem,
@@ -359,10 +384,8 @@ int launch_evaluate(dagsched *h, int32_t n_cand, const int32_t *placement, const
     p.lds = h->lds;
     p.out = out;
     const unsigned blocks = (unsigned)((n_cand + h->ring_G - 1) / h->ring_G);
-    if (h->ring_slots == 8)
-      hipLaunchKernelGGL(relax_ring_kernel<8>, dim3(blocks), dim3(kThreads), (size_t)h->lds.total, stream, p);
-    else
-      hipLaunchKernelGGL(relax_ring_kernel<4>, dim3(blocks), dim3(kThreads), (size_t)h->lds.total, stream, p);
+    hipLaunchKernelGGL(ring_kernel_for(h), dim3(blocks), dim3(ring_threads(h->ring_feeders)), (size_t)h->lds.total,
+                       stream, p);
     if (optimistic) launch_general(h, n_cand, pl, rk, out, h->d_fb_list, h->d_fb_count, stream);
   }
   if (!hip_ok(hipGetLastError(), "kernel launch")) return DAGSCHED_EHIP;
@@ -430,7 +453,7 @@ int dagsched_create(const dagsched_desc_t *desc, dagsched_t **out) {
   }
   if (ok && plan.ok) {
     h->variant = plan.exact ? kVariantRingExact : kVariantRingOptimistic;
-    h->ring_G = plan.G; h->ring_slots = plan.ring; h->lds = plan.lds; h->time_scale = plan.scale;
+    h->ring_G = plan.G; h->ring_slots = plan.ring; h->ring_preds = plan.preds; h->ring_feeders = plan.feeders; h->lds = plan.lds; h->time_scale = plan.scale;
     h->rec_plane = plan.rec_plane; h->id_bits = plan.id_bits;
     const int64_t cap = ((int64_t)h->N + h->E + 1024) * 64;
     h->spin_cap = (uint32_t)std::min<int64_t>(cap, 0x7FFFFFFF);
@@ -440,10 +463,8 @@ int dagsched_create(const dagsched_desc_t *desc, dagsched_t **out) {
          dev_alloc(&h->ws_list16, maxc * (size_t)h->list_stride);
     if (ok && !plan.exact) ok = dev_alloc(&h->d_fb_count, 1) && dev_alloc(&h->d_fb_list, maxc);
     if (ok && h->lds.total > 48 * 1024)
-      ok = hip_ok(hipFuncSetAttribute(h->ring_slots == 8 ? (const void *)relax_ring_kernel<8>
-                                                         : (const void *)relax_ring_kernel<4>,
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)h->lds.total),
-                  "hipFuncSetAttribute");
+      ok = hip_ok(hipFuncSetAttribute((const void *)ring_kernel_for(h), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      (int)h->lds.total), "hipFuncSetAttribute");
   }
   if (ok && h->layout == DAGSCHED_CAND_MINOR)
     ok = dev_alloc(&h->ws_tp, maxc * (size_t)h->N) && dev_alloc(&h->ws_tr, maxc * (size_t)h->N);
@@ -502,11 +523,12 @@ int dagsched_get_info(const dagsched_t *h, dagsched_info_t *info) {
   info->variant = h->variant;
   const bool ring = h->variant == kVariantRingExact || h->variant == kVariantRingOptimistic;
   info->cand_per_block = ring ? h->ring_G : h->gen_G;
-  info->block_threads = ring ? kThreads : kWave;
+  info->block_threads = ring ? ring_threads(h->ring_feeders) : kWave;
   info->lds_bytes = ring ? (int32_t)h->lds.total : h->gen_lds;
   info->state_bits = ring ? 16 : 32;
   info->reserved[0] = ring ? h->ring_slots : 0;
   info->reserved[1] = h->time_scale;
+  info->reserved[2] = ring ? h->ring_preds * 10 + h->ring_feeders : 0;
   return DAGSCHED_OK;
 }
 

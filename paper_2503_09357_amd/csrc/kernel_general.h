@@ -87,8 +87,7 @@ __global__ __launch_bounds__(kWave) void relax_general_kernel(GeneralParams p) {
       else st_agent(list + s_off[gg * Pseg + pi] + r, v);
     }
   }
-  __threadfence();
-  __syncthreads();
+  __syncthreads();                   // workgroup scope is enough: one wavefront writes and reads these lists
   // every (machine, rank) slot must be hit exactly once: a slot written twice keeps one writer only
   for (int gg = 0; gg < ng; ++gg) {
     if (s_flag[gg]) continue;
@@ -156,8 +155,7 @@ __global__ __launch_bounds__(kWave) void relax_general_kernel(GeneralParams p) {
         }
       }
     }
-    if (!LDS_STATE) __threadfence();
-    __syncthreads();
+    __syncthreads();                 // orders this round's end-time stores before the next round's loads
     const uint64_t bal_prog = __ballot(progressed);
     if (active && (bal_prog & segmask) == 0) {
       // nothing of this candidate moved although operations remain: the combined graph is cyclic

@@ -45,24 +45,31 @@ typedef DAGSCHED_LDS volatile uint16_t lds_vu16_t;
 typedef DAGSCHED_LDS volatile int32_t lds_vi32_t;
 typedef DAGSCHED_LDS const uint8_t lds_cu8_t;
 
-// Op layout (five dwords).  "Half-address" = LDS byte address / 2 of a 16-bit end-time cell; the
-// end-time arrays start at LDS offset 0, so every half-address fits 16 bits.
-//   w0 = ha(pred0) | ha(pred1) << 16       unused predecessor slots name the candidate's dummy cell
-//   w1 = ha(pred2) | ha(pred3) << 16       (end time 0, delay 0)
-//   w2 = delta0 | delta1 << 8 | delta2 << 16 | delta3 << 24
-//   w3 = duration (0 for every part but the last of an operation)
-//   w4 = ha(v) | LAST << 17 | seq << 18     seq = (index of the op in its lane + 1) mod 2^14; a part that
-//        does not end its operation names the candidate's trash cell instead of v
-constexpr int kOpWords = 5;
-constexpr uint32_t kOpIdle = 1u << 16;    // relaxer-private: the lane holds no op (never set by the feeder)
-constexpr uint32_t kOpLast = 1u << 17;    // last op of this lane's order list
-constexpr int kOpSeqShift = 18;
-constexpr uint32_t kOpSeqMask = 0x3FFFu;
+// Op layouts.  "Half-address" (ha) = LDS byte address / 2 of a 16-bit end-time cell; the end-time arrays
+// start at LDS offset 0, so every half-address fits 16 bits.  Unused predecessor slots name the
+// candidate's dummy cell (end time 0, delay 0); a part that does not end its operation names the
+// candidate's trash cell instead of v.  seq = (index of the op in its lane + 1) mod (SeqMask + 1).
+//   PREDS = 4, five dwords                           PREDS = 3, four dwords
+//     w0 = ha(pred0) | ha(pred1) << 16                 w0 = ha(pred0) | ha(pred1) << 16
+//     w1 = ha(pred2) | ha(pred3) << 16                 w1 = ha(pred2) | ha(v) << 16
+//     w2 = delta0 | delta1 << 8 | delta2 << 16         w2 = duration
+//          | delta3 << 24                              w3 = delta0 | delta1 << 8 | delta2 << 16
+//     w3 = duration                                         | LAST << 24 | seq << 25        (tag word)
+//     w4 = ha(v) | LAST << 17 | seq << 18  (tag word)
+// The duration is 0 for every part but the last of an operation.
+template <int PREDS> struct OpFormat;
+template <> struct OpFormat<4> {
+  static constexpr int kWords = 5, kTagWord = 4, kSeqShift = 18;
+  static constexpr uint32_t kLast = 1u << 17, kSeqMask = 0x3FFFu;
+};
+template <> struct OpFormat<3> {
+  static constexpr int kWords = 4, kTagWord = 3, kSeqShift = 25;
+  static constexpr uint32_t kLast = 1u << 24, kSeqMask = 0x7Fu;
+};
 constexpr uint32_t kNotDone16 = 0xFFFFu;
-constexpr int kFeeders = 2;               // feeder wavefronts; feeder f owns the parts with (seq - 1) % kFeeders == f
-constexpr int kThreads = (2 + kFeeders) * kWave;   // relaxer, feeders, accountant
+constexpr int ring_threads(int feeders) { return (2 + feeders) * kWave; }   // relaxer, feeders, accountant
 
-// One shared record per operation part: up to four DAG predecessors (unused slots name the dummy
+// One shared record per operation part: up to PREDS DAG predecessors (unused slots name the dummy
 // node N).  Part i of operation v sits at rec[i * rec_plane + v]; only the last part carries the
 // duration.
 //   x = u0 | u1 << 16, y = u2 | u3 << 16, z = dur (30 bits) | first_part << 30 | has_more << 31, w = v << 16
@@ -91,8 +98,13 @@ struct RingParams {
   OutPtrs out;
 };
 
-template <int RING>
-__global__ __launch_bounds__(kThreads) void relax_ring_kernel(RingParams p) {
+// FEEDERS feeder wavefronts share a lane's stream: feeder f owns the parts with (seq - 1) % FEEDERS == f.
+template <int RING, int PREDS, int FEEDERS>
+__global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingParams p) {
+  using Fmt = OpFormat<PREDS>;
+  constexpr int kOpWords = Fmt::kWords;
+  constexpr int kThreads = ring_threads(FEEDERS);
+  constexpr int kFeeders = FEEDERS;
   extern __shared__ __align__(16) unsigned char lds[];
   static_assert((RING & (RING - 1)) == 0, "RING must be a power of two");
   constexpr uint32_t kPlaneBytes = RING * kWave * 4;        // ring layout: [word][slot][lane]
@@ -113,13 +125,13 @@ __global__ __launch_bounds__(kThreads) void relax_ring_kernel(RingParams p) {
   int32_t *offw = (int32_t *)(lds + o.o_off);              // [64] start of the machine inside the list
   int32_t *flagw = (int32_t *)(lds + o.o_flag);            // [64] (G used)
   int32_t *abortw = (int32_t *)(lds + o.o_abort);          // [64] (G used)
-  uint8_t *commb = (uint8_t *)(lds + o.o_comm);            // [(P+1)][64], diagonal and dummy row zero
+  uint8_t *commb = (uint8_t *)(lds + o.o_comm);            // [(P+1)][Pseg], diagonal and dummy row zero
 
   // ---------------------------------------------------------------- ingest (both wavefronts)
   if (tid < kWave) { cntw[tid] = 0; tailw[tid] = 0; flagw[tid] = 0; abortw[tid] = 0; peakw[tid] = 0; }
   for (int i = tid; i < kOpWords * RING * kWave; i += kThreads) ringw[i] = 0;
-  for (int i = tid; i < (P + 1) * kWave; i += kThreads) {   // rows of 64 bytes: [source machine][destination]
-    const int a = i >> 6, b = i & 63;
+  for (int i = tid; i < (P + 1) * Pseg; i += kThreads) {    // rows of Pseg bytes: [source machine][destination]
+    const int a = i >> p.log_pseg, b = i & (Pseg - 1);
     commb[i] = (a < P && b < P && a != b) ? (uint8_t)p.comm[a * P + b] : (uint8_t)0;
   }
   const int bm_words = (N + 31) >> 5;                       // rank bitmap, aliased over the state array
@@ -232,8 +244,7 @@ __global__ __launch_bounds__(kThreads) void relax_ring_kernel(RingParams p) {
       for (int v = tid; v < N; v += kThreads) place(v, pib[v], rk[v]);
     }
   }
-  __threadfence();
-  __syncthreads();
+  __syncthreads();                                          // workgroup scope: the lists are read by this workgroup only
   // end-time state: every operation "not ended"; the dummy node N has ended at time 0 on a dummy
   // machine P whose delays are all zero; cell N+1 is a trash cell for parts that do not end an operation
   for (int gg = 0; gg < ng; ++gg) {
@@ -267,61 +278,70 @@ __global__ __launch_bounds__(kThreads) void relax_ring_kernel(RingParams p) {
     const uint32_t dummy = sbase_half + (uint32_t)N;
     constexpr uint32_t kWantNothing = 0xFFFFFFFFu;        // no sequence number matches: the list is exhausted
     // The loop body is branch-free: "this lane holds no op" is an op that can never run (duration
-    // 0xFFFF, flagged idle) and every trip stores x somewhere (the trash cell unless the op ran).
+    // 0xFFFF) and every trip stores x somewhere (the trash cell unless the op ran).
     const uint32_t trash = sbase_half + (uint32_t)N + 1u;
-    const uint32_t idle_w4 = trash | kOpIdle;
+    bool idle = true;
     uint32_t t = 0, want = has_ops ? 1u : kWantNothing, x_acc = 0;
-    uint32_t cw0 = dummy | (dummy << 16), cw1 = cw0, cw2 = 0, cw3 = kNotDone16, cw4 = idle_w4;
+    // current op: predecessor half-addresses (two words), packed delays, duration, destination half-address
+    uint32_t ca = dummy | (dummy << 16), cb = ca, cd = 0, cdur = kNotDone16, cdst = trash;
     uint64_t prog_acc = 0;
     bool expired = true;
     for (uint32_t it = 0; it < p.spin_cap; it += 8) {
 #pragma unroll
       for (int sub = 0; sub < 8; ++sub) {
         // end times of the current op's predecessors (the critical reads go first)
-        const uint32_t e0 = cells[cw0 & 0xFFFFu], e1 = cells[cw0 >> 16];
-        const uint32_t e2 = cells[cw1 & 0xFFFFu], e3 = cells[cw1 >> 16];
+        const uint32_t e0 = cells[ca & 0xFFFFu], e1 = cells[ca >> 16], e2 = cells[cb & 0xFFFFu];
+        const uint32_t e3 = (PREDS == 4) ? (uint32_t)cells[cb >> 16] : 0u;
         // next op of this lane, read speculatively every trip (tagged word first)
         lds_byte_t *const sp = ring_lane + ((t & (uint32_t)(RING - 1)) << 8);
-        const uint32_t r4 = *(lds_vu32_t *)(sp + 4 * kPlaneBytes);
+        const uint32_t rt = *(lds_vu32_t *)(sp + Fmt::kTagWord * kPlaneBytes);
         const uint32_t r0 = *(lds_vu32_t *)(sp);
         const uint32_t r1 = *(lds_vu32_t *)(sp + kPlaneBytes);
         const uint32_t r2 = *(lds_vu32_t *)(sp + 2 * kPlaneBytes);
-        const uint32_t r3 = *(lds_vu32_t *)(sp + 3 * kPlaneBytes);
-        uint32_t x = max(max(x_acc, e0 + (cw2 & 0xFFu)), e1 + ((cw2 >> 8) & 0xFFu));
-        x = max(max(x, e2 + ((cw2 >> 16) & 0xFFu)), e3 + (cw2 >> 24));
-        x += cw3;
+        const uint32_t r3 = (PREDS == 4) ? (uint32_t) * (lds_vu32_t *)(sp + 3 * kPlaneBytes) : 0u;
+        uint32_t x = max(max(x_acc, e0 + (cd & 0xFFu)), e1 + ((cd >> 8) & 0xFFu));
+        x = max(x, e2 + ((cd >> 16) & 0xFFu));
+        if (PREDS == 4) x = max(x, e3 + (cd >> 24));
+        x += cdur;
         const bool ready = x < kNotDone16;                  // every predecessor ended, no 16-bit overflow, not idle
         x_acc = ready ? x : x_acc;                          // the machine is busy until x (chain edge, eq. (7))
-        cells[ready ? (cw4 & 0xFFFFu) : trash] = (uint16_t)x;
-        const bool idle = (cw4 & kOpIdle) != 0;
-        const bool take = (ready || idle) && ((r4 >> kOpSeqShift) == want);
+        cells[ready ? cdst : trash] = (uint16_t)x;
+        const bool take = (ready || idle) && ((rt >> Fmt::kSeqShift) == want);
         prog_acc |= __ballot(ready || take);                // an op taken now has not been tested yet
-        cw0 = take ? r0 : cw0;
-        cw1 = take ? r1 : cw1;
-        cw2 = take ? r2 : cw2;
-        cw3 = take ? r3 : (ready ? kNotDone16 : cw3);
-        cw4 = take ? (r4 & ~kOpIdle) : (ready ? idle_w4 : cw4);
+        idle = take ? false : (ready || idle);
+        ca = take ? r0 : ca;
+        if (PREDS == 4) {
+          cb = take ? r1 : cb;
+          cd = take ? r2 : cd;
+          cdur = take ? r3 : (ready ? kNotDone16 : cdur);
+          cdst = take ? (rt & 0xFFFFu) : cdst;
+        } else {
+          cb = take ? (r1 & 0xFFFFu) : cb;                  // the upper half is the destination, not a predecessor
+          cd = take ? (rt & 0xFFFFFFu) : cd;
+          cdur = take ? r2 : (ready ? kNotDone16 : cdur);
+          cdst = take ? (r1 >> 16) : cdst;
+        }
         t += take ? 1u : 0u;
-        want = take ? ((r4 & kOpLast) ? kWantNothing : ((t + 1) & kOpSeqMask)) : want;
+        want = take ? ((rt & Fmt::kLast) ? kWantNothing : ((t + 1) & Fmt::kSeqMask)) : want;
         *tail_p = t;
       }
-      const bool have_cur = (cw4 & kOpIdle) == 0;
-      const bool fin = (want == kWantNothing) && !have_cur;
+      const bool fin = (want == kWantNothing) && idle;
       if (__ballot(!fin) == 0) { expired = false; break; }
-      const uint64_t hold = __ballot(have_cur || fin);
+      const uint64_t hold = __ballot(!idle || fin);
       if (!fin && (prog_acc & segmask) == 0 && (hold & segmask) == segmask) {
         // every unfinished machine of this candidate holds an op and none could run for a whole
         // window: deadlock, i.e. a cycle of the combined graph (or a 16-bit overflow when optimistic)
         stalled = true;
         want = kWantNothing;
-        cw3 = kNotDone16;
-        cw4 = idle_w4;
+        idle = true;
+        cdur = kNotDone16;
         *abort_p = 1;
       }
+      if (prog_acc == 0) __builtin_amdgcn_s_sleep(4);       // nothing could run: leave the issue slots to the feeders
       prog_acc = 0;
     }
     if (expired) {                                          // bounded wait ran out: report, release the feeder
-      const bool fin = (want == kWantNothing) && (cw4 & kOpIdle) != 0;
+      const bool fin = (want == kWantNothing) && idle;
       if (!fin) { flagw[g] = kBitInternal; *abort_p = 1; }
     }
     acc = (int32_t)x_acc;
@@ -337,6 +357,7 @@ __global__ __launch_bounds__(kThreads) void relax_ring_kernel(RingParams p) {
     //   trip t+2  channel delays read from LDS, op packed and written to the ring
     // The loop is unrolled by three so that the pipeline registers rotate by renaming, not by moves.
     const int f = wave - 1;
+    __builtin_amdgcn_s_setprio(2);                          // the relaxer only polls; feeding must not wait behind it
     lds_cu8_t *const pib = (lds_cu8_t *)(ldsb + o.o_pi + g * o.pi_stride);
     lds_cu8_t *const commr = (lds_cu8_t *)(ldsb + o.o_comm) + j;
     lds_byte_t *const ring_lane = ldsb + o.o_ring + (uint32_t)lane * 4u;
@@ -347,6 +368,7 @@ __global__ __launch_bounds__(kThreads) void relax_ring_kernel(RingParams p) {
     const uint32_t trash = sbase_half + (uint32_t)N + 1u;
     const uint32_t vbits = (uint32_t)p.id_bits, vmask = (1u << vbits) - 1u;
     const uint32_t n_plane = (uint32_t)p.rec_plane;
+    const uint32_t lps = (uint32_t)p.log_pseg;
     const int k0 = has_ops ? offw[ql] : 0;
     const int klast = has_ops ? k0 + cntw[ql] - 1 : 0;      // list position of the lane's last node
     bool stream_end = !has_ops, pending = false;
@@ -389,7 +411,8 @@ __global__ __launch_bounds__(kThreads) void relax_ring_kernel(RingParams p) {
         Entry &e1 = E[(s + 2) % 3];       // admitted one trip ago
         Entry &e2 = E[(s + 1) % 3];       // admitted two trips ago
         // (A) channel delays of e2 (its placement bytes were read one trip ago)
-        const uint32_t d0 = commr[e2.q0 << 6], d1 = commr[e2.q1 << 6], d2 = commr[e2.q2 << 6], d3 = commr[e2.q3 << 6];
+        const uint32_t d0 = commr[e2.q0 << lps], d1 = commr[e2.q1 << lps], d2 = commr[e2.q2 << lps];
+        const uint32_t d3 = (PREDS == 4) ? (uint32_t)commr[e2.q3 << lps] : 0u;
         // (1) move the cursor past the part admitted in the previous trip and the other feeders' parts
         if (pending) {
 #pragma unroll
@@ -409,18 +432,25 @@ __global__ __launch_bounds__(kThreads) void relax_ring_kernel(RingParams p) {
         admitted += pending ? 1u : 0u;
         // (B) placement bytes of e1's predecessors (its record was requested one trip ago)
         e1.q0 = pib[e1.rec.x & 0xFFFFu]; e1.q1 = pib[e1.rec.x >> 16];
-        e1.q2 = pib[e1.rec.y & 0xFFFFu]; e1.q3 = pib[e1.rec.y >> 16];
+        e1.q2 = pib[e1.rec.y & 0xFFFFu];
+        if (PREDS == 4) e1.q3 = pib[e1.rec.y >> 16];
         // (D) pack e2 and publish it
         if (e2.fl & 1u) {
           const bool more = (e2.rec.z >> 31) != 0;
-          const uint32_t w4 = (more ? trash : sbase_half + (e2.rec.w >> 16)) | ((e2.fl & 2u) ? kOpLast : 0u) |
-                              (((wseq + 1) & kOpSeqMask) << kOpSeqShift);
+          const uint32_t dst = more ? trash : sbase_half + (e2.rec.w >> 16);
+          const uint32_t tagbits = ((e2.fl & 2u) ? Fmt::kLast : 0u) | (((wseq + 1) & Fmt::kSeqMask) << Fmt::kSeqShift);
           lds_byte_t *const sp = ring_lane + ((wseq & (uint32_t)(RING - 1)) << 8);
           *(lds_vu32_t *)(sp) = e2.rec.x + base2;
-          *(lds_vu32_t *)(sp + kPlaneBytes) = e2.rec.y + base2;
-          *(lds_vu32_t *)(sp + 2 * kPlaneBytes) = d0 | (d1 << 8) | (d2 << 16) | (d3 << 24);
-          *(lds_vu32_t *)(sp + 3 * kPlaneBytes) = e2.rec.z & 0x3FFFFFFFu;
-          *(lds_vu32_t *)(sp + 4 * kPlaneBytes) = w4;
+          if (PREDS == 4) {
+            *(lds_vu32_t *)(sp + kPlaneBytes) = e2.rec.y + base2;
+            *(lds_vu32_t *)(sp + 2 * kPlaneBytes) = d0 | (d1 << 8) | (d2 << 16) | (d3 << 24);
+            *(lds_vu32_t *)(sp + 3 * kPlaneBytes) = e2.rec.z & 0x3FFFFFFFu;
+            *(lds_vu32_t *)(sp + 4 * kPlaneBytes) = dst | tagbits;
+          } else {
+            *(lds_vu32_t *)(sp + kPlaneBytes) = ((e2.rec.y & 0xFFFFu) + sbase_half) | (dst << 16);
+            *(lds_vu32_t *)(sp + 2 * kPlaneBytes) = e2.rec.z & 0x3FFFFFFFu;
+            *(lds_vu32_t *)(sp + 3 * kPlaneBytes) = d0 | (d1 << 8) | (d2 << 16) | tagbits;
+          }
           wseq += kFeeders;
           ++written;
         }
