@@ -22,6 +22,37 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0     # MI355X published HBM3E bandwidth
 
 
+def kernel_sources_hash() -> str:
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2503_09357_amd", "csrc", "*"))):
+        if f.endswith((".h", ".hip")):
+            h.update(open(f, "rb").read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(cfg: int):
+    """HBM bytes per launch from the committed rocprofv3 counter summary, or None when the kernel
+    sources changed since the counters were taken (or no summary exists for this workload)."""
+    path = os.path.join(ROOT, "profiles", "relax_ring_kernel_cfg%d_counters.md" % cfg)
+    try:
+        text = open(path).read()
+    except OSError:
+        return None
+    vals = {}
+    for line in text.splitlines():
+        if ":" in line and line.split(":")[0] in ("traffic_bytes_per_launch", "csrc_sha256_16"):
+            k, v = line.split(":", 1)
+            vals[k.strip()] = v.strip()
+    if vals.get("csrc_sha256_16") != kernel_sources_hash():
+        return None
+    try:
+        return int(vals["traffic_bytes_per_launch"])
+    except (KeyError, ValueError):
+        return None
+
+
 def algorithmic_bytes(w) -> int:
     """Bytes the method must move per evaluate: per candidate placement+rank in (8 N) and
     makespan+bubble+flags+peak_mem out (16 + 8 P); the shared problem is read once."""
@@ -38,6 +69,9 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=4, help="workload 1..5 (default 4: MoE operator DAG)")
     ap.add_argument("--layout", type=int, default=0, help="0 candidate-major, 1 candidate-minor")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-workloads", action="store_true", help="skip the short runs of the other four workloads")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one 256 MiB elementwise copy kernel (known traffic, for counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this path runs on one GPU only (simulated machines are data inside the model; "
@@ -63,6 +97,13 @@ def main() -> int:
     tp, tr = torch.from_numpy(pl).to(dev), torch.from_numpy(rk).to(dev)
     out = ev.alloc_outputs(w.n_cand)
     torch.cuda.synchronize()
+
+    if args.copy_calibration:
+        src = torch.empty(64 * 1024 * 1024, dtype=torch.int32, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        torch.add(src, 1, out=dst)          # one elementwise kernel: reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         ev.evaluate(tp, tr, out)
@@ -103,7 +144,7 @@ def main() -> int:
         "edge_relax_per_s": cand_per_s * (w.n_edges + w.n_nodes - w.n_devices),
         "ms_kernel_hip_events": ms_kernel,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(args.config),
                      "algorithmic_bytes_per_launch": abytes},
         "workload_gen_s": t_gen,
     }
@@ -134,6 +175,29 @@ def main() -> int:
             print(json.dumps(result))
             return 1
     ev.close()
+    del tp, tr, out
+
+    if not args.no_other_workloads:
+        # short, untimed-by-the-driver runs of the other workloads (parity for them is in tests/)
+        others = []
+        for cfg in (1, 2, 3, 4, 5):
+            if cfg == args.config:
+                continue
+            w2 = W.gen_config(cfg)
+            ev2 = ds.Evaluator.for_workload(w2)
+            p2, r2 = torch.from_numpy(w2.placement).to(dev), torch.from_numpy(w2.rank).to(dev)
+            o2 = ev2.alloc_outputs(w2.n_cand)
+            ev2.evaluate(p2, r2, o2)
+            torch.cuda.synchronize()
+            ms2 = ev2.time_evaluate(p2, r2, o2, reps=5)
+            ab2 = algorithmic_bytes(w2)
+            others.append({"workload": w2.name, "cfg": cfg, "ms_kernel_hip_events": ms2,
+                           "candidates_per_s": w2.n_cand / (ms2 * 1e-3),
+                           "node_relax_per_s": w2.n_cand * w2.n_nodes / (ms2 * 1e-3),
+                           "roofline_frac": ab2 / (ms2 * 1e-3) / 1e9 / HBM_PEAK_GBS, "kernel": ev2.info()})
+            ev2.close()
+            del p2, r2, o2, w2
+        result["other_workloads"] = others
     print(json.dumps(result))
     return 0
 

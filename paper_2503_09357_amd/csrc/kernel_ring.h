@@ -286,19 +286,13 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
     uint32_t ca = dummy | (dummy << 16), cb = ca, cd = 0, cdur = kNotDone16, cdst = trash;
     uint64_t prog_acc = 0;
     bool expired = true;
+    uint32_t rt = 0, r0 = 0, r1 = 0, r2 = 0, r3 = 0;         // ring slot t as read at the end of the previous trip
     for (uint32_t it = 0; it < p.spin_cap; it += 8) {
 #pragma unroll
       for (int sub = 0; sub < 8; ++sub) {
         // end times of the current op's predecessors (the critical reads go first)
         const uint32_t e0 = cells[ca & 0xFFFFu], e1 = cells[ca >> 16], e2 = cells[cb & 0xFFFFu];
         const uint32_t e3 = (PREDS == 4) ? (uint32_t)cells[cb >> 16] : 0u;
-        // next op of this lane, read speculatively every trip (tagged word first)
-        lds_byte_t *const sp = ring_lane + ((t & (uint32_t)(RING - 1)) << 8);
-        const uint32_t rt = *(lds_vu32_t *)(sp + Fmt::kTagWord * kPlaneBytes);
-        const uint32_t r0 = *(lds_vu32_t *)(sp);
-        const uint32_t r1 = *(lds_vu32_t *)(sp + kPlaneBytes);
-        const uint32_t r2 = *(lds_vu32_t *)(sp + 2 * kPlaneBytes);
-        const uint32_t r3 = (PREDS == 4) ? (uint32_t) * (lds_vu32_t *)(sp + 3 * kPlaneBytes) : 0u;
         uint32_t x = max(max(x_acc, e0 + (cd & 0xFFu)), e1 + ((cd >> 8) & 0xFFu));
         x = max(x, e2 + ((cd >> 16) & 0xFFu));
         if (PREDS == 4) x = max(x, e3 + (cd >> 24));
@@ -324,6 +318,16 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
         t += take ? 1u : 0u;
         want = take ? ((rt & Fmt::kLast) ? kWantNothing : ((t + 1) & Fmt::kSeqMask)) : want;
         *tail_p = t;
+        // next op of this lane (tagged word first), read now and looked at in the next trip: its LDS
+        // latency hides behind the next trip's end-time reads
+        {
+          lds_byte_t *const sp = ring_lane + ((t & (uint32_t)(RING - 1)) << 8);
+          rt = *(lds_vu32_t *)(sp + Fmt::kTagWord * kPlaneBytes);
+          r0 = *(lds_vu32_t *)(sp);
+          r1 = *(lds_vu32_t *)(sp + kPlaneBytes);
+          r2 = *(lds_vu32_t *)(sp + 2 * kPlaneBytes);
+          if (PREDS == 4) r3 = *(lds_vu32_t *)(sp + 3 * kPlaneBytes);
+        }
       }
       const bool fin = (want == kWantNothing) && idle;
       if (__ballot(!fin) == 0) { expired = false; break; }

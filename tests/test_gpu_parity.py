@@ -191,3 +191,68 @@ def test_configs_full_size(gpu_lib, cfg):
         marked = np.zeros(w.n_cand, bool)
         marked[w.meta["cyclic"]] = True
         assert ((f == 1) == marked).all()
+
+
+# --------------------------------------------------------------------------- kernel variants and the 16-bit fallback
+
+def _with_env(env, fn):
+    old = {k: os.environ.get(k) for k in env}
+    os.environ.update({k: str(v) for k, v in env.items()})
+    try:
+        return fn()
+    finally:
+        for k, v in old.items():
+            if v is None:
+                os.environ.pop(k, None)
+            else:
+                os.environ[k] = v
+
+
+@pytest.mark.parametrize("env", [
+    {"DAGSCHED_FORCE_GENERAL": 1},
+    {"DAGSCHED_RING_PREDS": 4, "DAGSCHED_RING_FEEDERS": 1, "DAGSCHED_RING_SLOTS": 4},
+    {"DAGSCHED_RING_PREDS": 4, "DAGSCHED_RING_FEEDERS": 2, "DAGSCHED_RING_SLOTS": 8},
+    {"DAGSCHED_RING_PREDS": 3, "DAGSCHED_RING_FEEDERS": 1, "DAGSCHED_RING_SLOTS": 8},
+    {"DAGSCHED_RING_PREDS": 3, "DAGSCHED_RING_FEEDERS": 2, "DAGSCHED_RING_SLOTS": 4, "DAGSCHED_RING_G": 1},
+])
+def test_every_kernel_variant(gpu_lib, env):
+    """The tuning knobs only pick among kernel instantiations; each one must give the same bits."""
+    rng = np.random.default_rng(321)
+    cases = [W.gen_config(1, n_cand=100), W.gen_config(2, n_cand=150), W.gen_config(4, n_cand=9),
+             W.random_instance(rng, 333, 7, 41, max_fanin=6, frac_arbitrary=0.3, frac_bad=0.2)]
+    for w in cases:
+        (z, b, pk, f), info = _with_env(env, lambda: assert_parity(gpu_lib, w))
+        if "DAGSCHED_FORCE_GENERAL" in env:
+            assert info["state_bits"] == 32
+        else:
+            assert info["state_bits"] == 16 and info["preds_per_op"] == env["DAGSCHED_RING_PREDS"]
+            assert info["feeders"] == env["DAGSCHED_RING_FEEDERS"] and info["ring_slots"] == env["DAGSCHED_RING_SLOTS"]
+
+
+def test_sixteen_bit_overflow_falls_back(gpu_lib):
+    """End times that leave the 16-bit range: the ring kernel must hand exactly those candidates to the
+    int32 kernel.  A long chain on few machines whose makespan straddles 65535 for different orders."""
+    rng = np.random.default_rng(77)
+    n, p = 600, 3
+    rp, ci = W.random_dag(rng, n, 2, window=30)
+    dur = rng.integers(60, 160, n).astype(np.int32)          # sum ~ 66000, so z crosses 65535 with few machines
+    comm = rng.integers(1, 200, (p, p)).astype(np.int32)
+    mem = rng.integers(-9, 10, n).astype(np.int64)
+    pl, rk = W.list_schedules(rp, ci, p, 300, 4242)
+    pl1, rk1 = W.list_schedules(rp, ci, 1, 100, 99)          # every third candidate runs everything on machine 0
+    pl[::3], rk[::3] = pl1, rk1
+    w = W.Workload("straddles 16 bits", p, rp, ci, dur, comm, mem, pl, rk)
+    (z, b, pk, f), info = assert_parity(gpu_lib, w)
+    assert info["state_bits"] == 16 and info["variant"] == 4        # optimistic ring kernel
+    assert (z[f == 0] > 65535).any() and (z[f == 0] < 65535).any()
+    # a common factor in every duration and delay is divided out before the 16-bit test
+    w2 = W.Workload("scaled by 1000", p, rp, ci, dur * 1000, comm * 1000, mem, pl, rk)
+    (z2, b2, pk2, f2), info2 = assert_parity(gpu_lib, w2)
+    assert info2["time_scale"] == 1000 and (z2[f == 0] == 1000 * z[f == 0].astype(np.int64)).all()
+
+
+def test_large_delays_use_the_general_kernel(gpu_lib):
+    rng = np.random.default_rng(5)
+    w = W.random_instance(rng, 120, 5, 30, max_comm=4000, max_dur=977)
+    (z, b, pk, f), info = assert_parity(gpu_lib, w)
+    assert info["state_bits"] in (16, 32)
