@@ -181,6 +181,7 @@ LdsLayout ring_layout(int N, int P, int G, int ring, int op_words) {
   at = align_up(at, 16);
   o.o_ring = at;  at += (uint32_t)op_words * (uint32_t)ring * kWave * 4u;
   o.o_tail = at;  at += kWave * 4u;
+  o.o_total = at; at += kWave * 4u;
   at = align_up(at, 8);
   o.o_peak = at;  at += kWave * 8u;
   o.o_cnt = at;   at += kWave * 4u;
@@ -293,8 +294,9 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
   plan.comm_scaled.resize((size_t)P * P);
   for (int i = 0; i < P * P; ++i) plan.comm_scaled[i] = (i / P != i % P) ? (int32_t)(d->comm[i] / g) : 0;
 
-  // shape: most candidates resident per CU, then fewer wavefronts, then a deeper ring; a second
-  // feeder wavefront when the CU would otherwise hold few wavefronts (LDS-bound configurations)
+  // shape: most candidates resident per CU, where a four-slot ring counts 0.7 (measured: the relaxer's
+  // hot lanes outrun a four-deep ring), then more candidates per wavefront; two feeder wavefronts unless
+  // the CU would then hold more than 24 wavefronts
   const int force_g = env_int("DAGSCHED_RING_G", 0), force_ring = env_int("DAGSCHED_RING_SLOTS", 0);
   const int force_feeders = env_int("DAGSCHED_RING_FEEDERS", 0);
   const int op_words = PR == 4 ? 5 : 4;
@@ -308,23 +310,31 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
       if ((uint64_t)G * (o.s_stride >> 1) > 65536u) continue;   // half-addresses must fit 16 bits
       const int wgs = std::min(8, lds_max / (int)align_up(o.total, 512));
       if (wgs < 1) continue;
-      const int score = wgs * G * 64 + G * 2 + (ring == 8 ? 1 : 0);
+      const int score = wgs * G * (ring == 8 ? 100 : 70) + G;
       if (score > best_score) { best_score = score; best_wgs = wgs; plan.G = G; plan.ring = ring; plan.lds = o; }
     }
   }
-  plan.feeders = force_feeders ? force_feeders : (best_wgs * 4 <= 12 ? 2 : 1);
+  plan.feeders = force_feeders ? force_feeders : (best_wgs * 4 <= 24 ? 2 : 1);
   if (plan.feeders != 1 && plan.feeders != 2) return plan;
   plan.ok = best_score >= 0;
   return plan;
 }
 
 using RingKernel = void (*)(RingParams);
+template <int HALF>
+RingKernel ring_kernel_pick(int r8, int p4, int f2) {
+  static const RingKernel table[2][2][2] = {
+      {{relax_ring_kernel<4, 3, 1, HALF>, relax_ring_kernel<4, 3, 2, HALF>},
+       {relax_ring_kernel<4, 4, 1, HALF>, relax_ring_kernel<4, 4, 2, HALF>}},
+      {{relax_ring_kernel<8, 3, 1, HALF>, relax_ring_kernel<8, 3, 2, HALF>},
+       {relax_ring_kernel<8, 4, 1, HALF>, relax_ring_kernel<8, 4, 2, HALF>}}};
+  return table[r8][p4][f2];
+}
 RingKernel ring_kernel_for(const dagsched *h) {
   const int r8 = h->ring_slots == 8, p4 = h->ring_preds == 4, f2 = h->ring_feeders == 2;
-  static const RingKernel table[2][2][2] = {
-      {{relax_ring_kernel<4, 3, 1>, relax_ring_kernel<4, 3, 2>}, {relax_ring_kernel<4, 4, 1>, relax_ring_kernel<4, 4, 2>}},
-      {{relax_ring_kernel<8, 3, 1>, relax_ring_kernel<8, 3, 2>}, {relax_ring_kernel<8, 4, 1>, relax_ring_kernel<8, 4, 2>}}};
-  return table[r8][p4][f2];
+  // byte addresses when the workgroup's end-time arrays fit 64 KB, half addresses otherwise
+  const bool half = (uint64_t)h->ring_G * h->lds.s_stride > 65536u;
+  return half ? ring_kernel_pick<1>(r8, p4, f2) : ring_kernel_pick<0>(r8, p4, f2);
 }
 
 OutPtrs make_out(const dagsched *h, int32_t n_cand, int32_t *makespan, int64_t *bubble, int64_t *peak_mem,

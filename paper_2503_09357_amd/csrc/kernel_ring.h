@@ -45,26 +45,28 @@ typedef DAGSCHED_LDS volatile uint16_t lds_vu16_t;
 typedef DAGSCHED_LDS volatile int32_t lds_vi32_t;
 typedef DAGSCHED_LDS const uint8_t lds_cu8_t;
 
-// Op layouts.  "Half-address" (ha) = LDS byte address / 2 of a 16-bit end-time cell; the end-time arrays
-// start at LDS offset 0, so every half-address fits 16 bits.  Unused predecessor slots name the
-// candidate's dummy cell (end time 0, delay 0); a part that does not end its operation names the
-// candidate's trash cell instead of v.  seq = (index of the op in its lane + 1) mod (SeqMask + 1).
+// Op layouts.  ha(x) is the 16-bit address of the end-time cell of x: its LDS byte address when the
+// end-time arrays of the workgroup fit 64 KB (template HALF = 0), else the byte address / 2 (HALF = 1);
+// the arrays start at LDS offset 0.  Unused predecessor slots name the candidate's dummy cell (end time
+// 0, delay 0); a part that does not end its operation names the candidate's trash cell instead of v.
+// seq = index of the op in its lane, modulo (SeqMask + 1); ring tags start as all ones, which no op
+// matches before its slot has been rewritten.
 //   PREDS = 4, five dwords                           PREDS = 3, four dwords
 //     w0 = ha(pred0) | ha(pred1) << 16                 w0 = ha(pred0) | ha(pred1) << 16
 //     w1 = ha(pred2) | ha(pred3) << 16                 w1 = ha(pred2) | ha(v) << 16
 //     w2 = delta0 | delta1 << 8 | delta2 << 16         w2 = duration
 //          | delta3 << 24                              w3 = delta0 | delta1 << 8 | delta2 << 16
-//     w3 = duration                                         | LAST << 24 | seq << 25        (tag word)
-//     w4 = ha(v) | LAST << 17 | seq << 18  (tag word)
+//     w3 = duration                                         | seq << 24                    (tag word)
+//     w4 = ha(v) | seq << 16               (tag word)
 // The duration is 0 for every part but the last of an operation.
 template <int PREDS> struct OpFormat;
 template <> struct OpFormat<4> {
-  static constexpr int kWords = 5, kTagWord = 4, kSeqShift = 18;
-  static constexpr uint32_t kLast = 1u << 17, kSeqMask = 0x3FFFu;
+  static constexpr int kWords = 5, kTagWord = 4, kSeqShift = 16;
+  static constexpr uint32_t kSeqMask = 0xFFFFu;
 };
 template <> struct OpFormat<3> {
-  static constexpr int kWords = 4, kTagWord = 3, kSeqShift = 25;
-  static constexpr uint32_t kLast = 1u << 24, kSeqMask = 0x7Fu;
+  static constexpr int kWords = 4, kTagWord = 3, kSeqShift = 24;
+  static constexpr uint32_t kSeqMask = 0xFFu;
 };
 constexpr uint32_t kNotDone16 = 0xFFFFu;
 constexpr int ring_threads(int feeders) { return (2 + feeders) * kWave; }   // relaxer, feeders, accountant
@@ -75,7 +77,7 @@ constexpr int ring_threads(int feeders) { return (2 + feeders) * kWave; }   // r
 //   x = u0 | u1 << 16, y = u2 | u3 << 16, z = dur (30 bits) | first_part << 30 | has_more << 31, w = v << 16
 struct LdsLayout {
   uint32_t s_stride, pi_stride;                       // bytes per candidate; the state array starts at 0
-  uint32_t o_pi, o_ring, o_tail, o_peak, o_cnt, o_off, o_flag, o_abort, o_comm, total;
+  uint32_t o_pi, o_ring, o_tail, o_total, o_peak, o_cnt, o_off, o_flag, o_abort, o_comm, total;
 };
 
 struct RingParams {
@@ -99,7 +101,7 @@ struct RingParams {
 };
 
 // FEEDERS feeder wavefronts share a lane's stream: feeder f owns the parts with (seq - 1) % FEEDERS == f.
-template <int RING, int PREDS, int FEEDERS>
+template <int RING, int PREDS, int FEEDERS, int HALF>
 __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingParams p) {
   using Fmt = OpFormat<PREDS>;
   constexpr int kOpWords = Fmt::kWords;
@@ -120,6 +122,7 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
 
   uint32_t *ringw = (uint32_t *)(lds + o.o_ring);
   uint32_t *tailw = (uint32_t *)(lds + o.o_tail);          // [64] ops the relaxer has taken
+  uint32_t *totalw = (uint32_t *)(lds + o.o_total);        // [64] ops in the lane's stream, once a feeder knows
   int64_t *peakw = (int64_t *)(lds + o.o_peak);            // [64]
   int32_t *cntw = (int32_t *)(lds + o.o_cnt);              // [64] operations per (candidate, machine)
   int32_t *offw = (int32_t *)(lds + o.o_off);              // [64] start of the machine inside the list
@@ -128,8 +131,8 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
   uint8_t *commb = (uint8_t *)(lds + o.o_comm);            // [(P+1)][Pseg], diagonal and dummy row zero
 
   // ---------------------------------------------------------------- ingest (both wavefronts)
-  if (tid < kWave) { cntw[tid] = 0; tailw[tid] = 0; flagw[tid] = 0; abortw[tid] = 0; peakw[tid] = 0; }
-  for (int i = tid; i < kOpWords * RING * kWave; i += kThreads) ringw[i] = 0;
+  if (tid < kWave) { cntw[tid] = 0; tailw[tid] = 0; totalw[tid] = 0xFFFFFFFFu; flagw[tid] = 0; abortw[tid] = 0; peakw[tid] = 0; }
+  for (int i = tid; i < kOpWords * RING * kWave; i += kThreads) ringw[i] = 0xFFFFFFFFu;
   for (int i = tid; i < (P + 1) * Pseg; i += kThreads) {    // rows of Pseg bytes: [source machine][destination]
     const int a = i >> p.log_pseg, b = i & (Pseg - 1);
     commb[i] = (a < P && b < P && a != b) ? (uint8_t)p.comm[a * P + b] : (uint8_t)0;
@@ -263,44 +266,44 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
   const int g = ql >> p.log_pseg, j = ql & (Pseg - 1);
   const bool cand_ok = lane_on && g < ng && flagw[g] == 0;
   const bool has_ops = cand_ok && j < P && cntw[ql] > 0;
-  const uint32_t sbase_half = (uint32_t)g * (o.s_stride >> 1);   // half-address of this candidate's cell 0
+  const uint32_t sbase = (uint32_t)g * (o.s_stride >> HALF);   // 16-bit address of this candidate's cell 0
 
   int32_t acc = 0;
   bool stalled = false;
 
   if (wave == 0) {
     // ------------------------------------------------------------ relaxer
-    lds_vu16_t *const cells = (lds_vu16_t *)ldsb;                           // indexed by half-address
     lds_byte_t *const ring_lane = ldsb + o.o_ring + (uint32_t)lane * 4u;    // this lane's column of the ring
     lds_vu32_t *const tail_p = (lds_vu32_t *)(ldsb + o.o_tail) + lane;
+    lds_vu32_t *const total_p = (lds_vu32_t *)(ldsb + o.o_total) + lane;
     lds_vi32_t *const abort_p = (lds_vi32_t *)(ldsb + o.o_abort) + g;
     const uint64_t segmask = ((Pseg == kWave) ? ~0ull : ((1ull << Pseg) - 1ull)) << (g * Pseg);
-    const uint32_t dummy = sbase_half + (uint32_t)N;
-    constexpr uint32_t kWantNothing = 0xFFFFFFFFu;        // no sequence number matches: the list is exhausted
+    auto cell = [&](uint32_t a16) -> lds_vu16_t & { return *(lds_vu16_t *)(ldsb + (a16 << HALF)); };
+    const uint32_t dummy = sbase + ((uint32_t)N << (1 - HALF));
     // The loop body is branch-free: "this lane holds no op" is an op that can never run (duration
     // 0xFFFF) and every trip stores x somewhere (the trash cell unless the op ran).
-    const uint32_t trash = sbase_half + (uint32_t)N + 1u;
-    bool idle = true;
-    uint32_t t = 0, want = has_ops ? 1u : kWantNothing, x_acc = 0;
-    // current op: predecessor half-addresses (two words), packed delays, duration, destination half-address
+    const uint32_t trash = sbase + (((uint32_t)N + 1u) << (1 - HALF));
+    bool idle = true, dead = !has_ops;
+    uint32_t t = 0, x_acc = 0;
+    // current op: predecessor addresses (two words), packed delays, duration, destination address
     uint32_t ca = dummy | (dummy << 16), cb = ca, cd = 0, cdur = kNotDone16, cdst = trash;
     uint64_t prog_acc = 0;
     bool expired = true;
-    uint32_t rt = 0, r0 = 0, r1 = 0, r2 = 0, r3 = 0;         // ring slot t as read at the end of the previous trip
+    uint32_t rt = 0xFFFFFFFFu, r0 = 0, r1 = 0, r2 = 0, r3 = 0;   // ring slot t as read at the end of the previous trip
     for (uint32_t it = 0; it < p.spin_cap; it += 8) {
 #pragma unroll
       for (int sub = 0; sub < 8; ++sub) {
         // end times of the current op's predecessors (the critical reads go first)
-        const uint32_t e0 = cells[ca & 0xFFFFu], e1 = cells[ca >> 16], e2 = cells[cb & 0xFFFFu];
-        const uint32_t e3 = (PREDS == 4) ? (uint32_t)cells[cb >> 16] : 0u;
+        const uint32_t e0 = cell(ca & 0xFFFFu), e1 = cell(ca >> 16), e2 = cell(cb & 0xFFFFu);
+        const uint32_t e3 = (PREDS == 4) ? (uint32_t)cell(cb >> 16) : 0u;
         uint32_t x = max(max(x_acc, e0 + (cd & 0xFFu)), e1 + ((cd >> 8) & 0xFFu));
         x = max(x, e2 + ((cd >> 16) & 0xFFu));
         if (PREDS == 4) x = max(x, e3 + (cd >> 24));
         x += cdur;
         const bool ready = x < kNotDone16;                  // every predecessor ended, no 16-bit overflow, not idle
         x_acc = ready ? x : x_acc;                          // the machine is busy until x (chain edge, eq. (7))
-        cells[ready ? cdst : trash] = (uint16_t)x;
-        const bool take = (ready || idle) && ((rt >> Fmt::kSeqShift) == want);
+        cell(ready ? cdst : trash) = (uint16_t)x;
+        const bool take = (ready || idle) && ((rt >> Fmt::kSeqShift) == (t & Fmt::kSeqMask));
         prog_acc |= __ballot(ready || take);                // an op taken now has not been tested yet
         idle = take ? false : (ready || idle);
         ca = take ? r0 : ca;
@@ -316,7 +319,6 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
           cdst = take ? (r1 >> 16) : cdst;
         }
         t += take ? 1u : 0u;
-        want = take ? ((rt & Fmt::kLast) ? kWantNothing : ((t + 1) & Fmt::kSeqMask)) : want;
         *tail_p = t;
         // next op of this lane (tagged word first), read now and looked at in the next trip: its LDS
         // latency hides behind the next trip's end-time reads
@@ -329,23 +331,21 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
           if (PREDS == 4) r3 = *(lds_vu32_t *)(sp + 3 * kPlaneBytes);
         }
       }
-      const bool fin = (want == kWantNothing) && idle;
+      const bool fin = dead || (idle && t == *total_p);
       if (__ballot(!fin) == 0) { expired = false; break; }
       const uint64_t hold = __ballot(!idle || fin);
       if (!fin && (prog_acc & segmask) == 0 && (hold & segmask) == segmask) {
         // every unfinished machine of this candidate holds an op and none could run for a whole
         // window: deadlock, i.e. a cycle of the combined graph (or a 16-bit overflow when optimistic)
         stalled = true;
-        want = kWantNothing;
-        idle = true;
-        cdur = kNotDone16;
+        dead = true;
         *abort_p = 1;
       }
       if (prog_acc == 0) __builtin_amdgcn_s_sleep(4);       // nothing could run: leave the issue slots to the feeders
       prog_acc = 0;
     }
     if (expired) {                                          // bounded wait ran out: report, release the feeder
-      const bool fin = (want == kWantNothing) && idle;
+      const bool fin = dead || (idle && t == *total_p);
       if (!fin) { flagw[g] = kBitInternal; *abort_p = 1; }
     }
     acc = (int32_t)x_acc;
@@ -368,8 +368,9 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
     lds_vu32_t *const tail_p = (lds_vu32_t *)(ldsb + o.o_tail) + lane;
     lds_vi32_t *const abort_p = (lds_vi32_t *)(ldsb + o.o_abort) + g;
     const uint16_t *list = p.ws_list + (c0 + (cand_ok ? g : 0)) * p.list_stride;
-    const uint32_t base2 = sbase_half | (sbase_half << 16);
-    const uint32_t trash = sbase_half + (uint32_t)N + 1u;
+    lds_vu32_t *const total_p = (lds_vu32_t *)(ldsb + o.o_total) + lane;
+    const uint32_t base2 = sbase | (sbase << 16);
+    const uint32_t trash = sbase + (((uint32_t)N + 1u) << (1 - HALF));
     const uint32_t vbits = (uint32_t)p.id_bits, vmask = (1u << vbits) - 1u;
     const uint32_t n_plane = (uint32_t)p.rec_plane;
     const uint32_t lps = (uint32_t)p.log_pseg;
@@ -441,20 +442,22 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
         // (D) pack e2 and publish it
         if (e2.fl & 1u) {
           const bool more = (e2.rec.z >> 31) != 0;
-          const uint32_t dst = more ? trash : sbase_half + (e2.rec.w >> 16);
-          const uint32_t tagbits = ((e2.fl & 2u) ? Fmt::kLast : 0u) | (((wseq + 1) & Fmt::kSeqMask) << Fmt::kSeqShift);
+          const uint32_t dst = more ? trash : sbase + ((e2.rec.w >> 16) << (1 - HALF));
+          const uint32_t tagbits = (wseq & Fmt::kSeqMask) << Fmt::kSeqShift;
           lds_byte_t *const sp = ring_lane + ((wseq & (uint32_t)(RING - 1)) << 8);
-          *(lds_vu32_t *)(sp) = e2.rec.x + base2;
+          // node ids below 32768 whenever HALF == 0, so shifting both halves at once cannot carry over
+          *(lds_vu32_t *)(sp) = (e2.rec.x << (1 - HALF)) + base2;
           if (PREDS == 4) {
-            *(lds_vu32_t *)(sp + kPlaneBytes) = e2.rec.y + base2;
+            *(lds_vu32_t *)(sp + kPlaneBytes) = (e2.rec.y << (1 - HALF)) + base2;
             *(lds_vu32_t *)(sp + 2 * kPlaneBytes) = d0 | (d1 << 8) | (d2 << 16) | (d3 << 24);
             *(lds_vu32_t *)(sp + 3 * kPlaneBytes) = e2.rec.z & 0x3FFFFFFFu;
             *(lds_vu32_t *)(sp + 4 * kPlaneBytes) = dst | tagbits;
           } else {
-            *(lds_vu32_t *)(sp + kPlaneBytes) = ((e2.rec.y & 0xFFFFu) + sbase_half) | (dst << 16);
+            *(lds_vu32_t *)(sp + kPlaneBytes) = (((e2.rec.y & 0xFFFFu) << (1 - HALF)) + sbase) | (dst << 16);
             *(lds_vu32_t *)(sp + 2 * kPlaneBytes) = e2.rec.z & 0x3FFFFFFFu;
             *(lds_vu32_t *)(sp + 3 * kPlaneBytes) = d0 | (d1 << 8) | (d2 << 16) | tagbits;
           }
+          if (e2.fl & 2u) *total_p = wseq + 1;              // the lane's stream ends with this op
           wseq += kFeeders;
           ++written;
         }
