@@ -374,29 +374,26 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
     const uint32_t vbits = (uint32_t)p.id_bits, vmask = (1u << vbits) - 1u;
     const uint32_t n_plane = (uint32_t)p.rec_plane;
     const uint32_t lps = (uint32_t)p.log_pseg;
-    const int k0 = has_ops ? offw[ql] : 0;
-    const int klast = has_ops ? k0 + cntw[ql] - 1 : 0;      // list position of the lane's last node
-    bool stream_end = !has_ops, pending = false;
+    const uint32_t k0 = has_ops ? (uint32_t)offw[ql] : 1u;
+    const uint32_t klast = has_ops ? k0 + (uint32_t)cntw[ql] - 1u : 0u;   // list position of the lane's last node
+    bool pending = false;
     uint32_t admitted = 0, written = 0;
-    uint32_t aseq = (uint32_t)f;                            // (sequence number - 1) of the next part to admit
+    uint32_t aseq = (uint32_t)f;                            // index in the lane's stream of the next part to admit
     uint32_t wseq = (uint32_t)f;                            // ... of the next part to write
-    // cursor: the next part to admit is part `part` of node v (np parts) at list position k
-    int k = k0;
-    uint32_t w0 = has_ops ? (uint32_t)list[k0] : 0u;
-    uint32_t v = w0 & vmask, np = (w0 >> vbits) + 1u, part = 0;
-    uint32_t id1 = has_ops ? (uint32_t)list[min(k0 + 1, klast)] : 0u;
-    uint32_t id2 = has_ops ? (uint32_t)list[min(k0 + 2, klast)] : 0u;
-    // move the cursor one part ahead; returns true when it entered the next node
+    // cursor: the next part to admit is the record at `addr`; `rem` more parts of the same node follow;
+    // the node sits at list position k, and k > klast means the stream is exhausted
+    uint32_t k = k0;
+    const uint32_t w0 = has_ops ? (uint32_t)list[k0] : 0u;
+    uint32_t addr = w0 & vmask, rem = w0 >> vbits;
+    uint32_t id1 = has_ops ? (uint32_t)list[min(k0 + 1u, klast)] : 0u;
+    uint32_t id2 = has_ops ? (uint32_t)list[min(k0 + 2u, klast)] : 0u;
+    // move the cursor one part ahead; returns true when it entered the next node (or left the list)
     auto advance = [&](uint32_t next_id) -> bool {
-      const bool node_done = part + 1 == np;
-      const bool to_next = !stream_end && node_done && (k != klast);
-      const bool step = !stream_end && !node_done;
-      stream_end = stream_end || (node_done && k == klast);
-      part = to_next ? 0u : (step ? part + 1u : part);
-      v = to_next ? (next_id & vmask) : v;
-      np = to_next ? (next_id >> vbits) + 1u : np;
-      k += to_next ? 1 : 0;
-      return to_next;
+      const bool in_node = rem != 0;
+      addr = in_node ? addr + n_plane : (next_id & vmask);
+      rem = in_node ? rem - 1u : (next_id >> vbits);
+      k += in_node ? 0u : 1u;
+      return !in_node;
     };
     for (int i = 0; i < f; ++i) {                           // feeder f starts at its first own part
       const bool crossed = advance(id1);
@@ -408,8 +405,8 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
     for (int i = 0; i < 3; ++i) { E[i].rec = make_uint4(0, 0, 0, 0); E[i].q0 = E[i].q1 = E[i].q2 = E[i].q3 = 0; E[i].fl = 0; }
 
     for (uint32_t it = 0; it < p.spin_cap; it += 3) {
-      if (*abort_p) { stream_end = true; written = admitted; }   // the relaxer gave this candidate up
-      if (__ballot(!(stream_end && written == admitted)) == 0) break;
+      if (*abort_p) { k = klast + 1u; written = admitted; }   // the relaxer gave this candidate up
+      if (__ballot(!(k > klast && written == admitted)) == 0) break;
 #pragma unroll
       for (int s = 0; s < 3; ++s) {
         Entry &e0 = E[s];                 // admitted in this trip
@@ -428,12 +425,12 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
           aseq += kFeeders;
         }
         // (2) ids of the next two nodes (reloaded every trip; consumed one trip later at the earliest)
-        id1 = list[min(k + 1, klast)];
-        id2 = list[min(k + 2, klast)];
+        id1 = list[min(k + 1u, klast)];
+        id2 = list[min(k + 2u, klast)];
         // (3) admission
-        pending = !stream_end && (aseq - *tail_p) < (uint32_t)RING;
-        e0.fl = pending ? (1u | ((k == klast && part + 1 == np) ? 2u : 0u)) : 0u;
-        e0.rec = p.rec[part * n_plane + v];
+        pending = (k <= klast) && (aseq - *tail_p) < (uint32_t)RING;
+        e0.fl = pending ? (1u | ((k == klast && rem == 0u) ? 2u : 0u)) : 0u;
+        e0.rec = p.rec[addr];
         admitted += pending ? 1u : 0u;
         // (B) placement bytes of e1's predecessors (its record was requested one trip ago)
         e1.q0 = pib[e1.rec.x & 0xFFFFu]; e1.q1 = pib[e1.rec.x >> 16];
