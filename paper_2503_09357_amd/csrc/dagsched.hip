@@ -74,7 +74,7 @@ struct dagsched {
   int64_t *d_mem = nullptr;
   int32_t *ws_list = nullptr, *ws_end = nullptr;
   // ring kernel
-  int32_t ring_G = 0, ring_slots = 0, ring_preds = 4, ring_feeders = 1, rec_plane = 0, id_bits = 16, time_scale = 1;
+  int32_t ring_G = 0, ring_slots = 0, ring_feeders = 1, rec_plane = 0, id_bits = 16, time_scale = 1;
   uint8_t *d_nparts = nullptr;
   int64_t list_stride = 0;
   LdsLayout lds{};
@@ -171,7 +171,7 @@ int env_int(const char *name, int dflt) {
   return (s && *s) ? atoi(s) : dflt;
 }
 
-LdsLayout ring_layout(int N, int P, int G, int ring, int op_words) {
+LdsLayout ring_layout(int N, int P, int G, int ring) {
   LdsLayout o{};
   uint32_t at = 0;
   o.s_stride = align_up(2u * (uint32_t)(N + 2), 4);      // N cells + dummy + trash; the arrays start at LDS offset 0
@@ -179,8 +179,8 @@ LdsLayout ring_layout(int N, int P, int G, int ring, int op_words) {
   at += (uint32_t)G * o.s_stride;
   o.o_pi = at;    at += (uint32_t)G * o.pi_stride;
   at = align_up(at, 16);
-  o.o_ring = at;  at += (uint32_t)op_words * (uint32_t)ring * kWave * 4u;
-  o.o_tail = at;  at += kWave * 4u;
+  o.o_ring = at;  at += (uint32_t)ring * kWave * 16u;
+  o.o_scr = at;   at += kWave * 4u;
   o.o_total = at; at += kWave * 4u;
   at = align_up(at, 8);
   o.o_peak = at;  at += kWave * 8u;
@@ -199,7 +199,7 @@ LdsLayout ring_layout(int N, int P, int G, int ring, int op_words) {
 // footprint that fits a workgroup.
 struct RingPlan {
   bool ok = false, exact = false;
-  int G = 0, ring = 0, preds = 4, feeders = 1;
+  int G = 0, ring = 0, feeders = 1;
   int32_t scale = 1;
   LdsLayout lds{};
   std::vector<uint4> rec;
@@ -246,18 +246,8 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
   plan.exact = upper < (int64_t)kNotDone16;
   plan.scale = (int32_t)g;
 
-  // predecessors per op part: three (four-dword ops) unless that needs noticeably more parts than four
-  int64_t parts3 = 0, parts4 = 0;
-  for (int v = 0; v < N; ++v) {
-    const int deg = pred_ptr[v + 1] - pred_ptr[v];
-    parts3 += std::max(1, (deg + 2) / 3);
-    parts4 += std::max(1, (deg + 3) / 4);
-  }
-  const int forced_preds = env_int("DAGSCHED_RING_PREDS", 0);
-  const int PR = forced_preds ? forced_preds : ((parts3 * 50 <= parts4 * 51) ? 3 : 4);
-  if (PR != 3 && PR != 4) return plan;
-  plan.preds = PR;
-  // shared operator records, PR predecessors per part, part i of node v at [i * plane + v]
+  constexpr int PR = 4;                                // DAG predecessors per op part
+  // shared operator records, part i of node v at [i * plane + v]
   const uint32_t dummy = (uint32_t)N;
   int max_parts = 1;
   for (int v = 0; v < N; ++v) max_parts = std::max(max_parts, (pred_ptr[v + 1] - pred_ptr[v] + PR - 1) / PR);
@@ -299,13 +289,12 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
   // the CU would then hold more than 24 wavefronts
   const int force_g = env_int("DAGSCHED_RING_G", 0), force_ring = env_int("DAGSCHED_RING_SLOTS", 0);
   const int force_feeders = env_int("DAGSCHED_RING_FEEDERS", 0);
-  const int op_words = PR == 4 ? 5 : 4;
   int best_score = -1, best_wgs = 0;
   for (int G = kWave / Pseg; G >= 1; G >>= 1) {
     if (force_g && G != force_g) continue;
-    for (int ring : {8, 4}) {
+    for (int ring : {8, 4, 16}) {
       if (force_ring && ring != force_ring) continue;
-      LdsLayout o = ring_layout(N, P, G, ring, op_words);
+      LdsLayout o = ring_layout(N, P, G, ring);
       if ((int)o.total > lds_max) continue;
       if ((uint64_t)G * (o.s_stride >> 1) > 65536u) continue;   // half-addresses must fit 16 bits
       const int wgs = std::min(8, lds_max / (int)align_up(o.total, 512));
@@ -315,26 +304,28 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
     }
   }
   plan.feeders = force_feeders ? force_feeders : (best_wgs * 4 <= 24 ? 2 : 1);
-  if (plan.feeders != 1 && plan.feeders != 2) return plan;
+  if (plan.feeders != 1 && plan.feeders != 2) return plan;   // the feeders' cursor looks two nodes ahead
   plan.ok = best_score >= 0;
   return plan;
 }
 
 using RingKernel = void (*)(RingParams);
 template <int HALF>
-RingKernel ring_kernel_pick(int r8, int p4, int f2) {
-  static const RingKernel table[2][2][2] = {
-      {{relax_ring_kernel<4, 3, 1, HALF>, relax_ring_kernel<4, 3, 2, HALF>},
-       {relax_ring_kernel<4, 4, 1, HALF>, relax_ring_kernel<4, 4, 2, HALF>}},
-      {{relax_ring_kernel<8, 3, 1, HALF>, relax_ring_kernel<8, 3, 2, HALF>},
-       {relax_ring_kernel<8, 4, 1, HALF>, relax_ring_kernel<8, 4, 2, HALF>}}};
-  return table[r8][p4][f2];
+RingKernel ring_kernel_pick(int ring, int feeders) {
+  switch (ring * 10 + feeders) {
+    case 41:  return relax_ring_kernel<4, 1, HALF>;
+    case 42:  return relax_ring_kernel<4, 2, HALF>;
+    case 81:  return relax_ring_kernel<8, 1, HALF>;
+    case 82:  return relax_ring_kernel<8, 2, HALF>;
+    case 161: return relax_ring_kernel<16, 1, HALF>;
+    case 162: return relax_ring_kernel<16, 2, HALF>;
+    default:  return nullptr;
+  }
 }
 RingKernel ring_kernel_for(const dagsched *h) {
-  const int r8 = h->ring_slots == 8, p4 = h->ring_preds == 4, f2 = h->ring_feeders == 2;
   // byte addresses when the workgroup's end-time arrays fit 64 KB, half addresses otherwise
   const bool half = (uint64_t)h->ring_G * h->lds.s_stride > 65536u;
-  return half ? ring_kernel_pick<1>(r8, p4, f2) : ring_kernel_pick<0>(r8, p4, f2);
+  return half ? ring_kernel_pick<1>(h->ring_slots, h->ring_feeders) : ring_kernel_pick<0>(h->ring_slots, h->ring_feeders);
 }
 
 OutPtrs make_out(const dagsched *h, int32_t n_cand, int32_t *makespan, int64_t *bubble, int64_t *peak_mem,
@@ -463,7 +454,7 @@ int dagsched_create(const dagsched_desc_t *desc, dagsched_t **out) {
   }
   if (ok && plan.ok) {
     h->variant = plan.exact ? kVariantRingExact : kVariantRingOptimistic;
-    h->ring_G = plan.G; h->ring_slots = plan.ring; h->ring_preds = plan.preds; h->ring_feeders = plan.feeders; h->lds = plan.lds; h->time_scale = plan.scale;
+    h->ring_G = plan.G; h->ring_slots = plan.ring; h->ring_feeders = plan.feeders; h->lds = plan.lds; h->time_scale = plan.scale;
     h->rec_plane = plan.rec_plane; h->id_bits = plan.id_bits;
     const int64_t cap = ((int64_t)h->N + h->E + 1024) * 64;
     h->spin_cap = (uint32_t)std::min<int64_t>(cap, 0x7FFFFFFF);
@@ -538,7 +529,7 @@ int dagsched_get_info(const dagsched_t *h, dagsched_info_t *info) {
   info->state_bits = ring ? 16 : 32;
   info->reserved[0] = ring ? h->ring_slots : 0;
   info->reserved[1] = h->time_scale;
-  info->reserved[2] = ring ? h->ring_preds * 10 + h->ring_feeders : 0;
+  info->reserved[2] = ring ? h->ring_feeders : 0;
   return DAGSCHED_OK;
 }
 

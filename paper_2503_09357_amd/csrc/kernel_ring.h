@@ -1,35 +1,37 @@
 // Ring kernel: the fast evaluation path.
 //
-// Workgroup = two wavefronts that never meet at a barrier while the schedule is being relaxed:
+// Workgroup = 2 + FEEDERS wavefronts that never meet at a barrier while the schedule is being relaxed;
+// lane (g, j) of every wavefront stands for machine j of candidate g:
 //
-//   wave 0, the RELAXER  lane (g, j) owns machine j of candidate g.  It pops compact "ops" from a
-//                        per-lane ring in LDS and runs the max-plus recurrence
-//                          s_v = max(0, e_chainpred, max_u e_u + delta(u,v)),  e_v = s_v + D^o_v
-//                        (eqs. (3),(7),(11)-(13), Sec. III) against the end-time array of its
-//                        candidate in LDS.  Its loop touches LDS only.
-//   wave 1, the FEEDER   lane (g, j) walks machine j's order list, chases the shared operator
-//                        records in L2, looks up the placement of every DAG predecessor and the
-//                        channel delay, and pushes the resulting op into the relaxer's ring.  It
-//                        also accumulates the machine's memory level and peak (eqs. (17)-(19)),
-//                        which depend on the order only.
+//   wave 0, the RELAXER   pops compact "ops" from a per-lane ring in LDS and runs the max-plus
+//                         recurrence
+//                           s_v = max(0, e_chainpred, max_u e_u + delta(u,v)),  e_v = s_v + D^o_v
+//                         (eqs. (3),(7),(11)-(13), Sec. III) against the end-time array of its
+//                         candidate in LDS.  Its loop touches LDS only and is branch-free.
+//   waves 1..FEEDERS, the FEEDERS  walk machine j's order list, fetch the shared operator records from
+//                         L2, look up the placement of every DAG predecessor and the channel delay, and
+//                         push the resulting op into the relaxer's ring.
+//   last wave, the ACCOUNTANT  walks the order lists and takes the peak of each machine's running
+//                         memory level (eqs. (17)-(19)), which depends on the order only.
 //
-// The feeder runs ahead and absorbs every global-memory latency; the relaxer's critical loop is one
-// LDS round trip, a few integer ops and one LDS write per operation.  A lone wavefront issues at most
-// one instruction every four cycles, so the relaxer loop is written to be as short as possible.  The
-// CUs are LDS-capacity bound on the large configurations (only a few candidates fit), so the second
-// wavefront runs on a SIMD that would otherwise idle.
+// The feeders run ahead and absorb every global-memory latency.  A lone wavefront issues an instruction
+// every few cycles at best and waits out every LDS round trip, so the relaxer's trip is kept short and
+// its critical path (end times arrive -> add, max -> compare -> select next op -> next end-time reads)
+// carries no scalar instruction.  The CUs are LDS-capacity bound on the large configurations (only a
+// few candidates fit), so the other wavefronts run on SIMDs that would otherwise idle.
 //
 // End times are kept as 16-bit unsigned values (sentinel 0xFFFF = not yet ended), which halves the
 // LDS footprint.  When the host cannot prove that every end time stays below 0xFFFF the kernel runs
 // "optimistically": an operation whose end time would reach 0xFFFF is never completed, its candidate
 // stalls exactly like a cyclic one, and every stalled candidate is handed to the general int32 kernel.
 //
-// Ring protocol (single producer, single consumer per lane, no atomics): a lane's ring has RING
-// slots of kOpWords dwords; the last dword carries the op's sequence number.  The feeder writes the
-// payload first and the tagged dword last; the relaxer reads the tagged dword first.  LDS executes
-// one wavefront's accesses in order, so a matching tag proves the payload is complete.  The relaxer
-// publishes how many ops it has copied into registers (tail); the feeder only overwrites a slot
-// when fewer than RING ops are outstanding.
+// Ring protocol (single consumer per lane, no atomics, no counters): a lane's ring has RING slots of
+// 16 bytes; op i of the lane's stream goes to slot i mod RING.  The last dword of a slot is either
+// "duration | address << 16" of a delivered op (duration < 0xFFFF) or "0xFFFF | i << 16": free, op i
+// was the last one copied out of it (the ring starts as if ops -RING .. -1 had been).  A feeder
+// delivers op i once the slot says that op i - RING is out, writing the last dword last; the relaxer
+// copies a delivered slot into registers and writes the free mark.  LDS executes one wavefront's
+// accesses in order, so a delivered last dword proves that the rest of the slot is complete.
 #pragma once
 
 #include "device_common.h"
@@ -39,45 +41,33 @@ namespace dagsched_dev {
 // LDS pointers with an explicit address space: volatile accesses through generic pointers would be
 // compiled to flat loads, these compile to ds_read/ds_write.
 #define DAGSCHED_LDS __attribute__((address_space(3)))
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 typedef DAGSCHED_LDS unsigned char lds_byte_t;
 typedef DAGSCHED_LDS volatile uint32_t lds_vu32_t;
 typedef DAGSCHED_LDS volatile uint16_t lds_vu16_t;
 typedef DAGSCHED_LDS volatile int32_t lds_vi32_t;
 typedef DAGSCHED_LDS const uint8_t lds_cu8_t;
+typedef DAGSCHED_LDS volatile u32x4_t lds_vu32x4_t;
 
-// Op layouts.  ha(x) is the 16-bit address of the end-time cell of x: its LDS byte address when the
-// end-time arrays of the workgroup fit 64 KB (template HALF = 0), else the byte address / 2 (HALF = 1);
-// the arrays start at LDS offset 0.  Unused predecessor slots name the candidate's dummy cell (end time
-// 0, delay 0); a part that does not end its operation names the candidate's trash cell instead of v.
-// seq = index of the op in its lane, modulo (SeqMask + 1); ring tags start as all ones, which no op
-// matches before its slot has been rewritten.
-//   PREDS = 4, five dwords                           PREDS = 3, four dwords
-//     w0 = ha(pred0) | ha(pred1) << 16                 w0 = ha(pred0) | ha(pred1) << 16
-//     w1 = ha(pred2) | ha(pred3) << 16                 w1 = ha(pred2) | ha(v) << 16
-//     w2 = delta0 | delta1 << 8 | delta2 << 16         w2 = duration
-//          | delta3 << 24                              w3 = delta0 | delta1 << 8 | delta2 << 16
-//     w3 = duration                                         | seq << 24                    (tag word)
-//     w4 = ha(v) | seq << 16               (tag word)
-// The duration is 0 for every part but the last of an operation.
-template <int PREDS> struct OpFormat;
-template <> struct OpFormat<4> {
-  static constexpr int kWords = 5, kTagWord = 4, kSeqShift = 16;
-  static constexpr uint32_t kSeqMask = 0xFFFFu;
-};
-template <> struct OpFormat<3> {
-  static constexpr int kWords = 4, kTagWord = 3, kSeqShift = 24;
-  static constexpr uint32_t kSeqMask = 0xFFu;
-};
+// Op layout (one 16-byte slot).  ha(x) is the 16-bit address of the end-time cell of x: its LDS byte
+// address when the end-time arrays of the workgroup fit 64 KB (template HALF = 0), else the byte
+// address / 2 (HALF = 1); the arrays start at LDS offset 0.  Unused predecessor slots name the
+// candidate's dummy cell (end time 0, delay 0); a part that does not end its operation names the
+// candidate's trash cell instead of v and has duration 0.
+//   x = ha(pred0) | ha(pred1) << 16
+//   y = ha(pred2) | ha(pred3) << 16
+//   z = delta0 | delta1 << 8 | delta2 << 16 | delta3 << 24
+//   w = duration | ha(v) << 16
 constexpr uint32_t kNotDone16 = 0xFFFFu;
 constexpr int ring_threads(int feeders) { return (2 + feeders) * kWave; }   // relaxer, feeders, accountant
 
-// One shared record per operation part: up to PREDS DAG predecessors (unused slots name the dummy
+// One shared record per operation part: up to four DAG predecessors (unused slots name the dummy
 // node N).  Part i of operation v sits at rec[i * rec_plane + v]; only the last part carries the
 // duration.
 //   x = u0 | u1 << 16, y = u2 | u3 << 16, z = dur (30 bits) | first_part << 30 | has_more << 31, w = v << 16
 struct LdsLayout {
   uint32_t s_stride, pi_stride;                       // bytes per candidate; the state array starts at 0
-  uint32_t o_pi, o_ring, o_tail, o_total, o_peak, o_cnt, o_off, o_flag, o_abort, o_comm, total;
+  uint32_t o_pi, o_ring, o_scr, o_total, o_peak, o_cnt, o_off, o_flag, o_abort, o_comm, total;
 };
 
 struct RingParams {
@@ -101,15 +91,13 @@ struct RingParams {
 };
 
 // FEEDERS feeder wavefronts share a lane's stream: feeder f owns the parts with (seq - 1) % FEEDERS == f.
-template <int RING, int PREDS, int FEEDERS, int HALF>
+template <int RING, int FEEDERS, int HALF>
 __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingParams p) {
-  using Fmt = OpFormat<PREDS>;
-  constexpr int kOpWords = Fmt::kWords;
   constexpr int kThreads = ring_threads(FEEDERS);
   constexpr int kFeeders = FEEDERS;
   extern __shared__ __align__(16) unsigned char lds[];
   static_assert((RING & (RING - 1)) == 0, "RING must be a power of two");
-  constexpr uint32_t kPlaneBytes = RING * kWave * 4;        // ring layout: [word][slot][lane]
+  static_assert(FEEDERS <= 2 && RING >= FEEDERS, "the feeders' cursor looks two nodes ahead");
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63;
@@ -121,7 +109,6 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
   lds_byte_t *const ldsb = (lds_byte_t *)lds;
 
   uint32_t *ringw = (uint32_t *)(lds + o.o_ring);
-  uint32_t *tailw = (uint32_t *)(lds + o.o_tail);          // [64] ops the relaxer has taken
   uint32_t *totalw = (uint32_t *)(lds + o.o_total);        // [64] ops in the lane's stream, once a feeder knows
   int64_t *peakw = (int64_t *)(lds + o.o_peak);            // [64]
   int32_t *cntw = (int32_t *)(lds + o.o_cnt);              // [64] operations per (candidate, machine)
@@ -131,8 +118,9 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
   uint8_t *commb = (uint8_t *)(lds + o.o_comm);            // [(P+1)][Pseg], diagonal and dummy row zero
 
   // ---------------------------------------------------------------- ingest (both wavefronts)
-  if (tid < kWave) { cntw[tid] = 0; tailw[tid] = 0; totalw[tid] = 0xFFFFFFFFu; flagw[tid] = 0; abortw[tid] = 0; peakw[tid] = 0; }
-  for (int i = tid; i < kOpWords * RING * kWave; i += kThreads) ringw[i] = 0xFFFFFFFFu;
+  if (tid < kWave) { cntw[tid] = 0; totalw[tid] = 0xFFFFFFFFu; flagw[tid] = 0; abortw[tid] = 0; peakw[tid] = 0; }
+  for (int i = tid; i < RING * kWave; i += kThreads)       // every slot free, as if ops -RING .. -1 had been taken
+    ringw[4 * i + 3] = kNotDone16 | ((uint32_t)((i >> 6) - RING) << 16);
   for (int i = tid; i < (P + 1) * Pseg; i += kThreads) {    // rows of Pseg bytes: [source machine][destination]
     const int a = i >> p.log_pseg, b = i & (Pseg - 1);
     commb[i] = (a < P && b < P && a != b) ? (uint8_t)p.comm[a * P + b] : (uint8_t)0;
@@ -211,40 +199,44 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
     uint16_t *list = p.ws_list + (c0 + gg) * p.list_stride;
     const int32_t *cnt_g = cntw + gg * Pseg, *off_g = offw + gg * Pseg;
     int32_t *flag_g = flagw + gg;
-    auto place = [&](int v, int pi, int32_t r) {
+    // list entry: node | (parts - 1) << id_bits
+    auto place = [&](int v, int pi, int32_t r, uint32_t np1) {
       if ((uint32_t)r >= (uint32_t)cnt_g[pi]) {
         atomicOr(flag_g, kBitBadRank);
       } else {
         const uint32_t pos = (uint32_t)(off_g[pi] + r);
         const uint32_t bit = 1u << (pos & 31);
         if (atomicOr(&bm[pos >> 5], bit) & bit) atomicOr(flag_g, kBitBadRank);
-        else list[pos] = (uint16_t)(p.nparts ? (uint32_t)v | ((uint32_t)(p.nparts[v] - 1) << p.id_bits) : (uint32_t)v);
+        else list[pos] = (uint16_t)((uint32_t)v | (np1 << p.id_bits));
       }
     };
     if (vec_ok) {
       const int4 *rk4 = (const int4 *)rk;
       const uint32_t *piw = (const uint32_t *)pib;
+      const uint32_t *np4 = (const uint32_t *)p.nparts;     // four part counts per load (N % 4 == 0 here)
       for (int q0 = tid; q0 < nq; q0 += 4 * kThreads) {
         int4 a[4];
+        uint32_t npw[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
           const int q = q0 + u * kThreads;
           a[u] = (q < nq) ? rk4[q] : make_int4(0, 0, 0, 0);
+          npw[u] = (np4 && q < nq) ? np4[q] - 0x01010101u : 0u;   // every count is at least 1: no borrow between bytes
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
           const int q = q0 + u * kThreads;
           if (q < nq) {
             const uint32_t pw = piw[q];
-            place(4 * q + 0, pw & 0xFF, a[u].x);
-            place(4 * q + 1, (pw >> 8) & 0xFF, a[u].y);
-            place(4 * q + 2, (pw >> 16) & 0xFF, a[u].z);
-            place(4 * q + 3, pw >> 24, a[u].w);
+            place(4 * q + 0, pw & 0xFF, a[u].x, npw[u] & 0xFF);
+            place(4 * q + 1, (pw >> 8) & 0xFF, a[u].y, (npw[u] >> 8) & 0xFF);
+            place(4 * q + 2, (pw >> 16) & 0xFF, a[u].z, (npw[u] >> 16) & 0xFF);
+            place(4 * q + 3, pw >> 24, a[u].w, npw[u] >> 24);
           }
         }
       }
     } else {
-      for (int v = tid; v < N; v += kThreads) place(v, pib[v], rk[v]);
+      for (int v = tid; v < N; v += kThreads) place(v, pib[v], rk[v], p.nparts ? (uint32_t)p.nparts[v] - 1u : 0u);
     }
   }
   __syncthreads();                                          // workgroup scope: the lists are read by this workgroup only
@@ -273,70 +265,67 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
 
   if (wave == 0) {
     // ------------------------------------------------------------ relaxer
-    lds_byte_t *const ring_lane = ldsb + o.o_ring + (uint32_t)lane * 4u;    // this lane's column of the ring
-    lds_vu32_t *const tail_p = (lds_vu32_t *)(ldsb + o.o_tail) + lane;
+    lds_byte_t *const ring_lane = ldsb + o.o_ring + (uint32_t)lane * 16u;   // ring layout: [slot][lane] of 16 bytes
     lds_vu32_t *const total_p = (lds_vu32_t *)(ldsb + o.o_total) + lane;
     lds_vi32_t *const abort_p = (lds_vi32_t *)(ldsb + o.o_abort) + g;
     const uint64_t segmask = ((Pseg == kWave) ? ~0ull : ((1ull << Pseg) - 1ull)) << (g * Pseg);
     auto cell = [&](uint32_t a16) -> lds_vu16_t & { return *(lds_vu16_t *)(ldsb + (a16 << HALF)); };
     const uint32_t dummy = sbase + ((uint32_t)N << (1 - HALF));
-    // The loop body is branch-free: "this lane holds no op" is an op that can never run (duration
-    // 0xFFFF) and every trip stores x somewhere (the trash cell unless the op ran).
+    // The loop body is branch-free: every trip stores x somewhere (the trash cell unless an op ran).
     const uint32_t trash = sbase + (((uint32_t)N + 1u) << (1 - HALF));
-    bool idle = true, dead = !has_ops;
-    uint32_t t = 0, x_acc = 0;
-    // current op: predecessor addresses (two words), packed delays, duration, destination address
-    uint32_t ca = dummy | (dummy << 16), cb = ca, cd = 0, cdur = kNotDone16, cdst = trash;
+    bool idle = true, dead = !has_ops;                      // idle: the registers hold the no-op
+    uint32_t x_acc = 0;
+    uint32_t t10 = 0;                                       // ops taken from the ring, times 1024 (the slot stride)
+    constexpr uint32_t kSlotMask = (uint32_t)(RING - 1) << 10;
+    lds_byte_t *const scr_p = ldsb + o.o_scr + (uint32_t)lane * 4u;   // where lanes that take nothing write their "slot free" mark
+    // "This lane holds no op" is the no-op: predecessors = the dummy cell, duration 0, destination = the
+    // trash cell.  It is always ready, stores x_acc to the trash cell and leaves x_acc as it is, so the
+    // critical path of a trip carries no test for it.
+    const uint32_t z0 = dummy | (dummy << 16), z3 = trash << 16;
+    uint32_t w0 = z0, w1 = z0, w2 = 0, w3 = z3;             // current op, in ring format
     uint64_t prog_acc = 0;
     bool expired = true;
-    uint32_t rt = 0xFFFFFFFFu, r0 = 0, r1 = 0, r2 = 0, r3 = 0;   // ring slot t as read at the end of the previous trip
+    lds_byte_t *slot_p = ring_lane;                         // ring slot of op t
+    u32x4_t r = *(lds_vu32x4_t *)slot_p;                    // ... as read during the previous trip
+    // end times of the current op's predecessors, read at the end of the previous trip
+    uint32_t e0 = cell(dummy), e1 = e0, e2 = e0, e3 = e0;
     for (uint32_t it = 0; it < p.spin_cap; it += 8) {
 #pragma unroll
       for (int sub = 0; sub < 8; ++sub) {
-        // end times of the current op's predecessors (the critical reads go first)
-        const uint32_t e0 = cell(ca & 0xFFFFu), e1 = cell(ca >> 16), e2 = cell(cb & 0xFFFFu);
-        const uint32_t e3 = (PREDS == 4) ? (uint32_t)cell(cb >> 16) : 0u;
-        uint32_t x = max(max(x_acc, e0 + (cd & 0xFFu)), e1 + ((cd >> 8) & 0xFFu));
-        x = max(x, e2 + ((cd >> 16) & 0xFFu));
-        if (PREDS == 4) x = max(x, e3 + (cd >> 24));
-        x += cdur;
-        const bool ready = x < kNotDone16;                  // every predecessor ended, no 16-bit overflow, not idle
-        x_acc = ready ? x : x_acc;                          // the machine is busy until x (chain edge, eq. (7))
-        cell(ready ? cdst : trash) = (uint16_t)x;
-        const bool take = (ready || idle) && ((rt >> Fmt::kSeqShift) == (t & Fmt::kSeqMask));
-        prog_acc |= __ballot(ready || take);                // an op taken now has not been tested yet
-        idle = take ? false : (ready || idle);
-        ca = take ? r0 : ca;
-        if (PREDS == 4) {
-          cb = take ? r1 : cb;
-          cd = take ? r2 : cd;
-          cdur = take ? r3 : (ready ? kNotDone16 : cdur);
-          cdst = take ? (rt & 0xFFFFu) : cdst;
-        } else {
-          cb = take ? (r1 & 0xFFFFu) : cb;                  // the upper half is the destination, not a predecessor
-          cd = take ? (rt & 0xFFFFFFu) : cd;
-          cdur = take ? r2 : (ready ? kNotDone16 : cdur);
-          cdst = take ? (r1 >> 16) : cdst;
-        }
-        t += take ? 1u : 0u;
-        *tail_p = t;
-        // next op of this lane (tagged word first), read now and looked at in the next trip: its LDS
-        // latency hides behind the next trip's end-time reads
-        {
-          lds_byte_t *const sp = ring_lane + ((t & (uint32_t)(RING - 1)) << 8);
-          rt = *(lds_vu32_t *)(sp + Fmt::kTagWord * kPlaneBytes);
-          r0 = *(lds_vu32_t *)(sp);
-          r1 = *(lds_vu32_t *)(sp + kPlaneBytes);
-          r2 = *(lds_vu32_t *)(sp + 2 * kPlaneBytes);
-          if (PREDS == 4) r3 = *(lds_vu32_t *)(sp + 3 * kPlaneBytes);
-        }
+        // what follows the current op: the op delivered in slot t, else the no-op (known before the
+        // end times arrive, so it is off the critical path)
+        const bool valid = (r.w & 0xFFFFu) != kNotDone16;
+        const uint32_t f0 = valid ? r.x : z0, f1 = valid ? r.y : z0, f2 = valid ? r.z : 0u, f3 = valid ? r.w : z3;
+        uint32_t x = max(max(x_acc, e0 + (w2 & 0xFFu)), e1 + ((w2 >> 8) & 0xFFu));
+        x = max(max(x, e2 + ((w2 >> 16) & 0xFFu)), e3 + (w2 >> 24));
+        x += w3 & 0xFFFFu;
+        const bool ran = x < kNotDone16;                    // every predecessor ended and no 16-bit overflow (or the no-op)
+        x_acc = ran ? x : x_acc;                            // the machine is busy until x (chain edge, eq. (7))
+        cell(ran ? (w3 >> 16) : trash) = (uint16_t)x;
+        w0 = ran ? f0 : w0;
+        w1 = ran ? f1 : w1;
+        // The end-time reads of the next trip go out as early as possible (LDS accesses keep their
+        // program order, so everything below overlaps with their latency).
+        e0 = cell(w0 & 0xFFFFu); e1 = cell(w0 >> 16); e2 = cell(w1 & 0xFFFFu); e3 = cell(w1 >> 16);
+        const bool take = ran && valid;
+        // One trip without progress while every unfinished machine holds an op is already a deadlock
+        // (end times only change when some op runs), so progress is sampled once per window.
+        if (sub == 7) prog_acc = __ballot((ran && !idle) || take);   // an op taken now has not been tested yet
+        idle = ran && !valid;
+        w2 = ran ? f2 : w2;
+        w3 = ran ? f3 : w3;
+        // the slot just copied is free again: its last dword says so (and which op left it) to the feeders
+        *(lds_vu32_t *)(take ? slot_p + 12 : scr_p) = (t10 << 6) | kNotDone16;
+        t10 += take ? 1024u : 0u;
+        slot_p = ring_lane + (t10 & kSlotMask);
+        r = *(lds_vu32x4_t *)slot_p;                        // read now, looked at in the next trip
       }
-      const bool fin = dead || (idle && t == *total_p);
+      const bool fin = dead || (idle && (t10 >> 10) == *total_p);
       if (__ballot(!fin) == 0) { expired = false; break; }
       const uint64_t hold = __ballot(!idle || fin);
       if (!fin && (prog_acc & segmask) == 0 && (hold & segmask) == segmask) {
-        // every unfinished machine of this candidate holds an op and none could run for a whole
-        // window: deadlock, i.e. a cycle of the combined graph (or a 16-bit overflow when optimistic)
+        // every unfinished machine of this candidate holds an op and none could run: deadlock, i.e. a
+        // cycle of the combined graph (or a 16-bit overflow when optimistic)
         stalled = true;
         dead = true;
         *abort_p = 1;
@@ -345,7 +334,7 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
       prog_acc = 0;
     }
     if (expired) {                                          // bounded wait ran out: report, release the feeder
-      const bool fin = dead || (idle && t == *total_p);
+      const bool fin = dead || (idle && (t10 >> 10) == *total_p);
       if (!fin) { flagw[g] = kBitInternal; *abort_p = 1; }
     }
     acc = (int32_t)x_acc;
@@ -353,9 +342,8 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
     // ------------------------------------------------------------ feeders
     // Per lane the op parts of machine j form a stream (the parts of one operation are consecutive;
     // the order-list entry of a node carries its part count, so the stream is known from the ids
-    // alone).  Feeder f owns every kFeeders-th part.  A part is ADMITTED when its ring slot is free
-    // (fewer than RING parts between it and the relaxer's tail), then moves through a fixed pipeline
-    // without ever stalling:
+    // alone).  Feeder f owns every kFeeders-th part.  A part is ADMITTED when the relaxer has copied the
+    // previous part out of its ring slot, then moves through a fixed pipeline without ever stalling:
     //   trip t    record requested from L2
     //   trip t+1  placement bytes of its predecessors read from LDS
     //   trip t+2  channel delays read from LDS, op packed and written to the ring
@@ -364,8 +352,7 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
     __builtin_amdgcn_s_setprio(2);                          // the relaxer only polls; feeding must not wait behind it
     lds_cu8_t *const pib = (lds_cu8_t *)(ldsb + o.o_pi + g * o.pi_stride);
     lds_cu8_t *const commr = (lds_cu8_t *)(ldsb + o.o_comm) + j;
-    lds_byte_t *const ring_lane = ldsb + o.o_ring + (uint32_t)lane * 4u;
-    lds_vu32_t *const tail_p = (lds_vu32_t *)(ldsb + o.o_tail) + lane;
+    lds_byte_t *const ring_lane = ldsb + o.o_ring + (uint32_t)lane * 16u;
     lds_vi32_t *const abort_p = (lds_vi32_t *)(ldsb + o.o_abort) + g;
     const uint16_t *list = p.ws_list + (c0 + (cand_ok ? g : 0)) * p.list_stride;
     lds_vu32_t *const total_p = (lds_vu32_t *)(ldsb + o.o_total) + lane;
@@ -414,7 +401,7 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
         Entry &e2 = E[(s + 1) % 3];       // admitted two trips ago
         // (A) channel delays of e2 (its placement bytes were read one trip ago)
         const uint32_t d0 = commr[e2.q0 << lps], d1 = commr[e2.q1 << lps], d2 = commr[e2.q2 << lps];
-        const uint32_t d3 = (PREDS == 4) ? (uint32_t)commr[e2.q3 << lps] : 0u;
+        const uint32_t d3 = commr[e2.q3 << lps];
         // (1) move the cursor past the part admitted in the previous trip and the other feeders' parts
         if (pending) {
 #pragma unroll
@@ -428,32 +415,26 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
         id1 = list[min(k + 1u, klast)];
         id2 = list[min(k + 2u, klast)];
         // (3) admission
-        pending = (k <= klast) && (aseq - *tail_p) < (uint32_t)RING;
+        pending = (k <= klast) &&
+                  *(lds_vu32_t *)(ring_lane + ((aseq & (uint32_t)(RING - 1)) << 10) + 12) == (((aseq - (uint32_t)RING) << 16) | kNotDone16);
         e0.fl = pending ? (1u | ((k == klast && rem == 0u) ? 2u : 0u)) : 0u;
         e0.rec = p.rec[addr];
         admitted += pending ? 1u : 0u;
         // (B) placement bytes of e1's predecessors (its record was requested one trip ago)
         e1.q0 = pib[e1.rec.x & 0xFFFFu]; e1.q1 = pib[e1.rec.x >> 16];
-        e1.q2 = pib[e1.rec.y & 0xFFFFu];
-        if (PREDS == 4) e1.q3 = pib[e1.rec.y >> 16];
+        e1.q2 = pib[e1.rec.y & 0xFFFFu]; e1.q3 = pib[e1.rec.y >> 16];
         // (D) pack e2 and publish it
         if (e2.fl & 1u) {
           const bool more = (e2.rec.z >> 31) != 0;
           const uint32_t dst = more ? trash : sbase + ((e2.rec.w >> 16) << (1 - HALF));
-          const uint32_t tagbits = (wseq & Fmt::kSeqMask) << Fmt::kSeqShift;
-          lds_byte_t *const sp = ring_lane + ((wseq & (uint32_t)(RING - 1)) << 8);
-          // node ids below 32768 whenever HALF == 0, so shifting both halves at once cannot carry over
-          *(lds_vu32_t *)(sp) = (e2.rec.x << (1 - HALF)) + base2;
-          if (PREDS == 4) {
-            *(lds_vu32_t *)(sp + kPlaneBytes) = (e2.rec.y << (1 - HALF)) + base2;
-            *(lds_vu32_t *)(sp + 2 * kPlaneBytes) = d0 | (d1 << 8) | (d2 << 16) | (d3 << 24);
-            *(lds_vu32_t *)(sp + 3 * kPlaneBytes) = e2.rec.z & 0x3FFFFFFFu;
-            *(lds_vu32_t *)(sp + 4 * kPlaneBytes) = dst | tagbits;
-          } else {
-            *(lds_vu32_t *)(sp + kPlaneBytes) = (((e2.rec.y & 0xFFFFu) << (1 - HALF)) + sbase) | (dst << 16);
-            *(lds_vu32_t *)(sp + 2 * kPlaneBytes) = e2.rec.z & 0x3FFFFFFFu;
-            *(lds_vu32_t *)(sp + 3 * kPlaneBytes) = d0 | (d1 << 8) | (d2 << 16) | tagbits;
-          }
+          const uint32_t dur = e2.rec.z & 0xFFFFu;
+          lds_byte_t *const sp = ring_lane + ((wseq & (uint32_t)(RING - 1)) << 10);
+          // node ids below 32768 whenever HALF == 0, so shifting both halves at once cannot carry over;
+          // the whole slot first with its free mark unchanged, then the last dword
+          const u32x4_t val = {(e2.rec.x << (1 - HALF)) + base2, (e2.rec.y << (1 - HALF)) + base2,
+                               d0 | (d1 << 8) | (d2 << 16) | (d3 << 24), ((wseq - (uint32_t)RING) << 16) | kNotDone16};
+          *(lds_vu32x4_t *)sp = val;
+          *(lds_vu32_t *)(sp + 12) = dur | (dst << 16);
           if (e2.fl & 2u) *total_p = wseq + 1;              // the lane's stream ends with this op
           wseq += kFeeders;
           ++written;

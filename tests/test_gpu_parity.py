@@ -210,10 +210,11 @@ def _with_env(env, fn):
 
 @pytest.mark.parametrize("env", [
     {"DAGSCHED_FORCE_GENERAL": 1},
-    {"DAGSCHED_RING_PREDS": 4, "DAGSCHED_RING_FEEDERS": 1, "DAGSCHED_RING_SLOTS": 4},
-    {"DAGSCHED_RING_PREDS": 4, "DAGSCHED_RING_FEEDERS": 2, "DAGSCHED_RING_SLOTS": 8},
-    {"DAGSCHED_RING_PREDS": 3, "DAGSCHED_RING_FEEDERS": 1, "DAGSCHED_RING_SLOTS": 8},
-    {"DAGSCHED_RING_PREDS": 3, "DAGSCHED_RING_FEEDERS": 2, "DAGSCHED_RING_SLOTS": 4, "DAGSCHED_RING_G": 1},
+    {"DAGSCHED_RING_FEEDERS": 1, "DAGSCHED_RING_SLOTS": 4},
+    {"DAGSCHED_RING_FEEDERS": 2, "DAGSCHED_RING_SLOTS": 8},
+    {"DAGSCHED_RING_FEEDERS": 1, "DAGSCHED_RING_SLOTS": 8, "DAGSCHED_RING_G": 1},
+    {"DAGSCHED_RING_FEEDERS": 2, "DAGSCHED_RING_SLOTS": 4},
+    {"DAGSCHED_RING_FEEDERS": 2, "DAGSCHED_RING_SLOTS": 16},
 ])
 def test_every_kernel_variant(gpu_lib, env):
     """The tuning knobs only pick among kernel instantiations; each one must give the same bits."""
@@ -225,8 +226,10 @@ def test_every_kernel_variant(gpu_lib, env):
         if "DAGSCHED_FORCE_GENERAL" in env:
             assert info["state_bits"] == 32
         else:
-            assert info["state_bits"] == 16 and info["preds_per_op"] == env["DAGSCHED_RING_PREDS"]
+            assert info["state_bits"] == 16
             assert info["feeders"] == env["DAGSCHED_RING_FEEDERS"] and info["ring_slots"] == env["DAGSCHED_RING_SLOTS"]
+            if "DAGSCHED_RING_G" in env:
+                assert info["cand_per_block"] == env["DAGSCHED_RING_G"]
 
 
 def test_sixteen_bit_overflow_falls_back(gpu_lib):
