@@ -76,7 +76,8 @@ struct dagsched {
   // ring kernel
   int32_t ring_G = 0, ring_slots = 0, ring_feeders = 1, rec_plane = 0, id_bits = 16, time_scale = 1;
   uint8_t *d_nparts = nullptr;
-  int64_t list_stride = 0;
+  int64_t list_stride = 0, pib_stride = 0;
+  uint8_t *ws_pib = nullptr;
   LdsLayout lds{};
   uint4 *d_rec = nullptr;
   int32_t *d_comm_scaled = nullptr;
@@ -160,7 +161,7 @@ bool dev_alloc(T **dst, size_t n) {
 void free_handle(dagsched *h) {
   if (!h) return;
   void *bufs[] = {h->d_pred_ptr, h->d_pred_idx, h->d_dur, h->d_comm, h->d_mem, h->ws_list, h->ws_end, h->d_rec,
-                  h->d_comm_scaled, h->d_nparts, h->ws_list16, h->d_fb_count, h->d_fb_list, h->ws_tp, h->ws_tr};
+                  h->d_comm_scaled, h->d_nparts, h->ws_list16, h->ws_pib, h->d_fb_count, h->d_fb_list, h->ws_tp, h->ws_tr};
   for (void *b : bufs)
     if (b) (void)hipFree(b);
   delete h;
@@ -171,12 +172,12 @@ int env_int(const char *name, int dflt) {
   return (s && *s) ? atoi(s) : dflt;
 }
 
-LdsLayout ring_layout(int N, int P, int G, int ring) {
+LdsLayout ring_layout(int N, int P, int G, int ring, bool pib_lds) {
   LdsLayout o{};
   uint32_t at = 0;
   o.s_stride = align_up(2u * (uint32_t)(N + 2), 4);      // N cells + dummy + trash; the arrays start at LDS offset 0
-  o.pi_stride = align_up((uint32_t)(N + 1), 4);
   at += (uint32_t)G * o.s_stride;
+  o.pi_stride = pib_lds ? align_up((uint32_t)(N + 1), 4) : 0u;
   o.o_pi = at;    at += (uint32_t)G * o.pi_stride;
   at = align_up(at, 16);
   o.o_ring = at;  at += (uint32_t)ring * kWave * 16u;
@@ -284,23 +285,29 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
   plan.comm_scaled.resize((size_t)P * P);
   for (int i = 0; i < P * P; ++i) plan.comm_scaled[i] = (i / P != i % P) ? (int32_t)(d->comm[i] / g) : 0;
 
-  // shape: most candidates resident per CU, where a four-slot ring counts 0.7 (measured: the relaxer's
-  // hot lanes outrun a four-deep ring), then more candidates per wavefront; two feeder wavefronts unless
-  // the CU would then hold more than 24 wavefronts
+  // shape: most candidates resident per CU first.  Placement bytes in LDS give the fastest feeders but cost
+  // N bytes per candidate; in L2 they leave room for more candidates or a deeper ring.  Measured weights: a
+  // four-slot ring counts 0.7 (hot lanes outrun it), placement bytes in L2 count 0.97, and workgroups beyond
+  // five per CU count nothing.
   const int force_g = env_int("DAGSCHED_RING_G", 0), force_ring = env_int("DAGSCHED_RING_SLOTS", 0);
-  const int force_feeders = env_int("DAGSCHED_RING_FEEDERS", 0);
-  int best_score = -1, best_wgs = 0;
+  const int force_feeders = env_int("DAGSCHED_RING_FEEDERS", 0), force_pib = env_int("DAGSCHED_RING_PIB_LDS", -1);
+  int64_t best_score = -1;
+  int best_wgs = 0;
   for (int G = kWave / Pseg; G >= 1; G >>= 1) {
     if (force_g && G != force_g) continue;
-    for (int ring : {8, 4, 16}) {
-      if (force_ring && ring != force_ring) continue;
-      LdsLayout o = ring_layout(N, P, G, ring);
-      if ((int)o.total > lds_max) continue;
-      if ((uint64_t)G * (o.s_stride >> 1) > 65536u) continue;   // half-addresses must fit 16 bits
-      const int wgs = std::min(8, lds_max / (int)align_up(o.total, 512));
-      if (wgs < 1) continue;
-      const int score = wgs * G * (ring == 8 ? 100 : 70) + G;
-      if (score > best_score) { best_score = score; best_wgs = wgs; plan.G = G; plan.ring = ring; plan.lds = o; }
+    for (int pib_lds = 1; pib_lds >= 0; --pib_lds) {
+      if (force_pib >= 0 && pib_lds != force_pib) continue;
+      for (int ring : {8, 16, 32, 4}) {
+        if (force_ring && ring != force_ring) continue;
+        if (pib_lds ? ring > 8 : ring < 8) continue;     // instantiated: LDS with 4 or 8 slots, L2 with 8, 16 or 32
+        LdsLayout o = ring_layout(N, P, G, ring, pib_lds != 0);
+        if ((int)o.total > lds_max) continue;
+        if ((uint64_t)G * (o.s_stride >> 1) > 65536u) continue;   // half-addresses must fit 16 bits
+        const int wgs = std::min(5, lds_max / (int)align_up(o.total, 512));   // beyond ~20 wavefronts the CU is issue-bound
+        if (wgs < 1) continue;
+        const int64_t score = (int64_t)wgs * G * (ring >= 8 ? 100 : 70) * (pib_lds ? 100 : 97) + (ring == 16 ? 2 : 0) + G;
+        if (score > best_score) { best_score = score; best_wgs = wgs; plan.G = G; plan.ring = ring; plan.lds = o; }
+      }
     }
   }
   plan.feeders = force_feeders ? force_feeders : (best_wgs * 4 <= 24 ? 2 : 1);
@@ -311,21 +318,27 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
 
 using RingKernel = void (*)(RingParams);
 template <int HALF>
-RingKernel ring_kernel_pick(int ring, int feeders) {
-  switch (ring * 10 + feeders) {
-    case 41:  return relax_ring_kernel<4, 1, HALF>;
-    case 42:  return relax_ring_kernel<4, 2, HALF>;
-    case 81:  return relax_ring_kernel<8, 1, HALF>;
-    case 82:  return relax_ring_kernel<8, 2, HALF>;
-    case 161: return relax_ring_kernel<16, 1, HALF>;
-    case 162: return relax_ring_kernel<16, 2, HALF>;
-    default:  return nullptr;
+RingKernel ring_kernel_pick(int ring, int feeders, bool pib_lds) {
+  switch ((pib_lds ? 1000 : 0) + ring * 10 + feeders) {
+    case 1041: return relax_ring_kernel<4, 1, HALF, 1>;
+    case 1042: return relax_ring_kernel<4, 2, HALF, 1>;
+    case 1081: return relax_ring_kernel<8, 1, HALF, 1>;
+    case 1082: return relax_ring_kernel<8, 2, HALF, 1>;
+    case 81:   return relax_ring_kernel<8, 1, HALF, 0>;
+    case 82:   return relax_ring_kernel<8, 2, HALF, 0>;
+    case 161:  return relax_ring_kernel<16, 1, HALF, 0>;
+    case 162:  return relax_ring_kernel<16, 2, HALF, 0>;
+    case 321:  return relax_ring_kernel<32, 1, HALF, 0>;
+    case 322:  return relax_ring_kernel<32, 2, HALF, 0>;
+    default:   return nullptr;
   }
 }
 RingKernel ring_kernel_for(const dagsched *h) {
   // byte addresses when the workgroup's end-time arrays fit 64 KB, half addresses otherwise
   const bool half = (uint64_t)h->ring_G * h->lds.s_stride > 65536u;
-  return half ? ring_kernel_pick<1>(h->ring_slots, h->ring_feeders) : ring_kernel_pick<0>(h->ring_slots, h->ring_feeders);
+  const bool pib_lds = h->lds.pi_stride != 0;
+  return half ? ring_kernel_pick<1>(h->ring_slots, h->ring_feeders, pib_lds)
+              : ring_kernel_pick<0>(h->ring_slots, h->ring_feeders, pib_lds);
 }
 
 OutPtrs make_out(const dagsched *h, int32_t n_cand, int32_t *makespan, int64_t *bubble, int64_t *peak_mem,
@@ -379,7 +392,7 @@ int launch_evaluate(dagsched *h, int32_t n_cand, const int32_t *placement, const
     p.rec = h->d_rec; p.rec_plane = h->rec_plane; p.id_bits = h->id_bits; p.nparts = h->d_nparts; p.comm = h->d_comm_scaled; p.mem_delta = h->d_mem;
     p.sum_dur = h->sum_dur; p.time_scale = h->time_scale;
     p.placement = pl; p.rank = rk;
-    p.ws_list = h->ws_list16;
+    p.ws_list = h->ws_list16; p.ws_pib = h->ws_pib; p.pib_stride = h->pib_stride;
     p.fb_count = h->d_fb_count; p.fb_list = h->d_fb_list;
     p.spin_cap = h->spin_cap;
     p.lds = h->lds;
@@ -429,6 +442,7 @@ int dagsched_create(const dagsched_desc_t *desc, dagsched_t **out) {
   h->sum_dur = sum_dur;
   h->row_stride = ((int64_t)h->N + 31) / 32 * 32;     // 128-byte rows: no cache line shared by two candidates
   h->list_stride = ((int64_t)h->N + 63) / 64 * 64;
+  h->pib_stride = ((int64_t)h->N + 1 + 127) / 128 * 128;
   const size_t maxc = (size_t)h->max_cand;
 
   RingPlan plan;
@@ -461,7 +475,8 @@ int dagsched_create(const dagsched_desc_t *desc, dagsched_t **out) {
     ok = upload(&h->d_rec, plan.rec.data(), plan.rec.size()) &&
          upload(&h->d_comm_scaled, plan.comm_scaled.data(), plan.comm_scaled.size()) &&
          (plan.nparts.empty() || upload(&h->d_nparts, plan.nparts.data(), plan.nparts.size())) &&
-         dev_alloc(&h->ws_list16, maxc * (size_t)h->list_stride);
+         dev_alloc(&h->ws_list16, maxc * (size_t)h->list_stride) &&
+         dev_alloc(&h->ws_pib, maxc * (size_t)h->pib_stride);
     if (ok && !plan.exact) ok = dev_alloc(&h->d_fb_count, 1) && dev_alloc(&h->d_fb_list, maxc);
     if (ok && h->lds.total > 48 * 1024)
       ok = hip_ok(hipFuncSetAttribute((const void *)ring_kernel_for(h), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -529,7 +544,7 @@ int dagsched_get_info(const dagsched_t *h, dagsched_info_t *info) {
   info->state_bits = ring ? 16 : 32;
   info->reserved[0] = ring ? h->ring_slots : 0;
   info->reserved[1] = h->time_scale;
-  info->reserved[2] = ring ? h->ring_feeders : 0;
+  info->reserved[2] = ring ? (h->ring_feeders | ((h->lds.pi_stride != 0 ? 1 : 0) << 8)) : 0;
   return DAGSCHED_OK;
 }
 

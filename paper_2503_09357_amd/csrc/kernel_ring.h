@@ -9,7 +9,8 @@
 //                         (eqs. (3),(7),(11)-(13), Sec. III) against the end-time array of its
 //                         candidate in LDS.  Its loop touches LDS only and is branch-free.
 //   waves 1..FEEDERS, the FEEDERS  walk machine j's order list, fetch the shared operator records from
-//                         L2, look up the placement of every DAG predecessor and the channel delay, and
+//                         L2, look up the placement of every DAG predecessor (one byte per node, L2) and the
+//                         channel delay (LDS), and
 //                         push the resulting op into the relaxer's ring.
 //   last wave, the ACCOUNTANT  walks the order lists and takes the peak of each machine's running
 //                         memory level (eqs. (17)-(19)), which depends on the order only.
@@ -84,6 +85,8 @@ struct RingParams {
   int32_t time_scale;                  // gcd of every duration and delay
   const int32_t *placement, *rank;     // [C][N]
   uint16_t *ws_list;                   // [C][list_stride]
+  uint8_t *ws_pib;                     // [C][pib_stride] placement as one byte per node; entry N = P (the dummy node's machine)
+  int64_t pib_stride;
   int32_t *fb_count, *fb_list;         // candidates left to the general kernel
   uint32_t spin_cap;                   // bound on relaxer / feeder loop trips
   LdsLayout lds;
@@ -91,7 +94,9 @@ struct RingParams {
 };
 
 // FEEDERS feeder wavefronts share a lane's stream: feeder f owns the parts with (seq - 1) % FEEDERS == f.
-template <int RING, int FEEDERS, int HALF>
+// PIBL = 1: the placement bytes of the workgroup's candidates sit in LDS (fastest feeders); PIBL = 0: in an
+// L2-resident workspace, which leaves the LDS to more candidates or a deeper ring.
+template <int RING, int FEEDERS, int HALF, int PIBL>
 __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingParams p) {
   constexpr int kThreads = ring_threads(FEEDERS);
   constexpr int kFeeders = FEEDERS;
@@ -138,8 +143,9 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
   // placement in range (eq. (6)), operations per machine
   for (int gg = 0; gg < ng; ++gg) {
     const int32_t *pl = p.placement + (c0 + gg) * N;
-    uint8_t *pib = lds + o.o_pi + gg * o.pi_stride;
+    uint8_t *pib = PIBL ? lds + o.o_pi + gg * o.pi_stride : p.ws_pib + (c0 + gg) * p.pib_stride;
     int32_t *cnt_g = cntw + gg * Pseg;
+    if (tid == 0) pib[N] = (uint8_t)P;                      // the dummy node sits on a dummy machine whose delays are all zero
     if (vec_ok) {
       const int4 *pl4 = (const int4 *)pl;
       uint32_t *piw = (uint32_t *)pib;
@@ -194,7 +200,8 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
   for (int gg = 0; gg < ng; ++gg) {
     if (flagw[gg] & kBitBadPlacement) continue;
     const int32_t *rk = p.rank + (c0 + gg) * N;
-    const uint8_t *pib = lds + o.o_pi + gg * o.pi_stride;
+    const uint8_t *pib = PIBL ? lds + o.o_pi + gg * o.pi_stride
+                              : p.ws_pib + (c0 + gg) * p.pib_stride;   // written by this workgroup before the barrier above
     uint32_t *bm = (uint32_t *)(lds + gg * o.s_stride);
     uint16_t *list = p.ws_list + (c0 + gg) * p.list_stride;
     const int32_t *cnt_g = cntw + gg * Pseg, *off_g = offw + gg * Pseg;
@@ -248,7 +255,6 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
       const uint32_t lo = (2 * i < N) ? kNotDone16 : 0u, hi = (2 * i + 1 < N) ? kNotDone16 : 0u;
       sw[i] = lo | (hi << 16);
     }
-    if (tid == 0) (lds + o.o_pi + gg * o.pi_stride)[N] = (uint8_t)P;
   }
   __syncthreads();
 
@@ -345,12 +351,14 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
     // alone).  Feeder f owns every kFeeders-th part.  A part is ADMITTED when the relaxer has copied the
     // previous part out of its ring slot, then moves through a fixed pipeline without ever stalling:
     //   trip t    record requested from L2
-    //   trip t+1  placement bytes of its predecessors read from LDS
+    //   trip t+1  placement bytes of its predecessors requested from L2
     //   trip t+2  channel delays read from LDS, op packed and written to the ring
     // The loop is unrolled by three so that the pipeline registers rotate by renaming, not by moves.
     const int f = wave - 1;
     __builtin_amdgcn_s_setprio(2);                          // the relaxer only polls; feeding must not wait behind it
-    lds_cu8_t *const pib = (lds_cu8_t *)(ldsb + o.o_pi + g * o.pi_stride);
+    const uint8_t *const pib_g = p.ws_pib + (c0 + (cand_ok ? g : 0)) * p.pib_stride;   // L2-resident: this workgroup wrote it
+    lds_cu8_t *const pib_l = (lds_cu8_t *)(ldsb + o.o_pi + g * o.pi_stride);
+    auto pib = [&](uint32_t u) -> uint32_t { return PIBL ? (uint32_t)pib_l[u] : (uint32_t)pib_g[u]; };
     lds_cu8_t *const commr = (lds_cu8_t *)(ldsb + o.o_comm) + j;
     lds_byte_t *const ring_lane = ldsb + o.o_ring + (uint32_t)lane * 16u;
     lds_vi32_t *const abort_p = (lds_vi32_t *)(ldsb + o.o_abort) + g;
@@ -399,7 +407,7 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
         Entry &e0 = E[s];                 // admitted in this trip
         Entry &e1 = E[(s + 2) % 3];       // admitted one trip ago
         Entry &e2 = E[(s + 1) % 3];       // admitted two trips ago
-        // (A) channel delays of e2 (its placement bytes were read one trip ago)
+        // (A) channel delays of e2 (its placement bytes were requested one trip ago)
         const uint32_t d0 = commr[e2.q0 << lps], d1 = commr[e2.q1 << lps], d2 = commr[e2.q2 << lps];
         const uint32_t d3 = commr[e2.q3 << lps];
         // (1) move the cursor past the part admitted in the previous trip and the other feeders' parts
@@ -421,8 +429,8 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
         e0.rec = p.rec[addr];
         admitted += pending ? 1u : 0u;
         // (B) placement bytes of e1's predecessors (its record was requested one trip ago)
-        e1.q0 = pib[e1.rec.x & 0xFFFFu]; e1.q1 = pib[e1.rec.x >> 16];
-        e1.q2 = pib[e1.rec.y & 0xFFFFu]; e1.q3 = pib[e1.rec.y >> 16];
+        e1.q0 = pib(e1.rec.x & 0xFFFFu); e1.q1 = pib(e1.rec.x >> 16);
+        e1.q2 = pib(e1.rec.y & 0xFFFFu); e1.q3 = pib(e1.rec.y >> 16);
         // (D) pack e2 and publish it
         if (e2.fl & 1u) {
           const bool more = (e2.rec.z >> 31) != 0;

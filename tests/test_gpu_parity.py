@@ -210,11 +210,13 @@ def _with_env(env, fn):
 
 @pytest.mark.parametrize("env", [
     {"DAGSCHED_FORCE_GENERAL": 1},
-    {"DAGSCHED_RING_FEEDERS": 1, "DAGSCHED_RING_SLOTS": 4},
-    {"DAGSCHED_RING_FEEDERS": 2, "DAGSCHED_RING_SLOTS": 8},
-    {"DAGSCHED_RING_FEEDERS": 1, "DAGSCHED_RING_SLOTS": 8, "DAGSCHED_RING_G": 1},
-    {"DAGSCHED_RING_FEEDERS": 2, "DAGSCHED_RING_SLOTS": 4},
-    {"DAGSCHED_RING_FEEDERS": 2, "DAGSCHED_RING_SLOTS": 16},
+    {"DAGSCHED_RING_FEEDERS": 1, "DAGSCHED_RING_SLOTS": 4, "DAGSCHED_RING_PIB_LDS": 1},
+    {"DAGSCHED_RING_FEEDERS": 2, "DAGSCHED_RING_SLOTS": 8, "DAGSCHED_RING_PIB_LDS": 1},
+    {"DAGSCHED_RING_FEEDERS": 1, "DAGSCHED_RING_SLOTS": 8, "DAGSCHED_RING_PIB_LDS": 1, "DAGSCHED_RING_G": 1},
+    {"DAGSCHED_RING_FEEDERS": 2, "DAGSCHED_RING_SLOTS": 4, "DAGSCHED_RING_PIB_LDS": 1},
+    {"DAGSCHED_RING_FEEDERS": 2, "DAGSCHED_RING_SLOTS": 8, "DAGSCHED_RING_PIB_LDS": 0},
+    {"DAGSCHED_RING_FEEDERS": 2, "DAGSCHED_RING_SLOTS": 16, "DAGSCHED_RING_PIB_LDS": 0},
+    {"DAGSCHED_RING_FEEDERS": 1, "DAGSCHED_RING_SLOTS": 32, "DAGSCHED_RING_PIB_LDS": 0},
 ])
 def test_every_kernel_variant(gpu_lib, env):
     """The tuning knobs only pick among kernel instantiations; each one must give the same bits."""
@@ -228,6 +230,7 @@ def test_every_kernel_variant(gpu_lib, env):
         else:
             assert info["state_bits"] == 16
             assert info["feeders"] == env["DAGSCHED_RING_FEEDERS"] and info["ring_slots"] == env["DAGSCHED_RING_SLOTS"]
+            assert info["placement_bytes_in_lds"] == env["DAGSCHED_RING_PIB_LDS"]
             if "DAGSCHED_RING_G" in env:
                 assert info["cand_per_block"] == env["DAGSCHED_RING_G"]
 
