@@ -351,9 +351,10 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
     // alone).  Feeder f owns every kFeeders-th part.  A part is ADMITTED when the relaxer has copied the
     // previous part out of its ring slot, then moves through a fixed pipeline without ever stalling:
     //   trip t    record requested from L2
-    //   trip t+1  placement bytes of its predecessors requested from L2
-    //   trip t+2  channel delays read from LDS, op packed and written to the ring
-    // The loop is unrolled by three so that the pipeline registers rotate by renaming, not by moves.
+    //   trip t+1  placement bytes of its predecessors requested (L2), or read from LDS
+    //   trip t+2  (trip t+1 when the placement bytes are in LDS) channel delays read from LDS, op packed
+    //             and written to the ring
+    // The loop is unrolled by the pipeline depth so that the registers rotate by renaming, not by moves.
     const int f = wave - 1;
     __builtin_amdgcn_s_setprio(2);                          // the relaxer only polls; feeding must not wait behind it
     const uint8_t *const pib_g = p.ws_pib + (c0 + (cand_ok ? g : 0)) * p.pib_stride;   // L2-resident: this workgroup wrote it
@@ -395,19 +396,24 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
       id1 = crossed ? id2 : id1;
     }
     struct Entry { uint4 rec; uint32_t q0, q1, q2, q3, fl; };   // fl: 1 valid, 2 last part of the lane
-    Entry E[3];
+    constexpr int kStages = PIBL ? 2 : 3;
+    Entry E[kStages];
 #pragma unroll
-    for (int i = 0; i < 3; ++i) { E[i].rec = make_uint4(0, 0, 0, 0); E[i].q0 = E[i].q1 = E[i].q2 = E[i].q3 = 0; E[i].fl = 0; }
+    for (int i = 0; i < kStages; ++i) { E[i].rec = make_uint4(0, 0, 0, 0); E[i].q0 = E[i].q1 = E[i].q2 = E[i].q3 = 0; E[i].fl = 0; }
 
-    for (uint32_t it = 0; it < p.spin_cap; it += 3) {
+    for (uint32_t it = 0; it < p.spin_cap; it += kStages) {
       if (*abort_p) { k = klast + 1u; written = admitted; }   // the relaxer gave this candidate up
       if (__ballot(!(k > klast && written == admitted)) == 0) break;
 #pragma unroll
-      for (int s = 0; s < 3; ++s) {
-        Entry &e0 = E[s];                 // admitted in this trip
-        Entry &e1 = E[(s + 2) % 3];       // admitted one trip ago
-        Entry &e2 = E[(s + 1) % 3];       // admitted two trips ago
-        // (A) channel delays of e2 (its placement bytes were requested one trip ago)
+      for (int s = 0; s < kStages; ++s) {
+        Entry &e0 = E[s];                             // admitted in this trip
+        Entry &e1 = E[(s + kStages - 1) % kStages];   // admitted one trip ago: its record has arrived
+        Entry &e2 = E[(s + 1) % kStages];             // the oldest: written in this trip (e1 itself when the depth is two)
+        if (kStages == 2) {
+          e1.q0 = pib(e1.rec.x & 0xFFFFu); e1.q1 = pib(e1.rec.x >> 16);
+          e1.q2 = pib(e1.rec.y & 0xFFFFu); e1.q3 = pib(e1.rec.y >> 16);
+        }
+        // (A) channel delays of e2
         const uint32_t d0 = commr[e2.q0 << lps], d1 = commr[e2.q1 << lps], d2 = commr[e2.q2 << lps];
         const uint32_t d3 = commr[e2.q3 << lps];
         // (1) move the cursor past the part admitted in the previous trip and the other feeders' parts
@@ -429,8 +435,10 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
         e0.rec = p.rec[addr];
         admitted += pending ? 1u : 0u;
         // (B) placement bytes of e1's predecessors (its record was requested one trip ago)
-        e1.q0 = pib(e1.rec.x & 0xFFFFu); e1.q1 = pib(e1.rec.x >> 16);
-        e1.q2 = pib(e1.rec.y & 0xFFFFu); e1.q3 = pib(e1.rec.y >> 16);
+        if (kStages == 3) {
+          e1.q0 = pib(e1.rec.x & 0xFFFFu); e1.q1 = pib(e1.rec.x >> 16);
+          e1.q2 = pib(e1.rec.y & 0xFFFFu); e1.q3 = pib(e1.rec.y >> 16);
+        }
         // (D) pack e2 and publish it
         if (e2.fl & 1u) {
           const bool more = (e2.rec.z >> 31) != 0;
