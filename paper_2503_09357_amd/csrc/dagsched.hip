@@ -198,6 +198,10 @@ LdsLayout ring_layout(int N, int P, int G, int ring, bool pib_lds) {
 // Needs: every scaled delay <= 255, at most 65536 overflow records, the scaled lower bound on any
 // makespan (critical path of B, heaviest possible average load) below the 16-bit range, and an LDS
 // footprint that fits a workgroup.
+using RingKernel = void (*)(RingParams);
+template <int HALF>
+RingKernel ring_kernel_pick(int ring, int feeders, bool pib_lds);
+
 struct RingPlan {
   bool ok = false, exact = false;
   int G = 0, ring = 0, feeders = 1;
@@ -311,7 +315,7 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
     }
   }
   plan.feeders = force_feeders ? force_feeders : (best_wgs * 4 <= 24 ? 2 : 1);
-  if (plan.feeders != 1 && plan.feeders != 2) return plan;   // the feeders' cursor looks two nodes ahead
+  if (best_score < 0 || !ring_kernel_pick<0>(plan.ring, plan.feeders, plan.lds.pi_stride != 0)) return plan;   // shape not built
   plan.ok = best_score >= 0;
   return plan;
 }
@@ -324,10 +328,13 @@ RingKernel ring_kernel_pick(int ring, int feeders, bool pib_lds) {
     case 1042: return relax_ring_kernel<4, 2, HALF, 1>;
     case 1081: return relax_ring_kernel<8, 1, HALF, 1>;
     case 1082: return relax_ring_kernel<8, 2, HALF, 1>;
+    case 1083: return relax_ring_kernel<8, 3, HALF, 1>;
+    case 1084: return relax_ring_kernel<8, 4, HALF, 1>;
     case 81:   return relax_ring_kernel<8, 1, HALF, 0>;
     case 82:   return relax_ring_kernel<8, 2, HALF, 0>;
     case 161:  return relax_ring_kernel<16, 1, HALF, 0>;
     case 162:  return relax_ring_kernel<16, 2, HALF, 0>;
+    case 164:  return relax_ring_kernel<16, 4, HALF, 0>;
     case 321:  return relax_ring_kernel<32, 1, HALF, 0>;
     case 322:  return relax_ring_kernel<32, 2, HALF, 0>;
     default:   return nullptr;

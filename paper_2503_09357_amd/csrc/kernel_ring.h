@@ -102,7 +102,7 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
   constexpr int kFeeders = FEEDERS;
   extern __shared__ __align__(16) unsigned char lds[];
   static_assert((RING & (RING - 1)) == 0, "RING must be a power of two");
-  static_assert(FEEDERS <= 2 && RING >= FEEDERS, "the feeders' cursor looks two nodes ahead");
+  static_assert(RING >= FEEDERS, "every feeder needs a slot of its own");
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63;
@@ -381,20 +381,21 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
     uint32_t k = k0;
     const uint32_t w0 = has_ops ? (uint32_t)list[k0] : 0u;
     uint32_t addr = w0 & vmask, rem = w0 >> vbits;
-    uint32_t id1 = has_ops ? (uint32_t)list[min(k0 + 1u, klast)] : 0u;
-    uint32_t id2 = has_ops ? (uint32_t)list[min(k0 + 2u, klast)] : 0u;
-    // move the cursor one part ahead; returns true when it entered the next node (or left the list)
-    auto advance = [&](uint32_t next_id) -> bool {
+    // list entries of the next kFeeders nodes: one trip moves the cursor by kFeeders parts, so it can
+    // enter at most that many nodes
+    uint32_t ids[kFeeders];
+#pragma unroll
+    for (int i = 0; i < kFeeders; ++i) ids[i] = has_ops ? (uint32_t)list[min(k0 + 1u + (uint32_t)i, klast)] : 0u;
+    // move the cursor one part ahead
+    auto advance = [&]() {
       const bool in_node = rem != 0;
-      addr = in_node ? addr + n_plane : (next_id & vmask);
-      rem = in_node ? rem - 1u : (next_id >> vbits);
+      addr = in_node ? addr + n_plane : (ids[0] & vmask);
+      rem = in_node ? rem - 1u : (ids[0] >> vbits);
       k += in_node ? 0u : 1u;
-      return !in_node;
+#pragma unroll
+      for (int i = 0; i + 1 < kFeeders; ++i) ids[i] = in_node ? ids[i] : ids[i + 1];
     };
-    for (int i = 0; i < f; ++i) {                           // feeder f starts at its first own part
-      const bool crossed = advance(id1);
-      id1 = crossed ? id2 : id1;
-    }
+    for (int i = 0; i < f; ++i) advance();                  // feeder f starts at its first own part
     struct Entry { uint4 rec; uint32_t q0, q1, q2, q3, fl; };   // fl: 1 valid, 2 last part of the lane
     constexpr int kStages = PIBL ? 2 : 3;
     Entry E[kStages];
@@ -419,15 +420,12 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
         // (1) move the cursor past the part admitted in the previous trip and the other feeders' parts
         if (pending) {
 #pragma unroll
-          for (int a = 0; a < kFeeders; ++a) {
-            const bool crossed = advance(id1);
-            id1 = crossed ? id2 : id1;
-          }
+          for (int a = 0; a < kFeeders; ++a) advance();
           aseq += kFeeders;
         }
-        // (2) ids of the next two nodes (reloaded every trip; consumed one trip later at the earliest)
-        id1 = list[min(k + 1u, klast)];
-        id2 = list[min(k + 2u, klast)];
+        // (2) entries of the next nodes (reloaded every trip; consumed one trip later at the earliest)
+#pragma unroll
+        for (int i = 0; i < kFeeders; ++i) ids[i] = list[min(k + 1u + (uint32_t)i, klast)];
         // (3) admission
         pending = (k <= klast) &&
                   *(lds_vu32_t *)(ring_lane + ((aseq & (uint32_t)(RING - 1)) << 10) + 12) == (((aseq - (uint32_t)RING) << 16) | kNotDone16);

@@ -214,6 +214,8 @@ def _with_env(env, fn):
     {"DAGSCHED_RING_FEEDERS": 2, "DAGSCHED_RING_SLOTS": 8, "DAGSCHED_RING_PIB_LDS": 1},
     {"DAGSCHED_RING_FEEDERS": 1, "DAGSCHED_RING_SLOTS": 8, "DAGSCHED_RING_PIB_LDS": 1, "DAGSCHED_RING_G": 1},
     {"DAGSCHED_RING_FEEDERS": 2, "DAGSCHED_RING_SLOTS": 4, "DAGSCHED_RING_PIB_LDS": 1},
+    {"DAGSCHED_RING_FEEDERS": 3, "DAGSCHED_RING_SLOTS": 8, "DAGSCHED_RING_PIB_LDS": 1},
+    {"DAGSCHED_RING_FEEDERS": 4, "DAGSCHED_RING_SLOTS": 16, "DAGSCHED_RING_PIB_LDS": 0},
     {"DAGSCHED_RING_FEEDERS": 2, "DAGSCHED_RING_SLOTS": 8, "DAGSCHED_RING_PIB_LDS": 0},
     {"DAGSCHED_RING_FEEDERS": 2, "DAGSCHED_RING_SLOTS": 16, "DAGSCHED_RING_PIB_LDS": 0},
     {"DAGSCHED_RING_FEEDERS": 1, "DAGSCHED_RING_SLOTS": 32, "DAGSCHED_RING_PIB_LDS": 0},
