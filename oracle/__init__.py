@@ -49,6 +49,11 @@ def _load():
                                                  vp, vp, vp, vp]
         lib.dagsched_oracle_schedule.restype = ctypes.c_int
         lib.dagsched_oracle_schedule.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        lib.dagsched_oracle_evaluate_mem.restype = ctypes.c_int
+        lib.dagsched_oracle_evaluate_mem.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, i32, i64, vp, vp,
+                                                     i64, i64, vp, vp, vp, vp]
+        lib.dagsched_oracle_schedule_mem.restype = ctypes.c_int
+        lib.dagsched_oracle_schedule_mem.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         _lib = lib
     return _lib
 
@@ -62,9 +67,10 @@ def _ptr(a):
 
 
 class Problem:
-    """The candidate-independent part: DAG CSR, durations, comm matrix, memory deltas."""
+    """The candidate-independent part: DAG CSR, durations, comm matrix, memory deltas, and optionally the
+    static memory W_i of every operation (eq. (16)) and the memory limit of every machine."""
 
-    def __init__(self, n_devices, row_ptr, col_idx, dur, comm, mem_delta):
+    def __init__(self, n_devices, row_ptr, col_idx, dur, comm, mem_delta, weight=None, mem_limit=None):
         self.P = int(n_devices)
         self.row_ptr = _c(row_ptr, np.int32)
         self.col_idx = _c(col_idx, np.int32)
@@ -73,10 +79,19 @@ class Problem:
         self.mem_delta = _c(mem_delta, np.int64)
         self.N = len(self.row_ptr) - 1
         self.E = len(self.col_idx)
+        self.weight = None if weight is None else _c(weight, np.int64)
+        self.mem_limit = None if mem_limit is None else _c(mem_limit, np.int64)
+        assert self.weight is None or self.weight.shape == (self.N,)
+        assert self.mem_limit is None or self.mem_limit.shape == (self.P,)
 
     @classmethod
     def of(cls, w) -> "Problem":
-        return cls(w.n_devices, w.row_ptr, w.col_idx, w.dur, w.comm, w.mem_delta)
+        return cls(w.n_devices, w.row_ptr, w.col_idx, w.dur, w.comm, w.mem_delta,
+                   getattr(w, "weight", None), getattr(w, "mem_limit", None))
+
+    def _mem(self):
+        return (None if self.weight is None else _ptr(self.weight),
+                None if self.mem_limit is None else _ptr(self.mem_limit))
 
     def _head(self):
         return (self.N, self.E, self.P, _ptr(self.row_ptr), _ptr(self.col_idx), _ptr(self.dur),
@@ -109,9 +124,9 @@ class Problem:
         rcs = []
 
         def run(first, count):
-            rcs.append(lib.dagsched_oracle_evaluate(*self._head(), layout, C, _ptr(placement), _ptr(rank),
-                                                    first, count, _ptr(makespan), _ptr(bubble), _ptr(peak),
-                                                    _ptr(flags)))
+            rcs.append(lib.dagsched_oracle_evaluate_mem(*self._head(), *self._mem(), layout, C, _ptr(placement),
+                                                        _ptr(rank), first, count, _ptr(makespan), _ptr(bubble),
+                                                        _ptr(peak), _ptr(flags)))
 
         threads = max(1, min(int(threads), C if C else 1))
         if threads == 1:
@@ -135,7 +150,8 @@ class Problem:
         rank = _c(rank, np.int32).reshape(-1)
         assert placement.shape == (self.N,) and rank.shape == (self.N,)
         out = [np.zeros(self.N, dtype=np.int64) for _ in range(4)]
-        rc = _load().dagsched_oracle_schedule(*self._head(), _ptr(placement), _ptr(rank), *[_ptr(o) for o in out])
+        rc = _load().dagsched_oracle_schedule_mem(*self._head(), self._mem()[0], _ptr(placement), _ptr(rank),
+                                                  *[_ptr(o) for o in out])
         if rc < 0:
             raise OracleError(rc)
         return (rc, *out)

@@ -27,8 +27,15 @@
  *     peak_mem[j] = max(0, max_k sum_{t<k} A_{list_j[t]})               eqs. (17)-(19): m+ = m- + A,
  *                   the level after an operation is the level before the next one on that machine;
  *                   the level starts at 0 and 0 takes part in the maximum
- *     flags       = 2 BAD_PLACEMENT | 4 BAD_RANK | 1 CYCLIC | 0 (exactly one value, tested in that
- *                   order); flagged candidates return -1 in every other output.
+ *     flags       = 2 BAD_PLACEMENT | 4 BAD_RANK | 1 CYCLIC | 16 OVER_MEMORY | 0 (exactly one value,
+ *                   tested in that order); flagged candidates return -1 in every other output.
+ *
+ * Optional static memory (eq. (16)): with weights W_i >= 0 the level of machine j starts at
+ * base_j = sum of W_i over the operations placed on j (the least m- that eq. (16) allows for the
+ * machine's first operation), so peak_mem[j] = base_j + max(0, max_k sum_{t<k} A).  With limits
+ * M_j (the memory limit of a machine, Sec. III problem statement; the paper prints no inequality
+ * for it) a candidate that is otherwise feasible and has peak_mem[j] > M_j for some j is flagged
+ * OVER_MEMORY.
  *
  * A candidate is CYCLIC when DAG edges and chain edges together contain a directed cycle
  * (eqs. (5), (7), (8) cannot hold together).  The test is structural (Kahn's algorithm pops
@@ -49,7 +56,7 @@
 #include <string.h>
 
 enum { OR_OK = 0, OR_EINVAL = -1, OR_ECYCLE = -2, OR_EOVERFLOW = -3, OR_ENOMEM = -4 };
-enum { FLAG_CYCLIC = 1, FLAG_BAD_PLACEMENT = 2, FLAG_BAD_RANK = 4 };
+enum { FLAG_CYCLIC = 1, FLAG_BAD_PLACEMENT = 2, FLAG_BAD_RANK = 4, FLAG_OVER_MEMORY = 16 };
 enum { LAYOUT_CAND_MAJOR = 0, LAYOUT_CAND_MINOR = 1 };
 
 /*
@@ -144,6 +151,7 @@ static int scratch_alloc(scratch_t *w, int32_t N, int32_t P) {
  */
 static int32_t evaluate_one(int32_t N, int32_t P, const int32_t *row_ptr, const int32_t *col_idx,
                             const int32_t *dur, const int32_t *comm, const int64_t *mem_delta,
+                            const int64_t *weight, const int64_t *limit,
                             const int32_t *pl, const int32_t *rk, int64_t stride, scratch_t *w,
                             int32_t *makespan, int64_t *bubble, int64_t *peak, int64_t peak_stride) {
   /* 1. placement in range (eq. (6): exactly one machine of J) */
@@ -200,15 +208,20 @@ static int32_t evaluate_one(int32_t N, int32_t P, const int32_t *row_ptr, const 
   }
   *makespan = (int32_t)z;
   *bubble = (int64_t)P * z - sum_dur;
+  int32_t over = 0;
   for (int32_t j = 0; j < P; ++j) {
-    int64_t level = 0, top = 0;                        /* eqs. (17)-(19) along the chain */
+    int64_t base = 0;                                  /* eq. (16): static memory of everything placed on j */
+    if (weight)
+      for (int32_t k = 0; k < w->cnt[j]; ++k) base += weight[w->list[w->off[j] + k]];
+    int64_t level = base, top = base;                  /* eqs. (17)-(19) along the chain */
     for (int32_t k = 0; k < w->cnt[j]; ++k) {
       level += mem_delta[w->list[w->off[j] + k]];
       if (level > top) top = level;
     }
     peak[j * peak_stride] = top;
+    if (limit && top > limit[j]) over = 1;
   }
-  return 0;
+  return over ? FLAG_OVER_MEMORY : 0;
 }
 
 /*
@@ -216,14 +229,18 @@ static int32_t evaluate_one(int32_t N, int32_t P, const int32_t *row_ptr, const 
  * layout 0: placement[c*N + v], peak_mem[c*P + j];  layout 1: placement[v*n_cand + c], peak_mem[j*n_cand + c].
  * All pointers are host memory; outputs are indexed by the absolute candidate number.
  */
-int dagsched_oracle_evaluate(int32_t N, int32_t E, int32_t P, const int32_t *row_ptr,
-                             const int32_t *col_idx, const int32_t *dur, const int32_t *comm,
-                             const int64_t *mem_delta, int32_t layout, int64_t n_cand,
-                             const int32_t *placement, const int32_t *rank, int64_t first,
-                             int64_t count, int32_t *makespan, int64_t *bubble, int64_t *peak_mem,
-                             int32_t *flags) {
+int dagsched_oracle_evaluate_mem(int32_t N, int32_t E, int32_t P, const int32_t *row_ptr,
+                                 const int32_t *col_idx, const int32_t *dur, const int32_t *comm,
+                                 const int64_t *mem_delta, const int64_t *weight, const int64_t *mem_limit,
+                                 int32_t layout, int64_t n_cand,
+                                 const int32_t *placement, const int32_t *rank, int64_t first,
+                                 int64_t count, int32_t *makespan, int64_t *bubble, int64_t *peak_mem,
+                                 int32_t *flags) {
   int rc = dagsched_oracle_check_problem(N, E, P, row_ptr, col_idx, dur, comm, mem_delta);
   if (rc != OR_OK) return rc;
+  if (weight)
+    for (int32_t v = 0; v < N; ++v)
+      if (weight[v] < 0) return OR_EINVAL;
   if (layout != LAYOUT_CAND_MAJOR && layout != LAYOUT_CAND_MINOR) return OR_EINVAL;
   if (n_cand < 0 || first < 0 || count < 0 || first + count > n_cand) return OR_EINVAL;
   if (count == 0) return OR_OK;
@@ -245,8 +262,8 @@ int dagsched_oracle_evaluate(int32_t N, int32_t E, int32_t P, const int32_t *row
     }
     int32_t z = -1;
     int64_t b = -1;
-    int32_t f = evaluate_one(N, P, row_ptr, col_idx, dur, comm, mem_delta, pl, rk, stride, &w, &z,
-                             &b, peak, peak_stride);
+    int32_t f = evaluate_one(N, P, row_ptr, col_idx, dur, comm, mem_delta, weight, mem_limit, pl, rk, stride,
+                             &w, &z, &b, peak, peak_stride);
     flags[c] = f;
     if (f != 0) {
       z = -1; b = -1;
@@ -259,16 +276,29 @@ int dagsched_oracle_evaluate(int32_t N, int32_t E, int32_t P, const int32_t *row
   return OR_OK;
 }
 
+/* The same without static memory and without limits. */
+int dagsched_oracle_evaluate(int32_t N, int32_t E, int32_t P, const int32_t *row_ptr,
+                             const int32_t *col_idx, const int32_t *dur, const int32_t *comm,
+                             const int64_t *mem_delta, int32_t layout, int64_t n_cand,
+                             const int32_t *placement, const int32_t *rank, int64_t first,
+                             int64_t count, int32_t *makespan, int64_t *bubble, int64_t *peak_mem,
+                             int32_t *flags) {
+  return dagsched_oracle_evaluate_mem(N, E, P, row_ptr, col_idx, dur, comm, mem_delta, NULL, NULL, layout, n_cand,
+                                      placement, rank, first, count, makespan, bubble, peak_mem, flags);
+}
+
 /*
  * The full earliest-start schedule of ONE candidate (placement[N], rank[N]), for the constraint
  * checker: start/end times (eqs. (2),(3)) and memory level before/after every operation
- * (m-, m+ of eqs. (16)-(19), base level 0).  Returns the problem code (<0) or the flag (>= 0);
- * the arrays are filled only when the result is 0.
+ * (m-, m+ of eqs. (16)-(19); the base level of a machine is the static memory placed on it, 0
+ * when weight is NULL).  Returns the problem code (<0) or the flag (>= 0); the arrays are filled
+ * only when the result is 0.
  */
-int dagsched_oracle_schedule(int32_t N, int32_t E, int32_t P, const int32_t *row_ptr,
-                             const int32_t *col_idx, const int32_t *dur, const int32_t *comm,
-                             const int64_t *mem_delta, const int32_t *placement, const int32_t *rank,
-                             int64_t *start, int64_t *end, int64_t *m_minus, int64_t *m_plus) {
+int dagsched_oracle_schedule_mem(int32_t N, int32_t E, int32_t P, const int32_t *row_ptr,
+                                 const int32_t *col_idx, const int32_t *dur, const int32_t *comm,
+                                 const int64_t *mem_delta, const int64_t *weight, const int32_t *placement,
+                                 const int32_t *rank, int64_t *start, int64_t *end, int64_t *m_minus,
+                                 int64_t *m_plus) {
   int rc = dagsched_oracle_check_problem(N, E, P, row_ptr, col_idx, dur, comm, mem_delta);
   if (rc != OR_OK) return rc;
   if (!placement || !rank || !start || !end || !m_minus || !m_plus) return OR_EINVAL;
@@ -280,12 +310,14 @@ int dagsched_oracle_schedule(int32_t N, int32_t E, int32_t P, const int32_t *row
   if (!peak) { scratch_free(&w); return OR_ENOMEM; }
   int32_t z;
   int64_t b;
-  int32_t f = evaluate_one(N, P, row_ptr, col_idx, dur, comm, mem_delta, placement, rank, 1, &w, &z,
-                           &b, peak, 1);
+  int32_t f = evaluate_one(N, P, row_ptr, col_idx, dur, comm, mem_delta, weight, NULL, placement, rank, 1, &w,
+                           &z, &b, peak, 1);
   if (f == 0) {
     for (int32_t v = 0; v < N; ++v) { start[v] = w.start[v]; end[v] = w.end[v]; }
     for (int32_t j = 0; j < P; ++j) {
       int64_t level = 0;
+      if (weight)
+        for (int32_t k = 0; k < w.cnt[j]; ++k) level += weight[w.list[w.off[j] + k]];   /* eq. (16) */
       for (int32_t k = 0; k < w.cnt[j]; ++k) {
         int32_t v = w.list[w.off[j] + k];
         m_minus[v] = level;
@@ -297,4 +329,12 @@ int dagsched_oracle_schedule(int32_t N, int32_t E, int32_t P, const int32_t *row
   free(peak);
   scratch_free(&w);
   return f;
+}
+
+int dagsched_oracle_schedule(int32_t N, int32_t E, int32_t P, const int32_t *row_ptr,
+                             const int32_t *col_idx, const int32_t *dur, const int32_t *comm,
+                             const int64_t *mem_delta, const int32_t *placement, const int32_t *rank,
+                             int64_t *start, int64_t *end, int64_t *m_minus, int64_t *m_plus) {
+  return dagsched_oracle_schedule_mem(N, E, P, row_ptr, col_idx, dur, comm, mem_delta, NULL, placement, rank, start,
+                                      end, m_minus, m_plus);
 }

@@ -157,7 +157,7 @@ def critical_path(row_ptr, col_idx, dur, edge_delay=None) -> int:
 
 
 def check_constraints(P, row_ptr, col_idx, dur, comm, mem_delta, placement, rank, start, end, m_minus, m_plus,
-                      makespan) -> None:
+                      makespan, weight=None) -> None:
     """Assert the rows of the MIP with x, y, u fixed by (placement, rank), plus minimality."""
     n = len(dur)
     comm = np.asarray(comm).reshape(P, P)
@@ -195,11 +195,13 @@ def check_constraints(P, row_ptr, col_idx, dur, comm, mem_delta, placement, rank
             delay = int(comm[placement[u], placement[v]]) if placement[u] != placement[v] else 0
             bounds.append(int(end[u]) + delay)
         assert start[v] == max(bounds)
-    # eqs. (17)-(19): m+_i - m-_i = A_i ; m-_next = m+_prev along each machine ; base level 0
-    for lst in lists:
+    # eq. (16): m-_i >= sum of the static memory W of everything on i's machine, tight for the machine's first
+    # operation (base level 0 without weights); eqs. (17)-(19): m+_i - m-_i = A_i ; m-_next = m+_prev
+    for j, lst in enumerate(lists):
+        base = 0 if weight is None else sum(int(weight[v]) for v in range(n) if placement[v] == j)
         for r, v in enumerate(lst):
             assert m_plus[v] - m_minus[v] == mem_delta[v]
             if r == 0:
-                assert m_minus[v] == 0
+                assert m_minus[v] == base
             else:
                 assert m_minus[v] == m_plus[lst[r - 1]]

@@ -440,3 +440,90 @@ def test_empty_batch_and_isolated_nodes():
     z, b, pk, f = prob.evaluate(np.array([[0, 0, 0]]), np.array([[2, 0, 1]]))
     assert f[0] == 0 and z[0] == 15 and b[0] == 15 and pk[0].tolist() == [2, 0]
     # order 1, 2, 0 on machine 0: levels 2, -1, 0 -> peak 2; machine 1 is empty: peak 0
+
+
+# --------------------------------------------------------------------------- static memory and limits (eq. (16))
+
+def test_static_memory_shifts_every_peak_by_the_machine_base():
+    """Eq. (16): the level of a machine starts at the sum of the static memory W of what is placed on it.
+    Pinned against numpy: base_j = sum of W over placement == j; every other output is unchanged."""
+    rng = np.random.default_rng(1601)
+    for _ in range(6):
+        w = W.random_instance(rng, int(rng.integers(5, 60)), int(rng.integers(1, 7)), 25, frac_bad=0.2, frac_arbitrary=0.2)
+        weight = rng.integers(0, 50, w.n_nodes).astype(np.int64)
+        plain = oracle.Problem.of(w).evaluate(w.placement, w.rank)
+        prob = oracle.Problem(w.n_devices, w.row_ptr, w.col_idx, w.dur, w.comm, w.mem_delta, weight=weight)
+        z, b, pk, f = prob.evaluate(w.placement, w.rank)
+        assert (z == plain[0]).all() and (b == plain[1]).all() and (f == plain[3]).all()
+        for c in range(w.n_cand):
+            if f[c] == 0:
+                base = np.bincount(w.placement[c], weights=weight, minlength=w.n_devices).astype(np.int64)
+                assert (pk[c] == plain[2][c] + base).all()
+            else:
+                assert (pk[c] == -1).all()
+
+
+def test_static_memory_hand_example():
+    """Two machines, three operations: machine 0 runs a (W=5, A=+2) then c (W=1, A=-1); machine 1 runs b (W=7, A=+3).
+    Levels: machine 0 starts at 6, goes 8, 7 -> peak 8; machine 1 starts at 7, goes 10 -> peak 10."""
+    rp, ci = W.csr_from_edges(3, [0, 1], [1, 2])
+    prob = oracle.Problem(2, rp, ci, [1, 1, 1], [[0, 1], [1, 0]], [2, 3, -1], weight=[5, 7, 1])
+    z, b, pk, f = prob.evaluate(np.array([[0, 1, 0]]), np.array([[0, 0, 1]]))
+    assert f[0] == 0 and z[0] == 5 and pk[0].tolist() == [8, 10]
+    flag, s, e, mm, mp = prob.schedule([0, 1, 0], [0, 0, 1])
+    assert flag == 0 and mm.tolist() == [6, 7, 8] and mp.tolist() == [8, 10, 7]
+    # limits: exactly at the peak is allowed, one below is not; the flag wins over nothing else
+    for lim, want in (([8, 10], 0), ([7, 10], 16), ([8, 9], 16), ([0, 0], 16)):
+        pl = oracle.Problem(2, rp, ci, [1, 1, 1], [[0, 1], [1, 0]], [2, 3, -1], weight=[5, 7, 1], mem_limit=lim)
+        z2, b2, pk2, f2 = pl.evaluate(np.array([[0, 1, 0]]), np.array([[0, 0, 1]]))
+        assert f2[0] == want
+        if want:
+            assert z2[0] == -1 and b2[0] == -1 and (pk2 == -1).all()
+        else:
+            assert z2[0] == 5 and pk2[0].tolist() == [8, 10]
+
+
+def test_memory_limit_flag_equals_a_compare_on_the_unlimited_peaks():
+    """OVER_MEMORY is exactly "some peak above its limit" among candidates that carry no other flag, and it
+    never hides BAD_PLACEMENT, BAD_RANK or CYCLIC."""
+    rng = np.random.default_rng(1602)
+    for _ in range(6):
+        w = W.random_instance(rng, int(rng.integers(8, 70)), int(rng.integers(1, 6)), 40, frac_bad=0.3, frac_arbitrary=0.3)
+        weight = rng.integers(0, 9, w.n_nodes).astype(np.int64)
+        free = oracle.Problem(w.n_devices, w.row_ptr, w.col_idx, w.dur, w.comm, w.mem_delta, weight=weight)
+        z0, b0, pk0, f0 = free.evaluate(w.placement, w.rank)
+        ok = f0 == 0
+        limit = np.quantile(pk0[ok], 0.6, axis=0).astype(np.int64) if ok.any() else np.zeros(w.n_devices, np.int64)
+        lim = oracle.Problem(w.n_devices, w.row_ptr, w.col_idx, w.dur, w.comm, w.mem_delta, weight=weight, mem_limit=limit)
+        z, b, pk, f = lim.evaluate(w.placement, w.rank)
+        over = ok & (pk0 > limit[None, :]).any(axis=1)
+        assert (f[~ok] == f0[~ok]).all()
+        assert (f[over] == 16).all() and (f[ok & ~over] == 0).all()
+        assert (z[ok & ~over] == z0[ok & ~over]).all() and (pk[ok & ~over] == pk0[ok & ~over]).all()
+        assert (z[over] == -1).all() and (b[over] == -1).all() and (pk[over] == -1).all()
+
+
+def test_constraints_hold_with_static_memory():
+    rng = np.random.default_rng(1603)
+    w = W.random_instance(rng, 40, 4, 12)
+    weight = rng.integers(0, 30, w.n_nodes).astype(np.int64)
+    prob = oracle.Problem(w.n_devices, w.row_ptr, w.col_idx, w.dur, w.comm, w.mem_delta, weight=weight)
+    z, b, pk, f = prob.evaluate(w.placement, w.rank)
+    assert (f == 0).sum() >= 3
+    for c in np.flatnonzero(f == 0):
+        flag, s, e, mm, mp = prob.schedule(w.placement[c], w.rank[c])
+        assert flag == 0
+        K.check_constraints(w.n_devices, w.row_ptr, w.col_idx, w.dur, w.comm, w.mem_delta, w.placement[c], w.rank[c],
+                             s, e, mm, mp, int(z[c]), weight=weight)
+        lists = K.device_lists(w.n_devices, w.placement[c], w.rank[c])
+        for j, lst in enumerate(lists):
+            levels = [int(np.sum(weight[w.placement[c] == j]))] + [int(mp[v]) for v in lst]
+            assert pk[c, j] == max(levels)
+
+
+def test_negative_static_memory_is_rejected():
+    rp, ci = W.csr_from_edges(2, [0], [1])
+    prob = oracle.Problem(1, rp, ci, [1, 1], [[0]], [0, 0], weight=[1, -1])
+    with pytest.raises(oracle.OracleError):
+        prob.evaluate(np.array([[0, 0]]), np.array([[0, 1]]))
+
