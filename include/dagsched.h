@@ -16,7 +16,9 @@
  *              differ, else 0                                    (eqs. (1)-(3), (7), (11)-(13))
  *   bubble     P * z - sum_i D^o_i  (idle time of all P machines inside [0, z])
  *   peak_mem   per machine, the maximum over prefixes of its order of the running sum of A_i,
- *              the empty prefix (level 0) included                (eqs. (17)-(19))
+ *              the empty prefix included, on top of the machine's base level: the static memory
+ *              W_i of everything placed on it (eq. (16)), 0 when no weights are given
+ *                                                                 (eqs. (16)-(19))
  *   flags      0, or exactly one of DAGSCHED_FLAG_*; a flagged candidate has makespan = bubble =
  *              every peak_mem entry = -1.
  *
@@ -37,7 +39,7 @@ typedef struct dagsched dagsched_t; /* opaque, owned by the library */
 /* Return codes of create / validate / evaluate. */
 enum {
   DAGSCHED_OK = 0,
-  DAGSCHED_EINVAL = -1,    /* null pointer, size out of range, malformed CSR, negative dur / comm, bad layout,
+  DAGSCHED_EINVAL = -1,    /* null pointer, size out of range, malformed CSR, negative dur / comm / weight, bad layout,
                               n_cand > max_candidates */
   DAGSCHED_ECYCLE = -2,    /* the operator graph itself is cyclic (Sec. III requires a DAG) */
   DAGSCHED_EOVERFLOW = -3, /* sum(dur) + (N-1) * max off-diagonal comm > INT32_MAX: int32 times would not be exact */
@@ -52,8 +54,11 @@ enum {
   DAGSCHED_FLAG_BAD_RANK = 4,      /* some machine's ranks are not exactly {0..n_j-1}     (eqs. (7)-(8)) */
   DAGSCHED_FLAG_CYCLIC = 1,        /* DAG edges + chain edges contain a directed cycle: eqs. (5), (7), (8)
                                       cannot hold together.  Structural test, zero-duration cycles included. */
-  DAGSCHED_FLAG_INTERNAL = 8       /* a kernel's bounded wait expired; never expected, the candidate's other
+  DAGSCHED_FLAG_INTERNAL = 8,      /* a kernel's bounded wait expired; never expected, the candidate's other
                                       outputs are -1.  Reported instead of hanging the GPU. */
+  DAGSCHED_FLAG_OVER_MEMORY = 16   /* tested last: otherwise feasible, but some peak_mem[j] > mem_limit[j]
+                                      ("not exceeding the memory limit of any machine", Sec. III problem
+                                      statement; the paper prints no inequality for it) */
 };
 
 /* Memory layout of placement, rank and peak_mem. */
@@ -83,6 +88,8 @@ typedef struct {
   int32_t max_candidates;   /* capacity of the per-handle device workspace, >= 1                             */
   int32_t layout;           /* DAGSCHED_CAND_MAJOR or DAGSCHED_CAND_MINOR                                     */
   int32_t hip_device;       /* ordinal of the GPU that owns the handle                                       */
+  const int64_t *weight;    /* [N]   W_i >= 0, static memory of operation i (eq. (16)), or NULL: all zero    */
+  const int64_t *mem_limit; /* [P]   memory limit of machine j, or NULL: no limit, OVER_MEMORY never set     */
 } dagsched_desc_t;
 
 /*
@@ -111,7 +118,7 @@ int dagsched_create(const dagsched_desc_t *desc, dagsched_t **out);
  * Asynchronous: enqueues kernels only, performs no host synchronisation and no allocation.
  * Per-candidate problems are reported through flags, never through the return code.
  * Implements, per candidate, validation of x and y (eqs. (6)-(8)), the chain edges u, the
- * max-plus longest path (eqs. (2), (3), (5), (7), (11)-(13)), and the memory levels (eqs. (17)-(19)).
+ * max-plus longest path (eqs. (2), (3), (5), (7), (11)-(13)), and the memory levels (eqs. (16)-(19)).
  */
 int dagsched_evaluate(dagsched_t *h, int32_t n_cand, const int32_t *placement, const int32_t *rank,
                       int32_t *makespan, int64_t *bubble, int64_t *peak_mem, int32_t *flags,

@@ -71,7 +71,7 @@ struct dagsched {
   bool gen_lds_state = false;
   int64_t row_stride = 0;
   int32_t *d_pred_ptr = nullptr, *d_pred_idx = nullptr, *d_dur = nullptr, *d_comm = nullptr;
-  int64_t *d_mem = nullptr;
+  int64_t *d_mem = nullptr, *d_weight = nullptr, *d_limit = nullptr;
   int32_t *ws_list = nullptr, *ws_end = nullptr;
   // ring kernel
   int32_t ring_G = 0, ring_slots = 0, ring_feeders = 1, rec_plane = 0, id_bits = 16, time_scale = 1;
@@ -113,6 +113,9 @@ int validate_desc(const dagsched_desc_t *d, std::vector<int32_t> *pred_ptr, std:
     if (d->dur[v] < 0) return DAGSCHED_EINVAL;
     sum_dur += d->dur[v];
   }
+  if (d->weight)
+    for (int32_t v = 0; v < N; ++v)
+      if (d->weight[v] < 0) return DAGSCHED_EINVAL;
   for (int32_t a = 0; a < P; ++a)
     for (int32_t b = 0; b < P; ++b)
       if (a != b) {
@@ -160,7 +163,7 @@ bool dev_alloc(T **dst, size_t n) {
 
 void free_handle(dagsched *h) {
   if (!h) return;
-  void *bufs[] = {h->d_pred_ptr, h->d_pred_idx, h->d_dur, h->d_comm, h->d_mem, h->ws_list, h->ws_end, h->d_rec,
+  void *bufs[] = {h->d_pred_ptr, h->d_pred_idx, h->d_dur, h->d_comm, h->d_mem, h->d_weight, h->d_limit, h->ws_list, h->ws_end, h->d_rec,
                   h->d_comm_scaled, h->d_nparts, h->ws_list16, h->ws_pib, h->d_fb_count, h->d_fb_list, h->ws_tp, h->ws_tr};
   for (void *b : bufs)
     if (b) (void)hipFree(b);
@@ -363,6 +366,7 @@ void launch_general(dagsched *h, int32_t n_cand, const int32_t *pl, const int32_
   p.N = h->N; p.P = h->P; p.Pseg = h->Pseg; p.G = h->gen_G; p.C = n_cand;
   p.row_stride = h->row_stride;
   p.pred_ptr = h->d_pred_ptr; p.pred_idx = h->d_pred_idx; p.dur = h->d_dur; p.comm = h->d_comm; p.mem_delta = h->d_mem;
+  p.weight = h->d_weight; p.mem_limit = h->d_limit;
   p.sum_dur = h->sum_dur;
   p.placement = pl; p.rank = rk;
   p.ws_list = h->ws_list; p.ws_end = h->ws_end;
@@ -397,6 +401,7 @@ int launch_evaluate(dagsched *h, int32_t n_cand, const int32_t *placement, const
     p.optimistic = optimistic ? 1 : 0;
     p.list_stride = h->list_stride;
     p.rec = h->d_rec; p.rec_plane = h->rec_plane; p.id_bits = h->id_bits; p.nparts = h->d_nparts; p.comm = h->d_comm_scaled; p.mem_delta = h->d_mem;
+    p.weight = h->d_weight; p.mem_limit = h->d_limit;
     p.sum_dur = h->sum_dur; p.time_scale = h->time_scale;
     p.placement = pl; p.rank = rk;
     p.ws_list = h->ws_list16; p.ws_pib = h->ws_pib; p.pib_stride = h->pib_stride;
@@ -456,7 +461,9 @@ int dagsched_create(const dagsched_desc_t *desc, dagsched_t **out) {
   if (!env_int("DAGSCHED_FORCE_GENERAL", 0)) plan = plan_ring(desc, pred_ptr, pred_idx, sum_dur, lds_max);
   const bool need_general = !plan.ok || !plan.exact;
 
-  bool ok = upload(&h->d_mem, desc->mem_delta, (size_t)h->N);
+  bool ok = upload(&h->d_mem, desc->mem_delta, (size_t)h->N) &&
+            (!desc->weight || upload(&h->d_weight, desc->weight, (size_t)h->N)) &&
+            (!desc->mem_limit || upload(&h->d_limit, desc->mem_limit, (size_t)h->P));
   if (ok && need_general) {
     h->gen_G = kWave / h->Pseg;
     const int64_t lds_need = (int64_t)h->gen_G * h->N * 4;

@@ -11,13 +11,14 @@ namespace dagsched_dev {
 constexpr int kWave = 64;
 
 // bits collected per candidate while it is being evaluated; turned into one DAGSCHED_FLAG_* at the end
-constexpr int kBitCyclic = 1, kBitBadPlacement = 2, kBitBadRank = 4, kBitInternal = 8;
+constexpr int kBitCyclic = 1, kBitBadPlacement = 2, kBitBadRank = 4, kBitInternal = 8, kBitOverMemory = 16;
 
 __device__ __forceinline__ int flag_from_bits(int bits) {
   return (bits & kBitBadPlacement) ? DAGSCHED_FLAG_BAD_PLACEMENT
        : (bits & kBitBadRank)      ? DAGSCHED_FLAG_BAD_RANK
        : (bits & kBitInternal)     ? DAGSCHED_FLAG_INTERNAL
        : (bits & kBitCyclic)       ? DAGSCHED_FLAG_CYCLIC
+       : (bits & kBitOverMemory)   ? DAGSCHED_FLAG_OVER_MEMORY
                                    : DAGSCHED_FLAG_OK;
 }
 

@@ -20,6 +20,8 @@ struct GeneralParams {
   const int32_t *dur;          // [N]
   const int32_t *comm;         // [P*P]
   const int64_t *mem_delta;    // [N]
+  const int64_t *weight;       // [N] static memory per operation (eq. (16)), or NULL
+  const int64_t *mem_limit;    // [P] memory limit per machine, or NULL
   int64_t sum_dur;
   const int32_t *placement;    // [C][N] candidate-major
   const int32_t *rank;         // [C][N]
@@ -120,7 +122,8 @@ __global__ __launch_bounds__(kWave) void relax_general_kernel(GeneralParams p) {
     pe = p.pred_ptr[v + 1];
   }
   int32_t acc = 0;              // time at which machine j becomes free (end of its previous operation)
-  int64_t level = 0, peak = 0;  // running memory level on machine j and its maximum
+  int64_t level = 0, peak = 0;  // running memory level on machine j above its base level, and its maximum
+  int64_t base = 0;             // static memory of everything placed on machine j (eq. (16))
   const uint64_t segmask = ((Pseg == kWave) ? ~0ull : ((1ull << Pseg) - 1ull)) << (g * Pseg);
   const int64_t max_rounds = (int64_t)N + p.pred_ptr[N] + 4;
 
@@ -144,6 +147,7 @@ __global__ __launch_bounds__(kWave) void relax_general_kernel(GeneralParams p) {
         acc = e;
         level += p.mem_delta[v];      // eq. (19); the next operation starts from this level (eqs. (17)-(18))
         peak = max(peak, level);
+        if (p.weight) base += p.weight[v];
         ++k;
         progressed = true;
         if (k < kend) {
@@ -164,6 +168,7 @@ __global__ __launch_bounds__(kWave) void relax_general_kernel(GeneralParams p) {
     }
     if (__ballot(active) == 0) break;
   }
+  if (p.mem_limit && lane_valid && s_flag[g] == 0 && base + peak > p.mem_limit[j]) atomicOr(&s_flag[g], kBitOverMemory);
   __syncthreads();
 
   // reductions and outputs
@@ -171,7 +176,7 @@ __global__ __launch_bounds__(kWave) void relax_general_kernel(GeneralParams p) {
   for (int d = 1; d < Pseg; d <<= 1) z = max(z, __shfl_xor(z, d, Pseg));
   if (lane_valid) {
     const int flag = flag_from_bits(s_flag[g]);
-    p.out.peak_mem[c * p.out.peak_stride_c + j * p.out.peak_stride_j] = flag ? -1 : peak;
+    p.out.peak_mem[c * p.out.peak_stride_c + j * p.out.peak_stride_j] = flag ? -1 : base + peak;
     if (j == 0) {
       p.out.makespan[c] = flag ? -1 : z;
       p.out.bubble[c] = flag ? -1 : (int64_t)P * z - p.sum_dur;

@@ -81,6 +81,8 @@ struct RingParams {
   const uint8_t *nparts;               // [N] parts per node, or NULL when every node has one part
   const int32_t *comm;                 // [P*P] channel delays divided by time_scale (all <= 255)
   const int64_t *mem_delta;            // [N]
+  const int64_t *weight;               // [N] static memory per operation (eq. (16)), or NULL
+  const int64_t *mem_limit;            // [P] memory limit per machine, or NULL
   int64_t sum_dur;                     // in original units
   int32_t time_scale;                  // gcd of every duration and delay
   const int32_t *placement, *rank;     // [C][N]
@@ -463,18 +465,23 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
     const uint32_t vmask = (1u << p.id_bits) - 1u;
     const int k0 = has_ops ? offw[ql] : 0;
     const int kend = has_ops ? k0 + cntw[ql] : 0;
-    int64_t level = 0, peak = 0;
+    int64_t level = 0, peak = 0, base = 0;                  // level above the machine's base; base = static memory on it (eq. (16))
     for (int k = k0; __ballot(k < kend) != 0; k += 4) {
       uint32_t id[4];
-      int64_t m[4];
+      int64_t m[4], wt[4];
 #pragma unroll
       for (int u = 0; u < 4; ++u) id[u] = (k + u < kend) ? ((uint32_t)list[k + u] & vmask) : 0u;
 #pragma unroll
-      for (int u = 0; u < 4; ++u) m[u] = p.mem_delta[id[u]];
+      for (int u = 0; u < 4; ++u) {
+        m[u] = p.mem_delta[id[u]];
+        wt[u] = p.weight ? p.weight[id[u]] : 0;
+      }
 #pragma unroll
       for (int u = 0; u < 4; ++u)
-        if (k + u < kend) { level += m[u]; peak = max(peak, level); }   // eq. (19) along the chain
+        if (k + u < kend) { level += m[u]; peak = max(peak, level); base += wt[u]; }   // eq. (19) along the chain
     }
+    peak += base;
+    if (p.mem_limit && has_ops && peak > p.mem_limit[j]) atomicOr(&flagw[g], kBitOverMemory);
     if (lane_on) peakw[ql] = peak;
   }
   __syncthreads();

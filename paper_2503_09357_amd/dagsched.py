@@ -14,7 +14,7 @@ import numpy as np
 from . import _build
 
 OK, EINVAL, ECYCLE, EOVERFLOW, ENOMEM, EHIP = 0, -1, -2, -3, -4, -5
-FLAG_OK, FLAG_CYCLIC, FLAG_BAD_PLACEMENT, FLAG_BAD_RANK = 0, 1, 2, 4
+FLAG_OK, FLAG_CYCLIC, FLAG_BAD_PLACEMENT, FLAG_BAD_RANK, FLAG_INTERNAL, FLAG_OVER_MEMORY = 0, 1, 2, 4, 8, 16
 CAND_MAJOR, CAND_MINOR = 0, 1
 MAX_DEVICES, MAX_NODES = 64, 65535
 
@@ -26,7 +26,8 @@ class Desc(ctypes.Structure):
     _fields_ = [("n_nodes", ctypes.c_int32), ("n_edges", ctypes.c_int32), ("n_devices", ctypes.c_int32),
                 ("row_ptr", ctypes.c_void_p), ("col_idx", ctypes.c_void_p), ("dur", ctypes.c_void_p),
                 ("comm", ctypes.c_void_p), ("mem_delta", ctypes.c_void_p),
-                ("max_candidates", ctypes.c_int32), ("layout", ctypes.c_int32), ("hip_device", ctypes.c_int32)]
+                ("max_candidates", ctypes.c_int32), ("layout", ctypes.c_int32), ("hip_device", ctypes.c_int32),
+                ("weight", ctypes.c_void_p), ("mem_limit", ctypes.c_void_p)]
 
 
 class Info(ctypes.Structure):
@@ -85,7 +86,7 @@ class _HostProblem:
     """Keeps the contiguous host arrays alive while a Desc points at them."""
 
     def __init__(self, n_devices, row_ptr, col_idx, dur, comm, mem_delta, max_candidates, layout, hip_device,
-                 n_nodes=None, n_edges=None):
+                 n_nodes=None, n_edges=None, weight=None, mem_limit=None):
         self.row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int32)
         self.col_idx = np.ascontiguousarray(col_idx, dtype=np.int32)
         self.dur = np.ascontiguousarray(dur, dtype=np.int32)
@@ -103,13 +104,22 @@ class _HostProblem:
         d.max_candidates = max_candidates
         d.layout = layout
         d.hip_device = hip_device
+        self.weight = None if weight is None else np.ascontiguousarray(weight, dtype=np.int64)
+        self.mem_limit = None if mem_limit is None else np.ascontiguousarray(mem_limit, dtype=np.int64)
+        if self.weight is not None and self.weight.shape != (d.n_nodes,):
+            raise ValueError("weight must have one entry per node")
+        if self.mem_limit is not None and self.mem_limit.shape != (n_devices,):
+            raise ValueError("mem_limit must have one entry per machine")
+        d.weight = None if self.weight is None else self.weight.ctypes.data
+        d.mem_limit = None if self.mem_limit is None else self.mem_limit.ctypes.data
         self.desc = d
 
 
 def validate(n_devices, row_ptr, col_idx, dur, comm, mem_delta, max_candidates=1, layout=CAND_MAJOR,
-             n_nodes=None, n_edges=None) -> int:
+             n_nodes=None, n_edges=None, weight=None, mem_limit=None) -> int:
     """Host-only description check; returns the code dagsched_create would return."""
-    hp = _HostProblem(n_devices, row_ptr, col_idx, dur, comm, mem_delta, max_candidates, layout, 0, n_nodes, n_edges)
+    hp = _HostProblem(n_devices, row_ptr, col_idx, dur, comm, mem_delta, max_candidates, layout, 0, n_nodes, n_edges,
+                      weight, mem_limit)
     return load(import_torch_first=False).dagsched_validate(ctypes.byref(hp.desc))
 
 
@@ -117,9 +127,10 @@ class Evaluator:
     """dagsched_create / dagsched_evaluate / dagsched_destroy around torch device tensors."""
 
     def __init__(self, n_devices, row_ptr, col_idx, dur, comm, mem_delta, max_candidates: int,
-                 layout: int = CAND_MAJOR, hip_device: int = 0):
+                 layout: int = CAND_MAJOR, hip_device: int = 0, weight=None, mem_limit=None):
         lib = load()
-        hp = _HostProblem(n_devices, row_ptr, col_idx, dur, comm, mem_delta, max_candidates, layout, hip_device)
+        hp = _HostProblem(n_devices, row_ptr, col_idx, dur, comm, mem_delta, max_candidates, layout, hip_device,
+                          weight=weight, mem_limit=mem_limit)
         handle = ctypes.c_void_p()
         _check(lib.dagsched_create(ctypes.byref(hp.desc), ctypes.byref(handle)))
         self._h = handle
@@ -129,7 +140,8 @@ class Evaluator:
     @classmethod
     def for_workload(cls, w, max_candidates: Optional[int] = None, layout: int = CAND_MAJOR, hip_device: int = 0):
         return cls(w.n_devices, w.row_ptr, w.col_idx, w.dur, w.comm, w.mem_delta,
-                   w.n_cand if max_candidates is None else max_candidates, layout, hip_device)
+                   w.n_cand if max_candidates is None else max_candidates, layout, hip_device,
+                   weight=getattr(w, "weight", None), mem_limit=getattr(w, "mem_limit", None))
 
     def info(self) -> dict:
         i = Info()

@@ -54,6 +54,8 @@ class Workload:
     placement: np.ndarray    # int32 [C, N]
     rank: np.ndarray         # int32 [C, N]
     meta: Dict = field(default_factory=dict)
+    weight: Optional[np.ndarray] = None      # int64 [N] static memory per operation, or None
+    mem_limit: Optional[np.ndarray] = None   # int64 [P] memory limit per machine, or None
 
     @property
     def n_nodes(self) -> int:

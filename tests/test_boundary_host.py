@@ -7,6 +7,7 @@ import os
 import re
 
 import numpy as np
+import pytest
 
 import oracle
 from paper_2503_09357_amd import _build, dagsched
@@ -90,3 +91,16 @@ def test_generators_are_seeded_and_prefix_consistent():
         assert (w.n_nodes, w.n_edges, w.n_devices) == (n, e, p)
     w = W.gen_config(5, n_cand=1)
     assert w.n_nodes == 50000 and w.n_devices == 64 and 120000 < w.n_edges < 130000
+
+
+def test_validate_checks_static_memory():
+    rp, ci = W.csr_from_edges(3, [0, 1], [1, 2])
+    args = dict(n_devices=2, row_ptr=rp, col_idx=ci, dur=[1, 1, 1], comm=[[0, 1], [1, 0]], mem_delta=[0, 0, 0])
+    ds = dagsched
+    assert ds.validate(**args, weight=[0, 5, 7], mem_limit=[-3, 10]) == 0      # limits may be anything
+    assert ds.validate(**args, weight=[0, -1, 7]) == -1                        # W_i >= 0
+    with pytest.raises(ValueError):
+        ds.validate(**args, weight=[1, 2])
+    with pytest.raises(ValueError):
+        ds.validate(**args, mem_limit=[1, 2, 3])
+

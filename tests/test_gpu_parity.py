@@ -264,3 +264,35 @@ def test_large_delays_use_the_general_kernel(gpu_lib):
     w = W.random_instance(rng, 120, 5, 30, max_comm=4000, max_dur=977)
     (z, b, pk, f), info = assert_parity(gpu_lib, w)
     assert info["state_bits"] in (16, 32)
+
+
+# --------------------------------------------------------------------------- static memory and limits (eq. (16))
+
+@pytest.mark.parametrize("force_general", [0, 1])
+def test_static_memory_and_limits(gpu_lib, force_general):
+    """Base level = static memory placed on the machine; OVER_MEMORY is tested last.  The limits are set at a
+    quantile of the unlimited peaks so that both outcomes occur."""
+    import dataclasses
+    rng = np.random.default_rng(1616)
+    cases = [W.gen_config(1, n_cand=200), W.gen_config(2, n_cand=300), W.gen_config(4, n_cand=9), W.gen_config(5, n_cand=3),
+             W.random_instance(rng, 150, 6, 80, max_fanin=7, frac_arbitrary=0.3, frac_bad=0.3)]
+    seen = set()
+    for w in cases:
+        weight = rng.integers(0, 1000, w.n_nodes).astype(np.int64)
+        zo, bo, pko, fo = oracle.Problem(w.n_devices, w.row_ptr, w.col_idx, w.dur, w.comm, w.mem_delta,
+                                         weight=weight).evaluate(w.placement, w.rank, threads=8)
+        ok = fo == 0
+        limit = pko[ok].max(axis=0).astype(np.int64)             # loose everywhere ...
+        limit[0] = int(np.median(pko[ok][:, 0]))                 # ... but tight on machine 0
+        w2 = dataclasses.replace(w, name=w.name + " + weights", weight=weight)
+        w3 = dataclasses.replace(w, name=w.name + " + weights + limits", weight=weight, mem_limit=limit)
+        env = {"DAGSCHED_FORCE_GENERAL": 1} if force_general else {}
+        (z2, b2, pk2, f2), _ = _with_env(env, lambda: assert_parity(gpu_lib, w2))
+        assert (f2 == fo).all() and (pk2 == pko).all()
+        (z3, b3, pk3, f3), _ = _with_env(env, lambda: assert_parity(gpu_lib, w3))
+        seen.update(int(x) for x in f3)
+        assert (f3[~ok] == fo[~ok]).all()            # the new flag never hides another one
+        (z4, b4, pk4, f4), _ = _with_env(env, lambda: assert_parity(gpu_lib, w3, layout=1))
+        assert (f4 == f3).all()
+    assert {0, 16} <= seen
+
