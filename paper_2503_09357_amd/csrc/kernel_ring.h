@@ -481,7 +481,7 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
         if (k + u < kend) { level += m[u]; peak = max(peak, level); base += wt[u]; }   // eq. (19) along the chain
     }
     peak += base;
-    if (p.mem_limit && has_ops && peak > p.mem_limit[j]) atomicOr(&flagw[g], kBitOverMemory);
+    if (p.mem_limit && cand_ok && j < P && peak > p.mem_limit[j]) atomicOr(&flagw[g], kBitOverMemory);   // an empty machine has peak 0
     if (lane_on) peakw[ql] = peak;
   }
   __syncthreads();

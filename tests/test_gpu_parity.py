@@ -296,3 +296,19 @@ def test_static_memory_and_limits(gpu_lib, force_general):
         assert (f4 == f3).all()
     assert {0, 16} <= seen
 
+
+def test_memory_limit_on_an_empty_machine(gpu_lib):
+    """A machine that runs nothing has level 0; a negative limit on it still flags the candidate."""
+    import dataclasses
+    rng = np.random.default_rng(1617)
+    rp, ci = W.random_dag(rng, 40, 2, window=8)
+    pl, rk = W.list_schedules(rp, ci, 3, 50, 7)                # machines 0..2 used, machine 3 always empty
+    w = W.Workload("empty machine", 4, rp, ci, rng.integers(1, 9, 40).astype(np.int32),
+                   rng.integers(1, 5, (4, 4)).astype(np.int32), rng.integers(-3, 4, 40).astype(np.int64), pl, rk)
+    big = np.full(4, 10**9, dtype=np.int64)
+    for lim3, want in ((0, 0), (-1, 16)):
+        lim = big.copy()
+        lim[3] = lim3
+        (z, b, pk, f), _ = assert_parity(gpu_lib, dataclasses.replace(w, mem_limit=lim))
+        assert (f == want).all()
+
