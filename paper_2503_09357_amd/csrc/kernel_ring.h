@@ -133,9 +133,14 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
     commb[i] = (a < P && b < P && a != b) ? (uint8_t)p.comm[a * P + b] : (uint8_t)0;
   }
   const int bm_words = (N + 31) >> 5;                       // rank bitmap, aliased over the state array
-  for (int gg = 0; gg < ng; ++gg) {
+  // The candidates of the workgroup are ingested side by side: a team of kThreads / G consecutive threads
+  // per candidate, so that small problems do not pay one round of load latency per candidate.
+  const int tpc = kThreads / G;
+  const int gg = tid / tpc, tt = tid - gg * tpc;            // this thread's candidate and its place in the team
+  const bool team_on = gg < ng;
+  if (team_on) {
     uint32_t *bm = (uint32_t *)(lds + gg * o.s_stride);
-    for (int i = tid; i < bm_words; i += kThreads) bm[i] = 0;
+    for (int i = tt; i < bm_words; i += tpc) bm[i] = 0;
   }
   __syncthreads();
 
@@ -143,24 +148,24 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
   const int nq = N >> 2;
 
   // placement in range (eq. (6)), operations per machine
-  for (int gg = 0; gg < ng; ++gg) {
+  if (team_on) {
     const int32_t *pl = p.placement + (c0 + gg) * N;
     uint8_t *pib = PIBL ? lds + o.o_pi + gg * o.pi_stride : p.ws_pib + (c0 + gg) * p.pib_stride;
     int32_t *cnt_g = cntw + gg * Pseg;
-    if (tid == 0) pib[N] = (uint8_t)P;                      // the dummy node sits on a dummy machine whose delays are all zero
+    if (tt == 0) pib[N] = (uint8_t)P;                       // the dummy node sits on a dummy machine whose delays are all zero
     if (vec_ok) {
       const int4 *pl4 = (const int4 *)pl;
       uint32_t *piw = (uint32_t *)pib;
-      for (int q0 = tid; q0 < nq; q0 += 4 * kThreads) {
+      for (int q0 = tt; q0 < nq; q0 += 4 * tpc) {
         int4 a[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-          const int q = q0 + u * kThreads;
+          const int q = q0 + u * tpc;
           a[u] = (q < nq) ? pl4[q] : make_int4(0, 0, 0, 0);
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-          const int q = q0 + u * kThreads;
+          const int q = q0 + u * tpc;
           if (q < nq) {
             const uint32_t hi = (uint32_t)a[u].x | (uint32_t)a[u].y | (uint32_t)a[u].z | (uint32_t)a[u].w;
             const bool bad = hi >= 64u || a[u].x >= P || a[u].y >= P || a[u].z >= P || a[u].w >= P;
@@ -175,7 +180,7 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
         }
       }
     } else {
-      for (int v = tid; v < N; v += kThreads) {
+      for (int v = tt; v < N; v += tpc) {
         const int32_t pi = pl[v];
         if ((uint32_t)pi >= (uint32_t)P) {
           atomicOr(&flagw[gg], kBitBadPlacement);
@@ -199,8 +204,7 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
   }
   __syncthreads();
   // dense ranks (eqs. (7)-(8)): every (machine, rank) slot hit exactly once; order lists to HBM
-  for (int gg = 0; gg < ng; ++gg) {
-    if (flagw[gg] & kBitBadPlacement) continue;
+  if (team_on && !(flagw[gg] & kBitBadPlacement)) {
     const int32_t *rk = p.rank + (c0 + gg) * N;
     const uint8_t *pib = PIBL ? lds + o.o_pi + gg * o.pi_stride
                               : p.ws_pib + (c0 + gg) * p.pib_stride;   // written by this workgroup before the barrier above
@@ -223,18 +227,18 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
       const int4 *rk4 = (const int4 *)rk;
       const uint32_t *piw = (const uint32_t *)pib;
       const uint32_t *np4 = (const uint32_t *)p.nparts;     // four part counts per load (N % 4 == 0 here)
-      for (int q0 = tid; q0 < nq; q0 += 4 * kThreads) {
+      for (int q0 = tt; q0 < nq; q0 += 4 * tpc) {
         int4 a[4];
         uint32_t npw[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-          const int q = q0 + u * kThreads;
+          const int q = q0 + u * tpc;
           a[u] = (q < nq) ? rk4[q] : make_int4(0, 0, 0, 0);
           npw[u] = (np4 && q < nq) ? np4[q] - 0x01010101u : 0u;   // every count is at least 1: no borrow between bytes
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-          const int q = q0 + u * kThreads;
+          const int q = q0 + u * tpc;
           if (q < nq) {
             const uint32_t pw = piw[q];
             place(4 * q + 0, pw & 0xFF, a[u].x, npw[u] & 0xFF);
@@ -245,15 +249,15 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
         }
       }
     } else {
-      for (int v = tid; v < N; v += kThreads) place(v, pib[v], rk[v], p.nparts ? (uint32_t)p.nparts[v] - 1u : 0u);
+      for (int v = tt; v < N; v += tpc) place(v, pib[v], rk[v], p.nparts ? (uint32_t)p.nparts[v] - 1u : 0u);
     }
   }
   __syncthreads();                                          // workgroup scope: the lists are read by this workgroup only
   // end-time state: every operation "not ended"; the dummy node N has ended at time 0 on a dummy
   // machine P whose delays are all zero; cell N+1 is a trash cell for parts that do not end an operation
-  for (int gg = 0; gg < ng; ++gg) {
+  if (team_on) {
     uint32_t *sw = (uint32_t *)(lds + gg * o.s_stride);
-    for (int i = tid; i < (N + 3) / 2; i += kThreads) {
+    for (int i = tt; i < (N + 3) / 2; i += tpc) {
       const uint32_t lo = (2 * i < N) ? kNotDone16 : 0u, hi = (2 * i + 1 < N) ? kNotDone16 : 0u;
       sw[i] = lo | (hi << 16);
     }
