@@ -70,6 +70,7 @@ def main() -> int:
     ap.add_argument("--layout", type=int, default=0, help="0 candidate-major, 1 candidate-minor")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-workloads", action="store_true", help="skip the short runs of the other four workloads")
+    ap.add_argument("--no-search", action="store_true", help="skip the short local-search run")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 256 MiB elementwise copy kernel (known traffic, for counter calibration)")
     args = ap.parse_args()
@@ -174,6 +175,19 @@ def main() -> int:
             print("bench.py: GPU results differ from the oracle", file=sys.stderr)
             print(json.dumps(result))
             return 1
+    # a few iterations of the on-GPU local search (propose -> evaluate -> select) from candidate 0 of the workload
+    if not args.no_search:
+        from paper_2503_09357_amd import search
+        iters = 5
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        _, _, hist = search.local_search(ev, tp[0].contiguous() if args.layout == 0 else tp[:, 0].contiguous(),
+                                         tr[0].contiguous() if args.layout == 0 else tr[:, 0].contiguous(),
+                                         iterations=iters, n_cand=w.n_cand, seed=1)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        result["search"] = {"iterations": iters, "candidates_per_iteration": w.n_cand, "ms_per_iteration": 1e3 * dt / iters,
+                            "makespan_first_candidate": int(got[0][0]), "makespan_after": hist}
     ev.close()
     del tp, tr, out
 

@@ -132,6 +132,35 @@ void dagsched_destroy(dagsched_t *h);
 const char *dagsched_strerror(int code);
 
 /*
+ * Helpers for a planner that searches with dagsched_evaluate in its loop.  The paper hands the search over
+ * the binaries x, y to a MIP solver (Sec. IV-V); these three calls are what a local search needs instead.
+ * All pointers are DEVICE memory; all three calls are asynchronous on hip_stream and allocate nothing.
+ *
+ * dagsched_propose: the one-move neighbourhood of a base schedule (base_placement, base_rank: int32 [N], a
+ * valid candidate).  Writes n_cand candidates (n_cand <= max_candidates) into placement / rank in the handle's
+ * layout.  Candidate 0 is the base itself.  Candidate c >= 1 is the base with one move fixed by the four
+ * words rnd[4c .. 4c+3] = (r0, r1, r2, r3) that the caller draws (rnd: uint32 [4 * n_cand]); with v = r1 mod N
+ * the operation that moves, m its machine, n_j the operations on machine j in the base:
+ *   r0 even  v trades places with the operation right after it on m (nothing when v is the last one there)
+ *   r0 odd   m2 = r2 mod P;  m2 == m: v is re-inserted at position r3 mod n_m of m;
+ *            m2 != m: v is inserted at position r3 mod (n_m2 + 1) of m2.
+ * Every other operation keeps its relative order, so every candidate is dense; it may be cyclic.
+ *
+ * dagsched_select: best[0] = index of the candidate with flags == 0 and the least makespan (lowest index
+ * among equals), best[1] = that makespan; (-1, -1) when no candidate is feasible.  best: int32 [2].
+ *
+ * dagsched_schedule: start and end time of every operation of ONE candidate (placement, rank, start, end:
+ * int32 [N], the earliest-start schedule of eqs. (2), (3), (7), (11)-(13)) and its flag (int32 [1]);
+ * start = end = -1 everywhere when the flag is not 0.  For Gantt charts like those of Sec. V.
+ */
+int dagsched_propose(dagsched_t *h, int32_t n_cand, const int32_t *base_placement, const int32_t *base_rank,
+                     const uint32_t *rnd, int32_t *placement, int32_t *rank, void *hip_stream);
+int dagsched_select(dagsched_t *h, int32_t n_cand, const int32_t *makespan, const int32_t *flags, int32_t *best,
+                    void *hip_stream);
+int dagsched_schedule(dagsched_t *h, const int32_t *placement, const int32_t *rank, int32_t *start, int32_t *end,
+                      int32_t *flag, void *hip_stream);
+
+/*
  * Introspection for benchmarks and tests: which kernel variant the handle selected and its launch
  * shape.  Fills the struct and returns DAGSCHED_OK, or DAGSCHED_EINVAL on NULL.
  */

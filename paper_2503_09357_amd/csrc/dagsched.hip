@@ -32,6 +32,7 @@
 #include "device_common.h"
 #include "kernel_general.h"
 #include "kernel_ring.h"
+#include "kernel_search.h"
 #include "kernel_util.h"
 
 using namespace dagsched_dev;
@@ -84,6 +85,9 @@ struct dagsched {
   uint16_t *ws_list16 = nullptr;
   int32_t *d_fb_count = nullptr, *d_fb_list = nullptr;
   uint32_t spin_cap = 0;
+  // search helpers: machine counts of a base schedule; one row of general-kernel workspace and outputs
+  int32_t *ws_cnt = nullptr, *ws_sched_list = nullptr, *ws_sched_end = nullptr;
+  unsigned char *ws_sched_out = nullptr;
   // candidate-minor input staging
   int32_t *ws_tp = nullptr, *ws_tr = nullptr;
 };
@@ -164,7 +168,8 @@ bool dev_alloc(T **dst, size_t n) {
 void free_handle(dagsched *h) {
   if (!h) return;
   void *bufs[] = {h->d_pred_ptr, h->d_pred_idx, h->d_dur, h->d_comm, h->d_mem, h->d_weight, h->d_limit, h->ws_list, h->ws_end, h->d_rec,
-                  h->d_comm_scaled, h->d_nparts, h->ws_list16, h->ws_pib, h->d_fb_count, h->d_fb_list, h->ws_tp, h->ws_tr};
+                  h->d_comm_scaled, h->d_nparts, h->ws_list16, h->ws_pib, h->ws_cnt, h->ws_sched_list, h->ws_sched_end,
+                  h->ws_sched_out, h->d_fb_count, h->d_fb_list, h->ws_tp, h->ws_tr};
   for (void *b : bufs)
     if (b) (void)hipFree(b);
   delete h;
@@ -464,16 +469,20 @@ int dagsched_create(const dagsched_desc_t *desc, dagsched_t **out) {
   bool ok = upload(&h->d_mem, desc->mem_delta, (size_t)h->N) &&
             (!desc->weight || upload(&h->d_weight, desc->weight, (size_t)h->N)) &&
             (!desc->mem_limit || upload(&h->d_limit, desc->mem_limit, (size_t)h->P));
+  // the general kernel's view of the problem is always resident: dagsched_schedule runs it on one candidate
+  ok = ok && upload(&h->d_pred_ptr, pred_ptr.data(), (size_t)h->N + 1) &&
+       upload(&h->d_pred_idx, pred_idx.data(), (size_t)h->E) &&
+       upload(&h->d_dur, desc->dur, (size_t)h->N) &&
+       upload(&h->d_comm, desc->comm, (size_t)h->P * h->P) &&
+       dev_alloc(&h->ws_cnt, (size_t)DAGSCHED_MAX_DEVICES) &&
+       dev_alloc(&h->ws_sched_list, (size_t)h->row_stride) && dev_alloc(&h->ws_sched_end, (size_t)h->row_stride) &&
+       dev_alloc(&h->ws_sched_out, (size_t)(32 + 8 * DAGSCHED_MAX_DEVICES));
   if (ok && need_general) {
     h->gen_G = kWave / h->Pseg;
     const int64_t lds_need = (int64_t)h->gen_G * h->N * 4;
     h->gen_lds_state = lds_need + 1024 <= lds_max;
     h->gen_lds = h->gen_lds_state ? (int32_t)lds_need : 0;
-    ok = upload(&h->d_pred_ptr, pred_ptr.data(), (size_t)h->N + 1) &&
-         upload(&h->d_pred_idx, pred_idx.data(), (size_t)h->E) &&
-         upload(&h->d_dur, desc->dur, (size_t)h->N) &&
-         upload(&h->d_comm, desc->comm, (size_t)h->P * h->P) &&
-         dev_alloc(&h->ws_list, maxc * (size_t)h->row_stride);
+    ok = dev_alloc(&h->ws_list, maxc * (size_t)h->row_stride);
     if (ok && !h->gen_lds_state) ok = dev_alloc(&h->ws_end, maxc * (size_t)h->row_stride);
     if (ok && h->gen_lds > 48 * 1024)
       ok = hip_ok(hipFuncSetAttribute((const void *)relax_general_kernel<true>,
@@ -545,6 +554,56 @@ void dagsched_destroy(dagsched_t *h) {
   (void)hipSetDevice(h->device);
   (void)hipDeviceSynchronize();
   free_handle(h);
+}
+
+int dagsched_propose(dagsched_t *h, int32_t n_cand, const int32_t *base_placement, const int32_t *base_rank,
+                     const uint32_t *rnd, int32_t *placement, int32_t *rank, void *hip_stream) {
+  if (!h || n_cand < 0 || n_cand > h->max_cand) return DAGSCHED_EINVAL;
+  if (n_cand == 0) return DAGSCHED_OK;
+  if (!base_placement || !base_rank || !rnd || !placement || !rank) return DAGSCHED_EINVAL;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  hipLaunchKernelGGL(machine_count_kernel, dim3(1), dim3(256), 0, stream, h->N, h->P, base_placement, h->ws_cnt);
+  ProposeParams p;
+  p.N = h->N; p.P = h->P; p.C = n_cand;
+  p.base_pl = base_placement; p.base_rk = base_rank; p.rnd = rnd; p.cnt = h->ws_cnt;
+  p.out_pl = placement; p.out_rk = rank;
+  if (h->layout == DAGSCHED_CAND_MAJOR) { p.stride_c = h->N; p.stride_n = 1; }
+  else { p.stride_c = 1; p.stride_n = n_cand; }
+  hipLaunchKernelGGL(propose_kernel, dim3((unsigned)n_cand), dim3(256), 0, stream, p);
+  if (!hip_ok(hipGetLastError(), "kernel launch")) return DAGSCHED_EHIP;
+  return DAGSCHED_OK;
+}
+
+int dagsched_select(dagsched_t *h, int32_t n_cand, const int32_t *makespan, const int32_t *flags, int32_t *best,
+                    void *hip_stream) {
+  if (!h || n_cand < 0 || !best || (n_cand > 0 && (!makespan || !flags))) return DAGSCHED_EINVAL;
+  hipLaunchKernelGGL(select_kernel, dim3(1), dim3(1024), 0, (hipStream_t)hip_stream, n_cand, makespan, flags, best);
+  if (!hip_ok(hipGetLastError(), "kernel launch")) return DAGSCHED_EHIP;
+  return DAGSCHED_OK;
+}
+
+int dagsched_schedule(dagsched_t *h, const int32_t *placement, const int32_t *rank, int32_t *start, int32_t *end,
+                      int32_t *flag, void *hip_stream) {
+  if (!h || !placement || !rank || !start || !end || !flag) return DAGSCHED_EINVAL;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  // one candidate through the int32 kernel with its end times in the workspace row
+  unsigned char *o = h->ws_sched_out;
+  GeneralParams p;
+  p.N = h->N; p.P = h->P; p.Pseg = h->Pseg; p.G = 1; p.C = 1;
+  p.row_stride = h->row_stride;
+  p.pred_ptr = h->d_pred_ptr; p.pred_idx = h->d_pred_idx; p.dur = h->d_dur; p.comm = h->d_comm; p.mem_delta = h->d_mem;
+  p.weight = h->d_weight; p.mem_limit = h->d_limit;
+  p.sum_dur = h->sum_dur;
+  p.placement = placement; p.rank = rank;
+  p.ws_list = h->ws_sched_list; p.ws_end = h->ws_sched_end;
+  p.cand_list = nullptr; p.cand_count = nullptr;
+  p.out.makespan = (int32_t *)o; p.out.flags = (int32_t *)(o + 4); p.out.bubble = (int64_t *)(o + 8);
+  p.out.peak_mem = (int64_t *)(o + 16); p.out.peak_stride_c = h->P; p.out.peak_stride_j = 1;
+  hipLaunchKernelGGL(relax_general_kernel<false>, dim3(1), dim3(kWave), 0, stream, p);
+  hipLaunchKernelGGL(schedule_out_kernel, dim3((unsigned)std::min(256, (h->N + 255) / 256)), dim3(256), 0, stream, h->N,
+                     h->d_dur, h->ws_sched_end, (const int32_t *)(o + 4), start, end, flag);
+  if (!hip_ok(hipGetLastError(), "kernel launch")) return DAGSCHED_EHIP;
+  return DAGSCHED_OK;
 }
 
 int dagsched_get_info(const dagsched_t *h, dagsched_info_t *info) {

@@ -19,7 +19,8 @@ CAND_MAJOR, CAND_MINOR = 0, 1
 MAX_DEVICES, MAX_NODES = 64, 65535
 
 EXPORTS = ("dagsched_validate", "dagsched_create", "dagsched_evaluate", "dagsched_destroy",
-           "dagsched_strerror", "dagsched_get_info", "dagsched_time_evaluate")
+           "dagsched_strerror", "dagsched_get_info", "dagsched_time_evaluate", "dagsched_propose", "dagsched_select",
+           "dagsched_schedule")
 
 
 class Desc(ctypes.Structure):
@@ -69,6 +70,12 @@ def load(import_torch_first: bool = True):
     lib.dagsched_strerror.argtypes = [ctypes.c_int]
     lib.dagsched_get_info.restype = ctypes.c_int
     lib.dagsched_get_info.argtypes = [vp, ctypes.POINTER(Info)]
+    lib.dagsched_propose.restype = ctypes.c_int
+    lib.dagsched_propose.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp]
+    lib.dagsched_select.restype = ctypes.c_int
+    lib.dagsched_select.argtypes = [vp, i32, vp, vp, vp, vp]
+    lib.dagsched_schedule.restype = ctypes.c_int
+    lib.dagsched_schedule.argtypes = [vp, vp, vp, vp, vp, vp, vp]
     _lib = lib
     return lib
 
@@ -198,6 +205,43 @@ class Evaluator:
                                              b.data_ptr(), pk.data_ptr(), f.data_ptr(), s.cuda_stream, reps,
                                              ctypes.byref(ms)))
         return float(ms.value)
+
+    def propose(self, base_placement, base_rank, rnd, out: Optional[Tuple] = None, stream=None):
+        """One-move neighbourhood of a base schedule (device int32 [N] each); ``rnd`` is a device tensor of
+        4 * n_cand random 32-bit words (int32 or uint32 storage).  Returns (placement, rank) in the handle's
+        layout; candidate 0 is the base."""
+        import torch
+        n_cand = rnd.numel() // 4
+        dev = torch.device("cuda", self.hip_device)
+        if out is None:
+            shape = (n_cand, self.N) if self.layout == CAND_MAJOR else (self.N, n_cand)
+            out = (torch.empty(shape, dtype=torch.int32, device=dev), torch.empty(shape, dtype=torch.int32, device=dev))
+        s = torch.cuda.current_stream(self.hip_device) if stream is None else stream
+        _check(load().dagsched_propose(self._h, n_cand, base_placement.data_ptr(), base_rank.data_ptr(), rnd.data_ptr(),
+                                       out[0].data_ptr(), out[1].data_ptr(), s.cuda_stream))
+        return out
+
+    def select(self, makespan, flags, out=None, stream=None):
+        """Device int32 [2]: (index, makespan) of the best feasible candidate, (-1, -1) if there is none."""
+        import torch
+        if out is None:
+            out = torch.empty(2, dtype=torch.int32, device=torch.device("cuda", self.hip_device))
+        s = torch.cuda.current_stream(self.hip_device) if stream is None else stream
+        _check(load().dagsched_select(self._h, makespan.numel(), makespan.data_ptr(), flags.data_ptr(), out.data_ptr(),
+                                      s.cuda_stream))
+        return out
+
+    def schedule(self, placement, rank, stream=None):
+        """Start / end times of ONE candidate (device int32 [N] each) -> (start int32 [N], end int32 [N], flag int32 [1])."""
+        import torch
+        dev = torch.device("cuda", self.hip_device)
+        start = torch.empty(self.N, dtype=torch.int32, device=dev)
+        end = torch.empty(self.N, dtype=torch.int32, device=dev)
+        flag = torch.empty(1, dtype=torch.int32, device=dev)
+        s = torch.cuda.current_stream(self.hip_device) if stream is None else stream
+        _check(load().dagsched_schedule(self._h, placement.data_ptr(), rank.data_ptr(), start.data_ptr(), end.data_ptr(),
+                                        flag.data_ptr(), s.cuda_stream))
+        return start, end, flag
 
     def close(self):
         if self._h:

@@ -1,0 +1,97 @@
+"""GPU parity of the local-search helpers through the C-ABI (propose / select / schedule) and a short search run."""
+from __future__ import annotations
+
+import json
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle import search_oracle as SO
+from paper_2503_09357_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+def _dev():
+    import torch
+    return torch.device("cuda", 0)
+
+
+@pytest.mark.parametrize("layout", [0, 1])
+def test_propose_matches_the_oracle(gpu_lib, layout):
+    import torch
+    ds = gpu_lib
+    rng = np.random.default_rng(5501)
+    for w in (W.gen_config(1, n_cand=2), W.gen_config(2, n_cand=2), W.gen_config(4, n_cand=1),
+              W.random_instance(rng, 37, 3, 2, frac_bad=0.0, frac_arbitrary=0.0)):
+        C = 700
+        rnd = rng.integers(0, 1 << 32, size=4 * C, dtype=np.uint64).astype(np.uint32)
+        with ds.Evaluator.for_workload(w, max_candidates=C, layout=layout) as ev:
+            pl, rk = ev.propose(torch.from_numpy(w.placement[0]).to(_dev()), torch.from_numpy(w.rank[0]).to(_dev()),
+                                torch.from_numpy(rnd.view(np.int32)).to(_dev()))
+            torch.cuda.synchronize()
+            got_pl, got_rk = pl.cpu().numpy(), rk.cpu().numpy()
+        want_pl, want_rk = SO.propose(w.placement[0], w.rank[0], rnd, w.n_devices)
+        if layout == 1:
+            got_pl, got_rk = got_pl.T, got_rk.T
+        assert (got_pl == want_pl).all() and (got_rk == want_rk).all(), w.name
+
+
+def test_select_matches_the_oracle(gpu_lib):
+    import torch
+    ds = gpu_lib
+    rng = np.random.default_rng(5502)
+    w = W.gen_config(1, n_cand=1)
+    with ds.Evaluator.for_workload(w, max_candidates=1) as ev:
+        for C, p_ok in ((1, 1.0), (5, 0.5), (4097, 0.3), (70000, 0.01), (300, 0.0)):
+            z = rng.integers(0, 50, C).astype(np.int32)          # many ties
+            f = np.where(rng.random(C) < p_ok, 0, rng.choice([1, 2, 4, 16], C)).astype(np.int32)
+            z[f != 0] = -1
+            best = ev.select(torch.from_numpy(z).to(_dev()), torch.from_numpy(f).to(_dev()))
+            torch.cuda.synchronize()
+            assert tuple(best.cpu().tolist()) == SO.select(z, f), (C, p_ok)
+
+
+def test_schedule_matches_the_oracle(gpu_lib):
+    import torch
+    ds = gpu_lib
+    rng = np.random.default_rng(5503)
+    for w in (W.gen_config(1, n_cand=3), W.gen_config(3, n_cand=2), W.gen_config(5, n_cand=1),
+              W.random_instance(rng, 90, 5, 12, frac_bad=0.3, frac_arbitrary=0.3)):
+        prob = oracle.Problem.of(w)
+        with ds.Evaluator.for_workload(w) as ev:
+            for c in range(w.n_cand):
+                s, e, f = ev.schedule(torch.from_numpy(w.placement[c]).to(_dev()), torch.from_numpy(w.rank[c]).to(_dev()))
+                torch.cuda.synchronize()
+                try:
+                    flag, so, eo, _, _ = prob.schedule(w.placement[c], w.rank[c])
+                except oracle.OracleError:
+                    raise
+                assert int(f.item()) == flag, (w.name, c)
+                if flag == 0:
+                    assert (s.cpu().numpy() == so).all() and (e.cpu().numpy() == eo).all(), (w.name, c)
+                else:
+                    assert (s.cpu().numpy() == -1).all() and (e.cpu().numpy() == -1).all()
+
+
+@pytest.mark.parametrize("layout", [0, 1])
+def test_local_search_never_gets_worse_and_ends_valid(gpu_lib, layout, tmp_path):
+    import torch
+    from paper_2503_09357_amd import search
+    ds = gpu_lib
+    w = W.gen_config(2, n_cand=1)
+    prob = oracle.Problem.of(w)
+    z0 = int(prob.evaluate(w.placement, w.rank)[0][0])
+    with ds.Evaluator.for_workload(w, max_candidates=512, layout=layout) as ev:
+        pl, rk, hist = search.local_search(ev, torch.from_numpy(w.placement[0]).to(_dev()),
+                                           torch.from_numpy(w.rank[0]).to(_dev()), iterations=12, n_cand=512, seed=3)
+        s, e, f = ev.schedule(pl, rk)
+        torch.cuda.synchronize()
+    assert len(hist) == 12 and hist[0] <= z0 and all(b <= a for a, b in zip(hist, hist[1:]))
+    zo, _, _, fo = prob.evaluate(pl.cpu().numpy()[None, :], rk.cpu().numpy()[None, :])
+    assert fo[0] == 0 and int(zo[0]) == hist[-1] and int(f.item()) == 0 and int(e.max().item()) == hist[-1]
+    path = os.path.join(tmp_path, "trace.json")
+    search.chrome_trace(path, s.cpu().tolist(), e.cpu().tolist(), pl.cpu().tolist())
+    assert len(json.load(open(path))["traceEvents"]) == w.n_nodes
