@@ -133,12 +133,14 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
     commb[i] = (a < P && b < P && a != b) ? (uint8_t)p.comm[a * P + b] : (uint8_t)0;
   }
   const int bm_words = (N + 31) >> 5;                       // rank bitmap, aliased over the state array
-  // The candidates of the workgroup are ingested side by side: a team of kThreads / G consecutive threads
-  // per candidate, so that small problems do not pay one round of load latency per candidate.
-  const int tpc = kThreads / G;
-  const int gg = tid / tpc, tt = tid - gg * tpc;            // this thread's candidate and its place in the team
-  const bool team_on = gg < ng;
-  if (team_on) {
+  // With four or more candidates per workgroup they are ingested side by side, a team of kThreads / G
+  // consecutive threads each, so that small problems do not pay one round of load latency per candidate.
+  // With one or two candidates the whole workgroup takes them in turn: their scattered 2-byte list
+  // writes then combine better on the way to HBM (measured: 3x fewer bytes written).
+  const int n_teams = G <= 2 ? 1 : G;
+  const int tpc = kThreads / n_teams;
+  const int team = tid / tpc, tt = tid - team * tpc;        // this thread's team and its place in it
+  for (int gg = team; gg < ng; gg += n_teams) {
     uint32_t *bm = (uint32_t *)(lds + gg * o.s_stride);
     for (int i = tt; i < bm_words; i += tpc) bm[i] = 0;
   }
@@ -148,7 +150,7 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
   const int nq = N >> 2;
 
   // placement in range (eq. (6)), operations per machine
-  if (team_on) {
+  for (int gg = team; gg < ng; gg += n_teams) {
     const int32_t *pl = p.placement + (c0 + gg) * N;
     uint8_t *pib = PIBL ? lds + o.o_pi + gg * o.pi_stride : p.ws_pib + (c0 + gg) * p.pib_stride;
     int32_t *cnt_g = cntw + gg * Pseg;
@@ -204,7 +206,8 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
   }
   __syncthreads();
   // dense ranks (eqs. (7)-(8)): every (machine, rank) slot hit exactly once; order lists to HBM
-  if (team_on && !(flagw[gg] & kBitBadPlacement)) {
+  for (int gg = team; gg < ng; gg += n_teams) {
+    if (flagw[gg] & kBitBadPlacement) continue;
     const int32_t *rk = p.rank + (c0 + gg) * N;
     const uint8_t *pib = PIBL ? lds + o.o_pi + gg * o.pi_stride
                               : p.ws_pib + (c0 + gg) * p.pib_stride;   // written by this workgroup before the barrier above
@@ -255,7 +258,7 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
   __syncthreads();                                          // workgroup scope: the lists are read by this workgroup only
   // end-time state: every operation "not ended"; the dummy node N has ended at time 0 on a dummy
   // machine P whose delays are all zero; cell N+1 is a trash cell for parts that do not end an operation
-  if (team_on) {
+  for (int gg = team; gg < ng; gg += n_teams) {
     uint32_t *sw = (uint32_t *)(lds + gg * o.s_stride);
     for (int i = tt; i < (N + 3) / 2; i += tpc) {
       const uint32_t lo = (2 * i < N) ? kNotDone16 : 0u, hi = (2 * i + 1 < N) ? kNotDone16 : 0u;
