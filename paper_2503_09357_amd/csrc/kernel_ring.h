@@ -341,11 +341,15 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
       if (__ballot(!fin) == 0) { expired = false; break; }
       const uint64_t hold = __ballot(!idle || fin);
       if (!fin && (prog_acc & segmask) == 0 && (hold & segmask) == segmask) {
-        // every unfinished machine of this candidate holds an op and none could run: deadlock, i.e. a
-        // cycle of the combined graph (or a 16-bit overflow when optimistic)
+        // every unfinished machine of this candidate holds an op and none could run: deadlock.  If one of
+        // the held ops has all its predecessors ended, only the 16-bit range stopped it (optimistic mode:
+        // the int32 kernel takes the candidate); otherwise every held op waits for an op that can never
+        // run, i.e. the combined graph has a cycle.
+        const bool range_stop = !idle && max(max(e0, e1), max(e2, e3)) < kNotDone16;
+        const bool overflow = (__ballot(range_stop) & segmask) != 0;
         stalled = true;
         dead = true;
-        *abort_p = 1;
+        *abort_p = overflow ? 1 : 2;
       }
       prog_acc = 0;
     }
@@ -501,7 +505,7 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
       const int64_t c = c0 + g;
       int bits = flagw[g];
       if (stalled || abortw[g]) {
-        if (p.optimistic && !(bits & kBitInternal)) {
+        if (p.optimistic && !(bits & kBitInternal) && abortw[g] != 2) {
           if (j == 0) { const int slot = atomicAdd(p.fb_count, 1); p.fb_list[slot] = (int32_t)c; }
           return;                                            // the general kernel writes this candidate
         }

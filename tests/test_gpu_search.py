@@ -95,3 +95,35 @@ def test_local_search_never_gets_worse_and_ends_valid(gpu_lib, layout, tmp_path)
     path = os.path.join(tmp_path, "trace.json")
     search.chrome_trace(path, s.cpu().tolist(), e.cpu().tolist(), pl.cpu().tolist())
     assert len(json.load(open(path))["traceEvents"]) == w.n_nodes
+
+
+def test_cycles_and_range_stops_are_told_apart(gpu_lib):
+    """In the optimistic 16-bit mode a deadlock is either a cycle (flagged at once) or an end time leaving the
+    16-bit range (handed to the int32 kernel).  A neighbourhood of the MoE workload has plenty of cycles; the
+    straddling instance has both kinds."""
+    import dataclasses
+    import test_gpu_parity as T
+    rng = np.random.default_rng(5505)
+    w = W.gen_config(4, n_cand=1)
+    rnd = rng.integers(0, 1 << 32, size=4 * 300, dtype=np.uint64).astype(np.uint32)
+    pl, rk = SO.propose(w.placement[0], w.rank[0], rnd, w.n_devices)
+    (z, b, pk, f), info = T.assert_parity(gpu_lib, dataclasses.replace(w, name="cfg4 neighbourhood", placement=pl, rank=rk))
+    assert info["variant"] == 4 and (f == 1).sum() >= 10 and (f == 0).sum() >= 10
+    # long chain on few machines: makespans on both sides of 65535, plus cycles made by neighbourhood moves
+    n, p = 600, 3
+    rp, ci = W.random_dag(rng, n, 2, window=30)
+    dur = rng.integers(60, 160, n).astype(np.int32)
+    comm = rng.integers(1, 200, (p, p)).astype(np.int32)
+    mem = rng.integers(-9, 10, n).astype(np.int64)
+    pl0, rk0 = W.list_schedules(rp, ci, p, 40, 4242)
+    pl1, rk1 = W.list_schedules(rp, ci, 1, 40, 99)
+    rows_pl, rows_rk = [pl0, pl1], [rk0, rk1]
+    for base_pl, base_rk in ((pl0[0], rk0[0]), (pl1[0], rk1[0])):
+        rnd = rng.integers(0, 1 << 32, size=4 * 100, dtype=np.uint64).astype(np.uint32)
+        a, c = SO.propose(base_pl, base_rk, rnd, p)
+        rows_pl.append(a)
+        rows_rk.append(c)
+    w2 = W.Workload("straddles 16 bits, with cycles", p, rp, ci, dur, comm, mem, np.concatenate(rows_pl), np.concatenate(rows_rk))
+    (z2, b2, pk2, f2), info2 = T.assert_parity(gpu_lib, w2)
+    assert info2["variant"] == 4 and (f2 == 1).any() and (z2[f2 == 0] > 65535).any() and (z2[f2 == 0] < 65535).any()
+
