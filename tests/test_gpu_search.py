@@ -127,3 +127,50 @@ def test_cycles_and_range_stops_are_told_apart(gpu_lib):
     (z2, b2, pk2, f2), info2 = T.assert_parity(gpu_lib, w2)
     assert info2["variant"] == 4 and (f2 == 1).any() and (z2[f2 == 0] > 65535).any() and (z2[f2 == 0] < 65535).any()
 
+
+
+def test_search_step_replays_from_a_hip_graph(gpu_lib):
+    """propose -> evaluate -> select enqueue kernels only (no allocation, no memset node), so one search step can
+    be captured once and replayed; every replay must give what the eager calls give."""
+    import torch
+    ds = gpu_lib
+    rng = np.random.default_rng(5506)
+    w = W.gen_config(4, n_cand=1)                      # optimistic 16-bit mode: counter reset + fallback kernel inside
+    C = 256
+    dev = _dev()
+    with ds.Evaluator.for_workload(w, max_candidates=C) as ev:
+        base_pl = torch.from_numpy(w.placement[0]).to(dev)
+        base_rk = torch.from_numpy(w.rank[0]).to(dev)
+        rnd = torch.zeros(4 * C, dtype=torch.int32, device=dev)
+        cand = ev.propose(base_pl, base_rk, rnd)
+        out = ev.alloc_outputs(C)
+        best = torch.empty(2, dtype=torch.int32, device=dev)
+        side = torch.cuda.Stream(device=dev)
+        side.wait_stream(torch.cuda.current_stream(dev))
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            ev.propose(base_pl, base_rk, rnd, out=cand)          # warm-up on the capture stream
+            ev.evaluate(cand[0], cand[1], out)
+            ev.select(out[0], out[3], out=best)
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                ev.propose(base_pl, base_rk, rnd, out=cand)
+                ev.evaluate(cand[0], cand[1], out)
+                ev.select(out[0], out[3], out=best)
+        torch.cuda.current_stream(dev).wait_stream(side)
+        for rep in range(4):
+            words = rng.integers(0, 1 << 31, size=4 * C).astype(np.int32)
+            rnd.copy_(torch.from_numpy(words).to(dev))
+            graph.replay()
+            torch.cuda.synchronize()
+            got = [t.clone() for t in out] + [best.clone()]
+            eager_c = ev.propose(base_pl, base_rk, rnd)           # the program's own eager work between replays
+            eager = ev.evaluate(eager_c[0], eager_c[1])
+            eager_best = ev.select(eager[0], eager[3])
+            torch.cuda.synchronize()
+            for a, b in zip(got, list(eager) + [eager_best]):
+                assert torch.equal(a, b), rep
+            want_pl, want_rk = SO.propose(w.placement[0], w.rank[0], words.view(np.uint32), w.n_devices)
+            zo, bo, pko, fo = oracle.Problem.of(w).evaluate(want_pl, want_rk, threads=8)
+            assert (got[0].cpu().numpy() == zo).all() and (got[3].cpu().numpy() == fo).all()
+            assert tuple(got[4].cpu().tolist()) == SO.select(zo, fo)
