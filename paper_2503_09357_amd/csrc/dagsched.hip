@@ -290,6 +290,10 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
   while ((1 << part_bits) < max_parts) ++part_bits;
   plan.id_bits = 16 - part_bits;
   if (N > (1 << plan.id_bits)) return plan;            // ids and part counts do not fit: general kernel
+  for (int v = 0; v < N; ++v) {                        // 0xFFFF marks an unwritten list slot during ingest
+    const int parts = std::max(1, (pred_ptr[v + 1] - pred_ptr[v] + PR - 1) / PR);
+    if (((uint32_t)v | ((uint32_t)(parts - 1) << plan.id_bits)) == 0xFFFFu) return plan;
+  }
   if (max_parts > 1) {
     plan.nparts.resize(N);
     for (int v = 0; v < N; ++v) plan.nparts[v] = (uint8_t)std::max(1, (pred_ptr[v + 1] - pred_ptr[v] + PR - 1) / PR);

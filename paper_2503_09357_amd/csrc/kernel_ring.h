@@ -132,17 +132,16 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
     const int a = i >> p.log_pseg, b = i & (Pseg - 1);
     commb[i] = (a < P && b < P && a != b) ? (uint8_t)p.comm[a * P + b] : (uint8_t)0;
   }
-  const int bm_words = (N + 31) >> 5;                       // rank bitmap, aliased over the state array
-  // With four or more candidates per workgroup they are ingested side by side, a team of kThreads / G
-  // consecutive threads each, so that small problems do not pay one round of load latency per candidate.
-  // With one or two candidates the whole workgroup takes them in turn: their scattered 2-byte list
-  // writes then combine better on the way to HBM (measured: 3x fewer bytes written).
-  const int n_teams = G <= 2 ? 1 : G;
+  // The candidates of the workgroup are ingested side by side, a team of kThreads / G consecutive threads
+  // each, so that small problems do not pay one round of load latency per candidate.
+  const int n_teams = G;
   const int tpc = kThreads / n_teams;
   const int team = tid / tpc, tt = tid - team * tpc;        // this thread's team and its place in it
+  // The order lists are first built in LDS, over the (not yet used) end-time arrays: every entry starts as
+  // "unwritten" (0xFFFF, which no list entry equals: the host checks that)
   for (int gg = team; gg < ng; gg += n_teams) {
-    uint32_t *bm = (uint32_t *)(lds + gg * o.s_stride);
-    for (int i = tt; i < bm_words; i += tpc) bm[i] = 0;
+    uint32_t *lw = (uint32_t *)(lds + gg * o.s_stride);
+    for (int i = tt; i < (N + 1) / 2; i += tpc) lw[i] = 0xFFFFFFFFu;
   }
   __syncthreads();
 
@@ -205,14 +204,14 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
     if (lane < L) offw[lane] = incl - my;
   }
   __syncthreads();
-  // dense ranks (eqs. (7)-(8)): every (machine, rank) slot hit exactly once; order lists to HBM
+  // dense ranks (eqs. (7)-(8)): every rank inside its machine's range and, after N writes into N slots,
+  // no slot left unwritten <=> every (machine, rank) slot hit exactly once
   for (int gg = team; gg < ng; gg += n_teams) {
     if (flagw[gg] & kBitBadPlacement) continue;
     const int32_t *rk = p.rank + (c0 + gg) * N;
     const uint8_t *pib = PIBL ? lds + o.o_pi + gg * o.pi_stride
                               : p.ws_pib + (c0 + gg) * p.pib_stride;   // written by this workgroup before the barrier above
-    uint32_t *bm = (uint32_t *)(lds + gg * o.s_stride);
-    uint16_t *list = p.ws_list + (c0 + gg) * p.list_stride;
+    uint16_t *lds_list = (uint16_t *)(lds + gg * o.s_stride);
     const int32_t *cnt_g = cntw + gg * Pseg, *off_g = offw + gg * Pseg;
     int32_t *flag_g = flagw + gg;
     // list entry: node | (parts - 1) << id_bits
@@ -220,10 +219,7 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
       if ((uint32_t)r >= (uint32_t)cnt_g[pi]) {
         atomicOr(flag_g, kBitBadRank);
       } else {
-        const uint32_t pos = (uint32_t)(off_g[pi] + r);
-        const uint32_t bit = 1u << (pos & 31);
-        if (atomicOr(&bm[pos >> 5], bit) & bit) atomicOr(flag_g, kBitBadRank);
-        else list[pos] = (uint16_t)((uint32_t)v | (np1 << p.id_bits));
+        lds_list[off_g[pi] + r] = (uint16_t)((uint32_t)v | (np1 << p.id_bits));
       }
     };
     if (vec_ok) {
@@ -254,6 +250,20 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
     } else {
       for (int v = tt; v < N; v += tpc) place(v, pib[v], rk[v], p.nparts ? (uint32_t)p.nparts[v] - 1u : 0u);
     }
+  }
+  __syncthreads();
+  // order lists to HBM (coalesced), looking for unwritten slots on the way
+  for (int gg = team; gg < ng; gg += n_teams) {
+    if (flagw[gg] & kBitBadPlacement) continue;
+    const uint32_t *lw = (const uint32_t *)(lds + gg * o.s_stride);
+    uint32_t *gw = (uint32_t *)(p.ws_list + (c0 + gg) * p.list_stride);     // rows are 128-byte aligned
+    bool hole = false;
+    for (int i = tt; i < (N + 1) / 2; i += tpc) {
+      const uint32_t w = lw[i];
+      hole |= (w & 0xFFFFu) == 0xFFFFu || (2 * i + 1 < N && (w >> 16) == 0xFFFFu);
+      gw[i] = w;
+    }
+    if (hole) atomicOr(&flagw[gg], kBitBadRank);
   }
   __syncthreads();                                          // workgroup scope: the lists are read by this workgroup only
   // end-time state: every operation "not ended"; the dummy node N has ended at time 0 on a dummy
