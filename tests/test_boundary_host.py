@@ -104,3 +104,19 @@ def test_validate_checks_static_memory():
     with pytest.raises(ValueError):
         ds.validate(**args, mem_limit=[1, 2, 3])
 
+
+
+def test_bench_refuses_more_than_one_gpu_and_reads_the_committed_counters():
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
+    sys.path.insert(0, root)
+    import bench
+    w = W.gen_config(4, n_cand=1)
+    per_cand = 8 * w.n_nodes + 16 + 8 * w.n_devices
+    assert bench.algorithmic_bytes(w) - per_cand == 4 * (w.n_nodes + 1) + 4 * w.n_edges + 12 * w.n_nodes + 4 * w.n_devices ** 2
+    t = bench.measured_traffic(4)                    # None once the kernel sources changed after the counters were taken
+    assert t is None or t > 0
+    assert bench.measured_traffic(99) is None
