@@ -270,12 +270,16 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
   for (int v = 0; v < N; ++v) {
     const int deg = pred_ptr[v + 1] - pred_ptr[v];
     const int parts = std::max(1, (deg + PR - 1) / PR);
+    // A part waits for its own predecessors and for the parts before it, so the operation ends one trip
+    // later for every part that follows the one holding its last predecessor.  Predecessors that end late
+    // on the critical path of B alone go last, and the first part takes the remainder.
+    std::vector<int32_t> ps(pred_idx.begin() + pred_ptr[v], pred_idx.begin() + pred_ptr[v + 1]);
+    std::stable_sort(ps.begin(), ps.end(), [&](int32_t a, int32_t b) { return fin[a] < fin[b]; });
+    const int first = deg - PR * (parts - 1);
     for (int part = 0; part < parts; ++part) {
       uint32_t u[4] = {dummy, dummy, dummy, dummy};
-      for (int i = 0; i < PR; ++i) {
-        const int k = pred_ptr[v] + part * PR + i;
-        if (k < pred_ptr[v + 1]) u[i] = (uint32_t)pred_idx[k];
-      }
+      const int lo = part == 0 ? 0 : first + (part - 1) * PR, hi = part == 0 ? first : lo + PR;
+      for (int k = lo; k < hi && k < deg; ++k) u[k - lo] = (uint32_t)ps[k];
       const bool more = part + 1 < parts;
       const uint32_t dur = more ? 0u : (uint32_t)std::min<int64_t>(d->dur[v] / g, kNotDone16);
       rec[(size_t)part * plane + v] = make_uint4(u[0] | (u[1] << 16), u[2] | (u[3] << 16),
