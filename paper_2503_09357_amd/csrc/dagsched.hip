@@ -260,20 +260,54 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
   plan.scale = (int32_t)g;
 
   constexpr int PR = 4;                                // DAG predecessors per op part
+  // Predecessor lists of the ops.  An edge (u, v) of an operation with more than PR predecessors is left
+  // out when B has another path u -> w1 -> ... -> wk -> v whose intermediate durations sum to at least the
+  // largest channel delay: then s_v >= e_wk >= ... >= e_u + sum D^o_wi >= e_u + delta(u, v) whatever the
+  // candidate, so eqs. (11)-(13) for (u, v) are implied (and a cycle through (u, v) also runs through that
+  // path).  Fewer parts mean fewer relaxer trips on the critical path.  Bounded search: four hops, 256 visits.
+  std::vector<std::vector<int32_t>> op_preds(N);
+  {
+    struct Item { int32_t node, hops; int64_t sum; };
+    std::vector<Item> stack;
+    auto implied = [&](int32_t u, int32_t v) {
+      stack.clear();
+      stack.push_back({u, 0, 0});
+      int visits = 0;
+      while (!stack.empty()) {
+        const Item it = stack.back();
+        stack.pop_back();
+        if (++visits > 256) return false;
+        for (int32_t k = d->row_ptr[it.node]; k < d->row_ptr[it.node + 1]; ++k) {
+          const int32_t y = d->col_idx[k];
+          if (y == v) {
+            if (it.hops >= 1 && it.sum >= max_comm) return true;
+          } else if (it.hops + 1 < 4) {
+            stack.push_back({y, it.hops + 1, it.sum + d->dur[y]});
+          }
+        }
+      }
+      return false;
+    };
+    for (int v = 0; v < N; ++v) {
+      const int deg = pred_ptr[v + 1] - pred_ptr[v];
+      for (int k = pred_ptr[v]; k < pred_ptr[v + 1]; ++k)
+        if (deg <= PR || !implied(pred_idx[k], v)) op_preds[v].push_back(pred_idx[k]);
+    }
+  }
   // shared operator records, part i of node v at [i * plane + v]
   const uint32_t dummy = (uint32_t)N;
   int max_parts = 1;
-  for (int v = 0; v < N; ++v) max_parts = std::max(max_parts, (pred_ptr[v + 1] - pred_ptr[v] + PR - 1) / PR);
+  for (int v = 0; v < N; ++v) max_parts = std::max(max_parts, ((int)op_preds[v].size() + PR - 1) / PR);
   if (max_parts > 16) return plan;                     // very wide fan-in: leave it to the general kernel
   const int plane = N;
   std::vector<uint4> rec((size_t)max_parts * plane, make_uint4(dummy | (dummy << 16), dummy | (dummy << 16), 0, 0));
   for (int v = 0; v < N; ++v) {
-    const int deg = pred_ptr[v + 1] - pred_ptr[v];
+    const int deg = (int)op_preds[v].size();
     const int parts = std::max(1, (deg + PR - 1) / PR);
     // A part waits for its own predecessors and for the parts before it, so the operation ends one trip
     // later for every part that follows the one holding its last predecessor.  Predecessors that end late
     // on the critical path of B alone go last, and the first part takes the remainder.
-    std::vector<int32_t> ps(pred_idx.begin() + pred_ptr[v], pred_idx.begin() + pred_ptr[v + 1]);
+    std::vector<int32_t> &ps = op_preds[v];
     std::stable_sort(ps.begin(), ps.end(), [&](int32_t a, int32_t b) { return fin[a] < fin[b]; });
     const int first = deg - PR * (parts - 1);
     for (int part = 0; part < parts; ++part) {
@@ -295,12 +329,12 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
   plan.id_bits = 16 - part_bits;
   if (N > (1 << plan.id_bits)) return plan;            // ids and part counts do not fit: general kernel
   for (int v = 0; v < N; ++v) {                        // 0xFFFF marks an unwritten list slot during ingest
-    const int parts = std::max(1, (pred_ptr[v + 1] - pred_ptr[v] + PR - 1) / PR);
+    const int parts = std::max(1, ((int)op_preds[v].size() + PR - 1) / PR);
     if (((uint32_t)v | ((uint32_t)(parts - 1) << plan.id_bits)) == 0xFFFFu) return plan;
   }
   if (max_parts > 1) {
     plan.nparts.resize(N);
-    for (int v = 0; v < N; ++v) plan.nparts[v] = (uint8_t)std::max(1, (pred_ptr[v + 1] - pred_ptr[v] + PR - 1) / PR);
+    for (int v = 0; v < N; ++v) plan.nparts[v] = (uint8_t)std::max(1, ((int)op_preds[v].size() + PR - 1) / PR);
   }
   plan.comm_scaled.resize((size_t)P * P);
   for (int i = 0; i < P * P; ++i) plan.comm_scaled[i] = (i / P != i % P) ? (int32_t)(d->comm[i] / g) : 0;

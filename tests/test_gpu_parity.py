@@ -312,3 +312,36 @@ def test_memory_limit_on_an_empty_machine(gpu_lib):
         (z, b, pk, f), _ = assert_parity(gpu_lib, dataclasses.replace(w, mem_limit=lim))
         assert (f == want).all()
 
+
+
+def test_shortcut_edges_next_to_longer_paths(gpu_lib):
+    """Wide operations whose predecessors are also reachable through longer paths: the fast kernel may leave such
+    an edge out of its ops only when the path's intermediate durations cover the largest channel delay.  Durations
+    of 0, 1, 2 and 50 against delays up to 60 put many edges on either side of that line."""
+    rng = np.random.default_rng(8080)
+    for trial in range(4):
+        n, p = 220, 5
+        src, dst = [], []
+        for v in range(1, n):
+            for u in rng.choice(np.arange(max(0, v - 12), v), size=min(v, int(rng.integers(1, 4))), replace=False):
+                src.append(int(u)); dst.append(v)
+        preds = {v: set() for v in range(n)}
+        for u, v in zip(src, dst):
+            preds[v].add(u)
+        for v in range(2, n):                                  # shortcuts from predecessors of predecessors (and theirs)
+            anc = set()
+            for u in preds[v]:
+                anc |= preds[u]
+                for t in preds[u]:
+                    anc |= preds[t]
+            for u in sorted(anc - preds[v])[: int(rng.integers(0, 6))]:
+                src.append(u); dst.append(v)
+        rp, ci = W.csr_from_edges(n, src, dst)
+        dur = rng.choice([0, 1, 2, 50], size=n, p=[0.2, 0.3, 0.3, 0.2]).astype(np.int32)
+        comm = rng.integers(0, 61, (p, p)).astype(np.int32)
+        mem = rng.integers(-5, 6, n).astype(np.int64)
+        pl, rk = W.list_schedules(rp, ci, p, 120, 1000 + trial)
+        w = W.Workload("shortcut edges %d" % trial, p, rp, ci, dur, comm, mem, pl, rk)
+        assert (np.diff(W.csr_from_edges(n, dst, src)[0]) > 4).sum() > 20      # plenty of wide operations
+        (z, b, pk, f), info = assert_parity(gpu_lib, w)
+        assert info["state_bits"] == 16 and (f == 0).all()
