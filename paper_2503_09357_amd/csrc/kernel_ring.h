@@ -73,7 +73,7 @@ struct LdsLayout {
 
 struct RingParams {
   int32_t N, P, Pseg, log_pseg, G, C;
-  int32_t optimistic;                  // 1: stalled candidates go to fb_list, 0: a stall is a cycle
+  int32_t optimistic;                  // 1: candidates stopped by the 16-bit range go to fb_list, 0: a deadlock is always a cycle
   int64_t list_stride;                 // uint16 elements per candidate in ws_list
   const uint4 *rec;                    // [parts][rec_plane] shared operator records (times divided by time_scale)
   int32_t rec_plane;                   // records per part plane (>= N)
@@ -95,7 +95,7 @@ struct RingParams {
   OutPtrs out;
 };
 
-// FEEDERS feeder wavefronts share a lane's stream: feeder f owns the parts with (seq - 1) % FEEDERS == f.
+// FEEDERS feeder wavefronts share a lane's stream: feeder f owns the parts with seq % FEEDERS == f.
 // PIBL = 1: the placement bytes of the workgroup's candidates sit in LDS (fastest feeders); PIBL = 0: in an
 // L2-resident workspace, which leaves the LDS to more candidates or a deeper ring.
 template <int RING, int FEEDERS, int HALF, int PIBL>
@@ -121,10 +121,10 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
   int32_t *cntw = (int32_t *)(lds + o.o_cnt);              // [64] operations per (candidate, machine)
   int32_t *offw = (int32_t *)(lds + o.o_off);              // [64] start of the machine inside the list
   int32_t *flagw = (int32_t *)(lds + o.o_flag);            // [64] (G used)
-  int32_t *abortw = (int32_t *)(lds + o.o_abort);          // [64] (G used)
+  int32_t *abortw = (int32_t *)(lds + o.o_abort);          // [64] (G used) 0, 1 = stopped by the 16-bit range (or internal), 2 = cycle
   uint8_t *commb = (uint8_t *)(lds + o.o_comm);            // [(P+1)][Pseg], diagonal and dummy row zero
 
-  // ---------------------------------------------------------------- ingest (both wavefronts)
+  // ---------------------------------------------------------------- ingest (all wavefronts)
   if (tid < kWave) { cntw[tid] = 0; totalw[tid] = 0xFFFFFFFFu; flagw[tid] = 0; abortw[tid] = 0; peakw[tid] = 0; }
   for (int i = tid; i < RING * kWave; i += kThreads)       // every slot free, as if ops -RING .. -1 had been taken
     ringw[4 * i + 3] = kNotDone16 | ((uint32_t)((i >> 6) - RING) << 16);
