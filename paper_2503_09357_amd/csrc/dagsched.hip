@@ -75,7 +75,7 @@ struct dagsched {
   int64_t *d_mem = nullptr, *d_weight = nullptr, *d_limit = nullptr;
   int32_t *ws_list = nullptr, *ws_end = nullptr;
   // ring kernel
-  int32_t ring_G = 0, ring_slots = 0, ring_feeders = 1, rec_plane = 0, id_bits = 16, time_scale = 1;
+  int32_t ring_G = 0, ring_slots = 0, ring_feeders = 1, ring_block = 256, rec_plane = 0, id_bits = 16, time_scale = 1;
   uint8_t *d_nparts = nullptr;
   int64_t list_stride = 0, pib_stride = 0;
   uint8_t *ws_pib = nullptr;
@@ -212,7 +212,7 @@ RingKernel ring_kernel_pick(int ring, int feeders, bool pib_lds);
 
 struct RingPlan {
   bool ok = false, exact = false;
-  int G = 0, ring = 0, feeders = 1;
+  int G = 0, ring = 0, feeders = 1, block = 256;
   int32_t scale = 1;
   LdsLayout lds{};
   std::vector<uint4> rec;
@@ -366,6 +366,13 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
   }
   plan.feeders = force_feeders ? force_feeders : (best_wgs * 4 <= 24 ? 2 : 1);
   if (best_score < 0 || !ring_kernel_pick<0>(plan.ring, plan.feeders, plan.lds.pi_stride != 0)) return plan;   // shape not built
+  // workgroup size: the wavefronts with a role, plus helpers for the ingest phase when the LDS leaves the CU
+  // nearly empty of wavefronts (one workgroup per CU: 1024 threads, two: 512)
+  plan.block = ring_threads(plan.feeders);
+  const int force_block = env_int("DAGSCHED_RING_BLOCK", 0);
+  if (force_block >= plan.block && force_block <= 1024 && force_block % kWave == 0) plan.block = force_block;
+  else if (best_wgs == 1) plan.block = 1024;
+  else if (best_wgs == 2) plan.block = std::max(plan.block, 512);
   plan.ok = best_score >= 0;
   return plan;
 }
@@ -457,7 +464,7 @@ int launch_evaluate(dagsched *h, int32_t n_cand, const int32_t *placement, const
     p.lds = h->lds;
     p.out = out;
     const unsigned blocks = (unsigned)((n_cand + h->ring_G - 1) / h->ring_G);
-    hipLaunchKernelGGL(ring_kernel_for(h), dim3(blocks), dim3(ring_threads(h->ring_feeders)), (size_t)h->lds.total,
+    hipLaunchKernelGGL(ring_kernel_for(h), dim3(blocks), dim3((unsigned)h->ring_block), (size_t)h->lds.total,
                        stream, p);
     if (optimistic) launch_general(h, n_cand, pl, rk, out, h->d_fb_list, h->d_fb_count, stream);
   }
@@ -533,7 +540,7 @@ int dagsched_create(const dagsched_desc_t *desc, dagsched_t **out) {
   }
   if (ok && plan.ok) {
     h->variant = plan.exact ? kVariantRingExact : kVariantRingOptimistic;
-    h->ring_G = plan.G; h->ring_slots = plan.ring; h->ring_feeders = plan.feeders; h->lds = plan.lds; h->time_scale = plan.scale;
+    h->ring_G = plan.G; h->ring_slots = plan.ring; h->ring_feeders = plan.feeders; h->ring_block = plan.block; h->lds = plan.lds; h->time_scale = plan.scale;
     h->rec_plane = plan.rec_plane; h->id_bits = plan.id_bits;
     const int64_t cap = ((int64_t)h->N + h->E + 1024) * 64;
     h->spin_cap = (uint32_t)std::min<int64_t>(cap, 0x7FFFFFFF);
@@ -654,7 +661,7 @@ int dagsched_get_info(const dagsched_t *h, dagsched_info_t *info) {
   info->variant = h->variant;
   const bool ring = h->variant == kVariantRingExact || h->variant == kVariantRingOptimistic;
   info->cand_per_block = ring ? h->ring_G : h->gen_G;
-  info->block_threads = ring ? ring_threads(h->ring_feeders) : kWave;
+  info->block_threads = ring ? h->ring_block : kWave;
   info->lds_bytes = ring ? (int32_t)h->lds.total : h->gen_lds;
   info->state_bits = ring ? 16 : 32;
   info->reserved[0] = ring ? h->ring_slots : 0;

@@ -99,8 +99,10 @@ struct RingParams {
 // PIBL = 1: the placement bytes of the workgroup's candidates sit in LDS (fastest feeders); PIBL = 0: in an
 // L2-resident workspace, which leaves the LDS to more candidates or a deeper ring.
 template <int RING, int FEEDERS, int HALF, int PIBL>
-__global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingParams p) {
-  constexpr int kThreads = ring_threads(FEEDERS);
+__global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
+  // ring_threads(FEEDERS) threads have a role while the schedule is relaxed; the host may launch more (a
+  // multiple of 64): the extra wavefronts only help with ingest and then wait at the final barrier.
+  const int kThreads = (int)blockDim.x;
   constexpr int kFeeders = FEEDERS;
   extern __shared__ __align__(16) unsigned char lds[];
   static_assert((RING & (RING - 1)) == 0, "RING must be a power of two");
@@ -478,7 +480,7 @@ __global__ __launch_bounds__(ring_threads(FEEDERS)) void relax_ring_kernel(RingP
         }
       }
     }
-  } else {
+  } else if (wave == kFeeders + 1) {
     // ------------------------------------------------------------ accountant
     // Peak of the running memory level of machine j (eqs. (17)-(19)): it depends on the order only,
     // so one wavefront walks the order lists on its own, four operations per trip.
