@@ -75,7 +75,7 @@ struct dagsched {
   int64_t *d_mem = nullptr, *d_weight = nullptr, *d_limit = nullptr;
   int32_t *ws_list = nullptr, *ws_end = nullptr;
   // ring kernel
-  int32_t ring_G = 0, ring_slots = 0, ring_feeders = 1, ring_block = 256, rec_plane = 0, id_bits = 16, time_scale = 1;
+  int32_t ring_G = 0, ring_slots = 0, ring_feeders = 1, ring_preds = 4, ring_block = 256, rec_plane = 0, id_bits = 16, time_scale = 1;
   uint8_t *d_nparts = nullptr;
   int64_t list_stride = 0, pib_stride = 0;
   uint8_t *ws_pib = nullptr;
@@ -208,11 +208,11 @@ LdsLayout ring_layout(int N, int P, int G, int ring, bool pib_lds) {
 // footprint that fits a workgroup.
 using RingKernel = void (*)(RingParams);
 template <int HALF>
-RingKernel ring_kernel_pick(int ring, int feeders, bool pib_lds);
+RingKernel ring_kernel_pick(int ring, int feeders, bool pib_lds, int preds);
 
 struct RingPlan {
   bool ok = false, exact = false;
-  int G = 0, ring = 0, feeders = 1, block = 256;
+  int G = 0, ring = 0, feeders = 1, preds = 4, block = 256;
   int32_t scale = 1;
   LdsLayout lds{};
   std::vector<uint4> rec;
@@ -299,6 +299,10 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
   int max_parts = 1;
   for (int v = 0; v < N; ++v) max_parts = std::max(max_parts, ((int)op_preds[v].size() + PR - 1) / PR);
   if (max_parts > 16) return plan;                     // very wide fan-in: leave it to the general kernel
+  // no operation with more than two DAG predecessors: the kernels that look at two per op are enough
+  size_t max_deg = 0;
+  for (int v = 0; v < N; ++v) max_deg = std::max(max_deg, op_preds[v].size());
+  plan.preds = (max_deg <= 2 && env_int("DAGSCHED_RING_PREDS", 2) == 2) ? 2 : 4;
   const int plane = N;
   std::vector<uint4> rec((size_t)max_parts * plane, make_uint4(dummy | (dummy << 16), dummy | (dummy << 16), 0, 0));
   for (int v = 0; v < N; ++v) {
@@ -365,7 +369,8 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
     }
   }
   plan.feeders = force_feeders ? force_feeders : (best_wgs * 4 <= 24 ? 2 : 1);
-  if (best_score < 0 || !ring_kernel_pick<0>(plan.ring, plan.feeders, plan.lds.pi_stride != 0)) return plan;   // shape not built
+  if (best_score < 0 || !ring_kernel_pick<0>(plan.ring, plan.feeders, plan.lds.pi_stride != 0, 4)) return plan;   // shape not built
+  if (!ring_kernel_pick<0>(plan.ring, plan.feeders, plan.lds.pi_stride != 0, plan.preds)) plan.preds = 4;
   // workgroup size: the wavefronts with a role, plus helpers for the ingest phase when the LDS leaves the CU
   // nearly empty of wavefronts (one workgroup per CU: 1024 threads, two: 512)
   plan.block = ring_threads(plan.feeders);
@@ -379,8 +384,8 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
 
 using RingKernel = void (*)(RingParams);
 template <int HALF>
-RingKernel ring_kernel_pick(int ring, int feeders, bool pib_lds) {
-  switch ((pib_lds ? 1000 : 0) + ring * 10 + feeders) {
+RingKernel ring_kernel_pick(int ring, int feeders, bool pib_lds, int preds) {
+  switch ((preds == 2 ? 10000 : 0) + (pib_lds ? 1000 : 0) + ring * 10 + feeders) {
     case 1041: return relax_ring_kernel<4, 1, HALF, 1>;
     case 1042: return relax_ring_kernel<4, 2, HALF, 1>;
     case 1081: return relax_ring_kernel<8, 1, HALF, 1>;
@@ -394,6 +399,16 @@ RingKernel ring_kernel_pick(int ring, int feeders, bool pib_lds) {
     case 164:  return relax_ring_kernel<16, 4, HALF, 0>;
     case 321:  return relax_ring_kernel<32, 1, HALF, 0>;
     case 322:  return relax_ring_kernel<32, 2, HALF, 0>;
+    case 11041: return relax_ring_kernel<4, 1, HALF, 1, 2>;
+    case 11042: return relax_ring_kernel<4, 2, HALF, 1, 2>;
+    case 11081: return relax_ring_kernel<8, 1, HALF, 1, 2>;
+    case 11082: return relax_ring_kernel<8, 2, HALF, 1, 2>;
+    case 10081: return relax_ring_kernel<8, 1, HALF, 0, 2>;
+    case 10082: return relax_ring_kernel<8, 2, HALF, 0, 2>;
+    case 10161: return relax_ring_kernel<16, 1, HALF, 0, 2>;
+    case 10162: return relax_ring_kernel<16, 2, HALF, 0, 2>;
+    case 10321: return relax_ring_kernel<32, 1, HALF, 0, 2>;
+    case 10322: return relax_ring_kernel<32, 2, HALF, 0, 2>;
     default:   return nullptr;
   }
 }
@@ -401,8 +416,8 @@ RingKernel ring_kernel_for(const dagsched *h) {
   // byte addresses when the workgroup's end-time arrays fit 64 KB, half addresses otherwise
   const bool half = (uint64_t)h->ring_G * h->lds.s_stride > 65536u;
   const bool pib_lds = h->lds.pi_stride != 0;
-  return half ? ring_kernel_pick<1>(h->ring_slots, h->ring_feeders, pib_lds)
-              : ring_kernel_pick<0>(h->ring_slots, h->ring_feeders, pib_lds);
+  return half ? ring_kernel_pick<1>(h->ring_slots, h->ring_feeders, pib_lds, h->ring_preds)
+              : ring_kernel_pick<0>(h->ring_slots, h->ring_feeders, pib_lds, h->ring_preds);
 }
 
 OutPtrs make_out(const dagsched *h, int32_t n_cand, int32_t *makespan, int64_t *bubble, int64_t *peak_mem,
@@ -540,7 +555,7 @@ int dagsched_create(const dagsched_desc_t *desc, dagsched_t **out) {
   }
   if (ok && plan.ok) {
     h->variant = plan.exact ? kVariantRingExact : kVariantRingOptimistic;
-    h->ring_G = plan.G; h->ring_slots = plan.ring; h->ring_feeders = plan.feeders; h->ring_block = plan.block; h->lds = plan.lds; h->time_scale = plan.scale;
+    h->ring_G = plan.G; h->ring_slots = plan.ring; h->ring_feeders = plan.feeders; h->ring_preds = plan.preds; h->ring_block = plan.block; h->lds = plan.lds; h->time_scale = plan.scale;
     h->rec_plane = plan.rec_plane; h->id_bits = plan.id_bits;
     const int64_t cap = ((int64_t)h->N + h->E + 1024) * 64;
     h->spin_cap = (uint32_t)std::min<int64_t>(cap, 0x7FFFFFFF);
@@ -666,7 +681,7 @@ int dagsched_get_info(const dagsched_t *h, dagsched_info_t *info) {
   info->state_bits = ring ? 16 : 32;
   info->reserved[0] = ring ? h->ring_slots : 0;
   info->reserved[1] = h->time_scale;
-  info->reserved[2] = ring ? (h->ring_feeders | ((h->lds.pi_stride != 0 ? 1 : 0) << 8)) : 0;
+  info->reserved[2] = ring ? (h->ring_feeders | ((h->lds.pi_stride != 0 ? 1 : 0) << 8) | (h->ring_preds << 16)) : 0;
   return DAGSCHED_OK;
 }
 

@@ -98,7 +98,9 @@ struct RingParams {
 // FEEDERS feeder wavefronts share a lane's stream: feeder f owns the parts with seq % FEEDERS == f.
 // PIBL = 1: the placement bytes of the workgroup's candidates sit in LDS (fastest feeders); PIBL = 0: in an
 // L2-resident workspace, which leaves the LDS to more candidates or a deeper ring.
-template <int RING, int FEEDERS, int HALF, int PIBL>
+// PR: DAG predecessors per op, 4 or 2.  With 2 (chosen by the host when no operation has more than two DAG
+// predecessors) the second pair of every record and op is the dummy and neither the feeders nor the relaxer look at it.
+template <int RING, int FEEDERS, int HALF, int PIBL, int PR = 4>
 __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
   // ring_threads(FEEDERS) threads have a role while the schedule is relaxed; the host may launch more (a
   // multiple of 64): the extra wavefronts only help with ingest and then wait at the final barrier.
@@ -107,6 +109,7 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
   extern __shared__ __align__(16) unsigned char lds[];
   static_assert((RING & (RING - 1)) == 0, "RING must be a power of two");
   static_assert(RING >= FEEDERS, "every feeder needs a slot of its own");
+  static_assert(PR == 4 || PR == 2, "two or four predecessors per op");
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63;
@@ -325,17 +328,18 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
         // end times arrive, so it is off the critical path)
         const bool valid = (r.w & 0xFFFFu) != kNotDone16;
         const uint32_t f0 = valid ? r.x : z0, f1 = valid ? r.y : z0, f2 = valid ? r.z : 0u, f3 = valid ? r.w : z3;
-        uint32_t x = max(max(x_acc, e0 + (w2 & 0xFFu)), e1 + ((w2 >> 8) & 0xFFu));
-        x = max(max(x, e2 + ((w2 >> 16) & 0xFFu)), e3 + (w2 >> 24));
+        uint32_t x = max(max(x_acc, e0 + (w2 & 0xFFu)), e1 + (PR == 4 ? (w2 >> 8) & 0xFFu : w2 >> 8));
+        if (PR == 4) x = max(max(x, e2 + ((w2 >> 16) & 0xFFu)), e3 + (w2 >> 24));
         x += w3 & 0xFFFFu;
         const bool ran = x < kNotDone16;                    // every predecessor ended and no 16-bit overflow (or the no-op)
         x_acc = ran ? x : x_acc;                            // the machine is busy until x (chain edge, eq. (7))
         cell(ran ? (w3 >> 16) : trash) = (uint16_t)x;
         w0 = ran ? f0 : w0;
-        w1 = ran ? f1 : w1;
+        if (PR == 4) w1 = ran ? f1 : w1;
         // The end-time reads of the next trip go out as early as possible (LDS accesses keep their
         // program order, so everything below overlaps with their latency).
-        e0 = cell(w0 & 0xFFFFu); e1 = cell(w0 >> 16); e2 = cell(w1 & 0xFFFFu); e3 = cell(w1 >> 16);
+        e0 = cell(w0 & 0xFFFFu); e1 = cell(w0 >> 16);
+        if (PR == 4) { e2 = cell(w1 & 0xFFFFu); e3 = cell(w1 >> 16); }
         const bool take = ran && valid;
         // One trip without progress while every unfinished machine holds an op is already a deadlock
         // (end times only change when some op runs), so progress is sampled once per window.
@@ -357,7 +361,7 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
         // the held ops has all its predecessors ended, only the 16-bit range stopped it (optimistic mode:
         // the int32 kernel takes the candidate); otherwise every held op waits for an op that can never
         // run, i.e. the combined graph has a cycle.
-        const bool range_stop = !idle && max(max(e0, e1), max(e2, e3)) < kNotDone16;
+        const bool range_stop = !idle && max(max(e0, e1), PR == 4 ? max(e2, e3) : 0u) < kNotDone16;
         const bool overflow = (__ballot(range_stop) & segmask) != 0;
         stalled = true;
         dead = true;
@@ -437,11 +441,11 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
         Entry &e2 = E[(s + 1) % kStages];             // the oldest: written in this trip (e1 itself when the depth is two)
         if (kStages == 2) {
           e1.q0 = pib(e1.rec.x & 0xFFFFu); e1.q1 = pib(e1.rec.x >> 16);
-          e1.q2 = pib(e1.rec.y & 0xFFFFu); e1.q3 = pib(e1.rec.y >> 16);
+          if (PR == 4) { e1.q2 = pib(e1.rec.y & 0xFFFFu); e1.q3 = pib(e1.rec.y >> 16); }
         }
         // (A) channel delays of e2
-        const uint32_t d0 = commr[e2.q0 << lps], d1 = commr[e2.q1 << lps], d2 = commr[e2.q2 << lps];
-        const uint32_t d3 = commr[e2.q3 << lps];
+        const uint32_t d0 = commr[e2.q0 << lps], d1 = commr[e2.q1 << lps];
+        const uint32_t d2 = PR == 4 ? commr[e2.q2 << lps] : 0u, d3 = PR == 4 ? commr[e2.q3 << lps] : 0u;
         // (1) move the cursor past the part admitted in the previous trip and the other feeders' parts
         if (pending) {
 #pragma unroll
@@ -460,7 +464,7 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
         // (B) placement bytes of e1's predecessors (its record was requested one trip ago)
         if (kStages == 3) {
           e1.q0 = pib(e1.rec.x & 0xFFFFu); e1.q1 = pib(e1.rec.x >> 16);
-          e1.q2 = pib(e1.rec.y & 0xFFFFu); e1.q3 = pib(e1.rec.y >> 16);
+          if (PR == 4) { e1.q2 = pib(e1.rec.y & 0xFFFFu); e1.q3 = pib(e1.rec.y >> 16); }
         }
         // (D) pack e2 and publish it
         if (e2.fl & 1u) {

@@ -156,6 +156,7 @@ class Evaluator:
         d = {k: getattr(i, k) for k in ("variant", "cand_per_block", "block_threads", "lds_bytes", "state_bits")}
         d["ring_slots"], d["time_scale"] = i.reserved[0], i.reserved[1]
         d["feeders"], d["placement_bytes_in_lds"] = i.reserved[2] & 0xFF, (i.reserved[2] >> 8) & 1
+        d["preds_per_op"] = (i.reserved[2] >> 16) & 0xFF
         return d
 
     def _n_cand(self, placement, rank) -> int:

@@ -219,6 +219,8 @@ def _with_env(env, fn):
     {"DAGSCHED_RING_FEEDERS": 2, "DAGSCHED_RING_SLOTS": 8, "DAGSCHED_RING_PIB_LDS": 0},
     {"DAGSCHED_RING_FEEDERS": 2, "DAGSCHED_RING_SLOTS": 16, "DAGSCHED_RING_PIB_LDS": 0},
     {"DAGSCHED_RING_FEEDERS": 1, "DAGSCHED_RING_SLOTS": 32, "DAGSCHED_RING_PIB_LDS": 0},
+    {"DAGSCHED_RING_FEEDERS": 2, "DAGSCHED_RING_SLOTS": 8, "DAGSCHED_RING_PIB_LDS": 1, "DAGSCHED_RING_PREDS": 4},
+    {"DAGSCHED_RING_FEEDERS": 2, "DAGSCHED_RING_SLOTS": 16, "DAGSCHED_RING_PIB_LDS": 0, "DAGSCHED_RING_PREDS": 4},
 ])
 def test_every_kernel_variant(gpu_lib, env):
     """The tuning knobs only pick among kernel instantiations; each one must give the same bits."""
@@ -235,6 +237,10 @@ def test_every_kernel_variant(gpu_lib, env):
             assert info["placement_bytes_in_lds"] == env["DAGSCHED_RING_PIB_LDS"]
             if "DAGSCHED_RING_G" in env:
                 assert info["cand_per_block"] == env["DAGSCHED_RING_G"]
+            # the pipeline workloads have at most two DAG predecessors per operation: the two-predecessor kernels
+            # take them where they are built (one or two feeders) unless the knob says otherwise
+            two = w.name.startswith(("cfg1", "cfg2")) and env["DAGSCHED_RING_FEEDERS"] <= 2 and env.get("DAGSCHED_RING_PREDS", 2) == 2
+            assert info["preds_per_op"] == (2 if two else 4), (w.name, info)
 
 
 def test_sixteen_bit_overflow_falls_back(gpu_lib):
