@@ -425,6 +425,8 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
       for (int i = 0; i + 1 < kFeeders; ++i) ids[i] = in_node ? ids[i] : ids[i + 1];
     };
     for (int i = 0; i < f; ++i) advance();                  // feeder f starts at its first own part
+#pragma unroll
+    for (int i = 0; i < kFeeders; ++i) ids[i] = has_ops ? (uint32_t)list[min(k + 1u + (uint32_t)i, klast)] : 0u;
     struct Entry { uint4 rec; uint32_t q0, q1, q2, q3, fl; };   // fl: 1 valid, 2 last part of the lane
     constexpr int kStages = PIBL ? 2 : 3;
     Entry E[kStages];
@@ -447,22 +449,28 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
         const uint32_t d0 = commr[e2.q0 << lps], d1 = commr[e2.q1 << lps];
         const uint32_t d2 = PR == 4 ? commr[e2.q2 << lps] : 0u, d3 = PR == 4 ? commr[e2.q3 << lps] : 0u;
         // (1) move the cursor past the part admitted in the previous trip and the other feeders' parts
+        const bool moved = pending;
         if (pending) {
 #pragma unroll
           for (int a = 0; a < kFeeders; ++a) advance();
           aseq += kFeeders;
         }
-        // (2) entries of the next nodes (reloaded every trip; consumed one trip later at the earliest)
+        // (2) entries of the next nodes (consumed one trip later at the earliest).  Lanes whose cursor stayed
+        // keep theirs and all read the same entry instead, which costs the vector cache one line, not one per lane.
 #pragma unroll
-        for (int i = 0; i < kFeeders; ++i) ids[i] = list[min(k + 1u + (uint32_t)i, klast)];
+        for (int i = 0; i < kFeeders; ++i) {
+          const uint32_t t = list[moved ? min(k + 1u + (uint32_t)i, klast) : 0u];
+          ids[i] = moved ? t : ids[i];
+        }
         // (3) admission
         pending = (k <= klast) &&
                   *(lds_vu32_t *)(ring_lane + ((aseq & (uint32_t)(RING - 1)) << 10) + 12) == (((aseq - (uint32_t)RING) << 16) | kNotDone16);
         e0.fl = pending ? (1u | ((k == klast && rem == 0u) ? 2u : 0u)) : 0u;
-        e0.rec = p.rec[addr];
+        e0.rec = p.rec[pending ? addr : 0u];                 // lanes that admit nothing share one record
         admitted += pending ? 1u : 0u;
         // (B) placement bytes of e1's predecessors (its record was requested one trip ago)
         if (kStages == 3) {
+          if (!(e1.fl & 1u)) e1.rec.x = e1.rec.y = (uint32_t)N | ((uint32_t)N << 16);   // nothing admitted: the dummy node's byte
           e1.q0 = pib(e1.rec.x & 0xFFFFu); e1.q1 = pib(e1.rec.x >> 16);
           if (PR == 4) { e1.q2 = pib(e1.rec.y & 0xFFFFu); e1.q3 = pib(e1.rec.y >> 16); }
         }
