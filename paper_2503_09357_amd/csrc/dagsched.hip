@@ -180,12 +180,14 @@ int env_int(const char *name, int dflt) {
   return (s && *s) ? atoi(s) : dflt;
 }
 
-LdsLayout ring_layout(int N, int P, int G, int ring, bool pib_lds) {
+// pib_lds: 0 placement bytes in L2, 1 in LDS, 2 in LDS as nibbles (P <= 16)
+LdsLayout ring_layout(int N, int P, int G, int ring, int pib_lds) {
   LdsLayout o{};
   uint32_t at = 0;
   o.s_stride = align_up(2u * (uint32_t)(N + 2), 4);      // N cells + dummy + trash; the arrays start at LDS offset 0
   at += (uint32_t)G * o.s_stride;
-  o.pi_stride = pib_lds ? align_up((uint32_t)(N + 1), 4) : 0u;
+  o.pi_stride = pib_lds == 1 ? align_up((uint32_t)(N + 1), 4) : pib_lds == 2 ? align_up((uint32_t)(N + 2) / 2u, 4) : 0u;
+  o.pib_mode = (uint32_t)pib_lds;
   o.o_pi = at;    at += (uint32_t)G * o.pi_stride;
   at = align_up(at, 16);
   o.o_ring = at;  at += (uint32_t)ring * kWave * 16u;
@@ -208,7 +210,7 @@ LdsLayout ring_layout(int N, int P, int G, int ring, bool pib_lds) {
 // footprint that fits a workgroup.
 using RingKernel = void (*)(RingParams);
 template <int HALF>
-RingKernel ring_kernel_pick(int ring, int feeders, bool pib_lds, int preds);
+RingKernel ring_kernel_pick(int ring, int feeders, int pib_lds, int preds);
 
 struct RingPlan {
   bool ok = false, exact = false;
@@ -256,7 +258,6 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
   const int64_t lower = std::max<int64_t>(crit, (sum_dur / g + P - 1) / P);
   if (lower >= (int64_t)kNotDone16) return plan;       // no candidate could stay inside 16 bits
   const int64_t upper = sum_dur / g + (int64_t)(N - 1) * (max_comm / g);
-  plan.exact = upper < (int64_t)kNotDone16;
   plan.scale = (int32_t)g;
 
   constexpr int PR = 4;                                // DAG predecessors per op part
@@ -353,24 +354,27 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
   int best_wgs = 0;
   for (int G = kWave / Pseg; G >= 1; G >>= 1) {
     if (force_g && G != force_g) continue;
-    for (int pib_lds = 1; pib_lds >= 0; --pib_lds) {
+    for (int pib_lds : {1, 2, 0}) {
       if (force_pib >= 0 && pib_lds != force_pib) continue;
+      if (pib_lds == 2 && P > 16) continue;               // a nibble per node
       for (int ring : {8, 16, 32, 4}) {
         if (force_ring && ring != force_ring) continue;
         if (pib_lds ? ring > 8 : ring < 8) continue;     // instantiated: LDS with 4 or 8 slots, L2 with 8, 16 or 32
-        LdsLayout o = ring_layout(N, P, G, ring, pib_lds != 0);
+        LdsLayout o = ring_layout(N, P, G, ring, pib_lds);
         if ((int)o.total > lds_max) continue;
         if ((uint64_t)G * (o.s_stride >> 1) > 65536u) continue;   // half-addresses must fit 16 bits
         const int wgs = std::min(5, lds_max / (int)align_up(o.total, 512));   // beyond ~20 wavefronts the CU is issue-bound
         if (wgs < 1) continue;
-        const int64_t score = (int64_t)wgs * G * (ring >= 8 ? 100 : 70) * (pib_lds ? 100 : 97) + (ring == 16 ? 2 : 0) + G;
+        const int64_t score = (int64_t)wgs * G * (ring >= 8 ? 100 : 70) * (pib_lds == 1 ? 100 : pib_lds == 2 ? 99 : 97) + (ring == 16 ? 2 : 0) + G;
         if (score > best_score) { best_score = score; best_wgs = wgs; plan.G = G; plan.ring = ring; plan.lds = o; }
       }
     }
   }
   plan.feeders = force_feeders ? force_feeders : (best_wgs * 4 <= 24 ? 2 : 1);
-  if (best_score < 0 || !ring_kernel_pick<0>(plan.ring, plan.feeders, plan.lds.pi_stride != 0, 4)) return plan;   // shape not built
-  if (!ring_kernel_pick<0>(plan.ring, plan.feeders, plan.lds.pi_stride != 0, plan.preds)) plan.preds = 4;
+  if (best_score < 0 || !ring_kernel_pick<0>(plan.ring, plan.feeders, (int)plan.lds.pib_mode, 4)) return plan;   // shape not built
+  if (!ring_kernel_pick<0>(plan.ring, plan.feeders, (int)plan.lds.pib_mode, plan.preds)) plan.preds = 4;
+  // the nibble kernels start time at 255 (see the kernel), which the 16-bit range must hold as well
+  plan.exact = upper + (plan.lds.pib_mode == 2 ? 255 : 0) < (int64_t)kNotDone16;
   // workgroup size: the wavefronts with a role, plus helpers for the ingest phase when the LDS leaves the CU
   // nearly empty of wavefronts (one workgroup per CU: 1024 threads, two: 512)
   plan.block = ring_threads(plan.feeders);
@@ -384,8 +388,8 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
 
 using RingKernel = void (*)(RingParams);
 template <int HALF>
-RingKernel ring_kernel_pick(int ring, int feeders, bool pib_lds, int preds) {
-  switch ((preds == 2 ? 10000 : 0) + (pib_lds ? 1000 : 0) + ring * 10 + feeders) {
+RingKernel ring_kernel_pick(int ring, int feeders, int pib_lds, int preds) {
+  switch ((preds == 2 ? 10000 : 0) + pib_lds * 1000 + ring * 10 + feeders) {
     case 1041: return relax_ring_kernel<4, 1, HALF, 1>;
     case 1042: return relax_ring_kernel<4, 2, HALF, 1>;
     case 1081: return relax_ring_kernel<8, 1, HALF, 1>;
@@ -409,13 +413,21 @@ RingKernel ring_kernel_pick(int ring, int feeders, bool pib_lds, int preds) {
     case 10162: return relax_ring_kernel<16, 2, HALF, 0, 2>;
     case 10321: return relax_ring_kernel<32, 1, HALF, 0, 2>;
     case 10322: return relax_ring_kernel<32, 2, HALF, 0, 2>;
+    case 2041:  return relax_ring_kernel<4, 1, HALF, 2>;
+    case 2042:  return relax_ring_kernel<4, 2, HALF, 2>;
+    case 2081:  return relax_ring_kernel<8, 1, HALF, 2>;
+    case 2082:  return relax_ring_kernel<8, 2, HALF, 2>;
+    case 12041: return relax_ring_kernel<4, 1, HALF, 2, 2>;
+    case 12042: return relax_ring_kernel<4, 2, HALF, 2, 2>;
+    case 12081: return relax_ring_kernel<8, 1, HALF, 2, 2>;
+    case 12082: return relax_ring_kernel<8, 2, HALF, 2, 2>;
     default:   return nullptr;
   }
 }
 RingKernel ring_kernel_for(const dagsched *h) {
   // byte addresses when the workgroup's end-time arrays fit 64 KB, half addresses otherwise
   const bool half = (uint64_t)h->ring_G * h->lds.s_stride > 65536u;
-  const bool pib_lds = h->lds.pi_stride != 0;
+  const int pib_lds = (int)h->lds.pib_mode;
   return half ? ring_kernel_pick<1>(h->ring_slots, h->ring_feeders, pib_lds, h->ring_preds)
               : ring_kernel_pick<0>(h->ring_slots, h->ring_feeders, pib_lds, h->ring_preds);
 }
@@ -681,7 +693,7 @@ int dagsched_get_info(const dagsched_t *h, dagsched_info_t *info) {
   info->state_bits = ring ? 16 : 32;
   info->reserved[0] = ring ? h->ring_slots : 0;
   info->reserved[1] = h->time_scale;
-  info->reserved[2] = ring ? (h->ring_feeders | ((h->lds.pi_stride != 0 ? 1 : 0) << 8) | (h->ring_preds << 16)) : 0;
+  info->reserved[2] = ring ? (h->ring_feeders | ((int)h->lds.pib_mode << 8) | (h->ring_preds << 16)) : 0;
   return DAGSCHED_OK;
 }
 

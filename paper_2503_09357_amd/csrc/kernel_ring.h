@@ -69,6 +69,7 @@ constexpr int ring_threads(int feeders) { return (2 + feeders) * kWave; }   // r
 struct LdsLayout {
   uint32_t s_stride, pi_stride;                       // bytes per candidate; the state array starts at 0
   uint32_t o_pi, o_ring, o_scr, o_total, o_peak, o_cnt, o_off, o_flag, o_abort, o_comm, total;
+  uint32_t pib_mode;                                  // where the placement bytes are: 0 L2 workspace, 1 LDS, 2 LDS as nibbles
 };
 
 struct RingParams {
@@ -97,7 +98,10 @@ struct RingParams {
 
 // FEEDERS feeder wavefronts share a lane's stream: feeder f owns the parts with seq % FEEDERS == f.
 // PIBL = 1: the placement bytes of the workgroup's candidates sit in LDS (fastest feeders); PIBL = 0: in an
-// L2-resident workspace, which leaves the LDS to more candidates or a deeper ring.
+// L2-resident workspace, which leaves the LDS to more candidates or a deeper ring; PIBL = 2 (P <= 16): in LDS,
+// four bits per node.  A nibble cannot name the dummy machine P, so in that mode time starts at kOrigin = 255
+// instead of 0: the dummy cell still holds 0, and 0 + any delay <= 255 never exceeds a machine-free time, which
+// makes the dummy's placement irrelevant.  The origin is subtracted from the makespan at the end.
 // PR: DAG predecessors per op, 4 or 2.  With 2 (chosen by the host when no operation has more than two DAG
 // predecessors) the second pair of every record and op is the dummy and neither the feeders nor the relaxer look at it.
 template <int RING, int FEEDERS, int HALF, int PIBL, int PR = 4>
@@ -110,6 +114,7 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
   static_assert((RING & (RING - 1)) == 0, "RING must be a power of two");
   static_assert(RING >= FEEDERS, "every feeder needs a slot of its own");
   static_assert(PR == 4 || PR == 2, "two or four predecessors per op");
+  constexpr uint32_t kOrigin = PIBL == 2 ? 255u : 0u;
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63;
@@ -158,10 +163,12 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
     const int32_t *pl = p.placement + (c0 + gg) * N;
     uint8_t *pib = PIBL ? lds + o.o_pi + gg * o.pi_stride : p.ws_pib + (c0 + gg) * p.pib_stride;
     int32_t *cnt_g = cntw + gg * Pseg;
-    if (tt == 0) pib[N] = (uint8_t)P;                       // the dummy node sits on a dummy machine whose delays are all zero
+    if (PIBL == 2) { if (tt == 0 && !(N & 1)) pib[N >> 1] = 0; }   // the dummy's nibble: any machine will do
+    else if (tt == 0) pib[N] = (uint8_t)P;                  // the dummy node sits on a dummy machine whose delays are all zero
     if (vec_ok) {
       const int4 *pl4 = (const int4 *)pl;
       uint32_t *piw = (uint32_t *)pib;
+      uint16_t *pih = (uint16_t *)pib;
       for (int q0 = tt; q0 < nq; q0 += 4 * tpc) {
         int4 a[4];
 #pragma unroll
@@ -178,11 +185,23 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
             if (bad) {
               atomicOr(&flagw[gg], kBitBadPlacement);
             } else {
-              piw[q] = (uint32_t)a[u].x | ((uint32_t)a[u].y << 8) | ((uint32_t)a[u].z << 16) | ((uint32_t)a[u].w << 24);
+              if (PIBL == 2) pih[q] = (uint16_t)((uint32_t)a[u].x | ((uint32_t)a[u].y << 4) | ((uint32_t)a[u].z << 8) | ((uint32_t)a[u].w << 12));
+              else piw[q] = (uint32_t)a[u].x | ((uint32_t)a[u].y << 8) | ((uint32_t)a[u].z << 16) | ((uint32_t)a[u].w << 24);
               atomicAdd(&cnt_g[a[u].x], 1); atomicAdd(&cnt_g[a[u].y], 1);
               atomicAdd(&cnt_g[a[u].z], 1); atomicAdd(&cnt_g[a[u].w], 1);
             }
           }
+        }
+      }
+    } else if (PIBL == 2) {
+      for (int h = tt; 2 * h < N; h += tpc) {               // two nodes per thread: one byte of nibbles (node N is the dummy)
+        const int32_t pa = pl[2 * h], pb = (2 * h + 1 < N) ? pl[2 * h + 1] : 0;
+        if ((uint32_t)pa >= (uint32_t)P || (uint32_t)pb >= (uint32_t)P) {
+          atomicOr(&flagw[gg], kBitBadPlacement);
+        } else {
+          pib[h] = (uint8_t)(pa | (pb << 4));
+          atomicAdd(&cnt_g[pa], 1);
+          if (2 * h + 1 < N) atomicAdd(&cnt_g[pb], 1);
         }
       }
     } else {
@@ -230,6 +249,7 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
     if (vec_ok) {
       const int4 *rk4 = (const int4 *)rk;
       const uint32_t *piw = (const uint32_t *)pib;
+      const uint16_t *pih = (const uint16_t *)pib;
       const uint32_t *np4 = (const uint32_t *)p.nparts;     // four part counts per load (N % 4 == 0 here)
       for (int q0 = tt; q0 < nq; q0 += 4 * tpc) {
         int4 a[4];
@@ -244,7 +264,13 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
         for (int u = 0; u < 4; ++u) {
           const int q = q0 + u * tpc;
           if (q < nq) {
-            const uint32_t pw = piw[q];
+            uint32_t pw;
+            if (PIBL == 2) {                                  // four nibbles, spread to four bytes
+              const uint32_t h = pih[q];
+              pw = (h & 0xFu) | ((h & 0xF0u) << 4) | ((h & 0xF00u) << 8) | ((h & 0xF000u) << 12);
+            } else {
+              pw = piw[q];
+            }
             place(4 * q + 0, pw & 0xFF, a[u].x, npw[u] & 0xFF);
             place(4 * q + 1, (pw >> 8) & 0xFF, a[u].y, (npw[u] >> 8) & 0xFF);
             place(4 * q + 2, (pw >> 16) & 0xFF, a[u].z, (npw[u] >> 16) & 0xFF);
@@ -253,7 +279,8 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
         }
       }
     } else {
-      for (int v = tt; v < N; v += tpc) place(v, pib[v], rk[v], p.nparts ? (uint32_t)p.nparts[v] - 1u : 0u);
+      for (int v = tt; v < N; v += tpc)
+        place(v, PIBL == 2 ? (pib[v >> 1] >> ((v & 1) << 2)) & 0xF : pib[v], rk[v], p.nparts ? (uint32_t)p.nparts[v] - 1u : 0u);
     }
   }
   __syncthreads();
@@ -306,7 +333,7 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
     __builtin_amdgcn_s_setprio(3);                          // the relaxer's trip is the critical path of the workgroup:
                                                             // it goes first wherever it shares a SIMD (measured: 4-5 % on the MoE workload)
     bool idle = true, dead = !has_ops;                      // idle: the registers hold the no-op
-    uint32_t x_acc = 0;
+    uint32_t x_acc = kOrigin;                               // the machine is free from the time origin on
     uint32_t t10 = 0;                                       // ops taken from the ring, times 1024 (the slot stride)
     constexpr uint32_t kSlotMask = (uint32_t)(RING - 1) << 10;
     lds_byte_t *const scr_p = ldsb + o.o_scr + (uint32_t)lane * 4u;   // where lanes that take nothing write their "slot free" mark
@@ -373,7 +400,7 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
       const bool fin = dead || (idle && (t10 >> 10) == *total_p);
       if (!fin) { flagw[g] = kBitInternal; *abort_p = 1; }
     }
-    acc = (int32_t)x_acc;
+    acc = (int32_t)(x_acc - kOrigin);
   } else if (wave <= kFeeders) {
     // ------------------------------------------------------------ feeders
     // Per lane the op parts of machine j form a stream (the parts of one operation are consecutive;
@@ -388,7 +415,10 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
     const int f = wave - 1;
     const uint8_t *const pib_g = p.ws_pib + (c0 + (cand_ok ? g : 0)) * p.pib_stride;   // L2-resident: this workgroup wrote it
     lds_cu8_t *const pib_l = (lds_cu8_t *)(ldsb + o.o_pi + g * o.pi_stride);
-    auto pib = [&](uint32_t u) -> uint32_t { return PIBL ? (uint32_t)pib_l[u] : (uint32_t)pib_g[u]; };
+    auto pib = [&](uint32_t u) -> uint32_t {
+      if (PIBL == 2) return ((uint32_t)pib_l[u >> 1] >> ((u & 1u) << 2)) & 0xFu;
+      return PIBL ? (uint32_t)pib_l[u] : (uint32_t)pib_g[u];
+    };
     lds_cu8_t *const commr = (lds_cu8_t *)(ldsb + o.o_comm) + j;
     lds_byte_t *const ring_lane = ldsb + o.o_ring + (uint32_t)lane * 16u;
     lds_vi32_t *const abort_p = (lds_vi32_t *)(ldsb + o.o_abort) + g;

@@ -155,7 +155,7 @@ class Evaluator:
         _check(load().dagsched_get_info(self._h, ctypes.byref(i)))
         d = {k: getattr(i, k) for k in ("variant", "cand_per_block", "block_threads", "lds_bytes", "state_bits")}
         d["ring_slots"], d["time_scale"] = i.reserved[0], i.reserved[1]
-        d["feeders"], d["placement_bytes_in_lds"] = i.reserved[2] & 0xFF, (i.reserved[2] >> 8) & 1
+        d["feeders"], d["placement_bytes_in_lds"] = i.reserved[2] & 0xFF, (i.reserved[2] >> 8) & 3
         d["preds_per_op"] = (i.reserved[2] >> 16) & 0xFF
         return d
 

@@ -243,6 +243,45 @@ def test_every_kernel_variant(gpu_lib, env):
             assert info["preds_per_op"] == (2 if two else 4), (w.name, info)
 
 
+@pytest.mark.parametrize("env", [
+    {"DAGSCHED_RING_FEEDERS": 2, "DAGSCHED_RING_SLOTS": 8, "DAGSCHED_RING_PIB_LDS": 2},
+    {"DAGSCHED_RING_FEEDERS": 1, "DAGSCHED_RING_SLOTS": 4, "DAGSCHED_RING_PIB_LDS": 2},
+    {"DAGSCHED_RING_FEEDERS": 2, "DAGSCHED_RING_SLOTS": 4, "DAGSCHED_RING_PIB_LDS": 2, "DAGSCHED_RING_PREDS": 4},
+    {"DAGSCHED_RING_FEEDERS": 1, "DAGSCHED_RING_SLOTS": 8, "DAGSCHED_RING_PIB_LDS": 2, "DAGSCHED_RING_G": 1},
+])
+def test_nibble_placement_kernels(gpu_lib, env):
+    """Up to 16 machines: the placement can sit in LDS as four bits per node (and time then starts at 255
+    inside the kernel).  Same bits as the oracle, on even and odd N, with bad inputs, with a machine count of
+    exactly 16 and with end times around the 16-bit limit."""
+    rng = np.random.default_rng(2024)
+    cases = [W.gen_config(1, n_cand=100), W.gen_config(2, n_cand=150), W.gen_config(3, n_cand=10),
+             W.random_instance(rng, 333, 16, 41, max_fanin=6, frac_arbitrary=0.3, frac_bad=0.2),
+             W.random_instance(rng, 201, 7, 50, max_fanin=2, frac_arbitrary=0.2, frac_bad=0.2),
+             W.random_instance(rng, 64, 16, 30, max_fanin=3)]
+    for w in cases:
+        (z, b, pk, f), info = _with_env(env, lambda: assert_parity(gpu_lib, w))
+        assert info["state_bits"] == 16 and info["placement_bytes_in_lds"] == 2, (w.name, info)
+    # end times around 65535: the origin of 255 must not turn an exact problem into a wrong one
+    n, p = 600, 3
+    rp, ci = W.random_dag(rng, n, 2, window=30)
+    dur = rng.integers(60, 160, n).astype(np.int32)
+    comm = rng.integers(1, 200, (p, p)).astype(np.int32)
+    mem = rng.integers(-9, 10, n).astype(np.int64)
+    pl, rk = W.list_schedules(rp, ci, p, 200, 4243)
+    pl1, rk1 = W.list_schedules(rp, ci, 1, 67, 98)
+    pl[::3], rk[::3] = pl1, rk1
+    w = W.Workload("straddles 16 bits", p, rp, ci, dur, comm, mem, pl, rk)
+    (z, b, pk, f), info = _with_env(env, lambda: assert_parity(gpu_lib, w))
+    assert info["placement_bytes_in_lds"] == 2 and info["variant"] == 4
+    # a makespan bound between 65280 and 65535: exact with bytes, optimistic with nibbles
+    dur2 = np.full(n, 100, np.int32)
+    dur2[1] = 101                                             # no common factor to divide out
+    dur2[0] += 65400 - int(dur2.sum())
+    w2 = W.Workload("just below 16 bits", p, rp, ci, dur2, np.zeros((p, p), np.int32), mem, pl, rk)
+    (z2, b2, pk2, f2), info2 = _with_env(env, lambda: assert_parity(gpu_lib, w2))
+    assert info2["variant"] == 4 and (z2[f2 == 0] > 65535 - 255).any()
+
+
 def test_sixteen_bit_overflow_falls_back(gpu_lib):
     """End times that leave the 16-bit range: the ring kernel must hand exactly those candidates to the
     int32 kernel.  A long chain on few machines whose makespan straddles 65535 for different orders."""
