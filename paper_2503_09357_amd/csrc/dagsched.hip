@@ -370,7 +370,11 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
       }
     }
   }
-  plan.feeders = force_feeders ? force_feeders : (best_wgs * 4 <= 24 ? 2 : 1);
+  // feeders: two; one when the CU is full of wavefronts anyway; four when a single workgroup has the CU to itself
+  // and every placement byte comes from L2 (a feeder trip then lasts an L2 round trip: measured 3.6 % on config 5)
+  plan.feeders = force_feeders ? force_feeders
+               : (best_wgs == 1 && plan.lds.pib_mode == 0 && plan.ring == 16) ? 4
+               : (best_wgs * 4 <= 24 ? 2 : 1);
   if (best_score < 0 || !ring_kernel_pick<0>(plan.ring, plan.feeders, (int)plan.lds.pib_mode, 4)) return plan;   // shape not built
   if (!ring_kernel_pick<0>(plan.ring, plan.feeders, (int)plan.lds.pib_mode, plan.preds)) plan.preds = 4;
   // the nibble kernels start time at 255 (see the kernel), which the 16-bit range must hold as well

@@ -1,7 +1,8 @@
 // Ring kernel: the fast evaluation path.
 //
-// Workgroup = 2 + FEEDERS wavefronts that never meet at a barrier while the schedule is being relaxed;
-// lane (g, j) of every wavefront stands for machine j of candidate g:
+// Workgroup = 2 + FEEDERS wavefronts with a role, which never meet at a barrier while the schedule is being
+// relaxed (further wavefronts, if launched, only help with ingest); lane (g, j) of every wavefront stands for
+// machine j of candidate g:
 //
 //   wave 0, the RELAXER   pops compact "ops" from a per-lane ring in LDS and runs the max-plus
 //                         recurrence
@@ -9,10 +10,10 @@
 //                         (eqs. (3),(7),(11)-(13), Sec. III) against the end-time array of its
 //                         candidate in LDS.  Its loop touches LDS only and is branch-free.
 //   waves 1..FEEDERS, the FEEDERS  walk machine j's order list, fetch the shared operator records from
-//                         L2, look up the placement of every DAG predecessor (one byte per node, L2) and the
-//                         channel delay (LDS), and
-//                         push the resulting op into the relaxer's ring.
-//   last wave, the ACCOUNTANT  walks the order lists and takes the peak of each machine's running
+//                         L2, look up the placement of every DAG predecessor (one byte or four bits per
+//                         node in LDS, or one byte in L2) and the channel delay (LDS), and push the
+//                         resulting op into the relaxer's ring.
+//   wave FEEDERS + 1, the ACCOUNTANT  walks the order lists and takes the peak of each machine's running
 //                         memory level (eqs. (17)-(19)), which depends on the order only.
 //
 // The feeders run ahead and absorb every global-memory latency.  A lone wavefront issues an instruction
@@ -24,7 +25,8 @@
 // End times are kept as 16-bit unsigned values (sentinel 0xFFFF = not yet ended), which halves the
 // LDS footprint.  When the host cannot prove that every end time stays below 0xFFFF the kernel runs
 // "optimistically": an operation whose end time would reach 0xFFFF is never completed, its candidate
-// stalls exactly like a cyclic one, and every stalled candidate is handed to the general int32 kernel.
+// stalls exactly like a cyclic one; the two are told apart at the deadlock (does some held op have all its
+// predecessors ended?) and the candidates stopped by the range are handed to the general int32 kernel.
 //
 // Ring protocol (single consumer per lane, no atomics, no counters): a lane's ring has RING slots of
 // 16 bytes; op i of the lane's stream goes to slot i mod RING.  The last dword of a slot is either
