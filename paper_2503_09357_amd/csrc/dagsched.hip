@@ -370,11 +370,14 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
       }
     }
   }
-  // feeders: two; one when the CU is full of wavefronts anyway; four when a single workgroup has the CU to itself
-  // and every placement byte comes from L2 (a feeder trip then lasts an L2 round trip: measured 3.6 % on config 5)
+  // feeders (measured): four when a single workgroup has the CU to itself and every placement byte comes from L2
+  // (config 5: 3.6 % over two), three with one or two workgroups per CU (config 3: 13 % over two, config 4: 2.4 %),
+  // two with more (config 2: three cost 16 %), one when the CU is full of wavefronts anyway
   plan.feeders = force_feeders ? force_feeders
                : (best_wgs == 1 && plan.lds.pib_mode == 0 && plan.ring == 16) ? 4
+               : best_wgs <= 2 ? 3
                : (best_wgs * 4 <= 24 ? 2 : 1);
+  if (!force_feeders && !ring_kernel_pick<0>(plan.ring, plan.feeders, (int)plan.lds.pib_mode, 4)) plan.feeders = 2;
   if (best_score < 0 || !ring_kernel_pick<0>(plan.ring, plan.feeders, (int)plan.lds.pib_mode, 4)) return plan;   // shape not built
   if (!ring_kernel_pick<0>(plan.ring, plan.feeders, (int)plan.lds.pib_mode, plan.preds)) plan.preds = 4;
   // the nibble kernels start time at 255 (see the kernel), which the 16-bit range must hold as well
@@ -402,19 +405,24 @@ RingKernel ring_kernel_pick(int ring, int feeders, int pib_lds, int preds) {
     case 1084: return relax_ring_kernel<8, 4, HALF, 1>;
     case 81:   return relax_ring_kernel<8, 1, HALF, 0>;
     case 82:   return relax_ring_kernel<8, 2, HALF, 0>;
+    case 83:   return relax_ring_kernel<8, 3, HALF, 0>;
     case 161:  return relax_ring_kernel<16, 1, HALF, 0>;
     case 162:  return relax_ring_kernel<16, 2, HALF, 0>;
+    case 163:  return relax_ring_kernel<16, 3, HALF, 0>;
     case 164:  return relax_ring_kernel<16, 4, HALF, 0>;
     case 321:  return relax_ring_kernel<32, 1, HALF, 0>;
     case 322:  return relax_ring_kernel<32, 2, HALF, 0>;
+    case 323:  return relax_ring_kernel<32, 3, HALF, 0>;
     case 11041: return relax_ring_kernel<4, 1, HALF, 1, 2>;
     case 11042: return relax_ring_kernel<4, 2, HALF, 1, 2>;
     case 11081: return relax_ring_kernel<8, 1, HALF, 1, 2>;
     case 11082: return relax_ring_kernel<8, 2, HALF, 1, 2>;
     case 10081: return relax_ring_kernel<8, 1, HALF, 0, 2>;
     case 10082: return relax_ring_kernel<8, 2, HALF, 0, 2>;
+    case 10083: return relax_ring_kernel<8, 3, HALF, 0, 2>;
     case 10161: return relax_ring_kernel<16, 1, HALF, 0, 2>;
     case 10162: return relax_ring_kernel<16, 2, HALF, 0, 2>;
+    case 10163: return relax_ring_kernel<16, 3, HALF, 0, 2>;
     case 10321: return relax_ring_kernel<32, 1, HALF, 0, 2>;
     case 10322: return relax_ring_kernel<32, 2, HALF, 0, 2>;
     case 2041:  return relax_ring_kernel<4, 1, HALF, 2>;
@@ -425,6 +433,9 @@ RingKernel ring_kernel_pick(int ring, int feeders, int pib_lds, int preds) {
     case 12042: return relax_ring_kernel<4, 2, HALF, 2, 2>;
     case 12081: return relax_ring_kernel<8, 1, HALF, 2, 2>;
     case 12082: return relax_ring_kernel<8, 2, HALF, 2, 2>;
+    case 2083:  return relax_ring_kernel<8, 3, HALF, 2>;
+    case 12083: return relax_ring_kernel<8, 3, HALF, 2, 2>;
+    case 11083: return relax_ring_kernel<8, 3, HALF, 1, 2>;
     default:   return nullptr;
   }
 }
@@ -579,7 +590,7 @@ int dagsched_create(const dagsched_desc_t *desc, dagsched_t **out) {
          upload(&h->d_comm_scaled, plan.comm_scaled.data(), plan.comm_scaled.size()) &&
          (plan.nparts.empty() || upload(&h->d_nparts, plan.nparts.data(), plan.nparts.size())) &&
          dev_alloc(&h->ws_list16, maxc * (size_t)h->list_stride) &&
-         dev_alloc(&h->ws_pib, maxc * (size_t)h->pib_stride);
+         (plan.lds.pib_mode != 0 || dev_alloc(&h->ws_pib, maxc * (size_t)h->pib_stride));   // only read when the placement is not in LDS
     if (ok && !plan.exact) ok = dev_alloc(&h->d_fb_count, 1) && dev_alloc(&h->d_fb_list, maxc);
     if (ok && h->lds.total > 48 * 1024)
       ok = hip_ok(hipFuncSetAttribute((const void *)ring_kernel_for(h), hipFuncAttributeMaxDynamicSharedMemorySize,
