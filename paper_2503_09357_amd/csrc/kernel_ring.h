@@ -439,9 +439,12 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
     uint32_t wseq = (uint32_t)f;                            // ... of the next part to write
     // cursor: the next part to admit is the record at `addr`; `rem` more parts of the same node follow;
     // the node sits at list position k, and k > klast means the stream is exhausted
-    uint32_t k = k0;
-    const uint32_t w0 = has_ops ? (uint32_t)list[k0] : 0u;
-    uint32_t addr = w0 & vmask, rem = w0 >> vbits;
+    // With two predecessors per op every operation is a single part (the host uses those kernels only then), so
+    // feeder f simply owns the nodes at list positions k0 + f, k0 + f + kFeeders, ... and looks one of them ahead.
+    constexpr bool kSingle = PR == 2;
+    uint32_t k = kSingle ? k0 + (uint32_t)f : k0;
+    const uint32_t w0 = has_ops ? (uint32_t)list[min(k, klast)] : 0u;
+    uint32_t addr = w0 & vmask, rem = kSingle ? 0u : w0 >> vbits;
     // list entries of the next kFeeders nodes: one trip moves the cursor by kFeeders parts, so it can
     // enter at most that many nodes
     uint32_t ids[kFeeders];
@@ -456,9 +459,13 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
 #pragma unroll
       for (int i = 0; i + 1 < kFeeders; ++i) ids[i] = in_node ? ids[i] : ids[i + 1];
     };
-    for (int i = 0; i < f; ++i) advance();                  // feeder f starts at its first own part
+    if (kSingle) {
+      ids[0] = has_ops ? (uint32_t)list[min(k + (uint32_t)kFeeders, klast)] : 0u;
+    } else {
+      for (int i = 0; i < f; ++i) advance();                // feeder f starts at its first own part
 #pragma unroll
-    for (int i = 0; i < kFeeders; ++i) ids[i] = has_ops ? (uint32_t)list[min(k + 1u + (uint32_t)i, klast)] : 0u;
+      for (int i = 0; i < kFeeders; ++i) ids[i] = has_ops ? (uint32_t)list[min(k + 1u + (uint32_t)i, klast)] : 0u;
+    }
     struct Entry { uint4 rec; uint32_t q0, q1, q2, q3, fl; };   // fl: 1 valid, 2 last part of the lane
     constexpr int kStages = PIBL ? 2 : 3;
     Entry E[kStages];
@@ -481,18 +488,26 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
         const uint32_t d0 = commr[e2.q0 << lps], d1 = commr[e2.q1 << lps];
         const uint32_t d2 = PR == 4 ? commr[e2.q2 << lps] : 0u, d3 = PR == 4 ? commr[e2.q3 << lps] : 0u;
         // (1) move the cursor past the part admitted in the previous trip and the other feeders' parts
-        const bool moved = pending;
-        if (pending) {
-#pragma unroll
-          for (int a = 0; a < kFeeders; ++a) advance();
-          aseq += kFeeders;
-        }
         // (2) entries of the next nodes (consumed one trip later at the earliest).  Lanes whose cursor stayed
         // keep theirs and all read the same entry instead, which costs the vector cache one line, not one per lane.
+        const bool moved = pending;
+        if (kSingle) {
+          addr = moved ? ids[0] & vmask : addr;
+          k += moved ? (uint32_t)kFeeders : 0u;
+          aseq += moved ? (uint32_t)kFeeders : 0u;
+          const uint32_t t = list[moved ? min(k + (uint32_t)kFeeders, klast) : 0u];
+          ids[0] = moved ? t : ids[0];
+        } else {
+          if (pending) {
 #pragma unroll
-        for (int i = 0; i < kFeeders; ++i) {
-          const uint32_t t = list[moved ? min(k + 1u + (uint32_t)i, klast) : 0u];
-          ids[i] = moved ? t : ids[i];
+            for (int a = 0; a < kFeeders; ++a) advance();
+            aseq += kFeeders;
+          }
+#pragma unroll
+          for (int i = 0; i < kFeeders; ++i) {
+            const uint32_t t = list[moved ? min(k + 1u + (uint32_t)i, klast) : 0u];
+            ids[i] = moved ? t : ids[i];
+          }
         }
         // (3) admission
         pending = (k <= klast) &&
