@@ -75,7 +75,7 @@ struct dagsched {
   int64_t *d_mem = nullptr, *d_weight = nullptr, *d_limit = nullptr;
   int32_t *ws_list = nullptr, *ws_end = nullptr;
   // ring kernel
-  int32_t ring_G = 0, ring_slots = 0, ring_feeders = 1, ring_preds = 4, ring_block = 256, rec_plane = 0, id_bits = 16, time_scale = 1;
+  int32_t ring_G = 0, ring_slots = 0, ring_feeders = 1, ring_kind = 0, ring_block = 256, rec_plane = 0, id_bits = 16, time_scale = 1;
   uint8_t *d_nparts = nullptr;
   int64_t list_stride = 0, pib_stride = 0;
   uint8_t *ws_pib = nullptr;
@@ -210,11 +210,11 @@ LdsLayout ring_layout(int N, int P, int G, int ring, int pib_lds) {
 // footprint that fits a workgroup.
 using RingKernel = void (*)(RingParams);
 template <int HALF>
-RingKernel ring_kernel_pick(int ring, int feeders, int pib_lds, int preds);
+RingKernel ring_kernel_pick(int ring, int feeders, int pib_lds, int kind);
 
 struct RingPlan {
   bool ok = false, exact = false;
-  int G = 0, ring = 0, feeders = 1, preds = 4, block = 256;
+  int G = 0, ring = 0, feeders = 1, kind = 0, block = 256;
   int32_t scale = 1;
   LdsLayout lds{};
   std::vector<uint4> rec;
@@ -300,10 +300,11 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
   int max_parts = 1;
   for (int v = 0; v < N; ++v) max_parts = std::max(max_parts, ((int)op_preds[v].size() + PR - 1) / PR);
   if (max_parts > 16) return plan;                     // very wide fan-in: leave it to the general kernel
-  // no operation with more than two DAG predecessors: the kernels that look at two per op are enough
+  // kernel kind: 2 when no operation has more than two DAG predecessors, 1 when none has more than four (every
+  // operation is a single part), 0 otherwise (or when DAGSCHED_RING_PREDS=4 asks for the general kernels)
   size_t max_deg = 0;
   for (int v = 0; v < N; ++v) max_deg = std::max(max_deg, op_preds[v].size());
-  plan.preds = (max_deg <= 2 && env_int("DAGSCHED_RING_PREDS", 2) == 2) ? 2 : 4;
+  plan.kind = env_int("DAGSCHED_RING_PREDS", 2) == 4 ? 0 : max_deg <= 2 ? 2 : max_parts == 1 ? 1 : 0;
   const int plane = N;
   std::vector<uint4> rec((size_t)max_parts * plane, make_uint4(dummy | (dummy << 16), dummy | (dummy << 16), 0, 0));
   for (int v = 0; v < N; ++v) {
@@ -377,9 +378,8 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
                : (best_wgs == 1 && plan.lds.pib_mode == 0 && plan.ring == 16) ? 4
                : best_wgs <= 2 ? 3
                : (best_wgs * 4 <= 24 ? 2 : 1);
-  if (!force_feeders && !ring_kernel_pick<0>(plan.ring, plan.feeders, (int)plan.lds.pib_mode, 4)) plan.feeders = 2;
-  if (best_score < 0 || !ring_kernel_pick<0>(plan.ring, plan.feeders, (int)plan.lds.pib_mode, 4)) return plan;   // shape not built
-  if (!ring_kernel_pick<0>(plan.ring, plan.feeders, (int)plan.lds.pib_mode, plan.preds)) plan.preds = 4;
+  if (!force_feeders && !ring_kernel_pick<0>(plan.ring, plan.feeders, (int)plan.lds.pib_mode, plan.kind)) plan.feeders = 2;
+  if (best_score < 0 || !ring_kernel_pick<0>(plan.ring, plan.feeders, (int)plan.lds.pib_mode, plan.kind)) return plan;   // shape not built
   // the nibble kernels start time at 255 (see the kernel), which the 16-bit range must hold as well
   plan.exact = upper + (plan.lds.pib_mode == 2 ? 255 : 0) < (int64_t)kNotDone16;
   // workgroup size: the wavefronts with a role, plus helpers for the ingest phase when the LDS leaves the CU
@@ -394,57 +394,32 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
 }
 
 using RingKernel = void (*)(RingParams);
+// The instantiated shapes: placement bytes in LDS with 4 or 8 ring slots, as nibbles in LDS likewise, in L2 with 8, 16
+// or 32; one to four feeders where that was ever measured useful; each in the three kinds of the kernel.
+#define DAGSCHED_RING_CASES(PIB, RING, F)                                                         \
+  case 0 * 10000 + PIB * 1000 + RING * 10 + F: return relax_ring_kernel<RING, F, HALF, PIB, 0>;    \
+  case 1 * 10000 + PIB * 1000 + RING * 10 + F: return relax_ring_kernel<RING, F, HALF, PIB, 1>;    \
+  case 2 * 10000 + PIB * 1000 + RING * 10 + F: return relax_ring_kernel<RING, F, HALF, PIB, 2>;
 template <int HALF>
-RingKernel ring_kernel_pick(int ring, int feeders, int pib_lds, int preds) {
-  switch ((preds == 2 ? 10000 : 0) + pib_lds * 1000 + ring * 10 + feeders) {
-    case 1041: return relax_ring_kernel<4, 1, HALF, 1>;
-    case 1042: return relax_ring_kernel<4, 2, HALF, 1>;
-    case 1081: return relax_ring_kernel<8, 1, HALF, 1>;
-    case 1082: return relax_ring_kernel<8, 2, HALF, 1>;
-    case 1083: return relax_ring_kernel<8, 3, HALF, 1>;
-    case 1084: return relax_ring_kernel<8, 4, HALF, 1>;
-    case 81:   return relax_ring_kernel<8, 1, HALF, 0>;
-    case 82:   return relax_ring_kernel<8, 2, HALF, 0>;
-    case 83:   return relax_ring_kernel<8, 3, HALF, 0>;
-    case 161:  return relax_ring_kernel<16, 1, HALF, 0>;
-    case 162:  return relax_ring_kernel<16, 2, HALF, 0>;
-    case 163:  return relax_ring_kernel<16, 3, HALF, 0>;
-    case 164:  return relax_ring_kernel<16, 4, HALF, 0>;
-    case 321:  return relax_ring_kernel<32, 1, HALF, 0>;
-    case 322:  return relax_ring_kernel<32, 2, HALF, 0>;
-    case 323:  return relax_ring_kernel<32, 3, HALF, 0>;
-    case 11041: return relax_ring_kernel<4, 1, HALF, 1, 2>;
-    case 11042: return relax_ring_kernel<4, 2, HALF, 1, 2>;
-    case 11081: return relax_ring_kernel<8, 1, HALF, 1, 2>;
-    case 11082: return relax_ring_kernel<8, 2, HALF, 1, 2>;
-    case 10081: return relax_ring_kernel<8, 1, HALF, 0, 2>;
-    case 10082: return relax_ring_kernel<8, 2, HALF, 0, 2>;
-    case 10083: return relax_ring_kernel<8, 3, HALF, 0, 2>;
-    case 10161: return relax_ring_kernel<16, 1, HALF, 0, 2>;
-    case 10162: return relax_ring_kernel<16, 2, HALF, 0, 2>;
-    case 10163: return relax_ring_kernel<16, 3, HALF, 0, 2>;
-    case 10321: return relax_ring_kernel<32, 1, HALF, 0, 2>;
-    case 10322: return relax_ring_kernel<32, 2, HALF, 0, 2>;
-    case 2041:  return relax_ring_kernel<4, 1, HALF, 2>;
-    case 2042:  return relax_ring_kernel<4, 2, HALF, 2>;
-    case 2081:  return relax_ring_kernel<8, 1, HALF, 2>;
-    case 2082:  return relax_ring_kernel<8, 2, HALF, 2>;
-    case 12041: return relax_ring_kernel<4, 1, HALF, 2, 2>;
-    case 12042: return relax_ring_kernel<4, 2, HALF, 2, 2>;
-    case 12081: return relax_ring_kernel<8, 1, HALF, 2, 2>;
-    case 12082: return relax_ring_kernel<8, 2, HALF, 2, 2>;
-    case 2083:  return relax_ring_kernel<8, 3, HALF, 2>;
-    case 12083: return relax_ring_kernel<8, 3, HALF, 2, 2>;
-    case 11083: return relax_ring_kernel<8, 3, HALF, 1, 2>;
-    default:   return nullptr;
+RingKernel ring_kernel_pick(int ring, int feeders, int pib_lds, int kind) {
+  switch (kind * 10000 + pib_lds * 1000 + ring * 10 + feeders) {
+    DAGSCHED_RING_CASES(1, 4, 1) DAGSCHED_RING_CASES(1, 4, 2)
+    DAGSCHED_RING_CASES(1, 8, 1) DAGSCHED_RING_CASES(1, 8, 2) DAGSCHED_RING_CASES(1, 8, 3) DAGSCHED_RING_CASES(1, 8, 4)
+    DAGSCHED_RING_CASES(2, 4, 1) DAGSCHED_RING_CASES(2, 4, 2)
+    DAGSCHED_RING_CASES(2, 8, 1) DAGSCHED_RING_CASES(2, 8, 2) DAGSCHED_RING_CASES(2, 8, 3)
+    DAGSCHED_RING_CASES(0, 8, 1) DAGSCHED_RING_CASES(0, 8, 2) DAGSCHED_RING_CASES(0, 8, 3)
+    DAGSCHED_RING_CASES(0, 16, 1) DAGSCHED_RING_CASES(0, 16, 2) DAGSCHED_RING_CASES(0, 16, 3) DAGSCHED_RING_CASES(0, 16, 4)
+    DAGSCHED_RING_CASES(0, 32, 1) DAGSCHED_RING_CASES(0, 32, 2) DAGSCHED_RING_CASES(0, 32, 3)
+    default: return nullptr;
   }
 }
+#undef DAGSCHED_RING_CASES
 RingKernel ring_kernel_for(const dagsched *h) {
   // byte addresses when the workgroup's end-time arrays fit 64 KB, half addresses otherwise
   const bool half = (uint64_t)h->ring_G * h->lds.s_stride > 65536u;
   const int pib_lds = (int)h->lds.pib_mode;
-  return half ? ring_kernel_pick<1>(h->ring_slots, h->ring_feeders, pib_lds, h->ring_preds)
-              : ring_kernel_pick<0>(h->ring_slots, h->ring_feeders, pib_lds, h->ring_preds);
+  return half ? ring_kernel_pick<1>(h->ring_slots, h->ring_feeders, pib_lds, h->ring_kind)
+              : ring_kernel_pick<0>(h->ring_slots, h->ring_feeders, pib_lds, h->ring_kind);
 }
 
 OutPtrs make_out(const dagsched *h, int32_t n_cand, int32_t *makespan, int64_t *bubble, int64_t *peak_mem,
@@ -582,7 +557,7 @@ int dagsched_create(const dagsched_desc_t *desc, dagsched_t **out) {
   }
   if (ok && plan.ok) {
     h->variant = plan.exact ? kVariantRingExact : kVariantRingOptimistic;
-    h->ring_G = plan.G; h->ring_slots = plan.ring; h->ring_feeders = plan.feeders; h->ring_preds = plan.preds; h->ring_block = plan.block; h->lds = plan.lds; h->time_scale = plan.scale;
+    h->ring_G = plan.G; h->ring_slots = plan.ring; h->ring_feeders = plan.feeders; h->ring_kind = plan.kind; h->ring_block = plan.block; h->lds = plan.lds; h->time_scale = plan.scale;
     h->rec_plane = plan.rec_plane; h->id_bits = plan.id_bits;
     const int64_t cap = ((int64_t)h->N + h->E + 1024) * 64;
     h->spin_cap = (uint32_t)std::min<int64_t>(cap, 0x7FFFFFFF);
@@ -708,7 +683,7 @@ int dagsched_get_info(const dagsched_t *h, dagsched_info_t *info) {
   info->state_bits = ring ? 16 : 32;
   info->reserved[0] = ring ? h->ring_slots : 0;
   info->reserved[1] = h->time_scale;
-  info->reserved[2] = ring ? (h->ring_feeders | ((int)h->lds.pib_mode << 8) | (h->ring_preds << 16)) : 0;
+  info->reserved[2] = ring ? (h->ring_feeders | ((int)h->lds.pib_mode << 8) | ((h->ring_kind == 2 ? 2 : 4) << 16) | (h->ring_kind << 24)) : 0;
   return DAGSCHED_OK;
 }
 

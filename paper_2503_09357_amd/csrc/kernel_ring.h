@@ -104,9 +104,10 @@ struct RingParams {
 // four bits per node.  A nibble cannot name the dummy machine P, so in that mode time starts at kOrigin = 255
 // instead of 0: the dummy cell still holds 0, and 0 + any delay <= 255 never exceeds a machine-free time, which
 // makes the dummy's placement irrelevant.  The origin is subtracted from the makespan at the end.
-// PR: DAG predecessors per op, 4 or 2.  With 2 (chosen by the host when no operation has more than two DAG
-// predecessors) the second pair of every record and op is the dummy and neither the feeders nor the relaxer look at it.
-template <int RING, int FEEDERS, int HALF, int PIBL, int PR = 4>
+// KIND: 0 general; 1 every operation is a single part (at most four DAG predecessors each): the feeders walk
+// the order lists directly; 2 at most two DAG predecessors each (single parts as well): the second pair of
+// every record and op is the dummy and neither the feeders nor the relaxer look at it.  Chosen by the host.
+template <int RING, int FEEDERS, int HALF, int PIBL, int KIND = 0>
 __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
   // ring_threads(FEEDERS) threads have a role while the schedule is relaxed; the host may launch more (a
   // multiple of 64): the extra wavefronts only help with ingest and then wait at the final barrier.
@@ -115,7 +116,8 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
   extern __shared__ __align__(16) unsigned char lds[];
   static_assert((RING & (RING - 1)) == 0, "RING must be a power of two");
   static_assert(RING >= FEEDERS, "every feeder needs a slot of its own");
-  static_assert(PR == 4 || PR == 2, "two or four predecessors per op");
+  static_assert(KIND >= 0 && KIND <= 2, "general, single parts, two predecessors");
+  constexpr int PR = KIND == 2 ? 2 : 4;                     // DAG predecessors per op
   constexpr uint32_t kOrigin = PIBL == 2 ? 255u : 0u;
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -439,9 +441,9 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
     uint32_t wseq = (uint32_t)f;                            // ... of the next part to write
     // cursor: the next part to admit is the record at `addr`; `rem` more parts of the same node follow;
     // the node sits at list position k, and k > klast means the stream is exhausted
-    // With two predecessors per op every operation is a single part (the host uses those kernels only then), so
-    // feeder f simply owns the nodes at list positions k0 + f, k0 + f + kFeeders, ... and looks one of them ahead.
-    constexpr bool kSingle = PR == 2;
+    // When every operation is a single part, feeder f simply owns the nodes at list positions k0 + f,
+    // k0 + f + kFeeders, ... and looks one of them ahead.
+    constexpr bool kSingle = KIND != 0;
     uint32_t k = kSingle ? k0 + (uint32_t)f : k0;
     const uint32_t w0 = has_ops ? (uint32_t)list[min(k, klast)] : 0u;
     uint32_t addr = w0 & vmask, rem = kSingle ? 0u : w0 >> vbits;

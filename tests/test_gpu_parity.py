@@ -226,7 +226,8 @@ def test_every_kernel_variant(gpu_lib, env):
     """The tuning knobs only pick among kernel instantiations; each one must give the same bits."""
     rng = np.random.default_rng(321)
     cases = [W.gen_config(1, n_cand=100), W.gen_config(2, n_cand=150), W.gen_config(4, n_cand=9),
-             W.random_instance(rng, 333, 7, 41, max_fanin=6, frac_arbitrary=0.3, frac_bad=0.2)]
+             W.random_instance(rng, 333, 7, 41, max_fanin=6, frac_arbitrary=0.3, frac_bad=0.2),
+             W.random_instance(rng, 210, 5, 37, max_fanin=4, frac_arbitrary=0.3, frac_bad=0.2, dup_prob=0.0)]   # single-part operations
     for w in cases:
         (z, b, pk, f), info = _with_env(env, lambda: assert_parity(gpu_lib, w))
         if "DAGSCHED_FORCE_GENERAL" in env:
@@ -241,6 +242,10 @@ def test_every_kernel_variant(gpu_lib, env):
             # kernels take them (where that shape is built) unless the knob says otherwise
             two = w.name.startswith(("cfg1", "cfg2")) and env.get("DAGSCHED_RING_PREDS", 2) == 2
             assert info["preds_per_op"] in ((2, 4) if two else (4,)), (w.name, info)
+            if env.get("DAGSCHED_RING_PREDS", 2) == 4:
+                assert info["kernel_kind"] == 0
+            elif w.name.startswith("random n=210"):
+                assert info["kernel_kind"] in (1, 2), (w.name, info)
 
 
 @pytest.mark.parametrize("env", [
