@@ -355,13 +355,19 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
     for (uint32_t it = 0; it < p.spin_cap; it += 8) {
 #pragma unroll
       for (int sub = 0; sub < 8; ++sub) {
-        // what follows the current op: the op delivered in slot t, else the no-op (known before the
-        // end times arrive, so it is off the critical path)
-        const bool valid = (r.w & 0xFFFFu) != kNotDone16;
-        const uint32_t f0 = valid ? r.x : z0, f1 = valid ? r.y : z0, f2 = valid ? r.z : 0u, f3 = valid ? r.w : z3;
+        // What follows the current op: the op delivered in slot t, else the no-op.  The ring slot was read after
+        // the end times, so it arrives after them.  With four predecessors the empty statement keeps the compiler
+        // from waiting for it (and thereby for everything) before the end times have been used (2-3 %).
+        uint32_t rw = r.w;
         uint32_t x = max(max(x_acc, e0 + (w2 & 0xFFu)), e1 + (PR == 4 ? (w2 >> 8) & 0xFFu : w2 >> 8));
-        if (PR == 4) x = max(max(x, e2 + ((w2 >> 16) & 0xFFu)), e3 + (w2 >> 24));
-        x += w3 & 0xFFFFu;
+        if (PR == 4) {
+          x = max(max(x, e2 + ((w2 >> 16) & 0xFFu)), e3 + (w2 >> 24));
+          x += w3 & 0xFFFFu;
+          asm volatile("" : "+v"(rw) : "v"(x));
+        }
+        const bool valid = (rw & 0xFFFFu) != kNotDone16;
+        const uint32_t f0 = valid ? r.x : z0, f1 = valid ? r.y : z0, f2 = valid ? r.z : 0u, f3 = valid ? rw : z3;
+        if (PR != 4) x += w3 & 0xFFFFu;
         const bool ran = x < kNotDone16;                    // every predecessor ended and no 16-bit overflow (or the no-op)
         x_acc = ran ? x : x_acc;                            // the machine is busy until x (chain edge, eq. (7))
         cell(ran ? (w3 >> 16) : trash) = (uint16_t)x;
