@@ -355,29 +355,27 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
     for (uint32_t it = 0; it < p.spin_cap; it += 8) {
 #pragma unroll
       for (int sub = 0; sub < 8; ++sub) {
-        // What follows the current op: the op delivered in slot t, else the no-op.  The ring slot was read after
-        // the end times, so it arrives after them.  With four predecessors the empty statement keeps the compiler
-        // from waiting for it (and thereby for everything) before the end times have been used (2-3 %).
-        uint32_t rw = r.w;
+        // what follows the current op: the op delivered in slot t, else the no-op
+        const bool valid = (r.w & 0xFFFFu) != kNotDone16;
+        const uint32_t f0 = valid ? r.x : z0, f1 = valid ? r.y : z0, f2 = valid ? r.z : 0u, f3 = valid ? r.w : z3;
         uint32_t x = max(max(x_acc, e0 + (w2 & 0xFFu)), e1 + (PR == 4 ? (w2 >> 8) & 0xFFu : w2 >> 8));
-        if (PR == 4) {
-          x = max(max(x, e2 + ((w2 >> 16) & 0xFFu)), e3 + (w2 >> 24));
-          x += w3 & 0xFFFFu;
-          asm volatile("" : "+v"(rw) : "v"(x));
-        }
-        const bool valid = (rw & 0xFFFFu) != kNotDone16;
-        const uint32_t f0 = valid ? r.x : z0, f1 = valid ? r.y : z0, f2 = valid ? r.z : 0u, f3 = valid ? rw : z3;
-        if (PR != 4) x += w3 & 0xFFFFu;
+        if (PR == 4) x = max(max(x, e2 + ((w2 >> 16) & 0xFFu)), e3 + (w2 >> 24));
+        x += w3 & 0xFFFFu;
         const bool ran = x < kNotDone16;                    // every predecessor ended and no 16-bit overflow (or the no-op)
         x_acc = ran ? x : x_acc;                            // the machine is busy until x (chain edge, eq. (7))
         cell(ran ? (w3 >> 16) : trash) = (uint16_t)x;
+        const bool take = ran && valid;
+        // The ring slot for the next trip.  With four predecessors per op it is requested before the end times
+        // (it arrives first, and what depends on it is done while they are on their way: 1-5 %); with two, where
+        // the feeders are what limits, after everything else (a delivery is then seen a little earlier: 1-3 %).
+        lds_byte_t *const next_p = ring_lane + ((t10 + (take ? 1024u : 0u)) & kSlotMask);
+        if (PR == 4) r = *(lds_vu32x4_t *)next_p;
         w0 = ran ? f0 : w0;
         if (PR == 4) w1 = ran ? f1 : w1;
-        // The end-time reads of the next trip go out as early as possible (LDS accesses keep their
-        // program order, so everything below overlaps with their latency).
+        // The end-time reads of the next trip (LDS accesses keep their program order, so everything below
+        // overlaps with their latency).
         e0 = cell(w0 & 0xFFFFu); e1 = cell(w0 >> 16);
         if (PR == 4) { e2 = cell(w1 & 0xFFFFu); e3 = cell(w1 >> 16); }
-        const bool take = ran && valid;
         // One trip without progress while every unfinished machine holds an op is already a deadlock
         // (end times only change when some op runs), so progress is sampled once per window.
         if (sub == 7) prog_acc = __ballot((ran && !idle) || take);   // an op taken now has not been tested yet
@@ -387,8 +385,8 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
         // the slot just copied is free again: its last dword says so (and which op left it) to the feeders
         *(lds_vu32_t *)(take ? slot_p + 12 : scr_p) = (t10 << 6) | kNotDone16;
         t10 += take ? 1024u : 0u;
-        slot_p = ring_lane + (t10 & kSlotMask);
-        r = *(lds_vu32x4_t *)slot_p;                        // read now, looked at in the next trip
+        slot_p = next_p;
+        if (PR != 4) r = *(lds_vu32x4_t *)next_p;
       }
       const bool fin = dead || (idle && (t10 >> 10) == *total_p);
       if (__ballot(!fin) == 0) { expired = false; break; }
