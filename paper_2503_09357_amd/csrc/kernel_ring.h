@@ -140,8 +140,10 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
 
   // ---------------------------------------------------------------- ingest (all wavefronts)
   if (tid < kWave) { cntw[tid] = 0; totalw[tid] = 0xFFFFFFFFu; flagw[tid] = 0; abortw[tid] = 0; peakw[tid] = 0; }
-  for (int i = tid; i < RING * kWave; i += kThreads)       // every slot free, as if ops -RING .. -1 had been taken
+  for (int i = tid; i < RING * kWave; i += kThreads) {     // every slot free, as if ops -RING .. -1 had been taken
+    ringw[4 * i + 0] = ringw[4 * i + 1] = ringw[4 * i + 2] = 0;   // (a free slot is copied and looked at like an op: cell 0, no delay)
     ringw[4 * i + 3] = kNotDone16 | ((uint32_t)((i >> 6) - RING) << 16);
+  }
   for (int i = tid; i < (P + 1) * Pseg; i += kThreads) {    // rows of Pseg bytes: [source machine][destination]
     const int a = i >> p.log_pseg, b = i & (Pseg - 1);
     commb[i] = (a < P && b < P && a != b) ? (uint8_t)p.comm[a * P + b] : (uint8_t)0;
@@ -336,16 +338,15 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
     const uint32_t trash = sbase + (((uint32_t)N + 1u) << (1 - HALF));
     __builtin_amdgcn_s_setprio(3);                          // the relaxer's trip is the critical path of the workgroup:
                                                             // it goes first wherever it shares a SIMD (measured: 4-5 % on the MoE workload)
-    bool idle = true, dead = !has_ops;                      // idle: the registers hold the no-op
+    bool idle = true, dead = !has_ops;                      // idle: the registers hold a free slot's content, not an op
     uint32_t x_acc = kOrigin;                               // the machine is free from the time origin on
     uint32_t t10 = 0;                                       // ops taken from the ring, times 1024 (the slot stride)
     constexpr uint32_t kSlotMask = (uint32_t)(RING - 1) << 10;
     lds_byte_t *const scr_p = ldsb + o.o_scr + (uint32_t)lane * 4u;   // where lanes that take nothing write their "slot free" mark
-    // "This lane holds no op" is the no-op: predecessors = the dummy cell, duration 0, destination = the
-    // trash cell.  It is always ready, stores x_acc to the trash cell and leaves x_acc as it is, so the
-    // critical path of a trip carries no test for it.
-    const uint32_t z0 = dummy | (dummy << 16), z3 = trash << 16;
-    uint32_t w0 = z0, w1 = z0, w2 = 0, w3 = z3;             // current op, in ring format
+    // "This lane holds no op": the registers hold the content of a free slot, whose "duration" 0xFFFF can never
+    // run; such a lane copies slot t again in every trip until an op is there.
+    const uint32_t z0 = dummy | (dummy << 16);
+    uint32_t w0 = z0, w1 = z0, w2 = 0, w3 = kNotDone16;     // current op, in ring format
     uint64_t prog_acc = 0;
     bool expired = true;
     lds_byte_t *slot_p = ring_lane;                         // ring slot of op t
@@ -355,33 +356,33 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
     for (uint32_t it = 0; it < p.spin_cap; it += 8) {
 #pragma unroll
       for (int sub = 0; sub < 8; ++sub) {
-        // what follows the current op: the op delivered in slot t, else the no-op
-        const bool valid = (r.w & 0xFFFFu) != kNotDone16;
-        const uint32_t f0 = valid ? r.x : z0, f1 = valid ? r.y : z0, f2 = valid ? r.z : 0u, f3 = valid ? r.w : z3;
+        const bool valid = (r.w & 0xFFFFu) != kNotDone16;   // slot t holds op t
         uint32_t x = max(max(x_acc, e0 + (w2 & 0xFFu)), e1 + (PR == 4 ? (w2 >> 8) & 0xFFu : w2 >> 8));
         if (PR == 4) x = max(max(x, e2 + ((w2 >> 16) & 0xFFu)), e3 + (w2 >> 24));
         x += w3 & 0xFFFFu;
-        const bool ran = x < kNotDone16;                    // every predecessor ended and no 16-bit overflow (or the no-op)
+        const bool ran = x < kNotDone16;                    // an op, every predecessor ended and no 16-bit overflow
         x_acc = ran ? x : x_acc;                            // the machine is busy until x (chain edge, eq. (7))
         cell(ran ? (w3 >> 16) : trash) = (uint16_t)x;
-        const bool take = ran && valid;
+        const bool next = ran || idle;                      // the registers take the content of slot t
+        const bool take = next && valid;                    // ... which is op t
         // The ring slot for the next trip.  With four predecessors per op it is requested before the end times
         // (it arrives first, and what depends on it is done while they are on their way: 1-5 %); with two, where
         // the feeders are what limits, after everything else (a delivery is then seen a little earlier: 1-3 %).
         lds_byte_t *const next_p = ring_lane + ((t10 + (take ? 1024u : 0u)) & kSlotMask);
+        const uint32_t c0 = r.x, c1 = r.y, c2 = r.z, c3 = r.w;
         if (PR == 4) r = *(lds_vu32x4_t *)next_p;
-        w0 = ran ? f0 : w0;
-        if (PR == 4) w1 = ran ? f1 : w1;
+        w0 = next ? c0 : w0;
+        if (PR == 4) w1 = next ? c1 : w1;
         // The end-time reads of the next trip (LDS accesses keep their program order, so everything below
         // overlaps with their latency).
         e0 = cell(w0 & 0xFFFFu); e1 = cell(w0 >> 16);
         if (PR == 4) { e2 = cell(w1 & 0xFFFFu); e3 = cell(w1 >> 16); }
         // One trip without progress while every unfinished machine holds an op is already a deadlock
         // (end times only change when some op runs), so progress is sampled once per window.
-        if (sub == 7) prog_acc = __ballot((ran && !idle) || take);   // an op taken now has not been tested yet
-        idle = ran && !valid;
-        w2 = ran ? f2 : w2;
-        w3 = ran ? f3 : w3;
+        if (sub == 7) prog_acc = __ballot(ran || take);     // an op taken now has not been tested yet
+        idle = next ? !valid : idle;
+        w2 = next ? c2 : w2;
+        w3 = next ? c3 : w3;
         // the slot just copied is free again: its last dword says so (and which op left it) to the feeders
         *(lds_vu32_t *)(take ? slot_p + 12 : scr_p) = (t10 << 6) | kNotDone16;
         t10 += take ? 1024u : 0u;
