@@ -130,7 +130,7 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
   lds_byte_t *const ldsb = (lds_byte_t *)lds;
 
   uint32_t *ringw = (uint32_t *)(lds + o.o_ring);
-  uint32_t *totalw = (uint32_t *)(lds + o.o_total);        // [64] ops in the lane's stream, once a feeder knows
+  uint32_t *totalw = (uint32_t *)(lds + o.o_total);        // [64] ops (operation parts) in the lane's stream
   int64_t *peakw = (int64_t *)(lds + o.o_peak);            // [64]
   int32_t *cntw = (int32_t *)(lds + o.o_cnt);              // [64] operations per (candidate, machine)
   int32_t *offw = (int32_t *)(lds + o.o_off);              // [64] start of the machine inside the list
@@ -139,7 +139,7 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
   uint8_t *commb = (uint8_t *)(lds + o.o_comm);            // [(P+1)][Pseg], diagonal and dummy row zero
 
   // ---------------------------------------------------------------- ingest (all wavefronts)
-  if (tid < kWave) { cntw[tid] = 0; totalw[tid] = 0xFFFFFFFFu; flagw[tid] = 0; abortw[tid] = 0; peakw[tid] = 0; }
+  if (tid < kWave) { cntw[tid] = 0; totalw[tid] = 0; flagw[tid] = 0; abortw[tid] = 0; peakw[tid] = 0; }
   for (int i = tid; i < RING * kWave; i += kThreads) {     // every slot free, as if ops -RING .. -1 had been taken
     ringw[4 * i + 0] = ringw[4 * i + 1] = ringw[4 * i + 2] = 0;   // (a free slot is copied and looked at like an op: cell 0, no delay)
     ringw[4 * i + 3] = kNotDone16 | ((uint32_t)((i >> 6) - RING) << 16);
@@ -245,11 +245,13 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
     const int32_t *cnt_g = cntw + gg * Pseg, *off_g = offw + gg * Pseg;
     int32_t *flag_g = flagw + gg;
     // list entry: node | (parts - 1) << id_bits
+    uint32_t *extra_g = totalw + gg * Pseg;                 // parts beyond the first, per machine
     auto place = [&](int v, int pi, int32_t r, uint32_t np1) {
       if ((uint32_t)r >= (uint32_t)cnt_g[pi]) {
         atomicOr(flag_g, kBitBadRank);
       } else {
         lds_list[off_g[pi] + r] = (uint16_t)((uint32_t)v | (np1 << p.id_bits));
+        if (KIND == 0 && np1) atomicAdd(&extra_g[pi], np1);
       }
     };
     if (vec_ok) {
@@ -304,6 +306,7 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
     if (hole) atomicOr(&flagw[gg], kBitBadRank);
   }
   __syncthreads();                                          // workgroup scope: the lists are read by this workgroup only
+  if (tid < kWave) totalw[tid] += (uint32_t)cntw[tid];      // ops per lane: its operations plus their further parts
   // end-time state: every operation "not ended"; the dummy node N has ended at time 0 on a dummy
   // machine P whose delays are all zero; cell N+1 is a trash cell for parts that do not end an operation
   for (int gg = team; gg < ng; gg += n_teams) {
@@ -432,7 +435,6 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
     lds_byte_t *const ring_lane = ldsb + o.o_ring + (uint32_t)lane * 16u;
     lds_vi32_t *const abort_p = (lds_vi32_t *)(ldsb + o.o_abort) + g;
     const uint16_t *list = p.ws_list + (c0 + (cand_ok ? g : 0)) * p.list_stride;
-    lds_vu32_t *const total_p = (lds_vu32_t *)(ldsb + o.o_total) + lane;
     const uint32_t base2 = sbase | (sbase << 16);
     const uint32_t trash = sbase + (((uint32_t)N + 1u) << (1 - HALF));
     const uint32_t vbits = (uint32_t)p.id_bits, vmask = (1u << vbits) - 1u;
@@ -473,7 +475,7 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
 #pragma unroll
       for (int i = 0; i < kFeeders; ++i) ids[i] = has_ops ? (uint32_t)list[min(k + 1u + (uint32_t)i, klast)] : 0u;
     }
-    struct Entry { uint4 rec; uint32_t q0, q1, q2, q3, fl; };   // fl: 1 valid, 2 last part of the lane
+    struct Entry { uint4 rec; uint32_t q0, q1, q2, q3, fl; };   // fl: 1 valid
     constexpr int kStages = PIBL ? 2 : 3;
     Entry E[kStages];
 #pragma unroll
@@ -519,7 +521,7 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
         // (3) admission
         pending = (k <= klast) &&
                   *(lds_vu32_t *)(ring_lane + ((aseq & (uint32_t)(RING - 1)) << 10) + 12) == (((aseq - (uint32_t)RING) << 16) | kNotDone16);
-        e0.fl = pending ? (1u | ((k == klast && rem == 0u) ? 2u : 0u)) : 0u;
+        e0.fl = pending ? 1u : 0u;
         e0.rec = p.rec[pending ? addr : 0u];                 // lanes that admit nothing share one record
         admitted += pending ? 1u : 0u;
         // (B) placement bytes of e1's predecessors (its record was requested one trip ago)
@@ -530,7 +532,7 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
         }
         // (D) pack e2 and publish it
         if (e2.fl & 1u) {
-          const bool more = (e2.rec.z >> 31) != 0;
+          const bool more = !kSingle && (e2.rec.z >> 31) != 0;
           const uint32_t dst = more ? trash : sbase + ((e2.rec.w >> 16) << (1 - HALF));
           const uint32_t dur = e2.rec.z & 0xFFFFu;
           lds_byte_t *const sp = ring_lane + ((wseq & (uint32_t)(RING - 1)) << 10);
@@ -540,7 +542,6 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
                                d0 | (d1 << 8) | (d2 << 16) | (d3 << 24), ((wseq - (uint32_t)RING) << 16) | kNotDone16};
           *(lds_vu32x4_t *)sp = val;
           *(lds_vu32_t *)(sp + 12) = dur | (dst << 16);
-          if (e2.fl & 2u) *total_p = wseq + 1;              // the lane's stream ends with this op
           wseq += kFeeders;
           ++written;
         }
