@@ -54,7 +54,7 @@ typedef DAGSCHED_LDS volatile u32x4_t lds_vu32x4_t;
 
 // Op layout (one 16-byte slot).  ha(x) is the 16-bit address of the end-time cell of x: its LDS byte
 // address when the end-time arrays of the workgroup fit 64 KB (template HALF = 0), else the byte
-// address / 2 (HALF = 1); the arrays start at LDS offset 0.  Unused predecessor slots name the
+// address / 2 (HALF = 1); the arrays come first in the workgroup's LDS.  Unused predecessor slots name the
 // candidate's dummy cell (end time 0, delay 0); a part that does not end its operation names the
 // candidate's trash cell instead of v and has duration 0.
 //   x = ha(pred0) | ha(pred1) << 16
@@ -141,7 +141,9 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
   // ---------------------------------------------------------------- ingest (all wavefronts)
   if (tid < kWave) { cntw[tid] = 0; totalw[tid] = 0; flagw[tid] = 0; abortw[tid] = 0; peakw[tid] = 0; }
   for (int i = tid; i < RING * kWave; i += kThreads) {     // every slot free, as if ops -RING .. -1 had been taken
-    ringw[4 * i + 0] = ringw[4 * i + 1] = ringw[4 * i + 2] = 0;   // (a free slot is copied and looked at like an op: cell 0, no delay)
+    // (a free slot is copied and looked at like an op: some cell of the workgroup, no delay)
+    ringw[4 * i + 0] = ringw[4 * i + 1] = ((uint32_t)(uintptr_t)ldsb >> HALF) * 0x10001u;
+    ringw[4 * i + 2] = 0;
     ringw[4 * i + 3] = kNotDone16 | ((uint32_t)((i >> 6) - RING) << 16);
   }
   for (int i = tid; i < (P + 1) * Pseg; i += kThreads) {    // rows of Pseg bytes: [source machine][destination]
@@ -324,7 +326,8 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
   const int g = ql >> p.log_pseg, j = ql & (Pseg - 1);
   const bool cand_ok = lane_on && g < ng && flagw[g] == 0;
   const bool has_ops = cand_ok && j < P && cntw[ql] > 0;
-  const uint32_t sbase = (uint32_t)g * (o.s_stride >> HALF);   // 16-bit address of this candidate's cell 0
+  // 16-bit address of this candidate's cell 0: LDS addresses (halved when HALF), so that the relaxer uses them as they are
+  const uint32_t sbase = ((uint32_t)(uintptr_t)ldsb >> HALF) + (uint32_t)g * (o.s_stride >> HALF);
 
   int32_t acc = 0;
   bool stalled = false;
@@ -335,7 +338,7 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
     lds_vu32_t *const total_p = (lds_vu32_t *)(ldsb + o.o_total) + lane;
     lds_vi32_t *const abort_p = (lds_vi32_t *)(ldsb + o.o_abort) + g;
     const uint64_t segmask = ((Pseg == kWave) ? ~0ull : ((1ull << Pseg) - 1ull)) << (g * Pseg);
-    auto cell = [&](uint32_t a16) -> lds_vu16_t & { return *(lds_vu16_t *)(ldsb + (a16 << HALF)); };
+    auto cell = [&](uint32_t a16) -> lds_vu16_t & { return *(lds_vu16_t *)(uintptr_t)(a16 << HALF); };
     const uint32_t dummy = sbase + ((uint32_t)N << (1 - HALF));
     // The loop body is branch-free: every trip stores x somewhere (the trash cell unless an op ran).
     const uint32_t trash = sbase + (((uint32_t)N + 1u) << (1 - HALF));
@@ -383,7 +386,7 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
         // One trip without progress while every unfinished machine holds an op is already a deadlock
         // (end times only change when some op runs), so progress is sampled once per window.
         if (sub == 7) prog_acc = __ballot(ran || take);     // an op taken now has not been tested yet
-        idle = next ? !valid : idle;
+        idle = next && !valid;                             // (not next: an op is held, so not idle)
         w2 = next ? c2 : w2;
         w3 = next ? c3 : w3;
         // the slot just copied is free again: its last dword says so (and which op left it) to the feeders
