@@ -346,9 +346,9 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
                                                             // it goes first wherever it shares a SIMD (measured: 4-5 % on the MoE workload)
     bool idle = true, dead = !has_ops;                      // idle: the registers hold a free slot's content, not an op
     uint32_t x_acc = kOrigin;                               // the machine is free from the time origin on
-    uint32_t t10 = 0;                                       // ops taken from the ring, times 1024 (the slot stride)
-    constexpr uint32_t kSlotMask = (uint32_t)(RING - 1) << 10;
-    lds_byte_t *const scr_p = ldsb + o.o_scr + (uint32_t)lane * 4u;   // where lanes that take nothing write their "slot free" mark
+    uint32_t t = 0;                                         // ops taken from the ring
+    // where lanes that take nothing write their "slot free" mark (the store adds 12, the place of a slot's last dword)
+    lds_byte_t *const scr_m12 = ldsb + o.o_scr + (uint32_t)lane * 4u - 12u;
     // "This lane holds no op": the registers hold the content of a free slot, whose "duration" 0xFFFF can never
     // run; such a lane copies slot t again in every trip until an op is there.
     const uint32_t z0 = dummy | (dummy << 16);
@@ -362,7 +362,7 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
     for (uint32_t it = 0; it < p.spin_cap; it += 8) {
 #pragma unroll
       for (int sub = 0; sub < 8; ++sub) {
-        const bool valid = (r.w & 0xFFFFu) != kNotDone16;   // slot t holds op t
+        const bool empty = (r.w & 0xFFFFu) == kNotDone16;   // slot t does not hold op t yet
         uint32_t x = max(max(x_acc, e0 + (w2 & 0xFFu)), e1 + (PR == 4 ? (w2 >> 8) & 0xFFu : w2 >> 8));
         if (PR == 4) x = max(max(x, e2 + ((w2 >> 16) & 0xFFu)), e3 + (w2 >> 24));
         x += w3 & 0xFFFFu;
@@ -370,11 +370,13 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
         x_acc = ran ? x : x_acc;                            // the machine is busy until x (chain edge, eq. (7))
         cell(ran ? (w3 >> 16) : trash) = (uint16_t)x;
         const bool next = ran || idle;                      // the registers take the content of slot t
-        const bool take = next && valid;                    // ... which is op t
+        const bool take = next && !empty;                   // ... which is op t
         // The ring slot for the next trip.  With four predecessors per op it is requested before the end times
         // (it arrives first, and what depends on it is done while they are on their way: 1-5 %); with two, where
         // the feeders are what limits, after everything else (a delivery is then seen a little earlier: 1-3 %).
-        lds_byte_t *const next_p = ring_lane + ((t10 + (take ? 1024u : 0u)) & kSlotMask);
+        const uint32_t mark = (t << 16) | kNotDone16;      // "free, op t was the last one taken from here"
+        t += take ? 1u : 0u;
+        lds_byte_t *const next_p = ring_lane + ((t & (uint32_t)(RING - 1)) << 10);
         const uint32_t c0 = r.x, c1 = r.y, c2 = r.z, c3 = r.w;
         if (PR == 4) r = *(lds_vu32x4_t *)next_p;
         w0 = next ? c0 : w0;
@@ -386,16 +388,15 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
         // One trip without progress while every unfinished machine holds an op is already a deadlock
         // (end times only change when some op runs), so progress is sampled once per window.
         if (sub == 7) prog_acc = __ballot(ran || take);     // an op taken now has not been tested yet
-        idle = next && !valid;                             // (not next: an op is held, so not idle)
+        idle = next && empty;                               // (not next: an op is held, so not idle)
         w2 = next ? c2 : w2;
         w3 = next ? c3 : w3;
         // the slot just copied is free again: its last dword says so (and which op left it) to the feeders
-        *(lds_vu32_t *)(take ? slot_p + 12 : scr_p) = (t10 << 6) | kNotDone16;
-        t10 += take ? 1024u : 0u;
+        *(lds_vu32_t *)((take ? slot_p : scr_m12) + 12) = mark;
         slot_p = next_p;
         if (PR != 4) r = *(lds_vu32x4_t *)next_p;
       }
-      const bool fin = dead || (idle && (t10 >> 10) == *total_p);
+      const bool fin = dead || (idle && t == *total_p);
       if (__ballot(!fin) == 0) { expired = false; break; }
       const uint64_t hold = __ballot(!idle || fin);
       if (!fin && (prog_acc & segmask) == 0 && (hold & segmask) == segmask) {
@@ -412,7 +413,7 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
       prog_acc = 0;
     }
     if (expired) {                                          // bounded wait ran out: report, release the feeder
-      const bool fin = dead || (idle && (t10 >> 10) == *total_p);
+      const bool fin = dead || (idle && t == *total_p);
       if (!fin) { flagw[g] = kBitInternal; *abort_p = 1; }
     }
     acc = (int32_t)(x_acc - kOrigin);
