@@ -300,6 +300,11 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
   int max_parts = 1;
   for (int v = 0; v < N; ++v) max_parts = std::max(max_parts, ((int)op_preds[v].size() + PR - 1) / PR);
   if (max_parts > 16) return plan;                     // very wide fan-in: leave it to the general kernel
+  {                                                    // the kernel counts a lane's op parts in 16 bits
+    int64_t total_parts = 0;
+    for (int v = 0; v < N; ++v) total_parts += std::max(1, ((int)op_preds[v].size() + PR - 1) / PR);
+    if (total_parts >= 65536) return plan;
+  }
   // kernel kind: 2 when no operation has more than two DAG predecessors, 1 when none has more than four (every
   // operation is a single part), 0 otherwise (or when DAGSCHED_RING_PREDS=4 asks for the general kernels)
   size_t max_deg = 0;

@@ -346,7 +346,10 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
                                                             // it goes first wherever it shares a SIMD (measured: 4-5 % on the MoE workload)
     bool idle = true, dead = !has_ops;                      // idle: the registers hold a free slot's content, not an op
     uint32_t x_acc = kOrigin;                               // the machine is free from the time origin on
-    uint32_t t = 0;                                         // ops taken from the ring
+    // ops taken from the ring, as t << 16 | 0xFFFF: the free mark that the slot of op t gets when op t is taken
+    // (the host sends a problem with 65536 op parts or more to the general kernel)
+    uint32_t tm = kNotDone16;
+    constexpr uint32_t kSlotMask = (uint32_t)(RING - 1) << 10;
     // where lanes that take nothing write their "slot free" mark (the store adds 12, the place of a slot's last dword)
     lds_byte_t *const scr_m12 = ldsb + o.o_scr + (uint32_t)lane * 4u - 12u;
     // "This lane holds no op": the registers hold the content of a free slot, whose "duration" 0xFFFF can never
@@ -374,9 +377,9 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
         // The ring slot for the next trip.  With four predecessors per op it is requested before the end times
         // (it arrives first, and what depends on it is done while they are on their way: 1-5 %); with two, where
         // the feeders are what limits, after everything else (a delivery is then seen a little earlier: 1-3 %).
-        const uint32_t mark = (t << 16) | kNotDone16;      // "free, op t was the last one taken from here"
-        t += take ? 1u : 0u;
-        lds_byte_t *const next_p = ring_lane + ((t & (uint32_t)(RING - 1)) << 10);
+        const uint32_t mark = tm;                           // "free, op t was the last one taken from here"
+        tm += take ? 0x10000u : 0u;
+        lds_byte_t *const next_p = ring_lane + ((tm >> 6) & kSlotMask);
         const uint32_t c0 = r.x, c1 = r.y, c2 = r.z, c3 = r.w;
         if (PR == 4) r = *(lds_vu32x4_t *)next_p;
         w0 = next ? c0 : w0;
@@ -396,7 +399,7 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
         slot_p = next_p;
         if (PR != 4) r = *(lds_vu32x4_t *)next_p;
       }
-      const bool fin = dead || (idle && t == *total_p);
+      const bool fin = dead || (idle && tm == ((*total_p << 16) | kNotDone16));
       if (__ballot(!fin) == 0) { expired = false; break; }
       const uint64_t hold = __ballot(!idle || fin);
       if (!fin && (prog_acc & segmask) == 0 && (hold & segmask) == segmask) {
@@ -413,7 +416,7 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
       prog_acc = 0;
     }
     if (expired) {                                          // bounded wait ran out: report, release the feeder
-      const bool fin = dead || (idle && t == *total_p);
+      const bool fin = dead || (idle && tm == ((*total_p << 16) | kNotDone16));
       if (!fin) { flagw[g] = kBitInternal; *abort_p = 1; }
     }
     acc = (int32_t)(x_acc - kOrigin);
