@@ -316,6 +316,21 @@ def test_large_delays_use_the_general_kernel(gpu_lib):
     assert info["state_bits"] in (16, 32)
 
 
+def test_many_op_parts_use_the_general_kernel(gpu_lib):
+    """The 16-bit kernel counts the op parts of a lane in 16 bits: a graph with 65536 parts or more (here 40000
+    operations of up to twelve predecessors each) must be left to the int32 kernel."""
+    rng = np.random.default_rng(11)
+    n, p = 40000, 6
+    rp, ci = W.random_dag(rng, n, 12, window=400)
+    dur = rng.integers(0, 2, n).astype(np.int32)             # short operations: hardly any edge is implied by a longer path
+    comm = rng.integers(3, 6, (p, p)).astype(np.int32)
+    mem = rng.integers(-3, 4, n).astype(np.int64)
+    pl, rk = W.list_schedules(rp, ci, p, 5, 1234)
+    w = W.Workload("many parts", p, rp, ci, dur, comm, mem, pl, rk)
+    (z, b, pk, f), info = assert_parity(gpu_lib, w)
+    assert info["state_bits"] == 32 and (f == 0).all()
+
+
 # --------------------------------------------------------------------------- static memory and limits (eq. (16))
 
 @pytest.mark.parametrize("force_general", [0, 1])
