@@ -72,6 +72,22 @@ enum {
 #define DAGSCHED_MAX_NODES 65535
 
 /*
+ * Optional launch shape of the 16-bit evaluation kernel.  dagsched_create chooses a shape by itself from the
+ * problem's size; a caller that evaluates very many batches of one problem can time a few shapes on a batch of
+ * its own (dagsched_time_evaluate) and keep the fastest.  Every field: 0 = chosen by the library
+ * (placement_mode: -1).  A shape that is not built or does not fit the GPU's LDS makes the library fall back
+ * to its general int32 kernel (dagsched_get_info tells); results never depend on the shape.
+ */
+typedef struct {
+  int32_t cand_per_block;   /* candidates per workgroup: a power of two, at most 64 / (P rounded up to a power of two) */
+  int32_t ring_slots;       /* 4 or 8 with the placement in LDS; 8, 16 or 32 with it in L2                  */
+  int32_t feeders;          /* wavefronts that prepare operations for the relaxing wavefront: 1..4          */
+  int32_t placement_mode;   /* -1 chosen by the library, 0 one byte per node in L2, 1 in LDS, 2 four bits per
+                               node in LDS (P <= 16)                                                        */
+  int32_t block_threads;    /* workgroup size: a multiple of 64, at least 64 * (2 + feeders), at most 1024  */
+} dagsched_shape_t;
+
+/*
  * The candidate-independent part of the problem.  Every pointer is HOST memory and is deep-copied
  * by dagsched_create; the caller may free it as soon as the call returns.
  */
@@ -90,6 +106,7 @@ typedef struct {
   int32_t hip_device;       /* ordinal of the GPU that owns the handle                                       */
   const int64_t *weight;    /* [N]   W_i >= 0, static memory of operation i (eq. (16)), or NULL: all zero    */
   const int64_t *mem_limit; /* [P]   memory limit of machine j, or NULL: no limit, OVER_MEMORY never set     */
+  const dagsched_shape_t *shape; /* launch shape to use, or NULL: chosen by the library                      */
 } dagsched_desc_t;
 
 /*

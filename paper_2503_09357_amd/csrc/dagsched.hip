@@ -102,6 +102,13 @@ int validate_desc(const dagsched_desc_t *d, std::vector<int32_t> *pred_ptr, std:
   if (!d->row_ptr || !d->dur || !d->comm || !d->mem_delta || (E > 0 && !d->col_idx)) return DAGSCHED_EINVAL;
   if (d->max_candidates < 1) return DAGSCHED_EINVAL;
   if (d->layout != DAGSCHED_CAND_MAJOR && d->layout != DAGSCHED_CAND_MINOR) return DAGSCHED_EINVAL;
+  if (const dagsched_shape_t *sh = d->shape) {
+    const int32_t g = sh->cand_per_block, r = sh->ring_slots, b = sh->block_threads;
+    if (g < 0 || g > kWave || (g & (g - 1))) return DAGSCHED_EINVAL;
+    if (r != 0 && r != 4 && r != 8 && r != 16 && r != 32) return DAGSCHED_EINVAL;
+    if (sh->feeders < 0 || sh->feeders > 4 || sh->placement_mode < -1 || sh->placement_mode > 2) return DAGSCHED_EINVAL;
+    if (b < 0 || b > 1024 || b % kWave) return DAGSCHED_EINVAL;
+  }
   if (d->row_ptr[0] != 0 || d->row_ptr[N] != E) return DAGSCHED_EINVAL;
   for (int32_t u = 0; u < N; ++u)
     if (d->row_ptr[u + 1] < d->row_ptr[u]) return DAGSCHED_EINVAL;
@@ -355,8 +362,12 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
   // four-slot ring counts 0.7 (hot lanes outrun it), placement bytes in L2 count 0.97, and workgroups beyond
   // five per CU count nothing; at equal counts, more workgroups of fewer candidates (two relaxers hide each
   // other's latency: 13 % on an 8000-operation, 8-machine pipeline).
-  const int force_g = env_int("DAGSCHED_RING_G", 0), force_ring = env_int("DAGSCHED_RING_SLOTS", 0);
-  const int force_feeders = env_int("DAGSCHED_RING_FEEDERS", 0), force_pib = env_int("DAGSCHED_RING_PIB_LDS", -1);
+  // a shape given with the description wins over the environment (which the tests use), field by field
+  const dagsched_shape_t *sh = d->shape;
+  const int force_g = sh && sh->cand_per_block ? sh->cand_per_block : env_int("DAGSCHED_RING_G", 0);
+  const int force_ring = sh && sh->ring_slots ? sh->ring_slots : env_int("DAGSCHED_RING_SLOTS", 0);
+  const int force_feeders = sh && sh->feeders ? sh->feeders : env_int("DAGSCHED_RING_FEEDERS", 0);
+  const int force_pib = sh && sh->placement_mode >= 0 ? sh->placement_mode : env_int("DAGSCHED_RING_PIB_LDS", -1);
   int64_t best_score = -1;
   int best_wgs = 0;
   for (int G = kWave / Pseg; G >= 1; G >>= 1) {
@@ -391,7 +402,7 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
   // workgroup size: the wavefronts with a role, plus helpers for the ingest phase when the LDS leaves the CU
   // nearly empty of wavefronts (one workgroup per CU: 1024 threads, two: 512)
   plan.block = ring_threads(plan.feeders);
-  const int force_block = env_int("DAGSCHED_RING_BLOCK", 0);
+  const int force_block = sh && sh->block_threads ? sh->block_threads : env_int("DAGSCHED_RING_BLOCK", 0);
   if (force_block >= plan.block && force_block <= 1024 && force_block % kWave == 0) plan.block = force_block;
   else if (best_wgs == 1) plan.block = 1024;
   else if (best_wgs == 2) plan.block = std::max(plan.block, 512);

@@ -28,7 +28,13 @@ class Desc(ctypes.Structure):
                 ("row_ptr", ctypes.c_void_p), ("col_idx", ctypes.c_void_p), ("dur", ctypes.c_void_p),
                 ("comm", ctypes.c_void_p), ("mem_delta", ctypes.c_void_p),
                 ("max_candidates", ctypes.c_int32), ("layout", ctypes.c_int32), ("hip_device", ctypes.c_int32),
-                ("weight", ctypes.c_void_p), ("mem_limit", ctypes.c_void_p)]
+                ("weight", ctypes.c_void_p), ("mem_limit", ctypes.c_void_p), ("shape", ctypes.c_void_p)]
+
+
+class Shape(ctypes.Structure):
+    """dagsched_shape_t: optional launch shape of the 16-bit kernel (0 / -1: chosen by the library)."""
+    _fields_ = [("cand_per_block", ctypes.c_int32), ("ring_slots", ctypes.c_int32), ("feeders", ctypes.c_int32),
+                ("placement_mode", ctypes.c_int32), ("block_threads", ctypes.c_int32)]
 
 
 class Info(ctypes.Structure):
@@ -93,7 +99,7 @@ class _HostProblem:
     """Keeps the contiguous host arrays alive while a Desc points at them."""
 
     def __init__(self, n_devices, row_ptr, col_idx, dur, comm, mem_delta, max_candidates, layout, hip_device,
-                 n_nodes=None, n_edges=None, weight=None, mem_limit=None):
+                 n_nodes=None, n_edges=None, weight=None, mem_limit=None, shape=None):
         self.row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int32)
         self.col_idx = np.ascontiguousarray(col_idx, dtype=np.int32)
         self.dur = np.ascontiguousarray(dur, dtype=np.int32)
@@ -119,14 +125,20 @@ class _HostProblem:
             raise ValueError("mem_limit must have one entry per machine")
         d.weight = None if self.weight is None else self.weight.ctypes.data
         d.mem_limit = None if self.mem_limit is None else self.mem_limit.ctypes.data
+        self.shape = None
+        if shape is not None:
+            self.shape = Shape(int(shape.get("cand_per_block", 0)), int(shape.get("ring_slots", 0)),
+                               int(shape.get("feeders", 0)), int(shape.get("placement_mode", -1)),
+                               int(shape.get("block_threads", 0)))
+        d.shape = None if self.shape is None else ctypes.addressof(self.shape)
         self.desc = d
 
 
 def validate(n_devices, row_ptr, col_idx, dur, comm, mem_delta, max_candidates=1, layout=CAND_MAJOR,
-             n_nodes=None, n_edges=None, weight=None, mem_limit=None) -> int:
+             n_nodes=None, n_edges=None, weight=None, mem_limit=None, shape=None) -> int:
     """Host-only description check; returns the code dagsched_create would return."""
     hp = _HostProblem(n_devices, row_ptr, col_idx, dur, comm, mem_delta, max_candidates, layout, 0, n_nodes, n_edges,
-                      weight, mem_limit)
+                      weight, mem_limit, shape)
     return load(import_torch_first=False).dagsched_validate(ctypes.byref(hp.desc))
 
 
@@ -134,10 +146,10 @@ class Evaluator:
     """dagsched_create / dagsched_evaluate / dagsched_destroy around torch device tensors."""
 
     def __init__(self, n_devices, row_ptr, col_idx, dur, comm, mem_delta, max_candidates: int,
-                 layout: int = CAND_MAJOR, hip_device: int = 0, weight=None, mem_limit=None):
+                 layout: int = CAND_MAJOR, hip_device: int = 0, weight=None, mem_limit=None, shape=None):
         lib = load()
         hp = _HostProblem(n_devices, row_ptr, col_idx, dur, comm, mem_delta, max_candidates, layout, hip_device,
-                          weight=weight, mem_limit=mem_limit)
+                          weight=weight, mem_limit=mem_limit, shape=shape)
         handle = ctypes.c_void_p()
         _check(lib.dagsched_create(ctypes.byref(hp.desc), ctypes.byref(handle)))
         self._h = handle
@@ -145,10 +157,50 @@ class Evaluator:
         self.layout, self.max_candidates, self.hip_device = layout, max_candidates, hip_device
 
     @classmethod
-    def for_workload(cls, w, max_candidates: Optional[int] = None, layout: int = CAND_MAJOR, hip_device: int = 0):
+    def for_workload(cls, w, max_candidates: Optional[int] = None, layout: int = CAND_MAJOR, hip_device: int = 0,
+                     shape=None):
         return cls(w.n_devices, w.row_ptr, w.col_idx, w.dur, w.comm, w.mem_delta,
                    w.n_cand if max_candidates is None else max_candidates, layout, hip_device,
-                   weight=getattr(w, "weight", None), mem_limit=getattr(w, "mem_limit", None))
+                   weight=getattr(w, "weight", None), mem_limit=getattr(w, "mem_limit", None), shape=shape)
+
+    @classmethod
+    def autotuned(cls, make, placement, rank, reps: int = 3, verbose: bool = False):
+        """Time the library's own launch shape and a few neighbours of it (one feeder more or fewer, half the
+        candidates per workgroup, the placement elsewhere) on the caller's batch and return the fastest evaluator
+        with the shape it uses.  `make(shape)` builds an Evaluator for the caller's problem with a dagsched_shape_t
+        given as a dict (None: the library's choice).  Shapes that the library answers with its int32 kernel are
+        skipped.  Worth it when very many batches of one problem follow (a search)."""
+        best = make(None)
+        base = best.info()
+        out = best.alloc_outputs(best._n_cand(placement, rank))
+        best.evaluate(placement, rank, out)
+        best_ms, best_shape = best.time_evaluate(placement, rank, out, reps=reps), None
+        if base["state_bits"] != 16:
+            return best, best_shape
+        trials = []
+        for f in (base["feeders"] - 1, base["feeders"] + 1):
+            if 1 <= f <= 4:
+                trials.append({"feeders": f})
+        if base["cand_per_block"] > 1:
+            trials.append({"cand_per_block": base["cand_per_block"] // 2})
+        trials += [{"placement_mode": m} for m in (0, 1, 2) if m != base["placement_bytes_in_lds"]]
+        for shape in trials:
+            try:
+                ev = make(shape)
+            except DagschedError:
+                continue
+            keep = False
+            if ev.info()["state_bits"] == 16:
+                ev.evaluate(placement, rank, out)
+                ms = ev.time_evaluate(placement, rank, out, reps=reps)
+                if verbose:
+                    print("autotune", shape, "%.4f ms (best so far %.4f ms)" % (ms, best_ms))
+                if ms < 0.97 * best_ms:                # a clear win only: timings of one batch are noisy
+                    best.close()
+                    best, best_ms, best_shape, keep = ev, ms, shape, True
+            if not keep:
+                ev.close()
+        return best, best_shape
 
     def info(self) -> dict:
         i = Info()

@@ -106,6 +106,17 @@ def test_validate_checks_static_memory():
 
 
 
+def test_validate_checks_the_launch_shape():
+    rp, ci = W.csr_from_edges(3, [0, 1], [1, 2])
+    args = dict(n_devices=2, row_ptr=rp, col_idx=ci, dur=[1, 1, 1], comm=[[0, 1], [1, 0]], mem_delta=[0, 0, 0])
+    ds = dagsched
+    assert ds.validate(**args, shape={}) == 0
+    assert ds.validate(**args, shape=dict(cand_per_block=8, ring_slots=16, feeders=3, placement_mode=0, block_threads=512)) == 0
+    for bad in (dict(cand_per_block=3), dict(cand_per_block=128), dict(ring_slots=5), dict(feeders=5), dict(feeders=-1),
+                dict(placement_mode=3), dict(placement_mode=-2), dict(block_threads=100), dict(block_threads=2048)):
+        assert ds.validate(**args, shape=bad) == -1, bad
+
+
 def test_bench_refuses_more_than_one_gpu_and_reads_the_committed_counters():
     import subprocess
     import sys

@@ -287,6 +287,38 @@ def test_nibble_placement_kernels(gpu_lib, env):
     assert info2["variant"] == 4 and (z2[f2 == 0] > 65535 - 255).any()
 
 
+def test_launch_shape_from_the_description_and_autotuning(gpu_lib):
+    """A shape given with the description is used as given and changes no result; the autotuning helper returns
+    an evaluator that is still right."""
+    import torch
+    from paper_2503_09357_amd import dagsched as ds
+    w = W.gen_config(3, n_cand=64)
+    want = oracle.evaluate_workload(w, 0, threads=8)
+    pl, rk = torch.from_numpy(w.placement).cuda(), torch.from_numpy(w.rank).cuda()
+    shape = dict(cand_per_block=2, ring_slots=16, feeders=1, placement_mode=0, block_threads=256)
+    with ds.Evaluator.for_workload(w, shape=shape) as ev:
+        info = ev.info()
+        assert (info["cand_per_block"], info["ring_slots"], info["feeders"], info["placement_bytes_in_lds"],
+                info["block_threads"]) == (2, 16, 1, 0, 256)
+        got = [t.cpu().numpy() for t in ev.evaluate(pl, rk)]
+        for a, b in zip(got, want):
+            assert np.array_equal(a, b)
+    # a shape that is not built: the int32 kernel answers, with the same results
+    with ds.Evaluator.for_workload(w, shape=dict(ring_slots=32, placement_mode=1)) as ev:
+        assert ev.info()["state_bits"] == 32
+        got = [t.cpu().numpy() for t in ev.evaluate(pl, rk)]
+        for a, b in zip(got, want):
+            assert np.array_equal(a, b)
+    ev, best_shape = ds.Evaluator.autotuned(lambda s: ds.Evaluator.for_workload(w, shape=s), pl, rk)
+    try:
+        assert ev.info()["state_bits"] == 16
+        got = [t.cpu().numpy() for t in ev.evaluate(pl, rk)]
+        for a, b in zip(got, want):
+            assert np.array_equal(a, b)
+    finally:
+        ev.close()
+
+
 def test_sixteen_bit_overflow_falls_back(gpu_lib):
     """End times that leave the 16-bit range: the ring kernel must hand exactly those candidates to the
     int32 kernel.  A long chain on few machines whose makespan straddles 65535 for different orders."""
