@@ -360,8 +360,8 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
   // shape: most candidates resident per CU first.  Placement bytes in LDS give the fastest feeders but cost
   // N bytes per candidate; in L2 they leave room for more candidates or a deeper ring.  Measured weights: a
   // four-slot ring counts 0.7 (hot lanes outrun it), placement bytes in L2 count 0.97, and workgroups beyond
-  // five per CU count nothing; at equal counts, more workgroups of fewer candidates (two relaxers hide each
-  // other's latency: 13 % on an 8000-operation, 8-machine pipeline).
+  // five per CU count nothing, half-empty wavefronts count 0.65 (the feeders do the same work for half the
+  // candidates); at equal counts, more workgroups of fewer candidates.
   // a shape given with the description wins over the environment (which the tests use), field by field
   const dagsched_shape_t *sh = d->shape;
   const int force_g = sh && sh->cand_per_block ? sh->cand_per_block : env_int("DAGSCHED_RING_G", 0);
@@ -383,7 +383,8 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
         if ((uint64_t)G * (o.s_stride >> 1) > 65536u) continue;   // half-addresses must fit 16 bits
         const int wgs = std::min(5, lds_max / (int)align_up(o.total, 512));   // beyond ~20 wavefronts the CU is issue-bound
         if (wgs < 1) continue;
-        const int64_t score = (int64_t)wgs * G * (ring >= 8 ? 100 : 70) * (pib_lds == 1 ? 100 : pib_lds == 2 ? 99 : 97) + (ring == 16 ? 2 : 0) - G;
+        const int64_t score = (int64_t)wgs * G * (ring >= 8 ? 100 : 70) * (pib_lds == 1 ? 100 : pib_lds == 2 ? 99 : 97) *
+                                  (G * Pseg < kWave ? 65 : 100) + (ring == 16 ? 2 : 0) - G;
         if (score > best_score) { best_score = score; best_wgs = wgs; plan.G = G; plan.ring = ring; plan.lds = o; }
       }
     }
