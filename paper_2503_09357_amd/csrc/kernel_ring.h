@@ -335,7 +335,8 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
   if (wave == 0) {
     // ------------------------------------------------------------ relaxer
     lds_byte_t *const ring_lane = ldsb + o.o_ring + (uint32_t)lane * 16u;   // ring layout: [slot][lane] of 16 bytes
-    lds_vu32_t *const total_p = (lds_vu32_t *)(ldsb + o.o_total) + lane;
+    // the lane is through when it has taken this many ops (counted at ingest) and holds none: tm then equals this
+    const uint32_t tm_end = (totalw[lane] << 16) | kNotDone16;
     lds_vi32_t *const abort_p = (lds_vi32_t *)(ldsb + o.o_abort) + g;
     const uint64_t segmask = ((Pseg == kWave) ? ~0ull : ((1ull << Pseg) - 1ull)) << (g * Pseg);
     auto cell = [&](uint32_t a16) -> lds_vu16_t & { return *(lds_vu16_t *)(uintptr_t)(a16 << HALF); };
@@ -399,7 +400,7 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
         slot_p = next_p;
         if (PR != 4) r = *(lds_vu32x4_t *)next_p;
       }
-      const bool fin = dead || (idle && tm == ((*total_p << 16) | kNotDone16));
+      const bool fin = dead || (idle && tm == tm_end);
       if (__ballot(!fin) == 0) { expired = false; break; }
       const uint64_t hold = __ballot(!idle || fin);
       if (!fin && (prog_acc & segmask) == 0 && (hold & segmask) == segmask) {
@@ -416,7 +417,7 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
       prog_acc = 0;
     }
     if (expired) {                                          // bounded wait ran out: report, release the feeder
-      const bool fin = dead || (idle && tm == ((*total_p << 16) | kNotDone16));
+      const bool fin = dead || (idle && tm == tm_end);
       if (!fin) { flagw[g] = kBitInternal; *abort_p = 1; }
     }
     acc = (int32_t)(x_acc - kOrigin);
