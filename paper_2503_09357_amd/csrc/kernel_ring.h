@@ -363,9 +363,12 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
     u32x4_t r = *(lds_vu32x4_t *)slot_p;                    // ... as read during the previous trip
     // end times of the current op's predecessors, read at the end of the previous trip
     uint32_t e0 = cell(dummy), e1 = e0, e2 = e0, e3 = e0;
-    for (uint32_t it = 0; it < p.spin_cap; it += 8) {
+    // The test for deadlocks costs about as much as a trip and the jump back to the top of the loop a little less, so
+    // the loop is unrolled 32 times with the deadlock test once per pass (1.22 -> 1.09 ms on the MoE workload against
+    // 8 times); "all through" is looked for every 8 trips, which short lists need.
+    for (uint32_t it = 0; it < p.spin_cap; it += 32) {
 #pragma unroll
-      for (int sub = 0; sub < 8; ++sub) {
+      for (int sub = 0; sub < 32; ++sub) {
         const bool empty = (r.w & 0xFFFFu) == kNotDone16;   // slot t does not hold op t yet
         uint32_t x = max(max(x_acc, e0 + (w2 & 0xFFu)), e1 + (PR == 4 ? (w2 >> 8) & 0xFFu : w2 >> 8));
         if (PR == 4) x = max(max(x, e2 + ((w2 >> 16) & 0xFFu)), e3 + (w2 >> 24));
@@ -391,7 +394,7 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
         if (PR == 4) { e2 = cell(w1 & 0xFFFFu); e3 = cell(w1 >> 16); }
         // One trip without progress while every unfinished machine holds an op is already a deadlock
         // (end times only change when some op runs), so progress is sampled once per window.
-        if (sub == 7) prog_acc = __ballot(ran || take);     // an op taken now has not been tested yet
+        if (sub == 31) prog_acc = __ballot(ran || take);    // an op taken now has not been tested yet
         idle = next && empty;                               // (not next: an op is held, so not idle)
         w2 = next ? c2 : w2;
         w3 = next ? c3 : w3;
@@ -399,23 +402,29 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
         *(lds_vu32_t *)((take ? slot_p : scr_m12) + 12) = mark;
         slot_p = next_p;
         if (PR != 4) r = *(lds_vu32x4_t *)next_p;
+        if ((sub & 7) == 7 && sub != 31 && __ballot(!(dead || (idle && tm == tm_end))) == 0) { expired = false; goto relaxed; }
       }
       const bool fin = dead || (idle && tm == tm_end);
-      if (__ballot(!fin) == 0) { expired = false; break; }
-      const uint64_t hold = __ballot(!idle || fin);
-      if (!fin && (prog_acc & segmask) == 0 && (hold & segmask) == segmask) {
-        // every unfinished machine of this candidate holds an op and none could run: deadlock.  If one of
-        // the held ops has all its predecessors ended, only the 16-bit range stopped it (optimistic mode:
-        // the int32 kernel takes the candidate); otherwise every held op waits for an op that can never
+      const uint64_t open = __ballot(!fin);
+      if (open == 0) { expired = false; break; }
+      // Deadlock: every unfinished machine of a candidate holds an op and none of its machines ran or took an op
+      // in the sampled trip.  The test is kept cheap (it runs once per window for every lane); what follows a
+      // deadlock is rare and sits behind a branch that the whole wavefront takes or skips.
+      const uint64_t stuck = (__ballot(!idle) | ~open) & ~prog_acc;
+      const bool deadlock = !fin && (stuck & segmask) == segmask;
+      if (__ballot(deadlock) != 0) {
+        // If one of the held ops has all its predecessors ended, only the 16-bit range stopped it (optimistic
+        // mode: the int32 kernel takes the candidate); otherwise every held op waits for an op that can never
         // run, i.e. the combined graph has a cycle.
-        const bool range_stop = !idle && max(max(e0, e1), PR == 4 ? max(e2, e3) : 0u) < kNotDone16;
+        const bool range_stop = deadlock && !idle && max(max(e0, e1), PR == 4 ? max(e2, e3) : 0u) < kNotDone16;
         const bool overflow = (__ballot(range_stop) & segmask) != 0;
-        stalled = true;
-        dead = true;
-        *abort_p = overflow ? 1 : 2;
+        if (deadlock) *abort_p = overflow ? 1 : 2;
+        stalled = stalled || deadlock;
+        dead = dead || deadlock;
       }
       prog_acc = 0;
     }
+  relaxed:
     if (expired) {                                          // bounded wait ran out: report, release the feeder
       const bool fin = dead || (idle && tm == tm_end);
       if (!fin) { flagw[g] = kBitInternal; *abort_p = 1; }
