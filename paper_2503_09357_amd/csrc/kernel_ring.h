@@ -498,11 +498,16 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
 #pragma unroll
     for (int i = 0; i < kStages; ++i) { E[i].rec = make_uint4(0, 0, 0, 0); E[i].q0 = E[i].q1 = E[i].q2 = E[i].q3 = 0; E[i].fl = 0; }
 
-    for (uint32_t it = 0; it < p.spin_cap; it += kStages) {
+    // The look at the relaxer's "given up" flag and the end test wait for LDS and cost a dozen instructions: once
+    // per kRounds turns of the pipeline.  Four turns where the relaxer limits (the general kind: 2 % on the MoE
+    // workload); one where the feeders do and a workgroup's last ops are waited for (3 % on the pipelines).
+    constexpr int kRounds = KIND == 0 ? 4 : 1;
+    for (uint32_t it = 0; it < p.spin_cap; it += kStages * kRounds) {
       if (*abort_p) { k = klast + 1u; written = admitted; }   // the relaxer gave this candidate up
       if (__ballot(!(k > klast && written == admitted)) == 0) break;
 #pragma unroll
-      for (int s = 0; s < kStages; ++s) {
+      for (int s_ = 0; s_ < kStages * kRounds; ++s_) {
+        const int s = s_ % kStages;
         Entry &e0 = E[s];                             // admitted in this trip
         Entry &e1 = E[(s + kStages - 1) % kStages];   // admitted one trip ago: its record has arrived
         Entry &e2 = E[(s + 1) % kStages];             // the oldest: written in this trip (e1 itself when the depth is two)
