@@ -377,7 +377,8 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
         x_acc = ran ? x : x_acc;                            // the machine is busy until x (chain edge, eq. (7))
         cell(ran ? (w3 >> 16) : trash) = (uint16_t)x;
         const bool next = ran || idle;                      // the registers take the content of slot t
-        const bool take = next && !empty;                   // ... which is op t
+        const bool idle_next = next && empty;               // ... which is still free: nothing held (not next: an op is held)
+        const bool take = next ^ idle_next;                 // ... which is op t
         // The ring slot for the next trip.  With four predecessors per op it is requested before the end times
         // (it arrives first, and what depends on it is done while they are on their way: 1-5 %); with two, where
         // the feeders are what limits, after everything else (a delivery is then seen a little earlier: 1-3 %).
@@ -395,7 +396,7 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
         // One trip without progress while every unfinished machine holds an op is already a deadlock
         // (end times only change when some op runs), so progress is sampled once per window.
         if (sub == 31) prog_acc = __ballot(ran || take);    // an op taken now has not been tested yet
-        idle = next && empty;                               // (not next: an op is held, so not idle)
+        idle = idle_next;
         w2 = next ? c2 : w2;
         w3 = next ? c3 : w3;
         // the slot just copied is free again: its last dword says so (and which op left it) to the feeders
