@@ -542,8 +542,15 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
           }
         }
         // (3) admission
-        pending = (k <= klast) &&
-                  *(lds_vu32_t *)(ring_lane + ((aseq & (uint32_t)(RING - 1)) << 10) + 12) == (((aseq - (uint32_t)RING) << 16) | kNotDone16);
+        // (measured: with two predecessors per op a branch around the read for exhausted lanes pays, 3 %; else not, 1 %)
+        lds_vu32_t *const mark_p = (lds_vu32_t *)(ring_lane + ((aseq & (uint32_t)(RING - 1)) << 10) + 12);
+        const uint32_t mark_free = ((aseq - (uint32_t)RING) << 16) | kNotDone16;
+        if (KIND == 2) {
+          pending = (k <= klast) && *mark_p == mark_free;
+        } else {
+          const uint32_t mark = *mark_p;
+          pending = (k <= klast) & (mark == mark_free);
+        }
         e0.fl = pending ? 1u : 0u;
         e0.rec = p.rec[pending ? addr : 0u];                 // lanes that admit nothing share one record
         admitted += pending ? 1u : 0u;
