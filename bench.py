@@ -64,8 +64,8 @@ def algorithmic_bytes(w) -> int:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=4, help="workload 1..5 (default 4: MoE operator DAG)")
     ap.add_argument("--layout", type=int, default=0, help="0 candidate-major, 1 candidate-minor")
     ap.add_argument("--no-cpu-baseline", action="store_true")
