@@ -319,6 +319,52 @@ def test_launch_shape_from_the_description_and_autotuning(gpu_lib):
         ev.close()
 
 
+def test_randomized_problems_and_launch_shapes(gpu_lib):
+    """Many small random problems (sizes, machine counts, fan-in, durations, delays, static memory and limits, both
+    layouts, malformed and cyclic candidates), each under a random launch shape: every kernel instantiation that
+    the shapes reach must give the oracle's bits."""
+    import torch
+    from paper_2503_09357_amd import dagsched as ds
+    seen = set()
+    for case in range(250):
+        rng = np.random.default_rng(90000 + case)
+        n = int(rng.integers(1, 400)) if rng.random() < 0.9 else int(rng.integers(400, 3000))
+        p, fanin, c = int(rng.integers(1, 65)), int(rng.integers(1, 11)), int(rng.integers(1, 120))
+        layout = int(rng.integers(0, 2))
+        w = W.random_instance(rng, n, p, c, max_fanin=fanin, max_dur=int(rng.integers(1, 400)),
+                              max_comm=int(rng.integers(0, 200)), frac_arbitrary=0.3, frac_bad=0.15,
+                              dup_prob=0.05 * int(rng.integers(0, 2)))
+        if rng.random() < 0.5:
+            w.weight = rng.integers(0, 50, n).astype(np.int64)
+            w.mem_limit = rng.integers(-5, 400, p).astype(np.int64)
+        shape = None
+        if rng.random() < 0.75:
+            mode = int(rng.integers(-1, 3))
+            if mode == 2 and p > 16:
+                mode = 1
+            ring = int(rng.choice([0, 8, 16, 32])) if mode == 0 else int(rng.choice([0, 4, 8])) if mode > 0 else 0
+            feeders = int(rng.integers(0, 4))
+            if ring == 4 and feeders == 3:
+                feeders = 2
+            pseg = 1
+            while pseg < p:
+                pseg *= 2
+            g = int(rng.choice([0, 1, 2, 4, 8, 16, 32, 64]))
+            shape = dict(cand_per_block=g if g <= 64 // pseg else 0, ring_slots=ring, feeders=feeders,
+                         placement_mode=mode, block_threads=int(rng.choice([0, 0, 384, 512, 1024])))
+        pl, rk = w.placement, w.rank
+        if layout == 1:
+            pl, rk = np.ascontiguousarray(pl.T), np.ascontiguousarray(rk.T)
+        with ds.Evaluator.for_workload(w, layout=layout, shape=shape) as ev:
+            info = ev.info()
+            got = [t.cpu().numpy() for t in ev.evaluate(torch.from_numpy(pl).cuda(), torch.from_numpy(rk).cuda())]
+        want = oracle.evaluate_workload(w, layout, threads=8)
+        for name, a, b in zip(("makespan", "bubble", "peak_mem", "flags"), got, want):
+            assert np.array_equal(a, b), (name, case, n, p, fanin, c, layout, shape, info)
+        seen.add((info["state_bits"], info["kernel_kind"], info["placement_bytes_in_lds"], info["feeders"], info["ring_slots"]))
+    assert len(seen) >= 25, sorted(seen)                      # the sweep does reach many instantiations
+
+
 def test_sixteen_bit_overflow_falls_back(gpu_lib):
     """End times that leave the 16-bit range: the ring kernel must hand exactly those candidates to the
     int32 kernel.  A long chain on few machines whose makespan straddles 65535 for different orders."""
