@@ -205,3 +205,70 @@ def check_constraints(P, row_ptr, col_idx, dur, comm, mem_delta, placement, rank
                 assert m_minus[v] == base
             else:
                 assert m_minus[v] == m_plus[lst[r - 1]]
+
+
+def tick_simulate_channels(P, row_ptr, col_idx, dur, comm, placement, rank, edge_order):
+    """Unit-step simulation of the model WITH channel contention (Sec. III, eqs. (11)-(15)), written from the
+    definition and independent of any graph rewriting: an edge (u, v) across machines is a transfer that occupies the
+    channel (pi(u), pi(v)) for comm[pi(u)][pi(v)] time units, cannot start before u has ended, and must have ended
+    before v starts; the transfers of a channel run one at a time in the order `edge_order[channel]` (a list of
+    edge indices k into col_idx).  Edges inside a machine need no transfer.  Returns None when the simulation
+    stalls, else (makespan, start [N], end [N], transfer_end {k: time}).
+    """
+    n = len(dur)
+    comm = np.asarray(comm).reshape(P, P)
+    src = np.repeat(np.arange(n), np.diff(row_ptr))
+    in_edges: List[List[int]] = [[] for _ in range(n)]
+    for k in range(len(col_idx)):
+        in_edges[int(col_idx[k])].append(k)
+    lists = device_lists(P, placement, rank)
+    assert lists is not None
+    ptr = [0] * P
+    busy_until = [0] * P
+    cptr = {ch: 0 for ch in edge_order}
+    cbusy = {ch: 0 for ch in edge_order}
+    start: Dict[int, int] = {}
+    end: Dict[int, int] = {}
+    t_end: Dict[int, int] = {}
+    horizon = int(np.sum(dur)) + (len(col_idx) + n) * (int(comm.max()) + 1) + 2
+    t = 0
+    while len(start) < n:
+        if t > horizon:
+            return None
+        changed = True
+        while changed:                      # zero durations may cascade inside one tick
+            changed = False
+            for ch, order in edge_order.items():
+                if cptr[ch] >= len(order) or cbusy[ch] > t:
+                    continue
+                k = order[cptr[ch]]
+                u = int(src[k])
+                if u in end and end[u] <= t:
+                    t_end[k] = t + int(comm[ch[0], ch[1]])
+                    cbusy[ch] = t_end[k]
+                    cptr[ch] += 1
+                    changed = True
+            for j in range(P):
+                if ptr[j] >= len(lists[j]) or busy_until[j] > t:
+                    continue
+                v = lists[j][ptr[j]]
+                ok = True
+                for k in in_edges[v]:
+                    u = int(src[k])
+                    if placement[u] == j:
+                        ok = u in end and end[u] <= t
+                    else:
+                        ok = k in t_end and t_end[k] <= t
+                    if not ok:
+                        break
+                if ok:
+                    start[v] = t
+                    end[v] = t + int(dur[v])
+                    busy_until[j] = end[v]
+                    ptr[j] += 1
+                    changed = True
+        t += 1
+    z = max(end.values()) if end else 0
+    s = np.array([start[v] for v in range(n)], dtype=np.int64)
+    e = np.array([end[v] for v in range(n)], dtype=np.int64)
+    return z, s, e, t_end
