@@ -365,7 +365,9 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
     uint32_t e0 = cell(dummy), e1 = e0, e2 = e0, e3 = e0;
     // The test for deadlocks costs about as much as a trip and the jump back to the top of the loop a little less, so
     // the loop is unrolled 32 times with the deadlock test once per pass (1.22 -> 1.09 ms on the MoE workload against
-    // 8 times); "all through" is looked for every 8 trips, which short lists need.
+    // 8 times); "all through" is looked for every 8 trips with two predecessors per op (the pipelines: short lists),
+    // else every 16 (1-2 % either way).
+    constexpr int kEndMask = KIND == 2 ? 7 : 15;
     for (uint32_t it = 0; it < p.spin_cap; it += 32) {
 #pragma unroll
       for (int sub = 0; sub < 32; ++sub) {
@@ -403,7 +405,7 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
         *(lds_vu32_t *)((take ? slot_p : scr_m12) + 12) = mark;
         slot_p = next_p;
         if (PR != 4) r = *(lds_vu32x4_t *)next_p;
-        if ((sub & 7) == 7 && sub != 31 && __ballot(!(dead || (idle && tm == tm_end))) == 0) { expired = false; goto relaxed; }
+        if ((sub & kEndMask) == kEndMask && sub != 31 && __ballot(!(dead || (idle && tm == tm_end))) == 0) { expired = false; goto relaxed; }
       }
       const bool fin = dead || (idle && tm == tm_end);
       const uint64_t open = __ballot(!fin);
