@@ -85,6 +85,8 @@ typedef struct {
   int32_t placement_mode;   /* -1 chosen by the library, 0 one byte per node in L2, 1 in LDS, 2 four bits per
                                node in LDS (P <= 16)                                                        */
   int32_t block_threads;    /* workgroup size: a multiple of 64, at least 64 * (2 + feeders), at most 1024  */
+  int32_t state_bits;       /* width of the end times kept on chip: 16 (twice the candidates resident; candidates
+                               whose end times leave the range are evaluated by the int32 kernel one by one) or 32 */
 } dagsched_shape_t;
 
 /*

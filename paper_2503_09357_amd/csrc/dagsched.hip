@@ -59,7 +59,8 @@ inline int ilog2(int x) {
 }
 inline uint32_t align_up(uint32_t x, uint32_t a) { return (x + a - 1) / a * a; }
 
-enum { kVariantGeneralLds = 1, kVariantGeneralGlobal = 2, kVariantRingExact = 3, kVariantRingOptimistic = 4 };
+enum { kVariantGeneralLds = 1, kVariantGeneralGlobal = 2, kVariantRingExact = 3, kVariantRingOptimistic = 4,
+       kVariantRing32 = 5 };
 
 }  // namespace
 
@@ -108,6 +109,7 @@ int validate_desc(const dagsched_desc_t *d, std::vector<int32_t> *pred_ptr, std:
     if (r != 0 && r != 4 && r != 8 && r != 16 && r != 32) return DAGSCHED_EINVAL;
     if (sh->feeders < 0 || sh->feeders > 4 || sh->placement_mode < -1 || sh->placement_mode > 2) return DAGSCHED_EINVAL;
     if (b < 0 || b > 1024 || b % kWave) return DAGSCHED_EINVAL;
+    if (sh->state_bits != 0 && sh->state_bits != 16 && sh->state_bits != 32) return DAGSCHED_EINVAL;
   }
   if (d->row_ptr[0] != 0 || d->row_ptr[N] != E) return DAGSCHED_EINVAL;
   for (int32_t u = 0; u < N; ++u)
@@ -188,10 +190,12 @@ int env_int(const char *name, int dflt) {
 }
 
 // pib_lds: 0 placement bytes in L2, 1 in LDS, 2 in LDS as nibbles (P <= 16)
-LdsLayout ring_layout(int N, int P, int G, int ring, int pib_lds) {
+// cell_bytes: 2 (16-bit end times) or 4
+LdsLayout ring_layout(int N, int P, int G, int ring, int pib_lds, int cell_bytes) {
   LdsLayout o{};
   uint32_t at = 0;
-  o.s_stride = align_up(2u * (uint32_t)(N + 2), 4);      // N cells + dummy + trash; the arrays start at LDS offset 0
+  o.s_stride = align_up((uint32_t)cell_bytes * (uint32_t)(N + 2), 4);   // N cells + dummy + trash; the arrays start at LDS offset 0
+  o.cell_bytes = (uint32_t)cell_bytes;
   at += (uint32_t)G * o.s_stride;
   o.pi_stride = pib_lds == 1 ? align_up((uint32_t)(N + 1), 4) : pib_lds == 2 ? align_up((uint32_t)(N + 2) / 2u, 4) : 0u;
   o.pib_mode = (uint32_t)pib_lds;
@@ -220,7 +224,7 @@ template <int HALF>
 RingKernel ring_kernel_pick(int ring, int feeders, int pib_lds, int kind);
 
 struct RingPlan {
-  bool ok = false, exact = false;
+  bool ok = false, exact = false, cell32 = false;
   int G = 0, ring = 0, feeders = 1, kind = 0, block = 256;
   int32_t scale = 1;
   LdsLayout lds{};
@@ -263,7 +267,6 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
   }
   const int64_t crit = *std::max_element(fin.begin(), fin.end());
   const int64_t lower = std::max<int64_t>(crit, (sum_dur / g + P - 1) / P);
-  if (lower >= (int64_t)kNotDone16) return plan;       // no candidate could stay inside 16 bits
   const int64_t upper = sum_dur / g + (int64_t)(N - 1) * (max_comm / g);
   plan.scale = (int32_t)g;
 
@@ -364,6 +367,17 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
   // candidates); at equal counts, more workgroups of fewer candidates.
   // a shape given with the description wins over the environment (which the tests use), field by field
   const dagsched_shape_t *sh = d->shape;
+  // Width of the end times.  16 bits when every end time provably fits, or when most candidates can be expected to
+  // fit (the rest then go to the int32 kernel one by one); 32 bits (half the candidates resident, always exact)
+  // when they cannot: makespans of list schedules lie around three times the lower bound.
+  int64_t max_dur_scaled = 0;
+  for (int v = 0; v < N; ++v) max_dur_scaled = std::max<int64_t>(max_dur_scaled, d->dur[v] / g);
+  const int force_bits = sh && sh->state_bits ? sh->state_bits : env_int("DAGSCHED_RING_STATE_BITS", 0);
+  const bool fits16 = upper + 255 < (int64_t)kNotDone16;
+  plan.cell32 = force_bits == 32 || (force_bits != 16 && !fits16 && 3 * lower >= (int64_t)kNotDone16);
+  if (plan.cell32 && max_dur_scaled >= (int64_t)kNotDone16) return plan;   // a duration does not fit an op: general kernel
+  if (!plan.cell32 && lower >= (int64_t)kNotDone16) return plan;   // 16 bits asked for, and no candidate could stay inside them
+  const int cell_bytes = plan.cell32 ? 4 : 2;
   const int force_g = sh && sh->cand_per_block ? sh->cand_per_block : env_int("DAGSCHED_RING_G", 0);
   const int force_ring = sh && sh->ring_slots ? sh->ring_slots : env_int("DAGSCHED_RING_SLOTS", 0);
   const int force_feeders = sh && sh->feeders ? sh->feeders : env_int("DAGSCHED_RING_FEEDERS", 0);
@@ -378,9 +392,9 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
       for (int ring : {8, 16, 32, 4}) {
         if (force_ring && ring != force_ring) continue;
         if (pib_lds ? ring > 8 : ring < 8) continue;     // instantiated: LDS with 4 or 8 slots, L2 with 8, 16 or 32
-        LdsLayout o = ring_layout(N, P, G, ring, pib_lds);
+        LdsLayout o = ring_layout(N, P, G, ring, pib_lds, cell_bytes);
         if ((int)o.total > lds_max) continue;
-        if ((uint64_t)G * (o.s_stride >> 1) > 65536u) continue;   // half-addresses must fit 16 bits
+        if ((uint64_t)G * (o.s_stride >> (plan.cell32 ? 2 : 1)) > 65536u) continue;   // half (quarter) addresses must fit 16 bits
         const int wgs = std::min(5, lds_max / (int)align_up(o.total, 512));   // beyond ~20 wavefronts the CU is issue-bound
         if (wgs < 1) continue;
         const int64_t score = (int64_t)wgs * G * (ring >= 8 ? 100 : 70) * (pib_lds == 1 ? 100 : pib_lds == 2 ? 99 : 97) *
@@ -396,10 +410,14 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
                : (best_wgs == 1 && plan.lds.pib_mode == 0 && plan.ring == 16) ? 4
                : best_wgs <= 2 ? 3
                : (best_wgs * 4 <= 24 ? 2 : 1);
-  if (!force_feeders && !ring_kernel_pick<0>(plan.ring, plan.feeders, (int)plan.lds.pib_mode, plan.kind)) plan.feeders = 2;
-  if (best_score < 0 || !ring_kernel_pick<0>(plan.ring, plan.feeders, (int)plan.lds.pib_mode, plan.kind)) return plan;   // shape not built
+  auto built = [&](int feeders) {
+    return plan.cell32 ? ring_kernel_pick<2>(plan.ring, feeders, (int)plan.lds.pib_mode, plan.kind) != nullptr
+                       : ring_kernel_pick<0>(plan.ring, feeders, (int)plan.lds.pib_mode, plan.kind) != nullptr;
+  };
+  if (!force_feeders && !built(plan.feeders)) plan.feeders = 2;
+  if (best_score < 0 || !built(plan.feeders)) return plan;   // shape not built
   // the nibble kernels start time at 255 (see the kernel), which the 16-bit range must hold as well
-  plan.exact = upper + (plan.lds.pib_mode == 2 ? 255 : 0) < (int64_t)kNotDone16;
+  plan.exact = plan.cell32 || upper + (plan.lds.pib_mode == 2 ? 255 : 0) < (int64_t)kNotDone16;
   // workgroup size: the wavefronts with a role, plus helpers for the ingest phase when the LDS leaves the CU
   // nearly empty of wavefronts (one workgroup per CU: 1024 threads, two: 512)
   plan.block = ring_threads(plan.feeders);
@@ -420,6 +438,14 @@ using RingKernel = void (*)(RingParams);
   case 2 * 10000 + PIB * 1000 + RING * 10 + F: return relax_ring_kernel<RING, F, HALF, PIB, 2>;
 template <int HALF>
 RingKernel ring_kernel_pick(int ring, int feeders, int pib_lds, int kind) {
+  if (HALF == 2) {                                       // 32-bit end times: the shapes that large problems get
+    switch (kind * 10000 + pib_lds * 1000 + ring * 10 + feeders) {
+      DAGSCHED_RING_CASES(1, 8, 1) DAGSCHED_RING_CASES(1, 8, 2) DAGSCHED_RING_CASES(1, 8, 3)
+      DAGSCHED_RING_CASES(2, 8, 2) DAGSCHED_RING_CASES(2, 8, 3)
+      DAGSCHED_RING_CASES(0, 8, 2) DAGSCHED_RING_CASES(0, 16, 2) DAGSCHED_RING_CASES(0, 16, 3) DAGSCHED_RING_CASES(0, 16, 4)
+      default: return nullptr;
+    }
+  }
   switch (kind * 10000 + pib_lds * 1000 + ring * 10 + feeders) {
     DAGSCHED_RING_CASES(1, 4, 1) DAGSCHED_RING_CASES(1, 4, 2)
     DAGSCHED_RING_CASES(1, 8, 1) DAGSCHED_RING_CASES(1, 8, 2) DAGSCHED_RING_CASES(1, 8, 3) DAGSCHED_RING_CASES(1, 8, 4)
@@ -436,6 +462,7 @@ RingKernel ring_kernel_for(const dagsched *h) {
   // byte addresses when the workgroup's end-time arrays fit 64 KB, half addresses otherwise
   const bool half = (uint64_t)h->ring_G * h->lds.s_stride > 65536u;
   const int pib_lds = (int)h->lds.pib_mode;
+  if (h->lds.cell_bytes == 4) return ring_kernel_pick<2>(h->ring_slots, h->ring_feeders, pib_lds, h->ring_kind);
   return half ? ring_kernel_pick<1>(h->ring_slots, h->ring_feeders, pib_lds, h->ring_kind)
               : ring_kernel_pick<0>(h->ring_slots, h->ring_feeders, pib_lds, h->ring_kind);
 }
@@ -574,7 +601,7 @@ int dagsched_create(const dagsched_desc_t *desc, dagsched_t **out) {
     h->variant = h->gen_lds_state ? kVariantGeneralLds : kVariantGeneralGlobal;
   }
   if (ok && plan.ok) {
-    h->variant = plan.exact ? kVariantRingExact : kVariantRingOptimistic;
+    h->variant = plan.cell32 ? kVariantRing32 : plan.exact ? kVariantRingExact : kVariantRingOptimistic;
     h->ring_G = plan.G; h->ring_slots = plan.ring; h->ring_feeders = plan.feeders; h->ring_kind = plan.kind; h->ring_block = plan.block; h->lds = plan.lds; h->time_scale = plan.scale;
     h->rec_plane = plan.rec_plane; h->id_bits = plan.id_bits;
     const int64_t cap = ((int64_t)h->N + h->E + 1024) * 64;
@@ -694,11 +721,11 @@ int dagsched_get_info(const dagsched_t *h, dagsched_info_t *info) {
   if (!h || !info) return DAGSCHED_EINVAL;
   memset(info, 0, sizeof(*info));
   info->variant = h->variant;
-  const bool ring = h->variant == kVariantRingExact || h->variant == kVariantRingOptimistic;
+  const bool ring = h->variant == kVariantRingExact || h->variant == kVariantRingOptimistic || h->variant == kVariantRing32;
   info->cand_per_block = ring ? h->ring_G : h->gen_G;
   info->block_threads = ring ? h->ring_block : kWave;
   info->lds_bytes = ring ? (int32_t)h->lds.total : h->gen_lds;
-  info->state_bits = ring ? 16 : 32;
+  info->state_bits = ring && h->variant != kVariantRing32 ? 16 : 32;
   info->reserved[0] = ring ? h->ring_slots : 0;
   info->reserved[1] = h->time_scale;
   info->reserved[2] = ring ? (h->ring_feeders | ((int)h->lds.pib_mode << 8) | ((h->ring_kind == 2 ? 2 : 4) << 16) | (h->ring_kind << 24)) : 0;

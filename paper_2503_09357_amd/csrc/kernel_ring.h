@@ -23,7 +23,8 @@
 // few candidates fit), so the other wavefronts run on SIMDs that would otherwise idle.
 //
 // End times are kept as 16-bit unsigned values (sentinel 0xFFFF = not yet ended), which halves the
-// LDS footprint.  When the host cannot prove that every end time stays below 0xFFFF the kernel runs
+// LDS footprint (template HALF = 0 or 1).  HALF = 2 keeps them in 32 bits (sentinel 0x80000000) for problems whose
+// times cannot stay below 0xFFFF: the same kernel with half the candidates resident, always exact.  When the host cannot prove that every end time stays below 0xFFFF the kernel runs
 // "optimistically": an operation whose end time would reach 0xFFFF is never completed, its candidate
 // stalls exactly like a cyclic one; the two are told apart at the deadlock (does some held op have all its
 // predecessors ended?) and the candidates stopped by the range are handed to the general int32 kernel.
@@ -54,7 +55,8 @@ typedef DAGSCHED_LDS volatile u32x4_t lds_vu32x4_t;
 
 // Op layout (one 16-byte slot).  ha(x) is the 16-bit address of the end-time cell of x: its LDS byte
 // address when the end-time arrays of the workgroup fit 64 KB (template HALF = 0), else the byte
-// address / 2 (HALF = 1); the arrays come first in the workgroup's LDS.  Unused predecessor slots name the
+// address / 2 (HALF = 1); with 32-bit end times (HALF = 2, see below) the byte address / 4.  The arrays come first in
+// the workgroup's LDS.  Unused predecessor slots name the
 // candidate's dummy cell (end time 0, delay 0); a part that does not end its operation names the
 // candidate's trash cell instead of v and has duration 0.
 //   x = ha(pred0) | ha(pred1) << 16
@@ -62,6 +64,7 @@ typedef DAGSCHED_LDS volatile u32x4_t lds_vu32x4_t;
 //   z = delta0 | delta1 << 8 | delta2 << 16 | delta3 << 24
 //   w = duration | ha(v) << 16
 constexpr uint32_t kNotDone16 = 0xFFFFu;
+constexpr uint32_t kNotDone32 = 0x80000000u;          // above every time the library accepts (INT32_MAX bounds them)
 constexpr int ring_threads(int feeders) { return (2 + feeders) * kWave; }   // relaxer, feeders, accountant
 
 // One shared record per operation part: up to four DAG predecessors (unused slots name the dummy
@@ -72,6 +75,7 @@ struct LdsLayout {
   uint32_t s_stride, pi_stride;                       // bytes per candidate; the state array starts at 0
   uint32_t o_pi, o_ring, o_scr, o_total, o_peak, o_cnt, o_off, o_flag, o_abort, o_comm, total;
   uint32_t pib_mode;                                  // where the placement bytes are: 0 L2 workspace, 1 LDS, 2 LDS as nibbles
+  uint32_t cell_bytes;                                // 2: 16-bit end times, 4: 32-bit
 };
 
 struct RingParams {
@@ -117,6 +121,10 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
   static_assert((RING & (RING - 1)) == 0, "RING must be a power of two");
   static_assert(RING >= FEEDERS, "every feeder needs a slot of its own");
   static_assert(KIND >= 0 && KIND <= 2, "general, single parts, two predecessors");
+  static_assert(HALF >= 0 && HALF <= 2, "byte, half or quarter addresses");
+  constexpr bool kCell32 = HALF == 2;                       // 32-bit end times
+  constexpr uint32_t kNotDone = kCell32 ? kNotDone32 : kNotDone16;
+  constexpr int kNodeShift = kCell32 ? 0 : 1 - HALF;        // node -> offset of its cell in the units of the 16-bit addresses
   constexpr int PR = KIND == 2 ? 2 : 4;                     // DAG predecessors per op
   constexpr uint32_t kOrigin = PIBL == 2 ? 255u : 0u;
   const int tid = threadIdx.x;
@@ -313,9 +321,13 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
   // machine P whose delays are all zero; cell N+1 is a trash cell for parts that do not end an operation
   for (int gg = team; gg < ng; gg += n_teams) {
     uint32_t *sw = (uint32_t *)(lds + gg * o.s_stride);
-    for (int i = tt; i < (N + 3) / 2; i += tpc) {
-      const uint32_t lo = (2 * i < N) ? kNotDone16 : 0u, hi = (2 * i + 1 < N) ? kNotDone16 : 0u;
-      sw[i] = lo | (hi << 16);
+    if (kCell32) {
+      for (int i = tt; i < N + 2; i += tpc) sw[i] = i < N ? kNotDone32 : 0u;
+    } else {
+      for (int i = tt; i < (N + 3) / 2; i += tpc) {
+        const uint32_t lo = (2 * i < N) ? kNotDone16 : 0u, hi = (2 * i + 1 < N) ? kNotDone16 : 0u;
+        sw[i] = lo | (hi << 16);
+      }
     }
   }
   __syncthreads();
@@ -339,10 +351,16 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
     const uint32_t tm_end = (totalw[lane] << 16) | kNotDone16;
     lds_vi32_t *const abort_p = (lds_vi32_t *)(ldsb + o.o_abort) + g;
     const uint64_t segmask = ((Pseg == kWave) ? ~0ull : ((1ull << Pseg) - 1ull)) << (g * Pseg);
-    auto cell = [&](uint32_t a16) -> lds_vu16_t & { return *(lds_vu16_t *)(uintptr_t)(a16 << HALF); };
-    const uint32_t dummy = sbase + ((uint32_t)N << (1 - HALF));
+    auto cell = [&](uint32_t a16) -> uint32_t {
+      return kCell32 ? *(lds_vu32_t *)(uintptr_t)(a16 << 2) : (uint32_t)*(lds_vu16_t *)(uintptr_t)(a16 << HALF);
+    };
+    auto set_cell = [&](uint32_t a16, uint32_t v) {
+      if (kCell32) *(lds_vu32_t *)(uintptr_t)(a16 << 2) = v;
+      else *(lds_vu16_t *)(uintptr_t)(a16 << HALF) = (uint16_t)v;
+    };
+    const uint32_t dummy = sbase + ((uint32_t)N << kNodeShift);
     // The loop body is branch-free: every trip stores x somewhere (the trash cell unless an op ran).
-    const uint32_t trash = sbase + (((uint32_t)N + 1u) << (1 - HALF));
+    const uint32_t trash = sbase + (((uint32_t)N + 1u) << kNodeShift);
     __builtin_amdgcn_s_setprio(3);                          // the relaxer's trip is the critical path of the workgroup:
                                                             // it goes first wherever it shares a SIMD (measured: 4-5 % on the MoE workload)
     bool idle = true, dead = !has_ops;                      // idle: the registers hold a free slot's content, not an op
@@ -375,9 +393,11 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
         uint32_t x = max(max(x_acc, e0 + (w2 & 0xFFu)), e1 + (PR == 4 ? (w2 >> 8) & 0xFFu : w2 >> 8));
         if (PR == 4) x = max(max(x, e2 + ((w2 >> 16) & 0xFFu)), e3 + (w2 >> 24));
         x += w3 & 0xFFFFu;
-        const bool ran = x < kNotDone16;                    // an op, every predecessor ended and no 16-bit overflow
+        // an op, every predecessor ended and no 16-bit overflow (a free slot's "duration" 0xFFFF lifts x over the
+        // 16-bit sentinel, not over the 32-bit one: there the lane's state is asked)
+        const bool ran = kCell32 ? (x < kNotDone && !idle) : x < kNotDone;
         x_acc = ran ? x : x_acc;                            // the machine is busy until x (chain edge, eq. (7))
-        cell(ran ? (w3 >> 16) : trash) = (uint16_t)x;
+        set_cell(ran ? (w3 >> 16) : trash, x);
         const bool next = ran || idle;                      // the registers take the content of slot t
         const bool idle_next = next && empty;               // ... which is still free: nothing held (not next: an op is held)
         const bool take = next ^ idle_next;                 // ... which is op t
@@ -419,7 +439,7 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
         // If one of the held ops has all its predecessors ended, only the 16-bit range stopped it (optimistic
         // mode: the int32 kernel takes the candidate); otherwise every held op waits for an op that can never
         // run, i.e. the combined graph has a cycle.
-        const bool range_stop = deadlock && !idle && max(max(e0, e1), PR == 4 ? max(e2, e3) : 0u) < kNotDone16;
+        const bool range_stop = deadlock && !idle && max(max(e0, e1), PR == 4 ? max(e2, e3) : 0u) < kNotDone;
         const bool overflow = (__ballot(range_stop) & segmask) != 0;
         if (deadlock) *abort_p = overflow ? 1 : 2;
         stalled = stalled || deadlock;
@@ -456,7 +476,7 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
     lds_vi32_t *const abort_p = (lds_vi32_t *)(ldsb + o.o_abort) + g;
     const uint16_t *list = p.ws_list + (c0 + (cand_ok ? g : 0)) * p.list_stride;
     const uint32_t base2 = sbase | (sbase << 16);
-    const uint32_t trash = sbase + (((uint32_t)N + 1u) << (1 - HALF));
+    const uint32_t trash = sbase + (((uint32_t)N + 1u) << kNodeShift);
     const uint32_t vbits = (uint32_t)p.id_bits, vmask = (1u << vbits) - 1u;
     const uint32_t n_plane = (uint32_t)p.rec_plane;
     const uint32_t lps = (uint32_t)p.log_pseg;
@@ -565,12 +585,12 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
         // (D) pack e2 and publish it
         if (e2.fl & 1u) {
           const bool more = !kSingle && (e2.rec.z >> 31) != 0;
-          const uint32_t dst = more ? trash : sbase + ((e2.rec.w >> 16) << (1 - HALF));
+          const uint32_t dst = more ? trash : sbase + ((e2.rec.w >> 16) << kNodeShift);
           const uint32_t dur = e2.rec.z & 0xFFFFu;
           lds_byte_t *const sp = ring_lane + ((wseq & (uint32_t)(RING - 1)) << 10);
-          // node ids below 32768 whenever HALF == 0, so shifting both halves at once cannot carry over;
+          // node ids below 32768 whenever they are shifted, so shifting both halves at once cannot carry over;
           // the whole slot first with its free mark unchanged, then the last dword
-          const u32x4_t val = {(e2.rec.x << (1 - HALF)) + base2, (e2.rec.y << (1 - HALF)) + base2,
+          const u32x4_t val = {(e2.rec.x << kNodeShift) + base2, (e2.rec.y << kNodeShift) + base2,
                                d0 | (d1 << 8) | (d2 << 16) | (d3 << 24), ((wseq - (uint32_t)RING) << 16) | kNotDone16};
           *(lds_vu32x4_t *)sp = val;
           *(lds_vu32_t *)(sp + 12) = dur | (dst << 16);

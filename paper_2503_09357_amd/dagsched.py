@@ -34,7 +34,7 @@ class Desc(ctypes.Structure):
 class Shape(ctypes.Structure):
     """dagsched_shape_t: optional launch shape of the 16-bit kernel (0 / -1: chosen by the library)."""
     _fields_ = [("cand_per_block", ctypes.c_int32), ("ring_slots", ctypes.c_int32), ("feeders", ctypes.c_int32),
-                ("placement_mode", ctypes.c_int32), ("block_threads", ctypes.c_int32)]
+                ("placement_mode", ctypes.c_int32), ("block_threads", ctypes.c_int32), ("state_bits", ctypes.c_int32)]
 
 
 class Info(ctypes.Structure):
@@ -129,7 +129,7 @@ class _HostProblem:
         if shape is not None:
             self.shape = Shape(int(shape.get("cand_per_block", 0)), int(shape.get("ring_slots", 0)),
                                int(shape.get("feeders", 0)), int(shape.get("placement_mode", -1)),
-                               int(shape.get("block_threads", 0)))
+                               int(shape.get("block_threads", 0)), int(shape.get("state_bits", 0)))
         d.shape = None if self.shape is None else ctypes.addressof(self.shape)
         self.desc = d
 

@@ -221,6 +221,10 @@ def _with_env(env, fn):
     {"DAGSCHED_RING_FEEDERS": 1, "DAGSCHED_RING_SLOTS": 32, "DAGSCHED_RING_PIB_LDS": 0},
     {"DAGSCHED_RING_FEEDERS": 2, "DAGSCHED_RING_SLOTS": 8, "DAGSCHED_RING_PIB_LDS": 1, "DAGSCHED_RING_PREDS": 4},
     {"DAGSCHED_RING_FEEDERS": 2, "DAGSCHED_RING_SLOTS": 16, "DAGSCHED_RING_PIB_LDS": 0, "DAGSCHED_RING_PREDS": 4},
+    {"DAGSCHED_RING_FEEDERS": 2, "DAGSCHED_RING_SLOTS": 8, "DAGSCHED_RING_PIB_LDS": 1, "DAGSCHED_RING_STATE_BITS": 32},
+    {"DAGSCHED_RING_FEEDERS": 3, "DAGSCHED_RING_SLOTS": 16, "DAGSCHED_RING_PIB_LDS": 0, "DAGSCHED_RING_STATE_BITS": 32},
+    {"DAGSCHED_RING_FEEDERS": 1, "DAGSCHED_RING_SLOTS": 8, "DAGSCHED_RING_PIB_LDS": 1, "DAGSCHED_RING_STATE_BITS": 32,
+     "DAGSCHED_RING_PREDS": 4},
 ])
 def test_every_kernel_variant(gpu_lib, env):
     """The tuning knobs only pick among kernel instantiations; each one must give the same bits."""
@@ -233,7 +237,8 @@ def test_every_kernel_variant(gpu_lib, env):
         if "DAGSCHED_FORCE_GENERAL" in env:
             assert info["state_bits"] == 32
         else:
-            assert info["state_bits"] == 16
+            assert info["state_bits"] == env.get("DAGSCHED_RING_STATE_BITS", 16)
+            assert info["variant"] == (5 if info["state_bits"] == 32 else info["variant"]) and info["variant"] in (3, 4, 5)
             assert info["feeders"] == env["DAGSCHED_RING_FEEDERS"] and info["ring_slots"] == env["DAGSCHED_RING_SLOTS"]
             assert info["placement_bytes_in_lds"] == env["DAGSCHED_RING_PIB_LDS"]
             if "DAGSCHED_RING_G" in env:
@@ -276,14 +281,15 @@ def test_nibble_placement_kernels(gpu_lib, env):
     pl1, rk1 = W.list_schedules(rp, ci, 1, 67, 98)
     pl[::3], rk[::3] = pl1, rk1
     w = W.Workload("straddles 16 bits", p, rp, ci, dur, comm, mem, pl, rk)
-    (z, b, pk, f), info = _with_env(env, lambda: assert_parity(gpu_lib, w))
+    env16 = dict(env, DAGSCHED_RING_STATE_BITS=16)           # (left alone the library would take 32-bit end times here)
+    (z, b, pk, f), info = _with_env(env16, lambda: assert_parity(gpu_lib, w))
     assert info["placement_bytes_in_lds"] == 2 and info["variant"] == 4
     # a makespan bound between 65280 and 65535: exact with bytes, optimistic with nibbles
     dur2 = np.full(n, 100, np.int32)
     dur2[1] = 101                                             # no common factor to divide out
     dur2[0] += 65400 - int(dur2.sum())
     w2 = W.Workload("just below 16 bits", p, rp, ci, dur2, np.zeros((p, p), np.int32), mem, pl, rk)
-    (z2, b2, pk2, f2), info2 = _with_env(env, lambda: assert_parity(gpu_lib, w2))
+    (z2, b2, pk2, f2), info2 = _with_env(env16, lambda: assert_parity(gpu_lib, w2))
     assert info2["variant"] == 4 and (z2[f2 == 0] > 65535 - 255).any()
 
 
@@ -351,7 +357,8 @@ def test_randomized_problems_and_launch_shapes(gpu_lib):
                 pseg *= 2
             g = int(rng.choice([0, 1, 2, 4, 8, 16, 32, 64]))
             shape = dict(cand_per_block=g if g <= 64 // pseg else 0, ring_slots=ring, feeders=feeders,
-                         placement_mode=mode, block_threads=int(rng.choice([0, 0, 384, 512, 1024])))
+                         placement_mode=mode, block_threads=int(rng.choice([0, 0, 384, 512, 1024])),
+                         state_bits=int(rng.choice([0, 0, 16, 32])))
         pl, rk = w.placement, w.rank
         if layout == 1:
             pl, rk = np.ascontiguousarray(pl.T), np.ascontiguousarray(rk.T)
@@ -363,6 +370,41 @@ def test_randomized_problems_and_launch_shapes(gpu_lib):
             assert np.array_equal(a, b), (name, case, n, p, fanin, c, layout, shape, info)
         seen.add((info["state_bits"], info["kernel_kind"], info["placement_bytes_in_lds"], info["feeders"], info["ring_slots"]))
     assert len(seen) >= 25, sorted(seen)                      # the sweep does reach many instantiations
+
+
+def test_thirty_two_bit_end_times(gpu_lib):
+    """Times that cannot stay below 65535: the same kernel with 32-bit end times on chip (variant 5), chosen by
+    the library from the lower bound on the makespan, or asked for; always exact, no fallback list."""
+    import torch
+    from paper_2503_09357_amd import dagsched as ds
+    rng = np.random.default_rng(32)
+    cases = []
+    for cfg, c in ((2, 300), (3, 60), (4, 40)):
+        w = W.gen_config(cfg, n_cand=c)
+        w.dur = (w.dur.astype(np.int64) * 211 + 7).astype(np.int32)      # no common factor, nothing fits 16 bits
+        w.comm = (w.comm.astype(np.int64) * 50).astype(np.int32)
+        cases.append((w, None))
+    big = W.random_instance(rng, 400, 16, 60, max_fanin=7, max_dur=60000, max_comm=250, frac_arbitrary=0.3, frac_bad=0.2)
+    big.weight = rng.integers(0, 50, 400).astype(np.int64)
+    big.mem_limit = rng.integers(400, 1500, 16).astype(np.int64)
+    cases += [(big, None), (big, dict(placement_mode=2)), (big, dict(placement_mode=0, ring_slots=16, feeders=3))]
+    small = W.random_instance(rng, 90, 3, 50, max_fanin=2, frac_arbitrary=0.4, frac_bad=0.2)
+    cases.append((small, dict(state_bits=32)))                            # asked for although 16 bits would do
+    for w, shape in cases:
+        with ds.Evaluator.for_workload(w, shape=shape) as ev:
+            info = ev.info()
+            got = [t.cpu().numpy() for t in ev.evaluate(torch.from_numpy(w.placement).cuda(), torch.from_numpy(w.rank).cuda())]
+        assert info["variant"] == 5 and info["state_bits"] == 32, (w.name, shape, info)
+        want = oracle.evaluate_workload(w, 0, threads=8)
+        for name, a, b in zip(("makespan", "bubble", "peak_mem", "flags"), got, want):
+            assert np.array_equal(a, b), (name, w.name, shape, info)
+        if w.name.startswith("cfg"):
+            assert (got[0][got[3] == 0] > 65535).all()
+    # a duration that does not fit an op's 16-bit field: the int32 kernel
+    w = W.random_instance(rng, 50, 4, 20, max_dur=70001, zero_dur=False)
+    w.dur[0] = 70001
+    (z, b, pk, f), info = assert_parity(gpu_lib, w)
+    assert info["variant"] in (1, 2)
 
 
 def test_sixteen_bit_overflow_falls_back(gpu_lib):
@@ -378,12 +420,13 @@ def test_sixteen_bit_overflow_falls_back(gpu_lib):
     pl1, rk1 = W.list_schedules(rp, ci, 1, 100, 99)          # every third candidate runs everything on machine 0
     pl[::3], rk[::3] = pl1, rk1
     w = W.Workload("straddles 16 bits", p, rp, ci, dur, comm, mem, pl, rk)
-    (z, b, pk, f), info = assert_parity(gpu_lib, w)
+    env16 = {"DAGSCHED_RING_STATE_BITS": 16}                 # (left alone the library would take 32-bit end times here)
+    (z, b, pk, f), info = _with_env(env16, lambda: assert_parity(gpu_lib, w))
     assert info["state_bits"] == 16 and info["variant"] == 4        # optimistic ring kernel
     assert (z[f == 0] > 65535).any() and (z[f == 0] < 65535).any()
     # a common factor in every duration and delay is divided out before the 16-bit test
     w2 = W.Workload("scaled by 1000", p, rp, ci, dur * 1000, comm * 1000, mem, pl, rk)
-    (z2, b2, pk2, f2), info2 = assert_parity(gpu_lib, w2)
+    (z2, b2, pk2, f2), info2 = _with_env(env16, lambda: assert_parity(gpu_lib, w2))
     assert info2["time_scale"] == 1000 and (z2[f == 0] == 1000 * z[f == 0].astype(np.int64)).all()
 
 

@@ -124,7 +124,7 @@ def test_cycles_and_range_stops_are_told_apart(gpu_lib):
         rows_pl.append(a)
         rows_rk.append(c)
     w2 = W.Workload("straddles 16 bits, with cycles", p, rp, ci, dur, comm, mem, np.concatenate(rows_pl), np.concatenate(rows_rk))
-    (z2, b2, pk2, f2), info2 = T.assert_parity(gpu_lib, w2)
+    (z2, b2, pk2, f2), info2 = T._with_env({"DAGSCHED_RING_STATE_BITS": 16}, lambda: T.assert_parity(gpu_lib, w2))
     assert info2["variant"] == 4 and (f2 == 1).any() and (z2[f2 == 0] > 65535).any() and (z2[f2 == 0] < 65535).any()
 
 
