@@ -175,7 +175,7 @@ class Evaluator:
         out = best.alloc_outputs(best._n_cand(placement, rank))
         best.evaluate(placement, rank, out)
         best_ms, best_shape = best.time_evaluate(placement, rank, out, reps=reps), None
-        if base["state_bits"] != 16:
+        if base["variant"] not in (3, 4, 5):              # the int32 kernel has no shapes to choose from
             return best, best_shape
         trials = []
         for f in (base["feeders"] - 1, base["feeders"] + 1):
@@ -190,7 +190,7 @@ class Evaluator:
             except DagschedError:
                 continue
             keep = False
-            if ev.info()["state_bits"] == 16:
+            if ev.info()["variant"] in (3, 4, 5):
                 ev.evaluate(placement, rank, out)
                 ms = ev.time_evaluate(placement, rank, out, reps=reps)
                 if verbose:
