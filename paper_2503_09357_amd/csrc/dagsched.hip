@@ -191,7 +191,7 @@ int env_int(const char *name, int dflt) {
 
 // pib_lds: 0 placement bytes in L2, 1 in LDS, 2 in LDS as nibbles (P <= 16)
 // cell_bytes: 2 (16-bit end times) or 4
-LdsLayout ring_layout(int N, int P, int G, int ring, int pib_lds, int cell_bytes) {
+LdsLayout ring_layout(int N, int P, int G, int ring, int pib_lds, int cell_bytes, bool wide) {
   LdsLayout o{};
   uint32_t at = 0;
   o.s_stride = align_up((uint32_t)cell_bytes * (uint32_t)(N + 2), 4);   // N cells + dummy + trash; the arrays start at LDS offset 0
@@ -210,7 +210,10 @@ LdsLayout ring_layout(int N, int P, int G, int ring, int pib_lds, int cell_bytes
   o.o_off = at;   at += kWave * 4u;
   o.o_flag = at;  at += kWave * 4u;
   o.o_abort = at; at += kWave * 4u;
-  o.o_comm = at;  at += align_up((uint32_t)(P + 1) * (uint32_t)next_pow2(P), 4);
+  o.wide = wide ? 1u : 0u;
+  // channel delays: a byte each, rows [source machine + the dummy's][destination]; wide ops: a dword each, 64 rows
+  o.o_comm = at;  at += wide ? (uint32_t)kWave * (uint32_t)next_pow2(P) * 4u
+                             : align_up((uint32_t)(P + 1) * (uint32_t)next_pow2(P), 4);
   o.total = align_up(at, 16);
   return o;
 }
@@ -247,7 +250,11 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
         max_comm = std::max<int64_t>(max_comm, d->comm[a * P + b]);
       }
   if (g == 0) g = 1;                                   // every duration and delay is zero
-  if (max_comm / g > 255) return plan;
+  // delays above 255 or durations above 65534 (in units of the gcd) do not fit the compact op: wide ops then
+  bool wide = max_comm / g > 255;
+  for (int v = 0; v < N; ++v) wide = wide || d->dur[v] / g >= (int64_t)kNotDone16;
+  for (int v = 0; v < N; ++v)
+    if (d->dur[v] / g >= 256 * 65535) return plan;       // ... whose durations are low + 65535 * high, high < 256
   // longest path of B alone in scaled units (no delays): a lower bound on every makespan
   std::vector<int64_t> fin(N, -1);
   {
@@ -336,7 +343,10 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
       const int lo = part == 0 ? 0 : first + (part - 1) * PR, hi = part == 0 ? first : lo + PR;
       for (int k = lo; k < hi && k < deg; ++k) u[k - lo] = (uint32_t)ps[k];
       const bool more = part + 1 < parts;
-      const uint32_t dur = more ? 0u : (uint32_t)std::min<int64_t>(d->dur[v] / g, kNotDone16);
+      // (wide ops: low part below 0xFFFF, which marks a free ring slot, and the high part above it)
+      const uint32_t dur = more ? 0u
+                         : wide ? (uint32_t)((d->dur[v] / g) % 65535) | ((uint32_t)((d->dur[v] / g) / 65535) << 16)
+                                : (uint32_t)std::min<int64_t>(d->dur[v] / g, kNotDone16);
       rec[(size_t)part * plane + v] = make_uint4(u[0] | (u[1] << 16), u[2] | (u[3] << 16),
                                                  dur | (part == 0 ? 0x40000000u : 0u) | (more ? 0x80000000u : 0u),
                                                  (uint32_t)v << 16);
@@ -374,8 +384,8 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
   for (int v = 0; v < N; ++v) max_dur_scaled = std::max<int64_t>(max_dur_scaled, d->dur[v] / g);
   const int force_bits = sh && sh->state_bits ? sh->state_bits : env_int("DAGSCHED_RING_STATE_BITS", 0);
   const bool fits16 = upper + 255 < (int64_t)kNotDone16;
-  plan.cell32 = force_bits == 32 || (force_bits != 16 && !fits16 && 3 * lower >= (int64_t)kNotDone16);
-  if (plan.cell32 && max_dur_scaled >= (int64_t)kNotDone16) return plan;   // a duration does not fit an op: general kernel
+  plan.cell32 = wide || force_bits == 32 || (force_bits != 16 && !fits16 && 3 * lower >= (int64_t)kNotDone16);
+  (void)max_dur_scaled;
   if (!plan.cell32 && lower >= (int64_t)kNotDone16) return plan;   // 16 bits asked for, and no candidate could stay inside them
   const int cell_bytes = plan.cell32 ? 4 : 2;
   const int force_g = sh && sh->cand_per_block ? sh->cand_per_block : env_int("DAGSCHED_RING_G", 0);
@@ -388,11 +398,11 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
     if (force_g && G != force_g) continue;
     for (int pib_lds : {1, 2, 0}) {
       if (force_pib >= 0 && pib_lds != force_pib) continue;
-      if (pib_lds == 2 && P > 16) continue;               // a nibble per node
+      if (pib_lds == 2 && (P > 16 || wide)) continue;     // a nibble per node; not with wide ops (see the kernel: time origin)
       for (int ring : {8, 16, 32, 4}) {
         if (force_ring && ring != force_ring) continue;
         if (pib_lds ? ring > 8 : ring < 8) continue;     // instantiated: LDS with 4 or 8 slots, L2 with 8, 16 or 32
-        LdsLayout o = ring_layout(N, P, G, ring, pib_lds, cell_bytes);
+        LdsLayout o = ring_layout(N, P, G, ring, pib_lds, cell_bytes, wide);
         if ((int)o.total > lds_max) continue;
         if ((uint64_t)G * (o.s_stride >> (plan.cell32 ? 2 : 1)) > 65536u) continue;   // half (quarter) addresses must fit 16 bits
         const int wgs = std::min(5, lds_max / (int)align_up(o.total, 512));   // beyond ~20 wavefronts the CU is issue-bound
@@ -411,7 +421,8 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
                : best_wgs <= 2 ? 3
                : (best_wgs * 4 <= 24 ? 2 : 1);
   auto built = [&](int feeders) {
-    return plan.cell32 ? ring_kernel_pick<2>(plan.ring, feeders, (int)plan.lds.pib_mode, plan.kind) != nullptr
+    return wide        ? ring_kernel_pick<3>(plan.ring, feeders, (int)plan.lds.pib_mode, plan.kind) != nullptr
+         : plan.cell32 ? ring_kernel_pick<2>(plan.ring, feeders, (int)plan.lds.pib_mode, plan.kind) != nullptr
                        : ring_kernel_pick<0>(plan.ring, feeders, (int)plan.lds.pib_mode, plan.kind) != nullptr;
   };
   if (!force_feeders && !built(plan.feeders)) plan.feeders = 2;
@@ -438,14 +449,20 @@ using RingKernel = void (*)(RingParams);
   case 2 * 10000 + PIB * 1000 + RING * 10 + F: return relax_ring_kernel<RING, F, HALF, PIB, 2>;
 template <int HALF>
 RingKernel ring_kernel_pick(int ring, int feeders, int pib_lds, int kind) {
-  if (HALF == 2) {                                       // 32-bit end times: the shapes that large problems get
+  if constexpr (HALF == 2) {                             // 32-bit end times: the shapes that large problems get
     switch (kind * 10000 + pib_lds * 1000 + ring * 10 + feeders) {
       DAGSCHED_RING_CASES(1, 8, 1) DAGSCHED_RING_CASES(1, 8, 2) DAGSCHED_RING_CASES(1, 8, 3)
       DAGSCHED_RING_CASES(2, 8, 2) DAGSCHED_RING_CASES(2, 8, 3)
       DAGSCHED_RING_CASES(0, 8, 2) DAGSCHED_RING_CASES(0, 16, 2) DAGSCHED_RING_CASES(0, 16, 3) DAGSCHED_RING_CASES(0, 16, 4)
       default: return nullptr;
     }
-  }
+  } else if constexpr (HALF == 3) {                      // ... and wide ops (no nibbles)
+    switch (kind * 10000 + pib_lds * 1000 + ring * 10 + feeders) {
+      DAGSCHED_RING_CASES(1, 8, 1) DAGSCHED_RING_CASES(1, 8, 2) DAGSCHED_RING_CASES(1, 8, 3)
+      DAGSCHED_RING_CASES(0, 8, 2) DAGSCHED_RING_CASES(0, 16, 2) DAGSCHED_RING_CASES(0, 16, 3) DAGSCHED_RING_CASES(0, 16, 4)
+      default: return nullptr;
+    }
+  } else {
   switch (kind * 10000 + pib_lds * 1000 + ring * 10 + feeders) {
     DAGSCHED_RING_CASES(1, 4, 1) DAGSCHED_RING_CASES(1, 4, 2)
     DAGSCHED_RING_CASES(1, 8, 1) DAGSCHED_RING_CASES(1, 8, 2) DAGSCHED_RING_CASES(1, 8, 3) DAGSCHED_RING_CASES(1, 8, 4)
@@ -456,12 +473,14 @@ RingKernel ring_kernel_pick(int ring, int feeders, int pib_lds, int kind) {
     DAGSCHED_RING_CASES(0, 32, 1) DAGSCHED_RING_CASES(0, 32, 2) DAGSCHED_RING_CASES(0, 32, 3)
     default: return nullptr;
   }
+  }
 }
 #undef DAGSCHED_RING_CASES
 RingKernel ring_kernel_for(const dagsched *h) {
   // byte addresses when the workgroup's end-time arrays fit 64 KB, half addresses otherwise
   const bool half = (uint64_t)h->ring_G * h->lds.s_stride > 65536u;
   const int pib_lds = (int)h->lds.pib_mode;
+  if (h->lds.wide) return ring_kernel_pick<3>(h->ring_slots, h->ring_feeders, pib_lds, h->ring_kind);
   if (h->lds.cell_bytes == 4) return ring_kernel_pick<2>(h->ring_slots, h->ring_feeders, pib_lds, h->ring_kind);
   return half ? ring_kernel_pick<1>(h->ring_slots, h->ring_feeders, pib_lds, h->ring_kind)
               : ring_kernel_pick<0>(h->ring_slots, h->ring_feeders, pib_lds, h->ring_kind);
@@ -728,7 +747,7 @@ int dagsched_get_info(const dagsched_t *h, dagsched_info_t *info) {
   info->state_bits = ring && h->variant != kVariantRing32 ? 16 : 32;
   info->reserved[0] = ring ? h->ring_slots : 0;
   info->reserved[1] = h->time_scale;
-  info->reserved[2] = ring ? (h->ring_feeders | ((int)h->lds.pib_mode << 8) | ((h->ring_kind == 2 ? 2 : 4) << 16) | (h->ring_kind << 24)) : 0;
+  info->reserved[2] = ring ? (h->ring_feeders | ((int)h->lds.pib_mode << 8) | ((h->ring_kind == 2 ? 2 : 4) << 16) | (h->ring_kind << 24) | ((int)h->lds.wide << 28)) : 0;
   return DAGSCHED_OK;
 }
 

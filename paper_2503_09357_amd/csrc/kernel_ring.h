@@ -24,7 +24,10 @@
 //
 // End times are kept as 16-bit unsigned values (sentinel 0xFFFF = not yet ended), which halves the
 // LDS footprint (template HALF = 0 or 1).  HALF = 2 keeps them in 32 bits (sentinel 0x80000000) for problems whose
-// times cannot stay below 0xFFFF: the same kernel with half the candidates resident, always exact.  When the host cannot prove that every end time stays below 0xFFFF the kernel runs
+// times cannot stay below 0xFFFF: the same kernel with half the candidates resident, always exact.  HALF = 3 does
+// so too and also lifts the limits of the op format on delays (255) and durations (65534): an op then names the
+// machines of its predecessors instead of the delays (six bits each), the relaxer looks the delays up in a 32-bit
+// table in LDS together with the end times, and the duration is low + 65535 * high with eight more bits for high.  When the host cannot prove that every end time stays below 0xFFFF the kernel runs
 // "optimistically": an operation whose end time would reach 0xFFFF is never completed, its candidate
 // stalls exactly like a cyclic one; the two are told apart at the deadlock (does some held op have all its
 // predecessors ended?) and the candidates stopped by the range are handed to the general int32 kernel.
@@ -76,6 +79,7 @@ struct LdsLayout {
   uint32_t o_pi, o_ring, o_scr, o_total, o_peak, o_cnt, o_off, o_flag, o_abort, o_comm, total;
   uint32_t pib_mode;                                  // where the placement bytes are: 0 L2 workspace, 1 LDS, 2 LDS as nibbles
   uint32_t cell_bytes;                                // 2: 16-bit end times, 4: 32-bit
+  uint32_t wide;                                      // 1: wide ops (machines instead of delays, durations below 256 * 65535)
 };
 
 struct RingParams {
@@ -121,8 +125,11 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
   static_assert((RING & (RING - 1)) == 0, "RING must be a power of two");
   static_assert(RING >= FEEDERS, "every feeder needs a slot of its own");
   static_assert(KIND >= 0 && KIND <= 2, "general, single parts, two predecessors");
-  static_assert(HALF >= 0 && HALF <= 2, "byte, half or quarter addresses");
-  constexpr bool kCell32 = HALF == 2;                       // 32-bit end times
+  static_assert(HALF >= 0 && HALF <= 3, "byte, half or quarter addresses; 3: quarter addresses and delays looked up by the relaxer");
+  constexpr bool kCell32 = HALF >= 2;                       // 32-bit end times
+  constexpr bool kWide = HALF == 3;                         // ops name machines, not delays; durations below 256 * 65535
+  constexpr int kAsh = kCell32 ? 2 : HALF;                  // 16-bit address -> LDS byte address
+  static_assert(!(kWide && PIBL == 2), "wide ops need the dummy machine, which a nibble cannot name");
   constexpr uint32_t kNotDone = kCell32 ? kNotDone32 : kNotDone16;
   constexpr int kNodeShift = kCell32 ? 0 : 1 - HALF;        // node -> offset of its cell in the units of the 16-bit addresses
   constexpr int PR = KIND == 2 ? 2 : 4;                     // DAG predecessors per op
@@ -150,13 +157,21 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
   if (tid < kWave) { cntw[tid] = 0; totalw[tid] = 0; flagw[tid] = 0; abortw[tid] = 0; peakw[tid] = 0; }
   for (int i = tid; i < RING * kWave; i += kThreads) {     // every slot free, as if ops -RING .. -1 had been taken
     // (a free slot is copied and looked at like an op: some cell of the workgroup, no delay)
-    ringw[4 * i + 0] = ringw[4 * i + 1] = ((uint32_t)(uintptr_t)ldsb >> HALF) * 0x10001u;
+    ringw[4 * i + 0] = ringw[4 * i + 1] = ((uint32_t)(uintptr_t)ldsb >> kAsh) * 0x10001u;
     ringw[4 * i + 2] = 0;
     ringw[4 * i + 3] = kNotDone16 | ((uint32_t)((i >> 6) - RING) << 16);
   }
-  for (int i = tid; i < (P + 1) * Pseg; i += kThreads) {    // rows of Pseg bytes: [source machine][destination]
-    const int a = i >> p.log_pseg, b = i & (Pseg - 1);
-    commb[i] = (a < P && b < P && a != b) ? (uint8_t)p.comm[a * P + b] : (uint8_t)0;
+  if (kWide) {                                              // 64 rows of Pseg dwords (any six-bit machine id stays inside)
+    uint32_t *commw = (uint32_t *)(lds + o.o_comm);
+    for (int i = tid; i < kWave * Pseg; i += kThreads) {
+      const int a = i >> p.log_pseg, b = i & (Pseg - 1);
+      commw[i] = (a < P && b < P && a != b) ? (uint32_t)p.comm[a * P + b] : 0u;
+    }
+  } else {
+    for (int i = tid; i < (P + 1) * Pseg; i += kThreads) {  // rows of Pseg bytes: [source machine][destination]
+      const int a = i >> p.log_pseg, b = i & (Pseg - 1);
+      commb[i] = (a < P && b < P && a != b) ? (uint8_t)p.comm[a * P + b] : (uint8_t)0;
+    }
   }
   // The candidates of the workgroup are ingested side by side, a team of kThreads / G consecutive threads
   // each, so that small problems do not pay one round of load latency per candidate.
@@ -339,7 +354,7 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
   const bool cand_ok = lane_on && g < ng && flagw[g] == 0;
   const bool has_ops = cand_ok && j < P && cntw[ql] > 0;
   // 16-bit address of this candidate's cell 0: LDS addresses (halved when HALF), so that the relaxer uses them as they are
-  const uint32_t sbase = ((uint32_t)(uintptr_t)ldsb >> HALF) + (uint32_t)g * (o.s_stride >> HALF);
+  const uint32_t sbase = ((uint32_t)(uintptr_t)ldsb >> kAsh) + (uint32_t)g * (o.s_stride >> kAsh);
 
   int32_t acc = 0;
   bool stalled = false;
@@ -352,11 +367,11 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
     lds_vi32_t *const abort_p = (lds_vi32_t *)(ldsb + o.o_abort) + g;
     const uint64_t segmask = ((Pseg == kWave) ? ~0ull : ((1ull << Pseg) - 1ull)) << (g * Pseg);
     auto cell = [&](uint32_t a16) -> uint32_t {
-      return kCell32 ? *(lds_vu32_t *)(uintptr_t)(a16 << 2) : (uint32_t)*(lds_vu16_t *)(uintptr_t)(a16 << HALF);
+      return kCell32 ? *(lds_vu32_t *)(uintptr_t)(a16 << 2) : (uint32_t)*(lds_vu16_t *)(uintptr_t)(a16 << kAsh);
     };
     auto set_cell = [&](uint32_t a16, uint32_t v) {
       if (kCell32) *(lds_vu32_t *)(uintptr_t)(a16 << 2) = v;
-      else *(lds_vu16_t *)(uintptr_t)(a16 << HALF) = (uint16_t)v;
+      else *(lds_vu16_t *)(uintptr_t)(a16 << kAsh) = (uint16_t)v;
     };
     const uint32_t dummy = sbase + ((uint32_t)N << kNodeShift);
     // The loop body is branch-free: every trip stores x somewhere (the trash cell unless an op ran).
@@ -381,6 +396,10 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
     u32x4_t r = *(lds_vu32x4_t *)slot_p;                    // ... as read during the previous trip
     // end times of the current op's predecessors, read at the end of the previous trip
     uint32_t e0 = cell(dummy), e1 = e0, e2 = e0, e3 = e0;
+    // wide ops: the delays of the current op's predecessors, looked up together with the end times
+    lds_vu32_t *const commw = (lds_vu32_t *)(ldsb + o.o_comm) + j;
+    const uint32_t lps = (uint32_t)p.log_pseg;
+    uint32_t d0 = 0, d1 = 0, d2 = 0, d3 = 0;
     // The test for deadlocks costs about as much as a trip and the jump back to the top of the loop a little less, so
     // the loop is unrolled 32 times with the deadlock test once per pass (1.22 -> 1.09 ms on the MoE workload against
     // 8 times); "all through" is looked for every 8 trips with two predecessors per op (the pipelines: short lists),
@@ -390,12 +409,26 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
 #pragma unroll
       for (int sub = 0; sub < 32; ++sub) {
         const bool empty = (r.w & 0xFFFFu) == kNotDone16;   // slot t does not hold op t yet
-        uint32_t x = max(max(x_acc, e0 + (w2 & 0xFFu)), e1 + (PR == 4 ? (w2 >> 8) & 0xFFu : w2 >> 8));
-        if (PR == 4) x = max(max(x, e2 + ((w2 >> 16) & 0xFFu)), e3 + (w2 >> 24));
-        x += w3 & 0xFFFFu;
-        // an op, every predecessor ended and no 16-bit overflow (a free slot's "duration" 0xFFFF lifts x over the
-        // 16-bit sentinel, not over the 32-bit one: there the lane's state is asked)
-        const bool ran = kCell32 ? (x < kNotDone && !idle) : x < kNotDone;
+        uint32_t x;
+        bool ran;
+        if (kWide) {
+          // (the sentinel plus a delay stays below 2^32; whatever ended, plus delay and duration, below 2^31: the
+          // library accepts no problem whose times could pass INT32_MAX)
+          x = max(max(x_acc, e0 + d0), e1 + d1);
+          if (PR == 4) x = max(max(x, e2 + d2), e3 + d3);
+          ran = x < kNotDone && !idle;
+          // duration = low + 65535 * high: the low part, which shares the slot's last dword with the free mark, is
+          // then never 0xFFFF
+          const uint32_t hi = w2 >> 24;
+          x += (w3 & 0xFFFFu) + (hi << 16) - hi;
+        } else {
+          x = max(max(x_acc, e0 + (w2 & 0xFFu)), e1 + (PR == 4 ? (w2 >> 8) & 0xFFu : w2 >> 8));
+          if (PR == 4) x = max(max(x, e2 + ((w2 >> 16) & 0xFFu)), e3 + (w2 >> 24));
+          x += w3 & 0xFFFFu;
+          // an op, every predecessor ended and no 16-bit overflow (a free slot's "duration" 0xFFFF lifts x over the
+          // 16-bit sentinel, not over the 32-bit one: there the lane's state is asked)
+          ran = kCell32 ? (x < kNotDone && !idle) : x < kNotDone;
+        }
         x_acc = ran ? x : x_acc;                            // the machine is busy until x (chain edge, eq. (7))
         set_cell(ran ? (w3 >> 16) : trash, x);
         const bool next = ran || idle;                      // the registers take the content of slot t
@@ -415,6 +448,11 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
         // overlaps with their latency).
         e0 = cell(w0 & 0xFFFFu); e1 = cell(w0 >> 16);
         if (PR == 4) { e2 = cell(w1 & 0xFFFFu); e3 = cell(w1 >> 16); }
+        if (kWide) {
+          const uint32_t m = next ? c2 : w2;                // (w2 itself is updated below)
+          d0 = commw[(m & 63u) << lps]; d1 = commw[((m >> 6) & 63u) << lps];
+          if (PR == 4) { d2 = commw[((m >> 12) & 63u) << lps]; d3 = commw[((m >> 18) & 63u) << lps]; }
+        }
         // One trip without progress while every unfinished machine holds an op is already a deadlock
         // (end times only change when some op runs), so progress is sampled once per window.
         if (sub == 31) prog_acc = __ballot(ran || take);    // an op taken now has not been tested yet
@@ -539,8 +577,11 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
           if (PR == 4) { e1.q2 = pib(e1.rec.y & 0xFFFFu); e1.q3 = pib(e1.rec.y >> 16); }
         }
         // (A) channel delays of e2
-        const uint32_t d0 = commr[e2.q0 << lps], d1 = commr[e2.q1 << lps];
-        const uint32_t d2 = PR == 4 ? commr[e2.q2 << lps] : 0u, d3 = PR == 4 ? commr[e2.q3 << lps] : 0u;
+        // (wide ops carry the machines themselves; the dummy node's machine P becomes this lane's own: no delay)
+        const uint32_t d0 = kWide ? (e2.q0 == (uint32_t)P ? (uint32_t)j : e2.q0) : commr[e2.q0 << lps];
+        const uint32_t d1 = kWide ? (e2.q1 == (uint32_t)P ? (uint32_t)j : e2.q1) : commr[e2.q1 << lps];
+        const uint32_t d2 = PR != 4 ? 0u : kWide ? (e2.q2 == (uint32_t)P ? (uint32_t)j : e2.q2) : commr[e2.q2 << lps];
+        const uint32_t d3 = PR != 4 ? 0u : kWide ? (e2.q3 == (uint32_t)P ? (uint32_t)j : e2.q3) : commr[e2.q3 << lps];
         // (1) move the cursor past the part admitted in the previous trip and the other feeders' parts
         // (2) entries of the next nodes (consumed one trip later at the earliest).  Lanes whose cursor stayed
         // keep theirs and all read the same entry instead, which costs the vector cache one line, not one per lane.
@@ -591,7 +632,9 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
           // node ids below 32768 whenever they are shifted, so shifting both halves at once cannot carry over;
           // the whole slot first with its free mark unchanged, then the last dword
           const u32x4_t val = {(e2.rec.x << kNodeShift) + base2, (e2.rec.y << kNodeShift) + base2,
-                               d0 | (d1 << 8) | (d2 << 16) | (d3 << 24), ((wseq - (uint32_t)RING) << 16) | kNotDone16};
+                               kWide ? d0 | (d1 << 6) | (d2 << 12) | (d3 << 18) | (((e2.rec.z >> 16) & 0xFFu) << 24)
+                                     : d0 | (d1 << 8) | (d2 << 16) | (d3 << 24),
+                               ((wseq - (uint32_t)RING) << 16) | kNotDone16};
           *(lds_vu32x4_t *)sp = val;
           *(lds_vu32_t *)(sp + 12) = dur | (dst << 16);
           wseq += kFeeders;

@@ -209,7 +209,8 @@ class Evaluator:
         d["ring_slots"], d["time_scale"] = i.reserved[0], i.reserved[1]
         d["feeders"], d["placement_bytes_in_lds"] = i.reserved[2] & 0xFF, (i.reserved[2] >> 8) & 3
         d["preds_per_op"] = (i.reserved[2] >> 16) & 0xFF
-        d["kernel_kind"] = (i.reserved[2] >> 24) & 0xFF   # 0 general, 1 single-part operations, 2 at most two predecessors
+        d["kernel_kind"] = (i.reserved[2] >> 24) & 0xF    # 0 general, 1 single-part operations, 2 at most two predecessors
+        d["wide_ops"] = (i.reserved[2] >> 28) & 1          # ops name machines (delays above 255 or durations above 65534)
         return d
 
     def _n_cand(self, placement, rank) -> int:

@@ -337,8 +337,8 @@ def test_randomized_problems_and_launch_shapes(gpu_lib):
         n = int(rng.integers(1, 400)) if rng.random() < 0.9 else int(rng.integers(400, 3000))
         p, fanin, c = int(rng.integers(1, 65)), int(rng.integers(1, 11)), int(rng.integers(1, 120))
         layout = int(rng.integers(0, 2))
-        w = W.random_instance(rng, n, p, c, max_fanin=fanin, max_dur=int(rng.integers(1, 400)),
-                              max_comm=int(rng.integers(0, 200)), frac_arbitrary=0.3, frac_bad=0.15,
+        w = W.random_instance(rng, n, p, c, max_fanin=fanin, max_dur=int(rng.integers(1, 400)) if rng.random() < 0.8 else 200000,
+                              max_comm=int(rng.integers(0, 200)) if rng.random() < 0.8 else 3000, frac_arbitrary=0.3, frac_bad=0.15,
                               dup_prob=0.05 * int(rng.integers(0, 2)))
         if rng.random() < 0.5:
             w.weight = rng.integers(0, 50, n).astype(np.int64)
@@ -400,9 +400,30 @@ def test_thirty_two_bit_end_times(gpu_lib):
             assert np.array_equal(a, b), (name, w.name, shape, info)
         if w.name.startswith("cfg"):
             assert (got[0][got[3] == 0] > 65535).all()
-    # a duration that does not fit an op's 16-bit field: the int32 kernel
+    # delays above 255 or durations above 65534 (after the common factor is divided out): wide ops, in which the
+    # relaxer looks the delays up and durations reach 256 * 65535 - 1
+    wide = []
+    for cfg, c in ((2, 300), (3, 60), (4, 40)):
+        w = W.gen_config(cfg, n_cand=c)
+        w.dur = (w.dur.astype(np.int64) * 997 + rng.integers(0, 900, w.n_nodes)).astype(np.int32)
+        w.comm = (w.comm.astype(np.int64) * 431 + 3).astype(np.int32)
+        wide.append((w, None))
+    r1 = W.random_instance(rng, 333, 7, 64, max_fanin=6, max_dur=900000, max_comm=50000, frac_arbitrary=0.3, frac_bad=0.2)
+    r2 = W.random_instance(rng, 100, 64, 64, max_fanin=2, max_dur=70000, max_comm=300, frac_arbitrary=0.3, frac_bad=0.2)
+    r3 = W.random_instance(rng, 60, 5, 30, max_dur=9, max_comm=300)          # long delays alone
+    r1.dur[:6] = [65535, 131071, 65534, 131070, 196605, 16776959]        # around the multiples of 65535; the largest one
+    wide += [(r1, None), (r1, dict(placement_mode=0, ring_slots=16, feeders=3)), (r2, None), (r3, None)]
+    for w, shape in wide:
+        with ds.Evaluator.for_workload(w, shape=shape) as ev:
+            info = ev.info()
+            got = [t.cpu().numpy() for t in ev.evaluate(torch.from_numpy(w.placement).cuda(), torch.from_numpy(w.rank).cuda())]
+        assert info["variant"] == 5 and info["wide_ops"] == 1, (w.name, shape, info)
+        want = oracle.evaluate_workload(w, 0, threads=8)
+        for name, a, b in zip(("makespan", "bubble", "peak_mem", "flags"), got, want):
+            assert np.array_equal(a, b), (name, w.name, shape, info)
+    # a duration beyond 256 * 65535 - 1: the int32 kernel
     w = W.random_instance(rng, 50, 4, 20, max_dur=70001, zero_dur=False)
-    w.dur[0] = 70001
+    w.dur[0] = 256 * 65535
     (z, b, pk, f), info = assert_parity(gpu_lib, w)
     assert info["variant"] in (1, 2)
 
@@ -430,11 +451,13 @@ def test_sixteen_bit_overflow_falls_back(gpu_lib):
     assert info2["time_scale"] == 1000 and (z2[f == 0] == 1000 * z[f == 0].astype(np.int64)).all()
 
 
-def test_large_delays_use_the_general_kernel(gpu_lib):
+def test_large_delays(gpu_lib):
     rng = np.random.default_rng(5)
     w = W.random_instance(rng, 120, 5, 30, max_comm=4000, max_dur=977)
     (z, b, pk, f), info = assert_parity(gpu_lib, w)
-    assert info["state_bits"] in (16, 32)
+    assert info["variant"] == 5 and info["wide_ops"] == 1
+    (z, b, pk, f), info = _with_env({"DAGSCHED_FORCE_GENERAL": 1}, lambda: assert_parity(gpu_lib, w))
+    assert info["variant"] in (1, 2)
 
 
 def test_many_op_parts_use_the_general_kernel(gpu_lib):
