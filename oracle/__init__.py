@@ -18,7 +18,8 @@ _SRC = os.path.join(_DIR, "dagsched_oracle.c")
 _LIB = os.path.join(_DIR, "libdagsched_oracle.so")
 
 OK, EINVAL, ECYCLE, EOVERFLOW, ENOMEM = 0, -1, -2, -3, -4
-FLAG_CYCLIC, FLAG_BAD_PLACEMENT, FLAG_BAD_RANK = 1, 2, 4
+FLAG_CYCLIC, FLAG_BAD_PLACEMENT, FLAG_BAD_RANK, FLAG_OVER_MEMORY, FLAG_NO_CHANNEL = 1, 2, 4, 16, 32
+NO_CHANNEL = -1      # off-diagonal comm entry of a machine pair without a channel (eq. (10))
 CAND_MAJOR, CAND_MINOR = 0, 1
 
 _lib = None

@@ -27,8 +27,14 @@
  *     peak_mem[j] = max(0, max_k sum_{t<k} A_{list_j[t]})               eqs. (17)-(19): m+ = m- + A,
  *                   the level after an operation is the level before the next one on that machine;
  *                   the level starts at 0 and 0 takes part in the maximum
- *     flags       = 2 BAD_PLACEMENT | 4 BAD_RANK | 1 CYCLIC | 16 OVER_MEMORY | 0 (exactly one value,
- *                   tested in that order); flagged candidates return -1 in every other output.
+ *     flags       = 2 BAD_PLACEMENT | 4 BAD_RANK | 32 NO_CHANNEL | 1 CYCLIC | 16 OVER_MEMORY | 0 (exactly
+ *                   one value, tested in that order); flagged candidates return -1 in every other output.
+ *
+ * Missing channels (eqs. (9)-(10)): an off-diagonal comm entry of -1 says that the cluster graph has
+ * no channel from the row's machine to the column's.  z = x * x of eq. (9) is then forced to 0 by
+ * eq. (10): a candidate that places the two ends of some edge of B on such a pair (in that
+ * direction) violates it and is flagged NO_CHANNEL.  Machines talk to themselves without a channel
+ * (the diagonal is never read).
  *
  * Optional static memory (eq. (16)): with weights W_i >= 0 the level of machine j starts at
  * base_j = sum of W_i over the operations placed on j (the least m- that eq. (16) allows for the
@@ -47,7 +53,8 @@
  * alternating path, critical-path and load lower bounds, an independent unit-time-step simulator,
  * brute-force enumeration of all linear extensions on tiny DAGs, the constraint system itself
  * (eqs. (2),(3),(7),(11)-(13),(17)-(19)) with tightness, scaling / relabelling / time-reversal
- * invariances, constructed cycles and malformed candidates.
+ * invariances, constructed cycles and malformed candidates; missing channels against the product
+ * form of eqs. (9)-(10) over one-hot allocations, and against pipelines on a chain-shaped cluster.
  * Parity unpinned: the DualPipe bubble values and the random-graph speed-up of Sec. V (the
  * instances and the schedules found there are not published).
  */
@@ -56,13 +63,14 @@
 #include <string.h>
 
 enum { OR_OK = 0, OR_EINVAL = -1, OR_ECYCLE = -2, OR_EOVERFLOW = -3, OR_ENOMEM = -4 };
-enum { FLAG_CYCLIC = 1, FLAG_BAD_PLACEMENT = 2, FLAG_BAD_RANK = 4, FLAG_OVER_MEMORY = 16 };
+enum { FLAG_CYCLIC = 1, FLAG_BAD_PLACEMENT = 2, FLAG_BAD_RANK = 4, FLAG_OVER_MEMORY = 16, FLAG_NO_CHANNEL = 32 };
+enum { NO_CHANNEL = -1 };   /* comm entry of a machine pair outside C */
 enum { LAYOUT_CAND_MAJOR = 0, LAYOUT_CAND_MINOR = 1 };
 
 /*
  * Checks on the problem itself (not on a candidate):
  *   EINVAL     sizes out of range, CSR not monotone, index out of range, self-loop, negative
- *              duration, negative off-diagonal comm entry
+ *              duration, off-diagonal comm entry below -1 (-1 itself: no channel, eq. (10))
  *   ECYCLE     the operator graph is not a DAG (Sec. III requires one)
  *   EOVERFLOW  sum(dur) + (N-1) * max off-diagonal comm > INT32_MAX: a path visits every node at
  *              most once and pays at most one delay per edge, so below this bound int32 times
@@ -87,7 +95,7 @@ int dagsched_oracle_check_problem(int32_t N, int32_t E, int32_t P, const int32_t
   for (int32_t a = 0; a < P; ++a)
     for (int32_t b = 0; b < P; ++b) {
       if (a == b) continue;
-      if (comm[a * P + b] < 0) return OR_EINVAL;
+      if (comm[a * P + b] < NO_CHANNEL) return OR_EINVAL;
       if (comm[a * P + b] > max_comm) max_comm = comm[a * P + b];
     }
   /* the DAG must be acyclic: Kahn on B alone */
@@ -171,7 +179,13 @@ static int32_t evaluate_one(int32_t N, int32_t P, const int32_t *row_ptr, const 
     if (w->list[w->off[j] + r] != -1) return FLAG_BAD_RANK;
     w->list[w->off[j] + r] = v;
   }
-  /* 3. Kahn on the combined graph: DAG edges B plus chain edges list_j[k] -> list_j[k+1] */
+  /* 3. every message has a channel: z_{u,x,ju,jx} = x_{u,ju} * x_{x,jx} must be 0 outside C (eqs. (9)-(10)) */
+  for (int32_t u = 0; u < N; ++u)
+    for (int32_t k = row_ptr[u]; k < row_ptr[u + 1]; ++k) {
+      int32_t ju = pl[u * stride], jx = pl[col_idx[k] * stride];
+      if (ju != jx && comm[ju * P + jx] == NO_CHANNEL) return FLAG_NO_CHANNEL;
+    }
+  /* 4. Kahn on the combined graph: DAG edges B plus chain edges list_j[k] -> list_j[k+1] */
   for (int32_t v = 0; v < N; ++v) {
     w->indeg[v] = w->indeg_b[v] + (rk[v * stride] > 0 ? 1 : 0);
     w->ready[v] = 0;                                   /* s_v >= 0 */
@@ -200,7 +214,7 @@ static int32_t evaluate_one(int32_t N, int32_t P, const int32_t *row_ptr, const 
     }
   }
   if (tail < N) return FLAG_CYCLIC;
-  /* 4. reductions */
+  /* 5. reductions */
   int64_t z = 0, sum_dur = 0;
   for (int32_t v = 0; v < N; ++v) {
     if (w->end[v] > z) z = w->end[v];                  /* eq. (2) */

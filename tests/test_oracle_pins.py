@@ -411,7 +411,7 @@ def test_problem_checks():
 
     assert code() == oracle.OK
     assert code(dur=[1, -2, 3]) == oracle.EINVAL
-    assert code(comm=[[0, -1], [1, 0]]) == oracle.EINVAL
+    assert code(comm=[[0, -2], [1, 0]]) == oracle.EINVAL                # (-1 stands for a missing channel)
     assert code(comm=[[-5, 1], [1, -9]]) == oracle.OK                   # the diagonal is never read
     assert code(P=65, comm=np.zeros((65, 65))) == oracle.EINVAL
     rp2, ci2 = W.csr_from_edges(3, [0, 1, 2], [1, 2, 0])
