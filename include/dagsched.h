@@ -39,8 +39,8 @@ typedef struct dagsched dagsched_t; /* opaque, owned by the library */
 /* Return codes of create / validate / evaluate. */
 enum {
   DAGSCHED_OK = 0,
-  DAGSCHED_EINVAL = -1,    /* null pointer, size out of range, malformed CSR, negative dur / comm / weight, bad layout,
-                              n_cand > max_candidates */
+  DAGSCHED_EINVAL = -1,    /* null pointer, size out of range, malformed CSR, negative dur / weight, comm entry
+                              below -1, bad layout, n_cand > max_candidates */
   DAGSCHED_ECYCLE = -2,    /* the operator graph itself is cyclic (Sec. III requires a DAG) */
   DAGSCHED_EOVERFLOW = -3, /* sum(dur) + (N-1) * max off-diagonal comm > INT32_MAX: int32 times would not be exact */
   DAGSCHED_ENOMEM = -4,    /* host or device allocation failed */
@@ -52,6 +52,8 @@ enum {
   DAGSCHED_FLAG_OK = 0,
   DAGSCHED_FLAG_BAD_PLACEMENT = 2, /* some placement[i] outside [0, P)                    (eq. (6))      */
   DAGSCHED_FLAG_BAD_RANK = 4,      /* some machine's ranks are not exactly {0..n_j-1}     (eqs. (7)-(8)) */
+  DAGSCHED_FLAG_NO_CHANNEL = 32,   /* some edge (u, v) of B has its ends on machines a != b whose comm[a*P + b] is
+                                      DAGSCHED_NO_CHANNEL: z = x * x of eq. (9) must be 0 there (eq. (10))      */
   DAGSCHED_FLAG_CYCLIC = 1,        /* DAG edges + chain edges contain a directed cycle: eqs. (5), (7), (8)
                                       cannot hold together.  Structural test, zero-duration cycles included. */
   DAGSCHED_FLAG_INTERNAL = 8,      /* a kernel's bounded wait expired; never expected, the candidate's other
@@ -66,6 +68,9 @@ enum {
   DAGSCHED_CAND_MAJOR = 0, /* placement[c*N + i], peak_mem[c*P + j] */
   DAGSCHED_CAND_MINOR = 1  /* placement[i*C + c], peak_mem[j*C + c]  (C = n_cand of the call) */
 };
+
+/* comm entry of an ordered machine pair that is not in the channel set C (eq. (10)). */
+#define DAGSCHED_NO_CHANNEL (-1)
 
 /* Limits of this implementation. */
 #define DAGSCHED_MAX_DEVICES 64
@@ -100,8 +105,8 @@ typedef struct {
   const int32_t *row_ptr;   /* [N+1] successor CSR of B: edges u -> col_idx[k], k in [row_ptr[u], row_ptr[u+1]) */
   const int32_t *col_idx;   /* [E]   duplicates allowed, self-loops rejected                                 */
   const int32_t *dur;       /* [N]   D^o_i >= 0                                                              */
-  const int32_t *comm;      /* [P*P] comm[src*P + dst] >= 0 off the diagonal; may be asymmetric; the diagonal
-                                     is never read                                                           */
+  const int32_t *comm;      /* [P*P] comm[src*P + dst] >= 0 off the diagonal, or DAGSCHED_NO_CHANNEL for a pair
+                                     without a channel; may be asymmetric; the diagonal is never read        */
   const int64_t *mem_delta; /* [N]   A_i, any sign                                                           */
   int32_t max_candidates;   /* capacity of the per-handle device workspace, >= 1                             */
   int32_t layout;           /* DAGSCHED_CAND_MAJOR or DAGSCHED_CAND_MINOR                                     */
@@ -136,7 +141,7 @@ int dagsched_create(const dagsched_desc_t *desc, dagsched_t **out);
  *   flags           : int32 [n_cand]
  * Asynchronous: enqueues kernels only, performs no host synchronisation and no allocation.
  * Per-candidate problems are reported through flags, never through the return code.
- * Implements, per candidate, validation of x and y (eqs. (6)-(8)), the chain edges u, the
+ * Implements, per candidate, validation of x and y (eqs. (6)-(8)), of the channels used (eqs. (9)-(10)), the chain edges u, the
  * max-plus longest path (eqs. (2), (3), (5), (7), (11)-(13)), and the memory levels (eqs. (16)-(19)).
  */
 int dagsched_evaluate(dagsched_t *h, int32_t n_cand, const int32_t *placement, const int32_t *rank,

@@ -50,6 +50,8 @@ def with_channels(w: Workload, max_machines: int = 64) -> Tuple[Workload, np.nda
             e_dst.append(v)
     rp, ci = csr_from_edges(n + ec, e_src, e_dst)
     comm = np.asarray(w.comm).reshape(p, p)
+    if any(comm[a, b] < 0 for a, b in pairs):
+        raise ValueError("the shared placement sends a message over a machine pair without a channel (eq. (10))")
     dur = np.concatenate([w.dur, np.array([comm[pl0[src[k]], pl0[dst[k]]] for k in cross], dtype=np.int32)]).astype(np.int32)
     mem = np.concatenate([w.mem_delta, np.zeros(ec, dtype=np.int64)])
     t_machine = np.array([chan[(int(pl0[src[k]]), int(pl0[dst[k]]))] for k in cross], dtype=np.int32)

@@ -83,6 +83,8 @@ struct dagsched {
   LdsLayout lds{};
   uint4 *d_rec = nullptr;
   int32_t *d_comm_scaled = nullptr;
+  uint64_t *d_no_channel = nullptr;   // [P] bit b of word a: no channel a -> b (eq. (10)); null when every pair has one
+  uint32_t *d_edges = nullptr;        // [E] u | v << 16 for the pass that flags candidates using such a pair
   uint16_t *ws_list16 = nullptr;
   int32_t *d_fb_count = nullptr, *d_fb_list = nullptr;
   uint32_t spin_cap = 0;
@@ -132,7 +134,7 @@ int validate_desc(const dagsched_desc_t *d, std::vector<int32_t> *pred_ptr, std:
   for (int32_t a = 0; a < P; ++a)
     for (int32_t b = 0; b < P; ++b)
       if (a != b) {
-        if (d->comm[a * P + b] < 0) return DAGSCHED_EINVAL;
+        if (d->comm[a * P + b] < DAGSCHED_NO_CHANNEL) return DAGSCHED_EINVAL;
         max_comm = std::max<int64_t>(max_comm, d->comm[a * P + b]);
       }
   // predecessor CSR (edge multiplicity kept) and acyclicity of B by peeling sources
@@ -178,7 +180,7 @@ void free_handle(dagsched *h) {
   if (!h) return;
   void *bufs[] = {h->d_pred_ptr, h->d_pred_idx, h->d_dur, h->d_comm, h->d_mem, h->d_weight, h->d_limit, h->ws_list, h->ws_end, h->d_rec,
                   h->d_comm_scaled, h->d_nparts, h->ws_list16, h->ws_pib, h->ws_cnt, h->ws_sched_list, h->ws_sched_end,
-                  h->ws_sched_out, h->d_fb_count, h->d_fb_list, h->ws_tp, h->ws_tr};
+                  h->ws_sched_out, h->d_fb_count, h->d_fb_list, h->ws_tp, h->ws_tr, h->d_no_channel, h->d_edges};
   for (void *b : bufs)
     if (b) (void)hipFree(b);
   delete h;
@@ -486,6 +488,10 @@ RingKernel ring_kernel_for(const dagsched *h) {
               : ring_kernel_pick<0>(h->ring_slots, h->ring_feeders, pib_lds, h->ring_kind);
 }
 
+size_t channel_flag_lds(int32_t n_nodes) {               // mask words + one byte per node
+  return (size_t)DAGSCHED_MAX_DEVICES * sizeof(uint64_t) + (size_t)n_nodes;
+}
+
 OutPtrs make_out(const dagsched *h, int32_t n_cand, int32_t *makespan, int64_t *bubble, int64_t *peak_mem,
                  int32_t *flags) {
   OutPtrs o;
@@ -549,6 +555,11 @@ int launch_evaluate(dagsched *h, int32_t n_cand, const int32_t *placement, const
                        stream, p);
     if (optimistic) launch_general(h, n_cand, pl, rk, out, h->d_fb_list, h->d_fb_count, stream);
   }
+  // the evaluation ran with delay 0 on pairs without a channel; candidates that use one are flagged now
+  if (h->d_no_channel)
+    // few candidates: larger workgroups, or the chip's wavefront slots stay empty
+    hipLaunchKernelGGL(channel_flag_kernel, dim3((unsigned)n_cand), dim3(n_cand < 2048 ? 1024 : 256), channel_flag_lds(N), stream, N, h->E,
+                       h->P, h->d_edges, h->d_no_channel, pl, out);
   if (!hip_ok(hipGetLastError(), "kernel launch")) return DAGSCHED_EHIP;
   return DAGSCHED_OK;
 }
@@ -566,12 +577,32 @@ extern "C" {
 
 int dagsched_validate(const dagsched_desc_t *desc) { return validate_desc(desc, nullptr, nullptr, nullptr); }
 
-int dagsched_create(const dagsched_desc_t *desc, dagsched_t **out) {
+int dagsched_create(const dagsched_desc_t *caller_desc, dagsched_t **out) {
   if (!out) return DAGSCHED_EINVAL;
   std::vector<int32_t> pred_ptr, pred_idx;
   int64_t sum_dur = 0;
-  int rc = validate_desc(desc, &pred_ptr, &pred_idx, &sum_dur);
+  int rc = validate_desc(caller_desc, &pred_ptr, &pred_idx, &sum_dur);
   if (rc != DAGSCHED_OK) return rc;
+  // pairs without a channel (eq. (10)) become a bit matrix for the flag pass; the evaluation itself sees delay 0
+  dagsched_desc_t cleaned = *caller_desc;
+  const dagsched_desc_t *desc = &cleaned;
+  std::vector<int32_t> comm_present((size_t)cleaned.n_devices * cleaned.n_devices);
+  std::vector<uint64_t> no_channel((size_t)cleaned.n_devices, 0);
+  bool any_missing = false;
+  for (int a = 0; a < cleaned.n_devices; ++a)
+    for (int b = 0; b < cleaned.n_devices; ++b) {
+      const int32_t d = caller_desc->comm[a * cleaned.n_devices + b];
+      const bool missing = a != b && d == DAGSCHED_NO_CHANNEL;
+      if (missing) no_channel[a] |= (uint64_t)1 << b;
+      any_missing = any_missing || missing;
+      comm_present[(size_t)a * cleaned.n_devices + b] = (a == b || missing) ? 0 : d;
+    }
+  cleaned.comm = comm_present.data();
+  std::vector<uint32_t> edges;                         // node ids fit 16 bits (DAGSCHED_MAX_NODES)
+  if (any_missing)
+    for (int32_t u = 0; u < cleaned.n_nodes; ++u)
+      for (int32_t k = cleaned.row_ptr[u]; k < cleaned.row_ptr[u + 1]; ++k)
+        edges.push_back((uint32_t)u | ((uint32_t)cleaned.col_idx[k] << 16));
   int n_dev = 0;
   if (!hip_ok(hipGetDeviceCount(&n_dev), "hipGetDeviceCount")) return DAGSCHED_EHIP;
   if (desc->hip_device < 0 || desc->hip_device >= n_dev) return DAGSCHED_EINVAL;
@@ -604,6 +635,12 @@ int dagsched_create(const dagsched_desc_t *desc, dagsched_t **out) {
        upload(&h->d_pred_idx, pred_idx.data(), (size_t)h->E) &&
        upload(&h->d_dur, desc->dur, (size_t)h->N) &&
        upload(&h->d_comm, desc->comm, (size_t)h->P * h->P) &&
+       (!any_missing || (upload(&h->d_no_channel, no_channel.data(), no_channel.size()) &&
+                         upload(&h->d_edges, edges.data(), edges.size()) &&
+                         (channel_flag_lds(h->N) <= 48 * 1024 ||
+                          hip_ok(hipFuncSetAttribute((const void *)channel_flag_kernel,
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                     (int)channel_flag_lds(h->N)), "hipFuncSetAttribute")))) &&
        dev_alloc(&h->ws_cnt, (size_t)DAGSCHED_MAX_DEVICES) &&
        dev_alloc(&h->ws_sched_list, (size_t)h->row_stride) && dev_alloc(&h->ws_sched_end, (size_t)h->row_stride) &&
        dev_alloc(&h->ws_sched_out, (size_t)(32 + 8 * DAGSCHED_MAX_DEVICES));
@@ -730,6 +767,9 @@ int dagsched_schedule(dagsched_t *h, const int32_t *placement, const int32_t *ra
   p.out.makespan = (int32_t *)o; p.out.flags = (int32_t *)(o + 4); p.out.bubble = (int64_t *)(o + 8);
   p.out.peak_mem = (int64_t *)(o + 16); p.out.peak_stride_c = h->P; p.out.peak_stride_j = 1;
   hipLaunchKernelGGL(relax_general_kernel<false>, dim3(1), dim3(kWave), 0, stream, p);
+  if (h->d_no_channel)
+    hipLaunchKernelGGL(channel_flag_kernel, dim3(1), dim3(1024), channel_flag_lds(h->N), stream, h->N, h->E, h->P,
+                       h->d_edges, h->d_no_channel, placement, p.out);
   hipLaunchKernelGGL(schedule_out_kernel, dim3((unsigned)std::min(256, (h->N + 255) / 256)), dim3(256), 0, stream, h->N,
                      h->d_dur, h->ws_sched_end, (const int32_t *)(o + 4), start, end, flag);
   if (!hip_ok(hipGetLastError(), "kernel launch")) return DAGSCHED_EHIP;

@@ -14,7 +14,8 @@ import numpy as np
 from . import _build
 
 OK, EINVAL, ECYCLE, EOVERFLOW, ENOMEM, EHIP = 0, -1, -2, -3, -4, -5
-FLAG_OK, FLAG_CYCLIC, FLAG_BAD_PLACEMENT, FLAG_BAD_RANK, FLAG_INTERNAL, FLAG_OVER_MEMORY = 0, 1, 2, 4, 8, 16
+FLAG_OK, FLAG_CYCLIC, FLAG_BAD_PLACEMENT, FLAG_BAD_RANK, FLAG_INTERNAL, FLAG_OVER_MEMORY, FLAG_NO_CHANNEL = 0, 1, 2, 4, 8, 16, 32
+NO_CHANNEL = -1      # off-diagonal comm entry of a machine pair without a channel (eq. (10))
 CAND_MAJOR, CAND_MINOR = 0, 1
 MAX_DEVICES, MAX_NODES = 64, 65535
 

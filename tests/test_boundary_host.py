@@ -44,7 +44,9 @@ def test_validate_codes_match_oracle_problem_check():
     cases = [
         ({}, dagsched.OK),
         ({"dur": [1, -2, 3]}, dagsched.EINVAL),
-        ({"comm": [[0, -1], [1, 0]]}, dagsched.EINVAL),
+        ({"comm": [[0, -2], [1, 0]]}, dagsched.EINVAL),
+        ({"comm": [[0, -1], [-1, 0]]}, dagsched.OK),                    # -1: the pair has no channel (eq. (10))
+        ({"dur": [big, 0, 0], "comm": [[0, -1], [-1, 0]]}, dagsched.OK),
         ({"comm": [[-5, 1], [1, -9]]}, dagsched.OK),
         ({"row_ptr": rp_cyc, "col_idx": ci_cyc}, dagsched.ECYCLE),
         ({"row_ptr": np.array([0, 1, 2, 2]), "col_idx": np.array([0, 2])}, dagsched.EINVAL),

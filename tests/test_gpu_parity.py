@@ -506,6 +506,55 @@ def test_static_memory_and_limits(gpu_lib, force_general):
     assert {0, 16} <= seen
 
 
+# --------------------------------------------------------------------------- missing channels (eqs. (9)-(10))
+
+@pytest.mark.parametrize("env", [{}, {"DAGSCHED_FORCE_GENERAL": 1}, {"DAGSCHED_RING_STATE_BITS": 32}])
+def test_missing_channels(gpu_lib, env):
+    """comm entry -1: the pair has no channel; a candidate with a message over it is NO_CHANNEL, after the flags of
+    malformed candidates and before every other one.  Random clusters on random instances (a third of the pairs
+    missing down to a few), a chain-shaped cluster under the pipelines, a few missing pairs under config 4."""
+    import dataclasses
+    rng = np.random.default_rng(910)
+    seen = {}
+
+    def run(w, layouts=(0,)):
+        for layout in layouts:
+            (z, b, pk, f), _ = _with_env(env, lambda: assert_parity(gpu_lib, w, layout=layout))
+            for x in f:
+                seen[int(x)] = seen.get(int(x), 0) + 1
+        return f
+
+    for trial in range(6):
+        p = int(rng.integers(2, 9))
+        w = W.random_instance(rng, int(rng.integers(20, 300)), p, 120, max_fanin=4, frac_bad=0.2)
+        missing = (rng.random((p, p)) < (0.35, 0.1, 0.03)[trial % 3]) & ~np.eye(p, dtype=bool)
+        comm = np.where(missing, oracle.NO_CHANNEL, w.comm).astype(np.int32)
+        np.fill_diagonal(comm, oracle.NO_CHANNEL if trial % 2 else 0)
+        limit = np.full(p, 3, dtype=np.int64) if trial % 3 == 0 else None          # OVER_MEMORY comes after NO_CHANNEL
+        run(dataclasses.replace(w, name=w.name + " missing channels", comm=comm, mem_limit=limit), layouts=(0, 1))
+    for cfg, n in ((1, 300), (2, 200)):                                             # pipelines: stage s on machine s
+        w = W.gen_config(cfg, n_cand=n)
+        p = w.n_devices
+        near = np.abs(np.arange(p)[:, None] - np.arange(p)[None, :]) == 1
+        chain = np.where(near, w.comm, oracle.NO_CHANNEL).astype(np.int32)
+        f_full = oracle.evaluate_workload(w)[3]
+        assert (run(dataclasses.replace(w, name=w.name + " chain cluster", comm=chain)) == f_full).all()
+        cut = chain.copy(); cut[2, 1] = oracle.NO_CHANNEL
+        assert (run(dataclasses.replace(w, name=w.name + " cut chain", comm=cut)) == ds_flag_no_channel()).all()
+    w = W.gen_config(4, n_cand=24)                                                  # a placement per candidate
+    comm = w.comm.copy()
+    comm[3, 17] = comm[30, 2] = oracle.NO_CHANNEL
+    f = run(dataclasses.replace(w, name=w.name + " two pairs missing", comm=comm))
+    assert 0 < (f == ds_flag_no_channel()).sum()
+    assert seen.get(0, 0) > 100 and seen.get(32, 0) > 100 and seen.get(1, 0) > 20 and seen.get(2, 0) and seen.get(4, 0), seen
+
+
+def ds_flag_no_channel():
+    from paper_2503_09357_amd import dagsched
+    assert dagsched.FLAG_NO_CHANNEL == oracle.FLAG_NO_CHANNEL and dagsched.NO_CHANNEL == oracle.NO_CHANNEL
+    return dagsched.FLAG_NO_CHANNEL
+
+
 def test_memory_limit_on_an_empty_machine(gpu_lib):
     """A machine that runs nothing has level 0; a negative limit on it still flags the candidate."""
     import dataclasses

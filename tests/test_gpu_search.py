@@ -54,12 +54,21 @@ def test_select_matches_the_oracle(gpu_lib):
             assert tuple(best.cpu().tolist()) == SO.select(z, f), (C, p_ok)
 
 
+def _without_some_channels(w):
+    """Three machine pairs lose their channel (eq. (10)): comm entry -1."""
+    import dataclasses
+    comm = w.comm.copy()
+    comm[0, 1] = comm[4, 2] = comm[5, 3] = oracle.NO_CHANNEL
+    return dataclasses.replace(w, name=w.name + " missing channels", comm=comm)
+
+
 def test_schedule_matches_the_oracle(gpu_lib):
     import torch
     ds = gpu_lib
     rng = np.random.default_rng(5503)
     for w in (W.gen_config(1, n_cand=3), W.gen_config(3, n_cand=2), W.gen_config(5, n_cand=1),
-              W.random_instance(rng, 90, 5, 12, frac_bad=0.3, frac_arbitrary=0.3)):
+              W.random_instance(rng, 90, 5, 12, frac_bad=0.3, frac_arbitrary=0.3),
+              _without_some_channels(W.random_instance(rng, 70, 6, 16, frac_bad=0.2, frac_arbitrary=0.2))):
         prob = oracle.Problem.of(w)
         with ds.Evaluator.for_workload(w) as ev:
             for c in range(w.n_cand):
