@@ -32,10 +32,10 @@ def kernel_sources_hash() -> str:
     return h.hexdigest()[:16]
 
 
-def measured_traffic(cfg: int):
-    """HBM bytes per launch from the committed rocprofv3 counter summary, or None when the kernel
-    sources changed since the counters were taken (or no summary exists for this workload)."""
-    path = os.path.join(ROOT, "profiles", "relax_ring_kernel_cfg%d_counters.md" % cfg)
+def measured_traffic(cfg: int, kernel: str = "relax_ring_kernel"):
+    """HBM bytes per launch from the committed rocprofv3 counter summary of the kernel that evaluates this
+    workload, or None when the kernel sources changed since the counters were taken (or no summary exists)."""
+    path = os.path.join(ROOT, "profiles", "%s_cfg%d_counters.md" % (kernel, cfg))
     try:
         text = open(path).read()
     except OSError:
@@ -51,6 +51,11 @@ def measured_traffic(cfg: int):
         return int(vals["traffic_bytes_per_launch"])
     except (KeyError, ValueError):
         return None
+
+
+def dominant_kernel(info: dict) -> str:
+    """Name of the kernel that does the evaluation, from dagsched_get_info's variant."""
+    return {1: "relax_general_kernel", 2: "relax_general_kernel", 6: "relax_static_kernel"}.get(info["variant"], "relax_ring_kernel")
 
 
 def algorithmic_bytes(w) -> int:
@@ -145,7 +150,8 @@ def main() -> int:
         "edge_relax_per_s": cand_per_s * (w.n_edges + w.n_nodes - w.n_devices),
         "ms_kernel_hip_events": ms_kernel,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(args.config),
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(args.config, dominant_kernel(ev.info())),
+                     "kernel": dominant_kernel(ev.info()),
                      "algorithmic_bytes_per_launch": abytes},
         "workload_gen_s": t_gen,
     }

@@ -114,6 +114,13 @@ typedef struct {
   const int64_t *weight;    /* [N]   W_i >= 0, static memory of operation i (eq. (16)), or NULL: all zero    */
   const int64_t *mem_limit; /* [P]   memory limit of machine j, or NULL: no limit, OVER_MEMORY never set     */
   const dagsched_shape_t *shape; /* launch shape to use, or NULL: chosen by the library                      */
+  const int32_t *shared_placement; /* [N] or NULL.  A hint: (nearly) every candidate of every batch will place
+                                     operation i on machine shared_placement[i] (a pipeline with a fixed stage ->
+                                     machine map, as in Sec. V) and only the orders differ.  The library may then
+                                     resolve the delay of every edge once (eqs. (11)-(13)) and evaluate such
+                                     candidates with a kernel of their own; candidates that place differently
+                                     are still evaluated, one by one and slowly.  Results never depend on it.
+                                     Entries outside [0, P): DAGSCHED_EINVAL                                   */
 } dagsched_desc_t;
 
 /*

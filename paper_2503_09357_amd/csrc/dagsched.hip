@@ -33,6 +33,7 @@
 #include "kernel_general.h"
 #include "kernel_ring.h"
 #include "kernel_search.h"
+#include "kernel_static.h"
 #include "kernel_util.h"
 
 using namespace dagsched_dev;
@@ -60,7 +61,7 @@ inline int ilog2(int x) {
 inline uint32_t align_up(uint32_t x, uint32_t a) { return (x + a - 1) / a * a; }
 
 enum { kVariantGeneralLds = 1, kVariantGeneralGlobal = 2, kVariantRingExact = 3, kVariantRingOptimistic = 4,
-       kVariantRing32 = 5 };
+       kVariantRing32 = 5, kVariantStatic = 6 };
 
 }  // namespace
 
@@ -88,6 +89,13 @@ struct dagsched {
   uint16_t *ws_list16 = nullptr;
   int32_t *d_fb_count = nullptr, *d_fb_list = nullptr;
   uint32_t spin_cap = 0;
+  // shared-placement kernel
+  StaticParams st{};
+  int32_t st_preds = 4;
+  uint4 *d_st_ops = nullptr;
+  uint8_t *d_st_machine = nullptr;
+  int32_t *d_st_off = nullptr;
+  int64_t *d_st_base = nullptr;
   // search helpers: machine counts of a base schedule; one row of general-kernel workspace and outputs
   int32_t *ws_cnt = nullptr, *ws_sched_list = nullptr, *ws_sched_end = nullptr;
   unsigned char *ws_sched_out = nullptr;
@@ -131,6 +139,9 @@ int validate_desc(const dagsched_desc_t *d, std::vector<int32_t> *pred_ptr, std:
   if (d->weight)
     for (int32_t v = 0; v < N; ++v)
       if (d->weight[v] < 0) return DAGSCHED_EINVAL;
+  if (d->shared_placement)
+    for (int32_t v = 0; v < N; ++v)
+      if (d->shared_placement[v] < 0 || d->shared_placement[v] >= P) return DAGSCHED_EINVAL;
   for (int32_t a = 0; a < P; ++a)
     for (int32_t b = 0; b < P; ++b)
       if (a != b) {
@@ -180,7 +191,8 @@ void free_handle(dagsched *h) {
   if (!h) return;
   void *bufs[] = {h->d_pred_ptr, h->d_pred_idx, h->d_dur, h->d_comm, h->d_mem, h->d_weight, h->d_limit, h->ws_list, h->ws_end, h->d_rec,
                   h->d_comm_scaled, h->d_nparts, h->ws_list16, h->ws_pib, h->ws_cnt, h->ws_sched_list, h->ws_sched_end,
-                  h->ws_sched_out, h->d_fb_count, h->d_fb_list, h->ws_tp, h->ws_tr, h->d_no_channel, h->d_edges};
+                  h->ws_sched_out, h->d_fb_count, h->d_fb_list, h->ws_tp, h->ws_tr, h->d_no_channel, h->d_edges,
+                  h->d_st_ops, h->d_st_machine, h->d_st_off, h->d_st_base};
   for (void *b : bufs)
     if (b) (void)hipFree(b);
   delete h;
@@ -488,6 +500,100 @@ RingKernel ring_kernel_for(const dagsched *h) {
               : ring_kernel_pick<0>(h->ring_slots, h->ring_feeders, pib_lds, h->ring_kind);
 }
 
+int static_threads(int relaxers) {                       // relaxers, accountants and as many wavefronts again for ingest
+  return std::min(1024, 4 * relaxers * kWave);
+}
+
+// Plan of the shared-placement kernel: one op per operation with its delays resolved, the machines' list segments,
+// and how many relaxing wavefronts share a workgroup.  Not taken (ok = false) when an operation has more than four
+// distinct DAG predecessors, a time does not fit the op format or 16 bits, or the LDS is too small.
+struct StaticPlan {
+  bool ok = false;
+  int G = 0, W = 0, preds = 4, scale = 1;
+  uint32_t o_mem = 0, o_cand = 0, cand_stride = 0, o_list = 0, o_book = 0, total = 0;
+  std::vector<uint4> ops;
+  std::vector<uint8_t> machine;
+  std::vector<int32_t> off;
+  std::vector<int64_t> base;
+};
+
+StaticPlan plan_static(const dagsched_desc_t *d, const std::vector<int32_t> &pred_ptr, const std::vector<int32_t> &pred_idx,
+                       int64_t sum_dur, int lds_max) {
+  StaticPlan plan;
+  const int N = d->n_nodes, P = d->n_devices, Pseg = next_pow2(P);
+  const int32_t *pi = d->shared_placement;
+  if (2 * (N + 4) > 65535) return plan;                // cell offsets are 16-bit
+  int64_t g = 0, max_delay = 0;
+  for (int v = 0; v < N; ++v) g = std::gcd<int64_t, int64_t>(g, d->dur[v]);
+  for (int v = 0; v < N; ++v)
+    for (int k = pred_ptr[v]; k < pred_ptr[v + 1]; ++k) {
+      const int u = pred_idx[k];
+      if (pi[u] != pi[v]) {
+        g = std::gcd<int64_t, int64_t>(g, d->comm[pi[u] * P + pi[v]]);
+        max_delay = std::max<int64_t>(max_delay, d->comm[pi[u] * P + pi[v]]);
+      }
+    }
+  if (g == 0) g = 1;
+  if (max_delay / g > 255) return plan;
+  if (sum_dur / g + (int64_t)(N - 1) * (max_delay / g) >= (int64_t)kNotDone16) return plan;   // every end time below 0xFFFF
+  plan.ops.resize(N);
+  int max_preds = 0;
+  for (int v = 0; v < N; ++v) {
+    // distinct predecessors; of two edges from one producer the delays are equal
+    std::vector<int32_t> us(pred_idx.begin() + pred_ptr[v], pred_idx.begin() + pred_ptr[v + 1]);
+    std::sort(us.begin(), us.end());
+    us.erase(std::unique(us.begin(), us.end()), us.end());
+    if (us.size() > 4) return plan;
+    max_preds = std::max<int>(max_preds, (int)us.size());
+    uint32_t o[4] = {2u * N, 2u * N, 2u * N, 2u * N}, dl[4] = {0, 0, 0, 0};
+    for (size_t i = 0; i < us.size(); ++i) {
+      o[i] = 2u * (uint32_t)us[i];
+      dl[i] = pi[us[i]] != pi[v] ? (uint32_t)(d->comm[pi[us[i]] * P + pi[v]] / g) : 0u;
+    }
+    plan.ops[v] = make_uint4(o[0] | (o[1] << 16), o[2] | (o[3] << 16), dl[0] | (dl[1] << 8) | (dl[2] << 16) | (dl[3] << 24),
+                             (uint32_t)(d->dur[v] / g) | ((2u * (uint32_t)v) << 16));
+  }
+  plan.preds = max_preds <= 2 ? 2 : 4;
+  plan.scale = (int)g;
+  plan.machine.assign((size_t)(N + 3) / 4 * 4, 0);
+  std::vector<int32_t> cnt(Pseg + 1, 0);
+  for (int v = 0; v < N; ++v) { plan.machine[v] = (uint8_t)pi[v]; ++cnt[pi[v]]; }
+  plan.off.assign(Pseg + 1, N);
+  for (int j = 0, at = 0; j <= Pseg; ++j) { plan.off[j] = at; at += j < Pseg ? cnt[j] : 0; }
+  if (d->weight) {
+    plan.base.assign(P, 0);
+    for (int v = 0; v < N; ++v) plan.base[pi[v]] += d->weight[v];
+  }
+  // LDS: op table, memory adjustments, then per candidate the cells (N + 3, padded) and the list (N + 4 entries), then bookkeeping
+  plan.G = kWave / Pseg;
+  const uint32_t cells = align_up((uint32_t)((N + 4) / 2) * 4u, 4u), list = (uint32_t)((N + 5) / 2) * 4u;
+  plan.o_mem = (uint32_t)N * 16u;
+  plan.o_cand = align_up(plan.o_mem + (uint32_t)N * 8u, 16u);
+  plan.o_list = cells;
+  plan.cand_stride = align_up(cells + list, 16u);
+  const int lds_cu = 160 * 1024;
+  int best_w = 0, best_score = -1;
+  const int forced_w = env_int("DAGSCHED_STATIC_WAVES", 0);
+  for (int w = 1; w <= 8; ++w) {
+    if (plan.G * w > kWave) break;                     // 64 flag words per workgroup
+    if (forced_w && w != forced_w) continue;
+    const uint32_t total = plan.o_cand + (uint32_t)(plan.G * w) * plan.cand_stride + 1024u + 512u * (uint32_t)w;
+    if ((int)total > lds_max) break;
+    const int wgs = std::min(lds_cu / (int)total, 32 / (static_threads(w) / kWave));
+    const int relaxers = std::min(wgs * w, 8);
+    // two workgroups per CU overlap one's ingest with the other's relaxing: worth about one relaxer (measured on the
+    // zero-bubble pipeline: 2 x 2 relaxers 0.308 ms, 1 x 5 0.325 ms, 1 x 4 0.320 ms, 3 x 1 0.383 ms)
+    const int score = relaxers * 4 + (wgs >= 2 ? 5 : 0) - (w > 1 ? 1 : 0);
+    if (score > best_score) { best_score = score; best_w = w; }
+  }
+  if (!best_w) return plan;
+  plan.W = best_w;
+  plan.o_book = plan.o_cand + (uint32_t)(plan.G * plan.W) * plan.cand_stride;
+  plan.total = plan.o_book + 1024u + 512u * (uint32_t)plan.W;
+  plan.ok = true;
+  return plan;
+}
+
 size_t channel_flag_lds(int32_t n_nodes) {               // mask words + one byte per node
   return (size_t)DAGSCHED_MAX_DEVICES * sizeof(uint64_t) + (size_t)n_nodes;
 }
@@ -534,6 +640,15 @@ int launch_evaluate(dagsched *h, int32_t n_cand, const int32_t *placement, const
   const OutPtrs out = make_out(h, n_cand, makespan, bubble, peak_mem, flags);
   if (h->variant == kVariantGeneralLds || h->variant == kVariantGeneralGlobal) {
     launch_general(h, n_cand, pl, rk, out, nullptr, nullptr, stream);
+  } else if (h->variant == kVariantStatic) {
+    hipLaunchKernelGGL(reset_counter_kernel, dim3(1), dim3(1), 0, stream, h->d_fb_count);
+    StaticParams p = h->st;
+    p.C = n_cand; p.placement = pl; p.rank = rk; p.out = out;
+    const int per_wg = p.G * p.W;
+    const unsigned blocks = (unsigned)((n_cand + per_wg - 1) / per_wg);
+    hipLaunchKernelGGL(h->st_preds == 2 ? relax_static_kernel<2> : relax_static_kernel<4>, dim3(blocks),
+                       dim3((unsigned)static_threads(p.W)), (size_t)p.total, stream, p);
+    launch_general(h, n_cand, pl, rk, out, h->d_fb_list, h->d_fb_count, stream);   // candidates with another placement
   } else {
     const bool optimistic = h->variant == kVariantRingOptimistic;
     if (optimistic) hipLaunchKernelGGL(reset_counter_kernel, dim3(1), dim3(1), 0, stream, h->d_fb_count);
@@ -624,8 +739,12 @@ int dagsched_create(const dagsched_desc_t *caller_desc, dagsched_t **out) {
   const size_t maxc = (size_t)h->max_cand;
 
   RingPlan plan;
-  if (!env_int("DAGSCHED_FORCE_GENERAL", 0)) plan = plan_ring(desc, pred_ptr, pred_idx, sum_dur, lds_max);
-  const bool need_general = !plan.ok || !plan.exact;
+  StaticPlan splan;
+  const bool force_general = env_int("DAGSCHED_FORCE_GENERAL", 0) != 0;
+  if (!force_general && desc->shared_placement && !env_int("DAGSCHED_NO_SHARED_PLACEMENT", 0))
+    splan = plan_static(desc, pred_ptr, pred_idx, sum_dur, lds_max);
+  if (!force_general && !splan.ok) plan = plan_ring(desc, pred_ptr, pred_idx, sum_dur, lds_max);
+  const bool need_general = splan.ok || !plan.ok || !plan.exact;
 
   bool ok = upload(&h->d_mem, desc->mem_delta, (size_t)h->N) &&
             (!desc->weight || upload(&h->d_weight, desc->weight, (size_t)h->N)) &&
@@ -655,6 +774,27 @@ int dagsched_create(const dagsched_desc_t *caller_desc, dagsched_t **out) {
       ok = hip_ok(hipFuncSetAttribute((const void *)relax_general_kernel<true>,
                                       hipFuncAttributeMaxDynamicSharedMemorySize, h->gen_lds), "hipFuncSetAttribute");
     h->variant = h->gen_lds_state ? kVariantGeneralLds : kVariantGeneralGlobal;
+  }
+  if (ok && splan.ok) {
+    h->variant = kVariantStatic;
+    h->time_scale = splan.scale;
+    h->st_preds = splan.preds;
+    ok = upload(&h->d_st_ops, splan.ops.data(), splan.ops.size()) &&
+         upload(&h->d_st_machine, splan.machine.data(), splan.machine.size()) &&
+         upload(&h->d_st_off, splan.off.data(), splan.off.size()) &&
+         (splan.base.empty() || upload(&h->d_st_base, splan.base.data(), splan.base.size())) &&
+         dev_alloc(&h->d_fb_count, 1) && dev_alloc(&h->d_fb_list, maxc);
+    StaticParams &s = h->st;
+    s.N = h->N; s.P = h->P; s.Pseg = h->Pseg; s.log_pseg = ilog2(h->Pseg); s.G = splan.G; s.W = splan.W;
+    s.ops = h->d_st_ops; s.machine = h->d_st_machine; s.off = h->d_st_off; s.mem_delta = h->d_mem;
+    s.base = h->d_st_base; s.mem_limit = h->d_limit;
+    s.sum_dur = h->sum_dur; s.time_scale = splan.scale;
+    s.fb_count = h->d_fb_count; s.fb_list = h->d_fb_list;
+    s.o_mem = splan.o_mem; s.o_cand = splan.o_cand; s.cand_stride = splan.cand_stride; s.o_list = splan.o_list; s.o_book = splan.o_book;
+    s.total = splan.total;
+    if (ok && s.total > 48 * 1024)
+      ok = hip_ok(hipFuncSetAttribute(splan.preds == 2 ? (const void *)relax_static_kernel<2> : (const void *)relax_static_kernel<4>,
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)s.total), "hipFuncSetAttribute");
   }
   if (ok && plan.ok) {
     h->variant = plan.cell32 ? kVariantRing32 : plan.exact ? kVariantRingExact : kVariantRingOptimistic;
@@ -785,6 +925,15 @@ int dagsched_get_info(const dagsched_t *h, dagsched_info_t *info) {
   info->block_threads = ring ? h->ring_block : kWave;
   info->lds_bytes = ring ? (int32_t)h->lds.total : h->gen_lds;
   info->state_bits = ring && h->variant != kVariantRing32 ? 16 : 32;
+  if (h->variant == kVariantStatic) {
+    info->cand_per_block = h->st.G * h->st.W;
+    info->block_threads = static_threads(h->st.W);
+    info->lds_bytes = (int32_t)h->st.total;
+    info->state_bits = 16;
+    info->reserved[1] = h->time_scale;
+    info->reserved[2] = h->st_preds << 16;
+    return DAGSCHED_OK;
+  }
   info->reserved[0] = ring ? h->ring_slots : 0;
   info->reserved[1] = h->time_scale;
   info->reserved[2] = ring ? (h->ring_feeders | ((int)h->lds.pib_mode << 8) | ((h->ring_kind == 2 ? 2 : 4) << 16) | (h->ring_kind << 24) | ((int)h->lds.wide << 28)) : 0;

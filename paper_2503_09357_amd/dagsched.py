@@ -29,7 +29,8 @@ class Desc(ctypes.Structure):
                 ("row_ptr", ctypes.c_void_p), ("col_idx", ctypes.c_void_p), ("dur", ctypes.c_void_p),
                 ("comm", ctypes.c_void_p), ("mem_delta", ctypes.c_void_p),
                 ("max_candidates", ctypes.c_int32), ("layout", ctypes.c_int32), ("hip_device", ctypes.c_int32),
-                ("weight", ctypes.c_void_p), ("mem_limit", ctypes.c_void_p), ("shape", ctypes.c_void_p)]
+                ("weight", ctypes.c_void_p), ("mem_limit", ctypes.c_void_p), ("shape", ctypes.c_void_p),
+                ("shared_placement", ctypes.c_void_p)]
 
 
 class Shape(ctypes.Structure):
@@ -100,7 +101,7 @@ class _HostProblem:
     """Keeps the contiguous host arrays alive while a Desc points at them."""
 
     def __init__(self, n_devices, row_ptr, col_idx, dur, comm, mem_delta, max_candidates, layout, hip_device,
-                 n_nodes=None, n_edges=None, weight=None, mem_limit=None, shape=None):
+                 n_nodes=None, n_edges=None, weight=None, mem_limit=None, shape=None, shared_placement=None):
         self.row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int32)
         self.col_idx = np.ascontiguousarray(col_idx, dtype=np.int32)
         self.dur = np.ascontiguousarray(dur, dtype=np.int32)
@@ -132,14 +133,18 @@ class _HostProblem:
                                int(shape.get("feeders", 0)), int(shape.get("placement_mode", -1)),
                                int(shape.get("block_threads", 0)), int(shape.get("state_bits", 0)))
         d.shape = None if self.shape is None else ctypes.addressof(self.shape)
+        self.shared_placement = None if shared_placement is None else np.ascontiguousarray(shared_placement, dtype=np.int32).reshape(-1)
+        if self.shared_placement is not None and self.shared_placement.shape != (d.n_nodes,):
+            raise ValueError("shared_placement must have one entry per node")
+        d.shared_placement = None if self.shared_placement is None else self.shared_placement.ctypes.data
         self.desc = d
 
 
 def validate(n_devices, row_ptr, col_idx, dur, comm, mem_delta, max_candidates=1, layout=CAND_MAJOR,
-             n_nodes=None, n_edges=None, weight=None, mem_limit=None, shape=None) -> int:
+             n_nodes=None, n_edges=None, weight=None, mem_limit=None, shape=None, shared_placement=None) -> int:
     """Host-only description check; returns the code dagsched_create would return."""
     hp = _HostProblem(n_devices, row_ptr, col_idx, dur, comm, mem_delta, max_candidates, layout, 0, n_nodes, n_edges,
-                      weight, mem_limit, shape)
+                      weight, mem_limit, shape, shared_placement)
     return load(import_torch_first=False).dagsched_validate(ctypes.byref(hp.desc))
 
 
@@ -147,10 +152,13 @@ class Evaluator:
     """dagsched_create / dagsched_evaluate / dagsched_destroy around torch device tensors."""
 
     def __init__(self, n_devices, row_ptr, col_idx, dur, comm, mem_delta, max_candidates: int,
-                 layout: int = CAND_MAJOR, hip_device: int = 0, weight=None, mem_limit=None, shape=None):
+                 layout: int = CAND_MAJOR, hip_device: int = 0, weight=None, mem_limit=None, shape=None,
+                 shared_placement=None):
+        """shared_placement: [N] machine of every operation when (nearly) all candidates will place alike and differ
+        in the orders only; a hint that selects a faster kernel, never changes a result."""
         lib = load()
         hp = _HostProblem(n_devices, row_ptr, col_idx, dur, comm, mem_delta, max_candidates, layout, hip_device,
-                          weight=weight, mem_limit=mem_limit, shape=shape)
+                          weight=weight, mem_limit=mem_limit, shape=shape, shared_placement=shared_placement)
         handle = ctypes.c_void_p()
         _check(lib.dagsched_create(ctypes.byref(hp.desc), ctypes.byref(handle)))
         self._h = handle
@@ -159,10 +167,16 @@ class Evaluator:
 
     @classmethod
     def for_workload(cls, w, max_candidates: Optional[int] = None, layout: int = CAND_MAJOR, hip_device: int = 0,
-                     shape=None):
+                     shape=None, shared_placement="auto"):
+        """shared_placement "auto": pass the hint when the workload has several candidates and all place alike."""
+        if isinstance(shared_placement, str):
+            pl = np.asarray(w.placement)
+            same = pl.shape[0] > 1 and bool((pl == pl[0]).all()) and bool(((pl[0] >= 0) & (pl[0] < w.n_devices)).all())
+            shared_placement = pl[0] if same else None
         return cls(w.n_devices, w.row_ptr, w.col_idx, w.dur, w.comm, w.mem_delta,
                    w.n_cand if max_candidates is None else max_candidates, layout, hip_device,
-                   weight=getattr(w, "weight", None), mem_limit=getattr(w, "mem_limit", None), shape=shape)
+                   weight=getattr(w, "weight", None), mem_limit=getattr(w, "mem_limit", None), shape=shape,
+                   shared_placement=shared_placement)
 
     @classmethod
     def autotuned(cls, make, placement, rank, reps: int = 3, verbose: bool = False):

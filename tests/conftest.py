@@ -8,6 +8,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 
+# Workloads whose candidates all place alike would be sent to the shared-placement kernel by Evaluator.for_workload;
+# the tests of the other kernels keep them where they were, tests/test_gpu_shared_placement.py switches it back on.
+os.environ.setdefault("DAGSCHED_NO_SHARED_PLACEMENT", "1")
+
+
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
 
