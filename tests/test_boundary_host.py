@@ -119,6 +119,16 @@ def test_validate_checks_the_launch_shape():
         assert ds.validate(**args, shape=bad) == -1, bad
 
 
+def test_validate_checks_the_shared_placement_hint():
+    rp, ci = W.csr_from_edges(3, [0, 1], [1, 2])
+    args = dict(n_devices=2, row_ptr=rp, col_idx=ci, dur=[1, 1, 1], comm=[[0, 1], [1, 0]], mem_delta=[0, 0, 0])
+    assert dagsched.validate(**args, shared_placement=[0, 1, 1]) == 0
+    assert dagsched.validate(**args, shared_placement=[0, 2, 1]) == -1
+    assert dagsched.validate(**args, shared_placement=[0, -1, 1]) == -1
+    with pytest.raises(ValueError):
+        dagsched.validate(**args, shared_placement=[0, 1])
+
+
 def test_bench_refuses_more_than_one_gpu_and_reads_the_committed_counters():
     import subprocess
     import sys
