@@ -196,7 +196,9 @@ int dagsched_schedule(dagsched_t *h, const int32_t *placement, const int32_t *ra
  * shape.  Fills the struct and returns DAGSCHED_OK, or DAGSCHED_EINVAL on NULL.
  */
 typedef struct {
-  int32_t variant;         /* internal kernel variant id */
+  int32_t variant;         /* 1, 2 general int32 kernel (end times in LDS / in HBM); 3 ring kernel, 16-bit times
+                              proven to fit; 4 the same run optimistically with the int32 kernel behind it;
+                              5 ring kernel with 32-bit times; 6 shared-placement kernel */
   int32_t cand_per_block;  /* candidates evaluated by one workgroup */
   int32_t block_threads;   /* workgroup size */
   int32_t lds_bytes;       /* dynamic LDS per workgroup */
