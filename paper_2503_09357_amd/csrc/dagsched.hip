@@ -91,7 +91,7 @@ struct dagsched {
   uint32_t spin_cap = 0;
   // shared-placement kernel
   StaticParams st{};
-  int32_t st_preds = 4;
+  int32_t st_preds = 4, st_grid = 1;      // st_grid: workgroups that are resident at once (each loops over batches)
   uint4 *d_st_ops = nullptr;
   uint8_t *d_st_machine = nullptr;
   int32_t *d_st_off = nullptr;
@@ -509,8 +509,8 @@ int static_threads(int relaxers) {                       // relaxers, accountant
 // distinct DAG predecessors, a time does not fit the op format or 16 bits, or the LDS is too small.
 struct StaticPlan {
   bool ok = false;
-  int G = 0, W = 0, preds = 4, scale = 1;
-  uint32_t o_mem = 0, o_cand = 0, cand_stride = 0, o_list = 0, o_book = 0, total = 0;
+  int G = 0, W = 0, preds = 4, scale = 1, wgs = 1;      // wgs: workgroups that fit a CU
+  uint32_t o_mem = 0, o_mach = 0, o_cand = 0, cand_stride = 0, o_list = 0, o_book = 0, total = 0;
   std::vector<uint4> ops;
   std::vector<uint8_t> machine;
   std::vector<int32_t> off;
@@ -518,7 +518,7 @@ struct StaticPlan {
 };
 
 StaticPlan plan_static(const dagsched_desc_t *d, const std::vector<int32_t> &pred_ptr, const std::vector<int32_t> &pred_idx,
-                       int64_t sum_dur, int lds_max) {
+                       int64_t sum_dur, int lds_max, int n_cu) {
   StaticPlan plan;
   const int N = d->n_nodes, P = d->n_devices, Pseg = next_pow2(P);
   const int32_t *pi = d->shared_placement;
@@ -568,7 +568,8 @@ StaticPlan plan_static(const dagsched_desc_t *d, const std::vector<int32_t> &pre
   plan.G = kWave / Pseg;
   const uint32_t cells = align_up((uint32_t)((N + 4) / 2) * 4u, 4u), list = (uint32_t)((N + 5) / 2) * 4u;
   plan.o_mem = (uint32_t)N * 16u;
-  plan.o_cand = align_up(plan.o_mem + (uint32_t)N * 8u, 16u);
+  plan.o_mach = plan.o_mem + (uint32_t)N * 8u;
+  plan.o_cand = align_up(plan.o_mach + (uint32_t)(N + 3) / 4u * 4u, 16u);
   plan.o_list = cells;
   plan.cand_stride = align_up(cells + list, 16u);
   const int lds_cu = 160 * 1024;
@@ -580,11 +581,14 @@ StaticPlan plan_static(const dagsched_desc_t *d, const std::vector<int32_t> &pre
     const uint32_t total = plan.o_cand + (uint32_t)(plan.G * w) * plan.cand_stride + 1024u + 512u * (uint32_t)w;
     if ((int)total > lds_max) break;
     const int wgs = std::min(lds_cu / (int)total, 32 / (static_threads(w) / kWave));
-    const int relaxers = std::min(wgs * w, 8);
-    // two workgroups per CU overlap one's ingest with the other's relaxing: worth about one relaxer (measured on the
-    // zero-bubble pipeline: 2 x 2 relaxers 0.308 ms, 1 x 5 0.325 ms, 1 x 4 0.320 ms, 3 x 1 0.383 ms)
-    const int score = relaxers * 4 + (wgs >= 2 ? 5 : 0) - (w > 1 ? 1 : 0);
-    if (score > best_score) { best_score = score; best_w = w; }
+    // a handle for small batches is better off with the ring kernel: one launch instead of three, and workgroups of
+    // this size would leave CUs idle (1F1B pipeline, 1024 candidates: 0.012 ms there, 0.015-0.019 ms here)
+    if (!forced_w && (int64_t)d->max_candidates < (int64_t)2 * n_cu * std::max(1, wgs) * plan.G * w) continue;
+    // one relaxer per SIMD is enough (measured on the zero-bubble pipeline: 1 x 4 relaxers 0.291 ms, 2 x 2 0.301 ms,
+    // 1 x 5 0.309 ms, 3 x 1 0.359 ms); among equals the larger workgroup: fewer copies of the tables
+    const int relaxers = std::min(wgs * w, 4);
+    const int score = relaxers * 8 + w - (wgs * w > 4 ? 4 : 0);
+    if (score > best_score) { best_score = score; best_w = w; plan.wgs = std::max(1, wgs); }
   }
   if (!best_w) return plan;
   plan.W = best_w;
@@ -645,7 +649,7 @@ int launch_evaluate(dagsched *h, int32_t n_cand, const int32_t *placement, const
     StaticParams p = h->st;
     p.C = n_cand; p.placement = pl; p.rank = rk; p.out = out;
     const int per_wg = p.G * p.W;
-    const unsigned blocks = (unsigned)((n_cand + per_wg - 1) / per_wg);
+    const unsigned blocks = (unsigned)std::min((n_cand + per_wg - 1) / per_wg, h->st_grid);
     hipLaunchKernelGGL(h->st_preds == 2 ? relax_static_kernel<2> : relax_static_kernel<4>, dim3(blocks),
                        dim3((unsigned)static_threads(p.W)), (size_t)p.total, stream, p);
     launch_general(h, n_cand, pl, rk, out, h->d_fb_list, h->d_fb_count, stream);   // candidates with another placement
@@ -722,10 +726,13 @@ int dagsched_create(const dagsched_desc_t *caller_desc, dagsched_t **out) {
   if (!hip_ok(hipGetDeviceCount(&n_dev), "hipGetDeviceCount")) return DAGSCHED_EHIP;
   if (desc->hip_device < 0 || desc->hip_device >= n_dev) return DAGSCHED_EINVAL;
   if (!hip_ok(hipSetDevice(desc->hip_device), "hipSetDevice")) return DAGSCHED_EHIP;
-  int lds_max = 0;
+  int lds_max = 0, n_cu = 0;
   if (!hip_ok(hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, desc->hip_device),
+              "hipDeviceGetAttribute") ||
+      !hip_ok(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, desc->hip_device),
               "hipDeviceGetAttribute"))
     return DAGSCHED_EHIP;
+  n_cu = std::max(1, n_cu);
 
   dagsched *h = new (std::nothrow) dagsched();
   if (!h) return DAGSCHED_ENOMEM;
@@ -742,7 +749,7 @@ int dagsched_create(const dagsched_desc_t *caller_desc, dagsched_t **out) {
   StaticPlan splan;
   const bool force_general = env_int("DAGSCHED_FORCE_GENERAL", 0) != 0;
   if (!force_general && desc->shared_placement && !env_int("DAGSCHED_NO_SHARED_PLACEMENT", 0))
-    splan = plan_static(desc, pred_ptr, pred_idx, sum_dur, lds_max);
+    splan = plan_static(desc, pred_ptr, pred_idx, sum_dur, lds_max, n_cu);
   if (!force_general && !splan.ok) plan = plan_ring(desc, pred_ptr, pred_idx, sum_dur, lds_max);
   const bool need_general = splan.ok || !plan.ok || !plan.exact;
 
@@ -779,6 +786,7 @@ int dagsched_create(const dagsched_desc_t *caller_desc, dagsched_t **out) {
     h->variant = kVariantStatic;
     h->time_scale = splan.scale;
     h->st_preds = splan.preds;
+    h->st_grid = n_cu * splan.wgs;
     ok = upload(&h->d_st_ops, splan.ops.data(), splan.ops.size()) &&
          upload(&h->d_st_machine, splan.machine.data(), splan.machine.size()) &&
          upload(&h->d_st_off, splan.off.data(), splan.off.size()) &&
@@ -790,7 +798,7 @@ int dagsched_create(const dagsched_desc_t *caller_desc, dagsched_t **out) {
     s.base = h->d_st_base; s.mem_limit = h->d_limit;
     s.sum_dur = h->sum_dur; s.time_scale = splan.scale;
     s.fb_count = h->d_fb_count; s.fb_list = h->d_fb_list;
-    s.o_mem = splan.o_mem; s.o_cand = splan.o_cand; s.cand_stride = splan.cand_stride; s.o_list = splan.o_list; s.o_book = splan.o_book;
+    s.o_mem = splan.o_mem; s.o_mach = splan.o_mach; s.o_cand = splan.o_cand; s.cand_stride = splan.cand_stride; s.o_list = splan.o_list; s.o_book = splan.o_book;
     s.total = splan.total;
     if (ok && s.total > 48 * 1024)
       ok = hip_ok(hipFuncSetAttribute(splan.preds == 2 ? (const void *)relax_static_kernel<2> : (const void *)relax_static_kernel<4>,

@@ -15,6 +15,12 @@ from test_gpu_parity import _say, _with_env, assert_parity
 pytestmark = pytest.mark.gpu
 
 SHARED = {"DAGSCHED_NO_SHARED_PLACEMENT": 0}          # tests/conftest.py switches the hint off for every other test
+
+
+def _forced(waves):
+    """The library keeps handles for small batches on the ring kernel; naming the number of relaxing wavefronts per
+    workgroup makes it take the shared-placement kernel whatever the batch size."""
+    return dict(SHARED, DAGSCHED_STATIC_WAVES=waves)
 STATIC = 6                                            # dagsched_get_info: the shared-placement kernel
 
 
@@ -58,7 +64,7 @@ def _fixed_placement_instance(rng, n, p, n_cand, max_fanin=3, max_dur=9, max_com
     return w, fixed
 
 
-def _run(ds, w, fixed, layout=0, want_variant=STATIC):
+def _run(ds, w, fixed, layout=0, want_variant=STATIC, waves=1):
     import torch
     dev = torch.device("cuda", 0)
     _say("%s | N=%d E=%d P=%d C=%d layout=%d" % (w.name, w.n_nodes, w.n_edges, w.n_devices, w.n_cand, layout))
@@ -73,7 +79,7 @@ def _run(ds, w, fixed, layout=0, want_variant=STATIC):
                 outs.append(tuple(t.cpu().numpy() for t in out))
             return outs, ev.info()
 
-    outs, info = _with_env(SHARED, go)
+    outs, info = _with_env(_forced(waves), go)
     assert info["variant"] in (want_variant if isinstance(want_variant, tuple) else (want_variant,)), info
     assert all((a == b).all() for a, b in zip(*outs)), "evaluation is not deterministic"
     z, b, pk, f = outs[0]
@@ -86,19 +92,24 @@ def _run(ds, w, fixed, layout=0, want_variant=STATIC):
     return f, info
 
 
-@pytest.mark.parametrize("cfg,c", [(1, 1024), (2, 3000), (2, 65536)])
-def test_pipeline_configurations(gpu_lib, cfg, c):
-    """for_workload finds the shared placement by itself ("auto"), as bench.py does."""
+@pytest.mark.parametrize("cfg,c,waves", [(1, 1024, 1), (1, 1024, 4), (2, 3000, 2), (2, 3000, 5), (2, 65536, 0)])
+def test_pipeline_configurations(gpu_lib, cfg, c, waves):
+    """for_workload finds the shared placement by itself ("auto"), as bench.py does; at full size the library takes
+    the shared-placement kernel by itself (waves = 0), the smaller batches are made to."""
     w = W.gen_config(cfg, n_cand=c)
-    (z, b, pk, f), info = _with_env(SHARED, lambda: assert_parity(gpu_lib, w))
+    env = _forced(waves) if waves else SHARED
+    (z, b, pk, f), info = _with_env(env, lambda: assert_parity(gpu_lib, w))
     assert info["variant"] == STATIC, info
     if cfg == 2:
         marked = np.zeros(w.n_cand, bool)
         marked[w.meta["cyclic"][w.meta["cyclic"] < c]] = True
         assert ((f == 1) == marked).all()
-    (z1, b1, pk1, f1), info = _with_env(SHARED, lambda: assert_parity(gpu_lib, dataclasses.replace(
+    (z1, b1, pk1, f1), info = _with_env(_forced(waves or 2), lambda: assert_parity(gpu_lib, dataclasses.replace(
         w, placement=w.placement[:257], rank=w.rank[:257]), layout=1))
     assert info["variant"] == STATIC and (f1 == f[:257]).all()
+    if not waves:                                             # the same handle parameters as bench.py: the ring kernel for small batches
+        _, info = _with_env(SHARED, lambda: assert_parity(gpu_lib, W.gen_config(1, n_cand=1024)))
+        assert info["variant"] == 3, info
 
 
 def test_random_problems_with_malformed_cyclic_and_stranger_candidates(gpu_lib):
@@ -113,7 +124,10 @@ def test_random_problems_with_malformed_cyclic_and_stranger_candidates(gpu_lib):
             w = dataclasses.replace(w, weight=rng.integers(0, 50, n).astype(np.int64), mem_limit=rng.integers(20, 400, p).astype(np.int64))
         if trial % 4 == 2:
             w = dataclasses.replace(w, dur=(w.dur * 12).astype(np.int32), comm=(w.comm * 18).astype(np.int32))   # gcd 6
-        f, info = _run(gpu_lib, w, fixed, layout=trial % 2)
+        g = 64 // (1 << (p - 1).bit_length())                 # candidates per relaxing wavefront
+        fits = [wv for wv in (1, 2, 3, 4, 8) if g * wv <= 64 and 25 * n + g * wv * (4 * n + 40) + 6000 <= 160 * 1024]
+        waves = fits[trial % 5 % len(fits)]
+        f, info = _run(gpu_lib, w, fixed, layout=trial % 2, waves=waves)
         for x in f:
             seen[int(x)] = seen.get(int(x), 0) + 1
     assert all(seen.get(k, 0) > 10 for k in (0, 1, 2, 4, 16)), seen
