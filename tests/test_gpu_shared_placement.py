@@ -133,6 +133,16 @@ def test_random_problems_with_malformed_cyclic_and_stranger_candidates(gpu_lib):
     assert all(seen.get(k, 0) > 10 for k in (0, 1, 2, 4, 16)), seen
 
 
+def test_largest_problems_the_kernel_takes(gpu_lib):
+    """Tables and one wavefront's candidates just fit the LDS: 5000 operations on 64 machines (one candidate per
+    wavefront), 3600 on 16 (four); a ragged candidate count, so the last batch of a workgroup is partly empty."""
+    rng = np.random.default_rng(611)
+    for n, p, c in ((5000, 64, 37), (3600, 16, 61), (1000, 3, 333)):
+        w, fixed = _fixed_placement_instance(rng, n, p, c, max_fanin=3, strangers=2)
+        f, info = _run(gpu_lib, w, fixed, waves=1)
+        assert (f == 0).sum() > c // 3, (n, p, np.bincount(f))
+
+
 def test_every_candidate_breaks_the_promise(gpu_lib):
     """A hint that is simply wrong: all candidates are evaluated by the int32 kernel, results as always."""
     rng = np.random.default_rng(607)
