@@ -14,6 +14,9 @@ GPU path and this oracle see the same draws):
       r0 odd   "move"      m2 = r2 mod P.  m2 == m: v is re-inserted at position r3 mod n_m of its own
                            machine;  m2 != m: v is inserted at position r3 mod (n_m2 + 1) of machine m2.
                            Every other operation keeps its relative order.
+    orders only            the same with m2 = m whatever r2 is: the allocation x of the base is kept and only the
+                           orders are searched, as in the pipeline experiments of Sec. V, where the stage ->
+                           machine map is given.
 
 A dense base gives dense candidates (each machine's ranks stay 0..n_j-1); a move may well make the
 combined graph cyclic, which the evaluator then flags.  `select` picks the feasible candidate of least
@@ -28,7 +31,7 @@ from typing import Tuple
 import numpy as np
 
 
-def propose(base_placement, base_rank, rnd, n_devices: int) -> Tuple[np.ndarray, np.ndarray]:
+def propose(base_placement, base_rank, rnd, n_devices: int, orders_only: bool = False) -> Tuple[np.ndarray, np.ndarray]:
     """-> (placement int32 [C, N], rank int32 [C, N]) with C = len(rnd) // 4."""
     pl0 = np.ascontiguousarray(base_placement, dtype=np.int32).reshape(-1)
     rk0 = np.ascontiguousarray(base_rank, dtype=np.int32).reshape(-1)
@@ -48,7 +51,7 @@ def propose(base_placement, base_rank, rnd, n_devices: int) -> Tuple[np.ndarray,
                 rk[other] = r
                 rk[v] = r + 1
         else:
-            m2 = r2 % n_devices
+            m2 = m if orders_only else r2 % n_devices
             if m2 == m:
                 r_new = r3 % int(cnt[m])
                 same = pl0 == m

@@ -24,7 +24,7 @@ def _from_lists(n, lists):
     return pl, rk
 
 
-def _apply_on_lists(P, pl0, rk0, words):
+def _apply_on_lists(P, pl0, rk0, words, orders_only=False):
     """The move of the oracle's docstring, carried out with list.pop / list.insert."""
     n = len(pl0)
     lists = [list(l) for l in _lists(P, pl0, rk0)]
@@ -35,7 +35,7 @@ def _apply_on_lists(P, pl0, rk0, words):
         if r + 1 < len(lists[m]):
             lists[m][r], lists[m][r + 1] = lists[m][r + 1], lists[m][r]
     else:
-        m2 = r2 % P
+        m2 = m if orders_only else r2 % P
         if m2 == m:
             pos = r3 % len(lists[m])
             lists[m].pop(r)
@@ -59,6 +59,23 @@ def test_moves_match_list_surgery():
         for c in range(1, 200):
             want_pl, want_rk = _apply_on_lists(P, pl[0], rk[0], rnd[4 * c:4 * c + 4])
             assert (out_pl[c] == want_pl).all() and (out_rk[c] == want_rk).all(), (c, rnd[4 * c:4 * c + 4])
+
+
+def test_orders_only_moves_match_list_surgery_and_keep_the_placement():
+    rng = np.random.default_rng(4402)
+    for _ in range(6):
+        n, P = int(rng.integers(3, 40)), int(rng.integers(1, 6))
+        rp, ci = W.random_dag(rng, n, 2)
+        pl, rk = W.list_schedules(rp, ci, P, 1, int(rng.integers(1, 1 << 30)))
+        rnd = rng.integers(0, 1 << 32, size=4 * 150, dtype=np.uint64).astype(np.uint32)
+        out_pl, out_rk = SO.propose(pl[0], rk[0], rnd, P, orders_only=True)
+        assert (out_pl == pl[0]).all()                                         # x of the base in every candidate
+        moved = 0
+        for c in range(1, 150):
+            want_pl, want_rk = _apply_on_lists(P, pl[0], rk[0], rnd[4 * c:4 * c + 4], orders_only=True)
+            assert (out_pl[c] == want_pl).all() and (out_rk[c] == want_rk).all(), c
+            moved += int((out_rk[c] != rk[0]).any())
+        assert moved > 30 or n < 6
 
 
 def test_candidates_stay_dense_and_move_one_operation():
