@@ -177,6 +177,11 @@ const char *dagsched_strerror(int code);
  *            m2 != m: v is inserted at position r3 mod (n_m2 + 1) of m2.
  * Every other operation keeps its relative order, so every candidate is dense; it may be cyclic.
  *
+ * dagsched_propose_orders: the same with m2 = m whatever r2 is: every candidate keeps the allocation x of the
+ * base and only the orders y change (the search of the pipeline experiments of Sec. V, where the stage ->
+ * machine map is given).  With the base's placement as dagsched_desc_t.shared_placement the whole search runs
+ * on the shared-placement kernel.
+ *
  * dagsched_select: best[0] = index of the candidate with flags == 0 and the least makespan (lowest index
  * among equals), best[1] = that makespan; (-1, -1) when no candidate is feasible.  best: int32 [2].
  *
@@ -186,6 +191,8 @@ const char *dagsched_strerror(int code);
  */
 int dagsched_propose(dagsched_t *h, int32_t n_cand, const int32_t *base_placement, const int32_t *base_rank,
                      const uint32_t *rnd, int32_t *placement, int32_t *rank, void *hip_stream);
+int dagsched_propose_orders(dagsched_t *h, int32_t n_cand, const int32_t *base_placement, const int32_t *base_rank,
+                            const uint32_t *rnd, int32_t *placement, int32_t *rank, void *hip_stream);
 int dagsched_select(dagsched_t *h, int32_t n_cand, const int32_t *makespan, const int32_t *flags, int32_t *best,
                     void *hip_stream);
 int dagsched_schedule(dagsched_t *h, const int32_t *placement, const int32_t *rank, int32_t *start, int32_t *end,

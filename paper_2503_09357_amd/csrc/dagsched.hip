@@ -871,8 +871,9 @@ void dagsched_destroy(dagsched_t *h) {
   free_handle(h);
 }
 
-int dagsched_propose(dagsched_t *h, int32_t n_cand, const int32_t *base_placement, const int32_t *base_rank,
-                     const uint32_t *rnd, int32_t *placement, int32_t *rank, void *hip_stream) {
+namespace {
+int launch_propose(dagsched_t *h, int32_t n_cand, const int32_t *base_placement, const int32_t *base_rank,
+                   const uint32_t *rnd, int32_t *placement, int32_t *rank, void *hip_stream, int orders_only) {
   if (!h || n_cand < 0 || n_cand > h->max_cand) return DAGSCHED_EINVAL;
   if (n_cand == 0) return DAGSCHED_OK;
   if (!base_placement || !base_rank || !rnd || !placement || !rank) return DAGSCHED_EINVAL;
@@ -881,12 +882,24 @@ int dagsched_propose(dagsched_t *h, int32_t n_cand, const int32_t *base_placemen
   ProposeParams p;
   p.N = h->N; p.P = h->P; p.C = n_cand;
   p.base_pl = base_placement; p.base_rk = base_rank; p.rnd = rnd; p.cnt = h->ws_cnt;
-  p.out_pl = placement; p.out_rk = rank;
+  p.out_pl = placement; p.out_rk = rank; p.orders_only = orders_only;
   if (h->layout == DAGSCHED_CAND_MAJOR) { p.stride_c = h->N; p.stride_n = 1; }
   else { p.stride_c = 1; p.stride_n = n_cand; }
   hipLaunchKernelGGL(propose_kernel, dim3((unsigned)n_cand), dim3(256), 0, stream, p);
   if (!hip_ok(hipGetLastError(), "kernel launch")) return DAGSCHED_EHIP;
   return DAGSCHED_OK;
+}
+
+}  // namespace
+
+int dagsched_propose(dagsched_t *h, int32_t n_cand, const int32_t *base_placement, const int32_t *base_rank,
+                     const uint32_t *rnd, int32_t *placement, int32_t *rank, void *hip_stream) {
+  return launch_propose(h, n_cand, base_placement, base_rank, rnd, placement, rank, hip_stream, 0);
+}
+
+int dagsched_propose_orders(dagsched_t *h, int32_t n_cand, const int32_t *base_placement, const int32_t *base_rank,
+                            const uint32_t *rnd, int32_t *placement, int32_t *rank, void *hip_stream) {
+  return launch_propose(h, n_cand, base_placement, base_rank, rnd, placement, rank, hip_stream, 1);
 }
 
 int dagsched_select(dagsched_t *h, int32_t n_cand, const int32_t *makespan, const int32_t *flags, int32_t *best,

@@ -28,6 +28,7 @@ struct ProposeParams {
   const int32_t *cnt;                  // [P] operations per machine of the base
   int32_t *out_pl, *out_rk;            // entry (c, i) at c * stride_c + i * stride_n
   int64_t stride_c, stride_n;
+  int32_t orders_only;                 // 1: moves stay on the operation's machine
 };
 
 // Candidate 0 = the base.  Candidate c >= 1 = the base with one move, (r0, r1, r2, r3) = rnd[4c .. 4c+3],
@@ -35,6 +36,7 @@ struct ProposeParams {
 //   r0 even: v trades places with the operation after it on m (nothing if it is the last);
 //   r0 odd:  m2 = r2 mod P; m2 == m: v is re-inserted at position r3 mod n_m of m;
 //            m2 != m: v is inserted at position r3 mod (n_m2 + 1) of m2.
+// orders_only: m2 = m whatever r2 is (the candidates keep the base's placement).
 // One workgroup per candidate; the move is the same for every thread, each thread rewrites some operations.
 __global__ __launch_bounds__(256) void propose_kernel(ProposeParams p) {
   const int c = blockIdx.x;
@@ -53,7 +55,7 @@ __global__ __launch_bounds__(256) void propose_kernel(ProposeParams p) {
       if ((r0 & 1u) == 0u) {
         if (r + 1 < n_m) mode = kSwap;
       } else {
-        m2 = (int32_t)(r2 % (uint32_t)p.P);
+        m2 = p.orders_only ? m : (int32_t)(r2 % (uint32_t)p.P);
         if (m2 == m) {
           r_new = (int32_t)(r3 % (uint32_t)n_m);
           mode = kWithin;

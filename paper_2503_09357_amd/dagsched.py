@@ -20,7 +20,7 @@ CAND_MAJOR, CAND_MINOR = 0, 1
 MAX_DEVICES, MAX_NODES = 64, 65535
 
 EXPORTS = ("dagsched_validate", "dagsched_create", "dagsched_evaluate", "dagsched_destroy",
-           "dagsched_strerror", "dagsched_get_info", "dagsched_time_evaluate", "dagsched_propose", "dagsched_select",
+           "dagsched_strerror", "dagsched_get_info", "dagsched_time_evaluate", "dagsched_propose", "dagsched_propose_orders", "dagsched_select",
            "dagsched_schedule")
 
 
@@ -80,6 +80,8 @@ def load(import_torch_first: bool = True):
     lib.dagsched_get_info.argtypes = [vp, ctypes.POINTER(Info)]
     lib.dagsched_propose.restype = ctypes.c_int
     lib.dagsched_propose.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp]
+    lib.dagsched_propose_orders.restype = ctypes.c_int
+    lib.dagsched_propose_orders.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp]
     lib.dagsched_select.restype = ctypes.c_int
     lib.dagsched_select.argtypes = [vp, i32, vp, vp, vp, vp]
     lib.dagsched_schedule.restype = ctypes.c_int
@@ -276,10 +278,10 @@ class Evaluator:
                                              ctypes.byref(ms)))
         return float(ms.value)
 
-    def propose(self, base_placement, base_rank, rnd, out: Optional[Tuple] = None, stream=None):
+    def propose(self, base_placement, base_rank, rnd, out: Optional[Tuple] = None, stream=None, orders_only: bool = False):
         """One-move neighbourhood of a base schedule (device int32 [N] each); ``rnd`` is a device tensor of
         4 * n_cand random 32-bit words (int32 or uint32 storage).  Returns (placement, rank) in the handle's
-        layout; candidate 0 is the base."""
+        layout; candidate 0 is the base.  orders_only: every candidate keeps the base's placement."""
         import torch
         n_cand = rnd.numel() // 4
         dev = torch.device("cuda", self.hip_device)
@@ -287,8 +289,9 @@ class Evaluator:
             shape = (n_cand, self.N) if self.layout == CAND_MAJOR else (self.N, n_cand)
             out = (torch.empty(shape, dtype=torch.int32, device=dev), torch.empty(shape, dtype=torch.int32, device=dev))
         s = torch.cuda.current_stream(self.hip_device) if stream is None else stream
-        _check(load().dagsched_propose(self._h, n_cand, base_placement.data_ptr(), base_rank.data_ptr(), rnd.data_ptr(),
-                                       out[0].data_ptr(), out[1].data_ptr(), s.cuda_stream))
+        call = load().dagsched_propose_orders if orders_only else load().dagsched_propose
+        _check(call(self._h, n_cand, base_placement.data_ptr(), base_rank.data_ptr(), rnd.data_ptr(),
+                    out[0].data_ptr(), out[1].data_ptr(), s.cuda_stream))
         return out
 
     def select(self, makespan, flags, out=None, stream=None):

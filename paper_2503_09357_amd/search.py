@@ -15,9 +15,11 @@ from typing import List, Optional, Tuple
 CAND_MAJOR = 0
 
 
-def local_search(ev, base_placement, base_rank, iterations: int, n_cand: int, seed: int = 0
-                 ) -> Tuple["torch.Tensor", "torch.Tensor", List[int]]:
-    """Hill-climb from a valid base schedule (device int32 [N] tensors).
+def local_search(ev, base_placement, base_rank, iterations: int, n_cand: int, seed: int = 0,
+                 orders_only: bool = False) -> Tuple["torch.Tensor", "torch.Tensor", List[int]]:
+    """Hill-climb from a valid base schedule (device int32 [N] tensors).  orders_only: keep the base's placement and
+    search the orders alone (an evaluator made with that placement as ``shared_placement`` then stays on its
+    fast kernel for the whole search).
 
     Returns (placement [N], rank [N], makespan after every iteration, fetched once at the end)."""
     import torch
@@ -30,7 +32,7 @@ def local_search(ev, base_placement, base_rank, iterations: int, n_cand: int, se
     best = torch.empty((iterations, 2), dtype=torch.int32, device=dev)
     for it in range(iterations):
         rnd = torch.randint(0, 2 ** 31 - 1, (4 * n_cand,), dtype=torch.int32, device=dev, generator=gen)
-        cand = ev.propose(pl, rk, rnd, out=cand)
+        cand = ev.propose(pl, rk, rnd, out=cand, orders_only=orders_only)
         z, _, _, f = ev.evaluate(cand[0], cand[1], out)
         ev.select(z, f, out=best[it])
         idx = best[it, 0:1].clamp(min=0).to(torch.int64)      # no feasible candidate cannot happen: candidate 0 is the base

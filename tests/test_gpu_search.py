@@ -33,10 +33,17 @@ def test_propose_matches_the_oracle(gpu_lib, layout):
                                 torch.from_numpy(rnd.view(np.int32)).to(_dev()))
             torch.cuda.synchronize()
             got_pl, got_rk = pl.cpu().numpy(), rk.cpu().numpy()
+            pl2, rk2 = ev.propose(torch.from_numpy(w.placement[0]).to(_dev()), torch.from_numpy(w.rank[0]).to(_dev()),
+                                  torch.from_numpy(rnd.view(np.int32)).to(_dev()), orders_only=True)
+            torch.cuda.synchronize()
+            got_pl2, got_rk2 = pl2.cpu().numpy(), rk2.cpu().numpy()
         want_pl, want_rk = SO.propose(w.placement[0], w.rank[0], rnd, w.n_devices)
+        want_pl2, want_rk2 = SO.propose(w.placement[0], w.rank[0], rnd, w.n_devices, orders_only=True)
         if layout == 1:
-            got_pl, got_rk = got_pl.T, got_rk.T
+            got_pl, got_rk, got_pl2, got_rk2 = got_pl.T, got_rk.T, got_pl2.T, got_rk2.T
         assert (got_pl == want_pl).all() and (got_rk == want_rk).all(), w.name
+        assert (got_pl2 == want_pl2).all() and (got_rk2 == want_rk2).all(), w.name
+        assert (got_pl2 == w.placement[0]).all()
 
 
 def test_select_matches_the_oracle(gpu_lib):
@@ -104,6 +111,33 @@ def test_local_search_never_gets_worse_and_ends_valid(gpu_lib, layout, tmp_path)
     path = os.path.join(tmp_path, "trace.json")
     search.chrome_trace(path, s.cpu().tolist(), e.cpu().tolist(), pl.cpu().tolist())
     assert len(json.load(open(path))["traceEvents"]) == w.n_nodes
+
+
+def test_search_over_the_orders_alone_stays_on_the_shared_placement_kernel(gpu_lib):
+    """The pipeline search of Sec. V: the stage -> machine map is given, the orders are searched.  With the base's
+    placement as the hint and moves that keep it, every batch is evaluated by the shared-placement kernel."""
+    import torch
+    from paper_2503_09357_amd import search
+    from test_gpu_parity import _with_env
+    ds = gpu_lib
+    w = W.gen_config(2, n_cand=1)
+    prob = oracle.Problem.of(w)
+    z0 = int(prob.evaluate(w.placement, w.rank)[0][0])
+
+    def go():
+        with ds.Evaluator.for_workload(w, max_candidates=2048, shared_placement=w.placement[0]) as ev:
+            assert ev.info()["variant"] == 6, ev.info()
+            pl, rk, hist = search.local_search(ev, torch.from_numpy(w.placement[0]).to(_dev()),
+                                               torch.from_numpy(w.rank[0]).to(_dev()), iterations=15, n_cand=2048, seed=5,
+                                               orders_only=True)
+            torch.cuda.synchronize()
+            return pl.cpu().numpy(), rk.cpu().numpy(), hist
+
+    pl, rk, hist = _with_env({"DAGSCHED_NO_SHARED_PLACEMENT": 0, "DAGSCHED_STATIC_WAVES": 2}, go)
+    assert (pl == w.placement[0]).all()
+    assert hist[0] <= z0 and all(b <= a for a, b in zip(hist, hist[1:])) and hist[-1] < z0
+    zo, _, _, fo = prob.evaluate(pl[None, :], rk[None, :])
+    assert fo[0] == 0 and int(zo[0]) == hist[-1]
 
 
 def test_cycles_and_range_stops_are_told_apart(gpu_lib):
