@@ -31,6 +31,17 @@ __device__ __forceinline__ void st_agent(int32_t *p, int32_t v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// LDS pointers with an explicit address space: volatile accesses through generic pointers would be
+// compiled to flat loads, these compile to ds_read/ds_write.
+#define DAGSCHED_LDS __attribute__((address_space(3)))
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef DAGSCHED_LDS unsigned char lds_byte_t;
+typedef DAGSCHED_LDS volatile uint32_t lds_vu32_t;
+typedef DAGSCHED_LDS volatile uint16_t lds_vu16_t;
+typedef DAGSCHED_LDS volatile int32_t lds_vi32_t;
+typedef DAGSCHED_LDS const uint8_t lds_cu8_t;
+typedef DAGSCHED_LDS volatile u32x4_t lds_vu32x4_t;
+
 // Where the outputs of one evaluate call go.
 struct OutPtrs {
   int32_t *makespan;

@@ -45,17 +45,6 @@
 
 namespace dagsched_dev {
 
-// LDS pointers with an explicit address space: volatile accesses through generic pointers would be
-// compiled to flat loads, these compile to ds_read/ds_write.
-#define DAGSCHED_LDS __attribute__((address_space(3)))
-typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
-typedef DAGSCHED_LDS unsigned char lds_byte_t;
-typedef DAGSCHED_LDS volatile uint32_t lds_vu32_t;
-typedef DAGSCHED_LDS volatile uint16_t lds_vu16_t;
-typedef DAGSCHED_LDS volatile int32_t lds_vi32_t;
-typedef DAGSCHED_LDS const uint8_t lds_cu8_t;
-typedef DAGSCHED_LDS volatile u32x4_t lds_vu32x4_t;
-
 // Op layout (one 16-byte slot).  ha(x) is the 16-bit address of the end-time cell of x: its LDS byte
 // address when the end-time arrays of the workgroup fit 64 KB (template HALF = 0), else the byte
 // address / 2 (HALF = 1); with 32-bit end times (HALF = 2, see below) the byte address / 4.  The arrays come first in

@@ -30,7 +30,6 @@
 #pragma once
 
 #include "device_common.h"
-#include "kernel_ring.h"   // LDS pointer types
 
 namespace dagsched_dev {
 
