@@ -172,16 +172,22 @@ def test_cycles_and_range_stops_are_told_apart(gpu_lib):
 
 
 
-def test_search_step_replays_from_a_hip_graph(gpu_lib):
+@pytest.mark.parametrize("shared", [False, True])
+def test_search_step_replays_from_a_hip_graph(gpu_lib, shared):
     """propose -> evaluate -> select enqueue kernels only (no allocation, no memset node), so one search step can
-    be captured once and replayed; every replay must give what the eager calls give."""
+    be captured once and replayed; every replay must give what the eager calls give.  With the MoE workload the
+    optimistic 16-bit kernel runs (counter reset + fallback kernel inside); with the pipeline and its placement as
+    the hint the shared-placement kernel does, and the moves across machines are its strangers."""
     import torch
+    import test_gpu_parity as T
     ds = gpu_lib
     rng = np.random.default_rng(5506)
-    w = W.gen_config(4, n_cand=1)                      # optimistic 16-bit mode: counter reset + fallback kernel inside
+    w = W.gen_config(2 if shared else 4, n_cand=1)
     C = 256
     dev = _dev()
-    with ds.Evaluator.for_workload(w, max_candidates=C) as ev:
+    make = lambda: ds.Evaluator.for_workload(w, max_candidates=C, shared_placement=w.placement[0] if shared else None)
+    with T._with_env({"DAGSCHED_NO_SHARED_PLACEMENT": 0, "DAGSCHED_STATIC_WAVES": 2}, make) as ev:
+        assert ev.info()["variant"] == (6 if shared else 4), ev.info()
         base_pl = torch.from_numpy(w.placement[0]).to(dev)
         base_rk = torch.from_numpy(w.rank[0]).to(dev)
         rnd = torch.zeros(4 * C, dtype=torch.int32, device=dev)
