@@ -59,8 +59,8 @@ enum {
   DAGSCHED_FLAG_INTERNAL = 8,      /* a kernel's bounded wait expired; never expected, the candidate's other
                                       outputs are -1.  Reported instead of hanging the GPU. */
   DAGSCHED_FLAG_OVER_MEMORY = 16   /* tested last: otherwise feasible, but some peak_mem[j] > mem_limit[j]
-                                      ("not exceeding the memory limit of any machine", Sec. III problem
-                                      statement; the paper prints no inequality for it) */
+                                      (the per-machine memory limit of the problem statement of Sec. III and of
+                                      the bounds of Sec. V-A; the paper prints no inequality for it) */
 };
 
 /* Memory layout of placement, rank and peak_mem. */
@@ -77,11 +77,12 @@ enum {
 #define DAGSCHED_MAX_NODES 65535
 
 /*
- * Optional launch shape of the 16-bit evaluation kernel.  dagsched_create chooses a shape by itself from the
+ * Optional launch shape of the evaluation kernels.  dagsched_create chooses a shape by itself from the
  * problem's size; a caller that evaluates very many batches of one problem can time a few shapes on a batch of
  * its own (dagsched_time_evaluate) and keep the fastest.  Every field: 0 = chosen by the library
  * (placement_mode: -1).  A shape that is not built or does not fit the GPU's LDS makes the library fall back
- * to its general int32 kernel (dagsched_get_info tells); results never depend on the shape.
+ * to its general int32 kernel (dagsched_get_info tells); results never depend on the shape.  The library reads
+ * no environment variable: this struct is the only way to steer the choice.
  */
 typedef struct {
   int32_t cand_per_block;   /* candidates per workgroup: a power of two, at most 64 / (P rounded up to a power of two) */
@@ -92,6 +93,12 @@ typedef struct {
   int32_t block_threads;    /* workgroup size: a multiple of 64, at least 64 * (2 + feeders), at most 1024  */
   int32_t state_bits;       /* width of the end times kept on chip: 16 (twice the candidates resident; candidates
                                whose end times leave the range are evaluated by the int32 kernel one by one) or 32 */
+  int32_t preds_per_op;     /* 4: the kernel kind that reads four predecessors per op and splits operations with
+                               more into parts, also where a leaner kind (single parts, two predecessors) applies */
+  int32_t kernel;           /* 1: the general int32 kernel, whatever else would apply                        */
+  int32_t static_waves;     /* relaxing wavefronts per workgroup of the shared-placement kernel (1..8); naming it
+                               also makes small handles take that kernel                                     */
+  int32_t ignore_shared_placement; /* 1: dagsched_desc_t.shared_placement is not used                        */
 } dagsched_shape_t;
 
 /*
@@ -210,9 +217,28 @@ typedef struct {
   int32_t block_threads;   /* workgroup size */
   int32_t lds_bytes;       /* dynamic LDS per workgroup */
   int32_t state_bits;      /* width of the per-node end-time state (16 or 32) */
-  int32_t reserved[3];
+  int16_t ring_slots;      /* ring kernel: slots per lane of the op ring, else 0 */
+  int8_t kernel_kind;      /* ring kernel: 0 operations split into parts of four predecessors, 1 every operation a
+                              single part, 2 at most two predecessors per operation */
+  int8_t wide_ops;         /* ring kernel: 1 when ops name machines instead of delays (delays above 255 or durations
+                              above 65534 after the common factor is divided out) */
+  int32_t time_scale;      /* common factor of every duration and delay, divided out inside the kernels */
+  int8_t feeders;          /* ring kernel: feeder wavefronts per workgroup */
+  int8_t placement_mode;   /* ring kernel: where the placement bytes sit (0 L2, 1 LDS, 2 LDS as four bits per node) */
+  int8_t preds_per_op;     /* predecessors read per op: 2 or 4 (ring and shared-placement kernels) */
+  int8_t reserved;
 } dagsched_info_t;
 int dagsched_get_info(const dagsched_t *h, dagsched_info_t *info);
+
+/*
+ * How many candidates of the handle's LAST evaluate were handed to the general int32 kernel one by one: those
+ * whose end times left the 16-bit range of an optimistic run (variant 4), or that do not use the shared placement
+ * (variant 6).  That path is an order of magnitude slower per candidate, so a caller who sees a large count should
+ * ask for 32-bit state (dagsched_shape_t.state_bits) or drop the hint.  Synchronises hip_stream, the stream the
+ * evaluate was enqueued on, and copies one word to the host: not for the asynchronous path.  *count = 0 for
+ * variants without such a list.
+ */
+int dagsched_last_fallbacks(dagsched_t *h, void *hip_stream, int32_t *count);
 
 /*
  * Timing aid: evaluate `reps` times back to back on hip_stream between two HIP events recorded on

@@ -45,11 +45,6 @@ def _load():
         vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
         lib.dagsched_oracle_check_problem.restype = ctypes.c_int
         lib.dagsched_oracle_check_problem.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp]
-        lib.dagsched_oracle_evaluate.restype = ctypes.c_int
-        lib.dagsched_oracle_evaluate.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, i32, i64, vp, vp, i64, i64,
-                                                 vp, vp, vp, vp]
-        lib.dagsched_oracle_schedule.restype = ctypes.c_int
-        lib.dagsched_oracle_schedule.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         lib.dagsched_oracle_evaluate_mem.restype = ctypes.c_int
         lib.dagsched_oracle_evaluate_mem.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, i32, i64, vp, vp,
                                                      i64, i64, vp, vp, vp, vp]

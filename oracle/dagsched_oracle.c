@@ -290,17 +290,6 @@ int dagsched_oracle_evaluate_mem(int32_t N, int32_t E, int32_t P, const int32_t 
   return OR_OK;
 }
 
-/* The same without static memory and without limits. */
-int dagsched_oracle_evaluate(int32_t N, int32_t E, int32_t P, const int32_t *row_ptr,
-                             const int32_t *col_idx, const int32_t *dur, const int32_t *comm,
-                             const int64_t *mem_delta, int32_t layout, int64_t n_cand,
-                             const int32_t *placement, const int32_t *rank, int64_t first,
-                             int64_t count, int32_t *makespan, int64_t *bubble, int64_t *peak_mem,
-                             int32_t *flags) {
-  return dagsched_oracle_evaluate_mem(N, E, P, row_ptr, col_idx, dur, comm, mem_delta, NULL, NULL, layout, n_cand,
-                                      placement, rank, first, count, makespan, bubble, peak_mem, flags);
-}
-
 /*
  * The full earliest-start schedule of ONE candidate (placement[N], rank[N]), for the constraint
  * checker: start/end times (eqs. (2),(3)) and memory level before/after every operation
@@ -343,12 +332,4 @@ int dagsched_oracle_schedule_mem(int32_t N, int32_t E, int32_t P, const int32_t 
   free(peak);
   scratch_free(&w);
   return f;
-}
-
-int dagsched_oracle_schedule(int32_t N, int32_t E, int32_t P, const int32_t *row_ptr,
-                             const int32_t *col_idx, const int32_t *dur, const int32_t *comm,
-                             const int64_t *mem_delta, const int32_t *placement, const int32_t *rank,
-                             int64_t *start, int64_t *end, int64_t *m_minus, int64_t *m_plus) {
-  return dagsched_oracle_schedule_mem(N, E, P, row_ptr, col_idx, dur, comm, mem_delta, NULL, placement, rank, start,
-                                      end, m_minus, m_plus);
 }

@@ -5,8 +5,8 @@ Two shared libraries live beside this file once built:
 * ``libdagsched.so``          - HIP kernels for gfx950 plus the C-ABI (csrc/dagsched.hip)
 * ``libdagsched_workload.so`` - seeded synthetic candidate generator (csrc/workload_gen.c)
 
-Nothing here is executed on import; ``ensure_*`` build only when the library is absent,
-``build_*`` always recompile.
+Nothing here is executed on import; ``ensure_*`` build when the library is absent or older than
+its sources, ``build_*`` always recompile.
 """
 from __future__ import annotations
 
@@ -78,8 +78,16 @@ def ensure_workload_gen() -> str:
     return GEN_LIB
 
 
+def hip_sources():
+    """Every file the HIP library is compiled from: the kernels, the host code and the public header."""
+    import glob
+    return sorted(glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(CSRC, "*.hip")) +
+                  glob.glob(os.path.join(INCLUDE, "*.h")))
+
+
 def ensure_hip() -> str:
-    """Return the built HIP library, compiling it only when no library is there."""
-    if not os.path.exists(HIP_LIB):
+    """Return the built HIP library; compile it when it is absent or older than one of its sources (where no
+    compiler is at hand, as on a box that only runs what was built elsewhere, a stale library is an error)."""
+    if _stale(HIP_LIB, hip_sources()):
         build_hip()
     return HIP_LIB

@@ -24,6 +24,8 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <map>
+#include <mutex>
 #include <new>
 #include <numeric>
 #include <vector>
@@ -120,6 +122,9 @@ int validate_desc(const dagsched_desc_t *d, std::vector<int32_t> *pred_ptr, std:
     if (sh->feeders < 0 || sh->feeders > 4 || sh->placement_mode < -1 || sh->placement_mode > 2) return DAGSCHED_EINVAL;
     if (b < 0 || b > 1024 || b % kWave) return DAGSCHED_EINVAL;
     if (sh->state_bits != 0 && sh->state_bits != 16 && sh->state_bits != 32) return DAGSCHED_EINVAL;
+    if (sh->preds_per_op != 0 && sh->preds_per_op != 4) return DAGSCHED_EINVAL;
+    if (sh->kernel < 0 || sh->kernel > 1 || sh->static_waves < 0 || sh->static_waves > 8) return DAGSCHED_EINVAL;
+    if (sh->ignore_shared_placement < 0 || sh->ignore_shared_placement > 1) return DAGSCHED_EINVAL;
   }
   if (d->row_ptr[0] != 0 || d->row_ptr[N] != E) return DAGSCHED_EINVAL;
   for (int32_t u = 0; u < N; ++u)
@@ -198,11 +203,6 @@ void free_handle(dagsched *h) {
   delete h;
 }
 
-int env_int(const char *name, int dflt) {
-  const char *s = getenv(name);
-  return (s && *s) ? atoi(s) : dflt;
-}
-
 // pib_lds: 0 placement bytes in L2, 1 in LDS, 2 in LDS as nibbles (P <= 16)
 // cell_bytes: 2 (16-bit end times) or 4
 LdsLayout ring_layout(int N, int P, int G, int ring, int pib_lds, int cell_bytes, bool wide) {
@@ -224,6 +224,7 @@ LdsLayout ring_layout(int N, int P, int G, int ring, int pib_lds, int cell_bytes
   o.o_off = at;   at += kWave * 4u;
   o.o_flag = at;  at += kWave * 4u;
   o.o_abort = at; at += kWave * 4u;
+  o.o_over = at;  at += kWave;
   o.wide = wide ? 1u : 0u;
   // channel delays: a byte each, rows [source machine + the dummy's][destination]; wide ops: a dword each, 64 rows
   o.o_comm = at;  at += wide ? (uint32_t)kWave * (uint32_t)next_pow2(P) * 4u
@@ -337,10 +338,10 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
     if (total_parts >= 65536) return plan;
   }
   // kernel kind: 2 when no operation has more than two DAG predecessors, 1 when none has more than four (every
-  // operation is a single part), 0 otherwise (or when DAGSCHED_RING_PREDS=4 asks for the general kernels)
+  // operation is a single part), 0 otherwise (or when the caller's shape asks for four predecessors per op)
   size_t max_deg = 0;
   for (int v = 0; v < N; ++v) max_deg = std::max(max_deg, op_preds[v].size());
-  plan.kind = env_int("DAGSCHED_RING_PREDS", 2) == 4 ? 0 : max_deg <= 2 ? 2 : max_parts == 1 ? 1 : 0;
+  plan.kind = (d->shape && d->shape->preds_per_op == 4) ? 0 : max_deg <= 2 ? 2 : max_parts == 1 ? 1 : 0;
   const int plane = N;
   std::vector<uint4> rec((size_t)max_parts * plane, make_uint4(dummy | (dummy << 16), dummy | (dummy << 16), 0, 0));
   for (int v = 0; v < N; ++v) {
@@ -389,23 +390,20 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
   // four-slot ring counts 0.7 (hot lanes outrun it), placement bytes in L2 count 0.97, and workgroups beyond
   // five per CU count nothing, half-empty wavefronts count 0.65 (the feeders do the same work for half the
   // candidates); at equal counts, more workgroups of fewer candidates.
-  // a shape given with the description wins over the environment (which the tests use), field by field
+  // a shape given with the description wins, field by field
   const dagsched_shape_t *sh = d->shape;
   // Width of the end times.  16 bits when every end time provably fits, or when most candidates can be expected to
   // fit (the rest then go to the int32 kernel one by one); 32 bits (half the candidates resident, always exact)
   // when they cannot: makespans of list schedules lie around three times the lower bound.
-  int64_t max_dur_scaled = 0;
-  for (int v = 0; v < N; ++v) max_dur_scaled = std::max<int64_t>(max_dur_scaled, d->dur[v] / g);
-  const int force_bits = sh && sh->state_bits ? sh->state_bits : env_int("DAGSCHED_RING_STATE_BITS", 0);
+  const int force_bits = sh ? sh->state_bits : 0;
   const bool fits16 = upper + 255 < (int64_t)kNotDone16;
   plan.cell32 = wide || force_bits == 32 || (force_bits != 16 && !fits16 && 3 * lower >= (int64_t)kNotDone16);
-  (void)max_dur_scaled;
   if (!plan.cell32 && lower >= (int64_t)kNotDone16) return plan;   // 16 bits asked for, and no candidate could stay inside them
   const int cell_bytes = plan.cell32 ? 4 : 2;
-  const int force_g = sh && sh->cand_per_block ? sh->cand_per_block : env_int("DAGSCHED_RING_G", 0);
-  const int force_ring = sh && sh->ring_slots ? sh->ring_slots : env_int("DAGSCHED_RING_SLOTS", 0);
-  const int force_feeders = sh && sh->feeders ? sh->feeders : env_int("DAGSCHED_RING_FEEDERS", 0);
-  const int force_pib = sh && sh->placement_mode >= 0 ? sh->placement_mode : env_int("DAGSCHED_RING_PIB_LDS", -1);
+  const int force_g = sh ? sh->cand_per_block : 0;
+  const int force_ring = sh ? sh->ring_slots : 0;
+  const int force_feeders = sh ? sh->feeders : 0;
+  const int force_pib = sh ? sh->placement_mode : -1;
   int64_t best_score = -1;
   int best_wgs = 0;
   for (int G = kWave / Pseg; G >= 1; G >>= 1) {
@@ -446,7 +444,7 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
   // workgroup size: the wavefronts with a role, plus helpers for the ingest phase when the LDS leaves the CU
   // nearly empty of wavefronts (one workgroup per CU: 1024 threads, two: 512)
   plan.block = ring_threads(plan.feeders);
-  const int force_block = sh && sh->block_threads ? sh->block_threads : env_int("DAGSCHED_RING_BLOCK", 0);
+  const int force_block = sh ? sh->block_threads : 0;
   if (force_block >= plan.block && force_block <= 1024 && force_block % kWave == 0) plan.block = force_block;
   else if (best_wgs == 1) plan.block = 1024;
   else if (best_wgs == 2) plan.block = std::max(plan.block, 512);
@@ -574,7 +572,7 @@ StaticPlan plan_static(const dagsched_desc_t *d, const std::vector<int32_t> &pre
   plan.cand_stride = align_up(cells + list, 16u);
   const int lds_cu = 160 * 1024;
   int best_w = 0, best_score = -1;
-  const int forced_w = env_int("DAGSCHED_STATIC_WAVES", 0);
+  const int forced_w = d->shape ? d->shape->static_waves : 0;
   for (int w = 1; w <= 8; ++w) {
     if (plan.G * w > kWave) break;                     // 64 flag words per workgroup
     if (forced_w && w != forced_w) continue;
@@ -596,6 +594,20 @@ StaticPlan plan_static(const dagsched_desc_t *d, const std::vector<int32_t> &pre
   plan.total = plan.o_book + 1024u + 512u * (uint32_t)plan.W;
   plan.ok = true;
   return plan;
+}
+
+// A kernel that asks for more than 48 KB of dynamic LDS must be allowed to.  The attribute belongs to the kernel
+// function (per device), not to a handle: it is only ever raised, so that a handle made later with a smaller
+// footprint never takes away what an earlier handle on the same kernel instantiation needs.
+bool allow_large_lds(const void *kernel, int device, int bytes) {
+  static std::mutex mu;
+  static std::map<std::pair<const void *, int>, int> allowed;
+  std::lock_guard<std::mutex> lock(mu);
+  int &have = allowed[{kernel, device}];
+  if (bytes <= have) return true;
+  if (!hip_ok(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes), "hipFuncSetAttribute")) return false;
+  have = bytes;
+  return true;
 }
 
 size_t channel_flag_lds(int32_t n_nodes) {               // mask words + one byte per node
@@ -747,8 +759,8 @@ int dagsched_create(const dagsched_desc_t *caller_desc, dagsched_t **out) {
 
   RingPlan plan;
   StaticPlan splan;
-  const bool force_general = env_int("DAGSCHED_FORCE_GENERAL", 0) != 0;
-  if (!force_general && desc->shared_placement && !env_int("DAGSCHED_NO_SHARED_PLACEMENT", 0))
+  const bool force_general = desc->shape && desc->shape->kernel == 1;
+  if (!force_general && desc->shared_placement && !(desc->shape && desc->shape->ignore_shared_placement))
     splan = plan_static(desc, pred_ptr, pred_idx, sum_dur, lds_max, n_cu);
   if (!force_general && !splan.ok) plan = plan_ring(desc, pred_ptr, pred_idx, sum_dur, lds_max);
   const bool need_general = splan.ok || !plan.ok || !plan.exact;
@@ -764,9 +776,7 @@ int dagsched_create(const dagsched_desc_t *caller_desc, dagsched_t **out) {
        (!any_missing || (upload(&h->d_no_channel, no_channel.data(), no_channel.size()) &&
                          upload(&h->d_edges, edges.data(), edges.size()) &&
                          (channel_flag_lds(h->N) <= 48 * 1024 ||
-                          hip_ok(hipFuncSetAttribute((const void *)channel_flag_kernel,
-                                                     hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                     (int)channel_flag_lds(h->N)), "hipFuncSetAttribute")))) &&
+                          allow_large_lds((const void *)channel_flag_kernel, h->device, (int)channel_flag_lds(h->N))))) &&
        dev_alloc(&h->ws_cnt, (size_t)DAGSCHED_MAX_DEVICES) &&
        dev_alloc(&h->ws_sched_list, (size_t)h->row_stride) && dev_alloc(&h->ws_sched_end, (size_t)h->row_stride) &&
        dev_alloc(&h->ws_sched_out, (size_t)(32 + 8 * DAGSCHED_MAX_DEVICES));
@@ -778,8 +788,7 @@ int dagsched_create(const dagsched_desc_t *caller_desc, dagsched_t **out) {
     ok = dev_alloc(&h->ws_list, maxc * (size_t)h->row_stride);
     if (ok && !h->gen_lds_state) ok = dev_alloc(&h->ws_end, maxc * (size_t)h->row_stride);
     if (ok && h->gen_lds > 48 * 1024)
-      ok = hip_ok(hipFuncSetAttribute((const void *)relax_general_kernel<true>,
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, h->gen_lds), "hipFuncSetAttribute");
+      ok = allow_large_lds((const void *)relax_general_kernel<true>, h->device, h->gen_lds);
     h->variant = h->gen_lds_state ? kVariantGeneralLds : kVariantGeneralGlobal;
   }
   if (ok && splan.ok) {
@@ -801,8 +810,7 @@ int dagsched_create(const dagsched_desc_t *caller_desc, dagsched_t **out) {
     s.o_mem = splan.o_mem; s.o_mach = splan.o_mach; s.o_cand = splan.o_cand; s.cand_stride = splan.cand_stride; s.o_list = splan.o_list; s.o_book = splan.o_book;
     s.total = splan.total;
     if (ok && s.total > 48 * 1024)
-      ok = hip_ok(hipFuncSetAttribute(splan.preds == 2 ? (const void *)relax_static_kernel<2> : (const void *)relax_static_kernel<4>,
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)s.total), "hipFuncSetAttribute");
+      ok = allow_large_lds(splan.preds == 2 ? (const void *)relax_static_kernel<2> : (const void *)relax_static_kernel<4>, h->device, (int)s.total);
   }
   if (ok && plan.ok) {
     h->variant = plan.cell32 ? kVariantRing32 : plan.exact ? kVariantRingExact : kVariantRingOptimistic;
@@ -817,8 +825,7 @@ int dagsched_create(const dagsched_desc_t *caller_desc, dagsched_t **out) {
          (plan.lds.pib_mode != 0 || dev_alloc(&h->ws_pib, maxc * (size_t)h->pib_stride));   // only read when the placement is not in LDS
     if (ok && !plan.exact) ok = dev_alloc(&h->d_fb_count, 1) && dev_alloc(&h->d_fb_list, maxc);
     if (ok && h->lds.total > 48 * 1024)
-      ok = hip_ok(hipFuncSetAttribute((const void *)ring_kernel_for(h), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                      (int)h->lds.total), "hipFuncSetAttribute");
+      ok = allow_large_lds((const void *)ring_kernel_for(h), h->device, (int)h->lds.total);
   }
   if (ok && h->layout == DAGSCHED_CAND_MINOR)
     ok = dev_alloc(&h->ws_tp, maxc * (size_t)h->N) && dev_alloc(&h->ws_tr, maxc * (size_t)h->N);
@@ -910,12 +917,12 @@ int dagsched_select(dagsched_t *h, int32_t n_cand, const int32_t *makespan, cons
   return DAGSCHED_OK;
 }
 
-int dagsched_schedule(dagsched_t *h, const int32_t *placement, const int32_t *rank, int32_t *start, int32_t *end,
-                      int32_t *flag, void *hip_stream) {
-  if (!h || !placement || !rank || !start || !end || !flag) return DAGSCHED_EINVAL;
-  hipStream_t stream = (hipStream_t)hip_stream;
-  // one candidate through the int32 kernel with its end times in the workspace row
-  unsigned char *o = h->ws_sched_out;
+namespace {
+// One candidate through the int32 kernel with its order list and end times in the given workspace rows (row_stride
+// int32 each; the kernel writes every entry it later reads, so the rows need no clearing), its outputs in `o`
+// (32 + 8 * DAGSCHED_MAX_DEVICES bytes), then start = end - duration.
+int launch_schedule(dagsched_t *h, int32_t *list_row, int32_t *end_row, unsigned char *o, const int32_t *placement,
+                    const int32_t *rank, int32_t *start, int32_t *end, int32_t *flag, hipStream_t stream) {
   GeneralParams p;
   p.N = h->N; p.P = h->P; p.Pseg = h->Pseg; p.G = 1; p.C = 1;
   p.row_stride = h->row_stride;
@@ -923,7 +930,7 @@ int dagsched_schedule(dagsched_t *h, const int32_t *placement, const int32_t *ra
   p.weight = h->d_weight; p.mem_limit = h->d_limit;
   p.sum_dur = h->sum_dur;
   p.placement = placement; p.rank = rank;
-  p.ws_list = h->ws_sched_list; p.ws_end = h->ws_sched_end;
+  p.ws_list = list_row; p.ws_end = end_row;
   p.cand_list = nullptr; p.cand_count = nullptr;
   p.out.makespan = (int32_t *)o; p.out.flags = (int32_t *)(o + 4); p.out.bubble = (int64_t *)(o + 8);
   p.out.peak_mem = (int64_t *)(o + 16); p.out.peak_stride_c = h->P; p.out.peak_stride_j = 1;
@@ -932,9 +939,17 @@ int dagsched_schedule(dagsched_t *h, const int32_t *placement, const int32_t *ra
     hipLaunchKernelGGL(channel_flag_kernel, dim3(1), dim3(1024), channel_flag_lds(h->N), stream, h->N, h->E, h->P,
                        h->d_edges, h->d_no_channel, placement, p.out);
   hipLaunchKernelGGL(schedule_out_kernel, dim3((unsigned)std::min(256, (h->N + 255) / 256)), dim3(256), 0, stream, h->N,
-                     h->d_dur, h->ws_sched_end, (const int32_t *)(o + 4), start, end, flag);
+                     h->d_dur, end_row, (const int32_t *)(o + 4), start, end, flag);
   if (!hip_ok(hipGetLastError(), "kernel launch")) return DAGSCHED_EHIP;
   return DAGSCHED_OK;
+}
+}  // namespace
+
+int dagsched_schedule(dagsched_t *h, const int32_t *placement, const int32_t *rank, int32_t *start, int32_t *end,
+                      int32_t *flag, void *hip_stream) {
+  if (!h || !placement || !rank || !start || !end || !flag) return DAGSCHED_EINVAL;
+  return launch_schedule(h, h->ws_sched_list, h->ws_sched_end, h->ws_sched_out, placement, rank, start, end, flag,
+                         (hipStream_t)hip_stream);
 }
 
 int dagsched_get_info(const dagsched_t *h, dagsched_info_t *info) {
@@ -951,13 +966,31 @@ int dagsched_get_info(const dagsched_t *h, dagsched_info_t *info) {
     info->block_threads = static_threads(h->st.W);
     info->lds_bytes = (int32_t)h->st.total;
     info->state_bits = 16;
-    info->reserved[1] = h->time_scale;
-    info->reserved[2] = h->st_preds << 16;
+    info->time_scale = h->time_scale;
+    info->preds_per_op = (int8_t)h->st_preds;
     return DAGSCHED_OK;
   }
-  info->reserved[0] = ring ? h->ring_slots : 0;
-  info->reserved[1] = h->time_scale;
-  info->reserved[2] = ring ? (h->ring_feeders | ((int)h->lds.pib_mode << 8) | ((h->ring_kind == 2 ? 2 : 4) << 16) | (h->ring_kind << 24) | ((int)h->lds.wide << 28)) : 0;
+  info->time_scale = h->time_scale;
+  if (ring) {
+    info->ring_slots = (int16_t)h->ring_slots;
+    info->feeders = (int8_t)h->ring_feeders;
+    info->placement_mode = (int8_t)h->lds.pib_mode;
+    info->preds_per_op = (int8_t)(h->ring_kind == 2 ? 2 : 4);
+    info->kernel_kind = (int8_t)h->ring_kind;
+    info->wide_ops = (int8_t)h->lds.wide;
+  }
+  return DAGSCHED_OK;
+}
+
+int dagsched_last_fallbacks(dagsched_t *h, void *hip_stream, int32_t *count) {
+  if (!h || !count) return DAGSCHED_EINVAL;
+  *count = 0;
+  const bool has_list = h->d_fb_count && (h->variant == kVariantRingOptimistic || h->variant == kVariantStatic);
+  if (!has_list) return DAGSCHED_OK;
+  if (!hip_ok(hipMemcpyAsync(count, h->d_fb_count, sizeof(int32_t), hipMemcpyDeviceToHost, (hipStream_t)hip_stream),
+              "hipMemcpyAsync") ||
+      !hip_ok(hipStreamSynchronize((hipStream_t)hip_stream), "hipStreamSynchronize"))
+    return DAGSCHED_EHIP;
   return DAGSCHED_OK;
 }
 

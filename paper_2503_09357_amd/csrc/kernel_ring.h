@@ -65,7 +65,7 @@ constexpr int ring_threads(int feeders) { return (2 + feeders) * kWave; }   // r
 //   x = u0 | u1 << 16, y = u2 | u3 << 16, z = dur (30 bits) | first_part << 30 | has_more << 31, w = v << 16
 struct LdsLayout {
   uint32_t s_stride, pi_stride;                       // bytes per candidate; the state array starts at 0
-  uint32_t o_pi, o_ring, o_scr, o_total, o_peak, o_cnt, o_off, o_flag, o_abort, o_comm, total;
+  uint32_t o_pi, o_ring, o_scr, o_total, o_peak, o_cnt, o_off, o_flag, o_abort, o_over, o_comm, total;
   uint32_t pib_mode;                                  // where the placement bytes are: 0 L2 workspace, 1 LDS, 2 LDS as nibbles
   uint32_t cell_bytes;                                // 2: 16-bit end times, 4: 32-bit
   uint32_t wide;                                      // 1: wide ops (machines instead of delays, durations below 256 * 65535)
@@ -140,10 +140,13 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
   int32_t *offw = (int32_t *)(lds + o.o_off);              // [64] start of the machine inside the list
   int32_t *flagw = (int32_t *)(lds + o.o_flag);            // [64] (G used)
   int32_t *abortw = (int32_t *)(lds + o.o_abort);          // [64] (G used) 0, 1 = stopped by the 16-bit range (or internal), 2 = cycle
+  // [64] (G used) 1 = some machine of the candidate is over its memory limit.  Kept apart from flagw, which every
+  // wavefront reads when it takes up its role: the accountant finds this out while the others are already relaxing.
+  uint8_t *overb = lds + o.o_over;
   uint8_t *commb = (uint8_t *)(lds + o.o_comm);            // [(P+1)][Pseg], diagonal and dummy row zero
 
   // ---------------------------------------------------------------- ingest (all wavefronts)
-  if (tid < kWave) { cntw[tid] = 0; totalw[tid] = 0; flagw[tid] = 0; abortw[tid] = 0; peakw[tid] = 0; }
+  if (tid < kWave) { cntw[tid] = 0; totalw[tid] = 0; flagw[tid] = 0; abortw[tid] = 0; peakw[tid] = 0; overb[tid] = 0; }
   for (int i = tid; i < RING * kWave; i += kThreads) {     // every slot free, as if ops -RING .. -1 had been taken
     // (a free slot is copied and looked at like an op: some cell of the workgroup, no delay)
     ringw[4 * i + 0] = ringw[4 * i + 1] = ((uint32_t)(uintptr_t)ldsb >> kAsh) * 0x10001u;
@@ -655,7 +658,7 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
         if (k + u < kend) { level += m[u]; peak = max(peak, level); base += wt[u]; }   // eq. (19) along the chain
     }
     peak += base;
-    if (p.mem_limit && cand_ok && j < P && peak > p.mem_limit[j]) atomicOr(&flagw[g], kBitOverMemory);   // an empty machine has peak 0
+    if (p.mem_limit && cand_ok && j < P && peak > p.mem_limit[j]) overb[g] = 1;   // an empty machine has peak 0
     if (lane_on) peakw[ql] = peak;
   }
   __syncthreads();
@@ -666,7 +669,7 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
     for (int d = 1; d < Pseg; d <<= 1) z = max(z, __shfl_xor(z, d, Pseg));
     if (lane_on && g < ng && j < P) {
       const int64_t c = c0 + g;
-      int bits = flagw[g];
+      int bits = flagw[g] | (overb[g] ? kBitOverMemory : 0);
       if (stalled || abortw[g]) {
         if (p.optimistic && !(bits & kBitInternal) && abortw[g] != 2) {
           if (j == 0) { const int slot = atomicAdd(p.fb_count, 1); p.fb_list[slot] = (int32_t)c; }

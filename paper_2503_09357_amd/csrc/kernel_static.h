@@ -69,6 +69,9 @@ __global__ __launch_bounds__(1024) void relax_static_kernel(StaticParams p) {
   int32_t *flagw = (int32_t *)(lds + p.o_book);             // [64]
   int32_t *offw = (int32_t *)(lds + p.o_book + 256);        // [Pseg + 1]
   uint32_t *pairw = (uint32_t *)(lds + p.o_book + 640);     // [Pseg] start | end << 16 of machine j in every order list
+  // [64] 1 = some machine of the candidate is over its memory limit; apart from flagw, which the relaxers read when
+  // they start on a batch while the accountants may already have found a limit exceeded
+  uint8_t *overb = lds + p.o_book + 896;
   int64_t *peakw = (int64_t *)(lds + p.o_book + 1024);      // [W][64]
   constexpr uint32_t kNever = 0xFFFFu;
 
@@ -125,7 +128,7 @@ __global__ __launch_bounds__(1024) void relax_static_kernel(StaticParams p) {
   const int tpa = kThreads / GW;                            // threads per candidate slot when all wavefronts take part
   const int slot_a = tid / tpa, ta = tid - slot_a * tpa;
   auto init_batch = [&]() {
-    if (tid < kWave) flagw[tid] = 0;
+    if (tid < kWave) { flagw[tid] = 0; overb[tid] = 0; }
     if (slot_a >= GW) return;
     const int cwords = (N + 4) / 2, lwords = (N + 5) / 2;   // the list follows the cells
     uint32_t *w = (uint32_t *)(lds + p.o_cand + slot_a * p.cand_stride);
@@ -200,7 +203,7 @@ __global__ __launch_bounds__(1024) void relax_static_kernel(StaticParams p) {
       for (int d = 1; d < Pseg; d <<= 1) z = max(z, __shfl_xor(z, d, Pseg));
       if (lane_on && gi < ng && j < P) {
         const int64_t c = c0 + gi;
-        const int bits = flagw[gi];
+        const int bits = flagw[gi] | (overb[gi] ? kBitOverMemory : 0);
         if ((bits & kBitOtherPlacement) && !(bits & kBitBadPlacement)) {
           if (j == 0) { const int slot = atomicAdd(p.fb_count, 1); p.fb_list[slot] = (int32_t)c; }   // the general kernel writes this candidate
         } else {
@@ -316,7 +319,7 @@ __global__ __launch_bounds__(1024) void relax_static_kernel(StaticParams p) {
             if (k + u < n_ops) { level += m[u]; peak = max(peak, level); }   // eq. (19) along the chain
         }
         if (ok && p.base) peak += p.base[j];
-        if (ok && p.mem_limit && peak > p.mem_limit[j]) atomicOr(&flagw[gi], kBitOverMemory);
+        if (ok && p.mem_limit && peak > p.mem_limit[j]) overb[gi] = 1;
         if (lane_on) peakw[role_wave * kWave + ql] = peak;
       }
       __syncthreads();                                       // the relaxers write the outputs ...

@@ -20,8 +20,8 @@ CAND_MAJOR, CAND_MINOR = 0, 1
 MAX_DEVICES, MAX_NODES = 64, 65535
 
 EXPORTS = ("dagsched_validate", "dagsched_create", "dagsched_evaluate", "dagsched_destroy",
-           "dagsched_strerror", "dagsched_get_info", "dagsched_time_evaluate", "dagsched_propose", "dagsched_propose_orders", "dagsched_select",
-           "dagsched_schedule")
+           "dagsched_strerror", "dagsched_get_info", "dagsched_last_fallbacks", "dagsched_time_evaluate", "dagsched_propose",
+           "dagsched_propose_orders", "dagsched_select", "dagsched_schedule")
 
 
 class Desc(ctypes.Structure):
@@ -34,14 +34,47 @@ class Desc(ctypes.Structure):
 
 
 class Shape(ctypes.Structure):
-    """dagsched_shape_t: optional launch shape of the 16-bit kernel (0 / -1: chosen by the library)."""
+    """dagsched_shape_t: optional launch shape of the evaluation kernels (0 / -1: chosen by the library)."""
     _fields_ = [("cand_per_block", ctypes.c_int32), ("ring_slots", ctypes.c_int32), ("feeders", ctypes.c_int32),
-                ("placement_mode", ctypes.c_int32), ("block_threads", ctypes.c_int32), ("state_bits", ctypes.c_int32)]
+                ("placement_mode", ctypes.c_int32), ("block_threads", ctypes.c_int32), ("state_bits", ctypes.c_int32),
+                ("preds_per_op", ctypes.c_int32), ("kernel", ctypes.c_int32), ("static_waves", ctypes.c_int32),
+                ("ignore_shared_placement", ctypes.c_int32)]
+
+
+SHAPE_FIELDS = tuple(name for name, _ in Shape._fields_)
+
+# Shape fields that every evaluator made inside a `shape_defaults` block starts from (an explicit `shape=` wins field
+# by field).  For tests and tuning sweeps, which make evaluators in many places; empty otherwise.
+_shape_defaults: dict = {}
+
+
+class shape_defaults:
+    """with shape_defaults(feeders=2, ring_slots=8): ...   (nests; restores the previous defaults on exit)"""
+
+    def __init__(self, **fields):
+        unknown = set(fields) - set(SHAPE_FIELDS)
+        if unknown:
+            raise ValueError("unknown shape fields: %s" % sorted(unknown))
+        self.fields = fields
+
+    def __enter__(self):
+        global _shape_defaults
+        self.old = _shape_defaults
+        _shape_defaults = dict(_shape_defaults, **self.fields)
+        return self
+
+    def __exit__(self, *exc):
+        global _shape_defaults
+        _shape_defaults = self.old
 
 
 class Info(ctypes.Structure):
     _fields_ = [("variant", ctypes.c_int32), ("cand_per_block", ctypes.c_int32), ("block_threads", ctypes.c_int32),
-                ("lds_bytes", ctypes.c_int32), ("state_bits", ctypes.c_int32), ("reserved", ctypes.c_int32 * 3)]
+                ("lds_bytes", ctypes.c_int32), ("state_bits", ctypes.c_int32),
+                ("ring_slots", ctypes.c_int16), ("kernel_kind", ctypes.c_int8), ("wide_ops", ctypes.c_int8),
+                ("time_scale", ctypes.c_int32),
+                ("feeders", ctypes.c_int8), ("placement_mode", ctypes.c_int8), ("preds_per_op", ctypes.c_int8),
+                ("reserved", ctypes.c_int8)]
 
 
 class DagschedError(RuntimeError):
@@ -78,6 +111,8 @@ def load(import_torch_first: bool = True):
     lib.dagsched_strerror.argtypes = [ctypes.c_int]
     lib.dagsched_get_info.restype = ctypes.c_int
     lib.dagsched_get_info.argtypes = [vp, ctypes.POINTER(Info)]
+    lib.dagsched_last_fallbacks.restype = ctypes.c_int
+    lib.dagsched_last_fallbacks.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_int32)]
     lib.dagsched_propose.restype = ctypes.c_int
     lib.dagsched_propose.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp]
     lib.dagsched_propose_orders.restype = ctypes.c_int
@@ -130,10 +165,12 @@ class _HostProblem:
         d.weight = None if self.weight is None else self.weight.ctypes.data
         d.mem_limit = None if self.mem_limit is None else self.mem_limit.ctypes.data
         self.shape = None
-        if shape is not None:
-            self.shape = Shape(int(shape.get("cand_per_block", 0)), int(shape.get("ring_slots", 0)),
-                               int(shape.get("feeders", 0)), int(shape.get("placement_mode", -1)),
-                               int(shape.get("block_threads", 0)), int(shape.get("state_bits", 0)))
+        if shape is not None or _shape_defaults:
+            shape = dict(_shape_defaults, **(shape or {}))
+            unknown = set(shape) - set(SHAPE_FIELDS)
+            if unknown:
+                raise ValueError("unknown shape fields: %s" % sorted(unknown))
+            self.shape = Shape(*[int(shape.get(f, -1 if f == "placement_mode" else 0)) for f in SHAPE_FIELDS])
         d.shape = None if self.shape is None else ctypes.addressof(self.shape)
         self.shared_placement = None if shared_placement is None else np.ascontiguousarray(shared_placement, dtype=np.int32).reshape(-1)
         if self.shared_placement is not None and self.shared_placement.shape != (d.n_nodes,):
@@ -222,13 +259,18 @@ class Evaluator:
     def info(self) -> dict:
         i = Info()
         _check(load().dagsched_get_info(self._h, ctypes.byref(i)))
-        d = {k: getattr(i, k) for k in ("variant", "cand_per_block", "block_threads", "lds_bytes", "state_bits")}
-        d["ring_slots"], d["time_scale"] = i.reserved[0], i.reserved[1]
-        d["feeders"], d["placement_bytes_in_lds"] = i.reserved[2] & 0xFF, (i.reserved[2] >> 8) & 3
-        d["preds_per_op"] = (i.reserved[2] >> 16) & 0xFF
-        d["kernel_kind"] = (i.reserved[2] >> 24) & 0xF    # 0 general, 1 single-part operations, 2 at most two predecessors
-        d["wide_ops"] = (i.reserved[2] >> 28) & 1          # ops name machines (delays above 255 or durations above 65534)
+        d = {k: getattr(i, k) for k in ("variant", "cand_per_block", "block_threads", "lds_bytes", "state_bits",
+                                        "ring_slots", "time_scale", "feeders", "preds_per_op", "kernel_kind", "wide_ops")}
+        d["placement_bytes_in_lds"] = i.placement_mode
         return d
+
+    def last_fallbacks(self, stream=None) -> int:
+        """Candidates of the last evaluate that went to the int32 kernel one by one (synchronises the stream)."""
+        import torch
+        s = torch.cuda.current_stream(self.hip_device) if stream is None else stream
+        n = ctypes.c_int32()
+        _check(load().dagsched_last_fallbacks(self._h, s.cuda_stream, ctypes.byref(n)))
+        return int(n.value)
 
     def _n_cand(self, placement, rank) -> int:
         import torch
@@ -304,16 +346,17 @@ class Evaluator:
                                       s.cuda_stream))
         return out
 
-    def schedule(self, placement, rank, stream=None):
+    def schedule(self, placement, rank, stream=None, out=None):
         """Start / end times of ONE candidate (device int32 [N] each) -> (start int32 [N], end int32 [N], flag int32 [1])."""
         import torch
         dev = torch.device("cuda", self.hip_device)
-        start = torch.empty(self.N, dtype=torch.int32, device=dev)
-        end = torch.empty(self.N, dtype=torch.int32, device=dev)
-        flag = torch.empty(1, dtype=torch.int32, device=dev)
+        if out is None:
+            out = (torch.empty(self.N, dtype=torch.int32, device=dev), torch.empty(self.N, dtype=torch.int32, device=dev),
+                   torch.empty(1, dtype=torch.int32, device=dev))
+        start, end, flag = out
         s = torch.cuda.current_stream(self.hip_device) if stream is None else stream
-        _check(load().dagsched_schedule(self._h, placement.data_ptr(), rank.data_ptr(), start.data_ptr(), end.data_ptr(),
-                                        flag.data_ptr(), s.cuda_stream))
+        _check(load().dagsched_schedule(self._h, placement.data_ptr(), rank.data_ptr(), start.data_ptr(), end.data_ptr(), flag.data_ptr(),
+                    s.cuda_stream))
         return start, end, flag
 
     def close(self):

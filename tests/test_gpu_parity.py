@@ -180,12 +180,16 @@ def test_configs_candidate_minor_layout(gpu_lib, cfg, c):
     assert_parity(gpu_lib, w, layout=1)
 
 
-@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
-def test_configs_full_size(gpu_lib, cfg):
-    """Full candidate counts, same handle parameters and launch shape as bench.py; the oracle
-    evaluates every candidate (seconds per configuration), so the comparison is exhaustive."""
+@pytest.mark.parametrize("cfg,hint", [(1, 1), (2, 1), (3, 1), (4, 1), (5, 1), (1, 0), (2, 0), (3, 0)])
+def test_configs_full_size(gpu_lib, cfg, hint):
+    """Full candidate counts; the oracle evaluates every candidate (seconds per configuration), so the comparison is
+    exhaustive.  hint = 1: the handle is made as bench.py makes it (Evaluator.for_workload passes the shared placement
+    of the pipeline workloads as the hint, and the library dispatches by itself); hint = 0: the pipeline workloads
+    without the hint, i.e. on the kernels that take a placement per candidate."""
     w = W.gen_config(cfg)
-    (z, b, pk, f), info = assert_parity(gpu_lib, w)
+    (z, b, pk, f), info = _with_env({"ignore_shared_placement": 1 - hint}, lambda: assert_parity(gpu_lib, w))
+    if cfg == 2:
+        assert info["variant"] == (6 if hint else 3), info
     _say("cfg%d full ok, kernel info %s, flags %s" % (cfg, info, np.bincount(f).tolist()))
     if cfg == 2:
         marked = np.zeros(w.n_cand, bool)
@@ -196,35 +200,29 @@ def test_configs_full_size(gpu_lib, cfg):
 # --------------------------------------------------------------------------- kernel variants and the 16-bit fallback
 
 def _with_env(env, fn):
-    old = {k: os.environ.get(k) for k in env}
-    os.environ.update({k: str(v) for k, v in env.items()})
-    try:
+    """Run fn with the given dagsched_shape_t fields as the defaults of every evaluator it makes."""
+    from paper_2503_09357_amd import dagsched as ds
+    with ds.shape_defaults(**env):
         return fn()
-    finally:
-        for k, v in old.items():
-            if v is None:
-                os.environ.pop(k, None)
-            else:
-                os.environ[k] = v
 
 
 @pytest.mark.parametrize("env", [
-    {"DAGSCHED_FORCE_GENERAL": 1},
-    {"DAGSCHED_RING_FEEDERS": 1, "DAGSCHED_RING_SLOTS": 4, "DAGSCHED_RING_PIB_LDS": 1},
-    {"DAGSCHED_RING_FEEDERS": 2, "DAGSCHED_RING_SLOTS": 8, "DAGSCHED_RING_PIB_LDS": 1},
-    {"DAGSCHED_RING_FEEDERS": 1, "DAGSCHED_RING_SLOTS": 8, "DAGSCHED_RING_PIB_LDS": 1, "DAGSCHED_RING_G": 1},
-    {"DAGSCHED_RING_FEEDERS": 2, "DAGSCHED_RING_SLOTS": 4, "DAGSCHED_RING_PIB_LDS": 1},
-    {"DAGSCHED_RING_FEEDERS": 3, "DAGSCHED_RING_SLOTS": 8, "DAGSCHED_RING_PIB_LDS": 1},
-    {"DAGSCHED_RING_FEEDERS": 4, "DAGSCHED_RING_SLOTS": 16, "DAGSCHED_RING_PIB_LDS": 0},
-    {"DAGSCHED_RING_FEEDERS": 2, "DAGSCHED_RING_SLOTS": 8, "DAGSCHED_RING_PIB_LDS": 0},
-    {"DAGSCHED_RING_FEEDERS": 2, "DAGSCHED_RING_SLOTS": 16, "DAGSCHED_RING_PIB_LDS": 0},
-    {"DAGSCHED_RING_FEEDERS": 1, "DAGSCHED_RING_SLOTS": 32, "DAGSCHED_RING_PIB_LDS": 0},
-    {"DAGSCHED_RING_FEEDERS": 2, "DAGSCHED_RING_SLOTS": 8, "DAGSCHED_RING_PIB_LDS": 1, "DAGSCHED_RING_PREDS": 4},
-    {"DAGSCHED_RING_FEEDERS": 2, "DAGSCHED_RING_SLOTS": 16, "DAGSCHED_RING_PIB_LDS": 0, "DAGSCHED_RING_PREDS": 4},
-    {"DAGSCHED_RING_FEEDERS": 2, "DAGSCHED_RING_SLOTS": 8, "DAGSCHED_RING_PIB_LDS": 1, "DAGSCHED_RING_STATE_BITS": 32},
-    {"DAGSCHED_RING_FEEDERS": 3, "DAGSCHED_RING_SLOTS": 16, "DAGSCHED_RING_PIB_LDS": 0, "DAGSCHED_RING_STATE_BITS": 32},
-    {"DAGSCHED_RING_FEEDERS": 1, "DAGSCHED_RING_SLOTS": 8, "DAGSCHED_RING_PIB_LDS": 1, "DAGSCHED_RING_STATE_BITS": 32,
-     "DAGSCHED_RING_PREDS": 4},
+    {"kernel": 1},
+    {"feeders": 1, "ring_slots": 4, "placement_mode": 1},
+    {"feeders": 2, "ring_slots": 8, "placement_mode": 1},
+    {"feeders": 1, "ring_slots": 8, "placement_mode": 1, "cand_per_block": 1},
+    {"feeders": 2, "ring_slots": 4, "placement_mode": 1},
+    {"feeders": 3, "ring_slots": 8, "placement_mode": 1},
+    {"feeders": 4, "ring_slots": 16, "placement_mode": 0},
+    {"feeders": 2, "ring_slots": 8, "placement_mode": 0},
+    {"feeders": 2, "ring_slots": 16, "placement_mode": 0},
+    {"feeders": 1, "ring_slots": 32, "placement_mode": 0},
+    {"feeders": 2, "ring_slots": 8, "placement_mode": 1, "preds_per_op": 4},
+    {"feeders": 2, "ring_slots": 16, "placement_mode": 0, "preds_per_op": 4},
+    {"feeders": 2, "ring_slots": 8, "placement_mode": 1, "state_bits": 32},
+    {"feeders": 3, "ring_slots": 16, "placement_mode": 0, "state_bits": 32},
+    {"feeders": 1, "ring_slots": 8, "placement_mode": 1, "state_bits": 32,
+     "preds_per_op": 4},
 ])
 def test_every_kernel_variant(gpu_lib, env):
     """The tuning knobs only pick among kernel instantiations; each one must give the same bits."""
@@ -234,30 +232,30 @@ def test_every_kernel_variant(gpu_lib, env):
              W.random_instance(rng, 210, 5, 37, max_fanin=4, frac_arbitrary=0.3, frac_bad=0.2, dup_prob=0.0)]   # single-part operations
     for w in cases:
         (z, b, pk, f), info = _with_env(env, lambda: assert_parity(gpu_lib, w))
-        if "DAGSCHED_FORCE_GENERAL" in env:
+        if "kernel" in env:
             assert info["state_bits"] == 32
         else:
-            assert info["state_bits"] == env.get("DAGSCHED_RING_STATE_BITS", 16)
+            assert info["state_bits"] == env.get("state_bits", 16)
             assert info["variant"] == (5 if info["state_bits"] == 32 else info["variant"]) and info["variant"] in (3, 4, 5)
-            assert info["feeders"] == env["DAGSCHED_RING_FEEDERS"] and info["ring_slots"] == env["DAGSCHED_RING_SLOTS"]
-            assert info["placement_bytes_in_lds"] == env["DAGSCHED_RING_PIB_LDS"]
-            if "DAGSCHED_RING_G" in env:
-                assert info["cand_per_block"] == env["DAGSCHED_RING_G"]
+            assert info["feeders"] == env["feeders"] and info["ring_slots"] == env["ring_slots"]
+            assert info["placement_bytes_in_lds"] == env["placement_mode"]
+            if "cand_per_block" in env:
+                assert info["cand_per_block"] == env["cand_per_block"]
             # the pipeline workloads have at most two DAG predecessors per operation: the two-predecessor
             # kernels take them (where that shape is built) unless the knob says otherwise
-            two = w.name.startswith(("cfg1", "cfg2")) and env.get("DAGSCHED_RING_PREDS", 2) == 2
+            two = w.name.startswith(("cfg1", "cfg2")) and env.get("preds_per_op", 2) == 2
             assert info["preds_per_op"] in ((2, 4) if two else (4,)), (w.name, info)
-            if env.get("DAGSCHED_RING_PREDS", 2) == 4:
+            if env.get("preds_per_op", 2) == 4:
                 assert info["kernel_kind"] == 0
             elif w.name.startswith("random n=210"):
                 assert info["kernel_kind"] in (1, 2), (w.name, info)
 
 
 @pytest.mark.parametrize("env", [
-    {"DAGSCHED_RING_FEEDERS": 2, "DAGSCHED_RING_SLOTS": 8, "DAGSCHED_RING_PIB_LDS": 2},
-    {"DAGSCHED_RING_FEEDERS": 1, "DAGSCHED_RING_SLOTS": 4, "DAGSCHED_RING_PIB_LDS": 2},
-    {"DAGSCHED_RING_FEEDERS": 2, "DAGSCHED_RING_SLOTS": 4, "DAGSCHED_RING_PIB_LDS": 2, "DAGSCHED_RING_PREDS": 4},
-    {"DAGSCHED_RING_FEEDERS": 1, "DAGSCHED_RING_SLOTS": 8, "DAGSCHED_RING_PIB_LDS": 2, "DAGSCHED_RING_G": 1},
+    {"feeders": 2, "ring_slots": 8, "placement_mode": 2},
+    {"feeders": 1, "ring_slots": 4, "placement_mode": 2},
+    {"feeders": 2, "ring_slots": 4, "placement_mode": 2, "preds_per_op": 4},
+    {"feeders": 1, "ring_slots": 8, "placement_mode": 2, "cand_per_block": 1},
 ])
 def test_nibble_placement_kernels(gpu_lib, env):
     """Up to 16 machines: the placement can sit in LDS as four bits per node (and time then starts at 255
@@ -281,7 +279,7 @@ def test_nibble_placement_kernels(gpu_lib, env):
     pl1, rk1 = W.list_schedules(rp, ci, 1, 67, 98)
     pl[::3], rk[::3] = pl1, rk1
     w = W.Workload("straddles 16 bits", p, rp, ci, dur, comm, mem, pl, rk)
-    env16 = dict(env, DAGSCHED_RING_STATE_BITS=16)           # (left alone the library would take 32-bit end times here)
+    env16 = dict(env, state_bits=16)           # (left alone the library would take 32-bit end times here)
     (z, b, pk, f), info = _with_env(env16, lambda: assert_parity(gpu_lib, w))
     assert info["placement_bytes_in_lds"] == 2 and info["variant"] == 4
     # a makespan bound between 65280 and 65535: exact with bytes, optimistic with nibbles
@@ -441,7 +439,7 @@ def test_sixteen_bit_overflow_falls_back(gpu_lib):
     pl1, rk1 = W.list_schedules(rp, ci, 1, 100, 99)          # every third candidate runs everything on machine 0
     pl[::3], rk[::3] = pl1, rk1
     w = W.Workload("straddles 16 bits", p, rp, ci, dur, comm, mem, pl, rk)
-    env16 = {"DAGSCHED_RING_STATE_BITS": 16}                 # (left alone the library would take 32-bit end times here)
+    env16 = {"state_bits": 16}                 # (left alone the library would take 32-bit end times here)
     (z, b, pk, f), info = _with_env(env16, lambda: assert_parity(gpu_lib, w))
     assert info["state_bits"] == 16 and info["variant"] == 4        # optimistic ring kernel
     assert (z[f == 0] > 65535).any() and (z[f == 0] < 65535).any()
@@ -451,12 +449,68 @@ def test_sixteen_bit_overflow_falls_back(gpu_lib):
     assert info2["time_scale"] == 1000 and (z2[f == 0] == 1000 * z[f == 0].astype(np.int64)).all()
 
 
+def test_fallback_count_is_reported(gpu_lib):
+    """dagsched_last_fallbacks: how many candidates of the last evaluate went to the int32 kernel one by one.  In an
+    optimistic 16-bit run those are the well-formed, acyclic candidates whose end times reach the 16-bit range."""
+    import torch
+    rng = np.random.default_rng(77)
+    n, p = 600, 3
+    rp, ci = W.random_dag(rng, n, 2, window=30)
+    dur = rng.integers(60, 160, n).astype(np.int32)
+    comm = rng.integers(1, 200, (p, p)).astype(np.int32)
+    pl, rk = W.list_schedules(rp, ci, p, 300, 4242)
+    pl1, rk1 = W.list_schedules(rp, ci, 1, 100, 99)
+    pl[::3], rk[::3] = pl1, rk1
+    w = W.Workload("straddles 16 bits", p, rp, ci, dur, comm, rng.integers(-9, 10, n).astype(np.int64), pl, rk)
+    zo, _, _, fo = oracle.evaluate_workload(w)
+    dev = torch.device("cuda", 0)
+    with gpu_lib.Evaluator.for_workload(w, shape={"state_bits": 16}) as ev:
+        assert ev.info()["variant"] == 4
+        z, _, _, f = ev.evaluate(torch.from_numpy(w.placement).to(dev), torch.from_numpy(w.rank).to(dev))
+        n_fb = ev.last_fallbacks()
+        assert (z.cpu().numpy() == zo).all() and (f.cpu().numpy() == fo).all()
+        # an end time of 65535 or more cannot be held: those candidates must have gone over, and only feasible ones can
+        assert int((zo >= 65535).sum()) <= n_fb <= int((fo == 0).sum()) and 0 < n_fb < w.n_cand, n_fb
+        z2, _, _, f2 = ev.evaluate(torch.from_numpy(w.placement[1::3].copy()).to(dev), torch.from_numpy(w.rank[1::3].copy()).to(dev))
+        n_fb2 = ev.last_fallbacks()
+        assert n_fb2 <= n_fb and (z2.cpu().numpy() == zo[1::3]).all()
+    with gpu_lib.Evaluator.for_workload(w) as ev:             # 32-bit state: nothing to hand over
+        ev.evaluate(torch.from_numpy(w.placement).to(dev), torch.from_numpy(w.rank).to(dev))
+        assert ev.info()["variant"] == 5 and ev.last_fallbacks() == 0
+
+
+def test_two_live_handles_on_one_kernel_instantiation(gpu_lib):
+    """Distinct handles are independent.  Two problems of different size that take the same kernel instantiation
+    (same machines, same shape; the larger one needs more than 48 KB of LDS, the smaller one a few KB) are made one
+    after the other and evaluated alternately: the kernel's LDS allowance belongs to the function, and the handle
+    made second must not take away what the first one needs."""
+    import torch
+    rng = np.random.default_rng(4711)
+    shape = {"feeders": 2, "ring_slots": 8, "placement_mode": 1, "cand_per_block": 8, "preds_per_op": 4}
+    big = W.random_instance(rng, 3500, 8, 70, max_fanin=4, frac_arbitrary=0.2, frac_bad=0.1)
+    small = W.random_instance(rng, 90, 8, 50, max_fanin=4, frac_arbitrary=0.2, frac_bad=0.1)
+    want = {id(w): oracle.evaluate_workload(w) for w in (big, small)}
+    dev = torch.device("cuda", 0)
+    with gpu_lib.Evaluator.for_workload(big, shape=shape) as eb, gpu_lib.Evaluator.for_workload(small, shape=shape) as es:
+        ib, is_ = eb.info(), es.info()
+        assert ib["lds_bytes"] > 48 * 1024 > is_["lds_bytes"], (ib, is_)
+        for k in ("variant", "cand_per_block", "ring_slots", "feeders", "placement_bytes_in_lds", "kernel_kind", "state_bits"):
+            assert ib[k] == is_[k], (k, ib, is_)
+        tens = {id(w): (torch.from_numpy(w.placement).to(dev), torch.from_numpy(w.rank).to(dev)) for w in (big, small)}
+        for turn in range(3):
+            for ev, w in ((eb, big), (es, small)):
+                out = ev.evaluate(*tens[id(w)])
+                torch.cuda.synchronize()
+                for name, a, o in zip(("makespan", "bubble", "peak_mem", "flags"), out, want[id(w)]):
+                    assert (a.cpu().numpy() == o).all(), (name, w.name, turn)
+
+
 def test_large_delays(gpu_lib):
     rng = np.random.default_rng(5)
     w = W.random_instance(rng, 120, 5, 30, max_comm=4000, max_dur=977)
     (z, b, pk, f), info = assert_parity(gpu_lib, w)
     assert info["variant"] == 5 and info["wide_ops"] == 1
-    (z, b, pk, f), info = _with_env({"DAGSCHED_FORCE_GENERAL": 1}, lambda: assert_parity(gpu_lib, w))
+    (z, b, pk, f), info = _with_env({"kernel": 1}, lambda: assert_parity(gpu_lib, w))
     assert info["variant"] in (1, 2)
 
 
@@ -495,7 +549,7 @@ def test_static_memory_and_limits(gpu_lib, force_general):
         limit[0] = int(np.median(pko[ok][:, 0]))                 # ... but tight on machine 0
         w2 = dataclasses.replace(w, name=w.name + " + weights", weight=weight)
         w3 = dataclasses.replace(w, name=w.name + " + weights + limits", weight=weight, mem_limit=limit)
-        env = {"DAGSCHED_FORCE_GENERAL": 1} if force_general else {}
+        env = {"kernel": 1} if force_general else {}
         (z2, b2, pk2, f2), _ = _with_env(env, lambda: assert_parity(gpu_lib, w2))
         assert (f2 == fo).all() and (pk2 == pko).all()
         (z3, b3, pk3, f3), _ = _with_env(env, lambda: assert_parity(gpu_lib, w3))
@@ -508,7 +562,7 @@ def test_static_memory_and_limits(gpu_lib, force_general):
 
 # --------------------------------------------------------------------------- missing channels (eqs. (9)-(10))
 
-@pytest.mark.parametrize("env", [{}, {"DAGSCHED_FORCE_GENERAL": 1}, {"DAGSCHED_RING_STATE_BITS": 32}])
+@pytest.mark.parametrize("env", [{}, {"kernel": 1}, {"state_bits": 32}])
 def test_missing_channels(gpu_lib, env):
     """comm entry -1: the pair has no channel; a candidate with a message over it is NO_CHANNEL, after the flags of
     malformed candidates and before every other one.  Random clusters on random instances (a third of the pairs

@@ -133,7 +133,7 @@ def test_search_over_the_orders_alone_stays_on_the_shared_placement_kernel(gpu_l
             torch.cuda.synchronize()
             return pl.cpu().numpy(), rk.cpu().numpy(), hist
 
-    pl, rk, hist = _with_env({"DAGSCHED_NO_SHARED_PLACEMENT": 0, "DAGSCHED_STATIC_WAVES": 2}, go)
+    pl, rk, hist = _with_env({"ignore_shared_placement": 0, "static_waves": 2}, go)
     assert (pl == w.placement[0]).all()
     assert hist[0] <= z0 and all(b <= a for a, b in zip(hist, hist[1:])) and hist[-1] < z0
     zo, _, _, fo = prob.evaluate(pl[None, :], rk[None, :])
@@ -167,7 +167,7 @@ def test_cycles_and_range_stops_are_told_apart(gpu_lib):
         rows_pl.append(a)
         rows_rk.append(c)
     w2 = W.Workload("straddles 16 bits, with cycles", p, rp, ci, dur, comm, mem, np.concatenate(rows_pl), np.concatenate(rows_rk))
-    (z2, b2, pk2, f2), info2 = T._with_env({"DAGSCHED_RING_STATE_BITS": 16}, lambda: T.assert_parity(gpu_lib, w2))
+    (z2, b2, pk2, f2), info2 = T._with_env({"state_bits": 16}, lambda: T.assert_parity(gpu_lib, w2))
     assert info2["variant"] == 4 and (f2 == 1).any() and (z2[f2 == 0] > 65535).any() and (z2[f2 == 0] < 65535).any()
 
 
@@ -186,7 +186,7 @@ def test_search_step_replays_from_a_hip_graph(gpu_lib, shared):
     C = 256
     dev = _dev()
     make = lambda: ds.Evaluator.for_workload(w, max_candidates=C, shared_placement=w.placement[0] if shared else None)
-    with T._with_env({"DAGSCHED_NO_SHARED_PLACEMENT": 0, "DAGSCHED_STATIC_WAVES": 2}, make) as ev:
+    with T._with_env({"ignore_shared_placement": 0, "static_waves": 2}, make) as ev:
         assert ev.info()["variant"] == (6 if shared else 4), ev.info()
         base_pl = torch.from_numpy(w.placement[0]).to(dev)
         base_rk = torch.from_numpy(w.rank[0]).to(dev)

@@ -14,13 +14,13 @@ from test_gpu_parity import _say, _with_env, assert_parity
 
 pytestmark = pytest.mark.gpu
 
-SHARED = {"DAGSCHED_NO_SHARED_PLACEMENT": 0}          # tests/conftest.py switches the hint off for every other test
+SHARED = {"ignore_shared_placement": 0}          # the library's default, said aloud
 
 
 def _forced(waves):
     """The library keeps handles for small batches on the ring kernel; naming the number of relaxing wavefronts per
     workgroup makes it take the shared-placement kernel whatever the batch size."""
-    return dict(SHARED, DAGSCHED_STATIC_WAVES=waves)
+    return dict(SHARED, static_waves=waves)
 STATIC = 6                                            # dagsched_get_info: the shared-placement kernel
 
 
