@@ -44,7 +44,8 @@ enum {
   DAGSCHED_ECYCLE = -2,    /* the operator graph itself is cyclic (Sec. III requires a DAG) */
   DAGSCHED_EOVERFLOW = -3, /* sum(dur) + (N-1) * max off-diagonal comm > INT32_MAX: int32 times would not be exact */
   DAGSCHED_ENOMEM = -4,    /* host or device allocation failed */
-  DAGSCHED_EHIP = -5       /* any other HIP runtime failure */
+  DAGSCHED_EHIP = -5,      /* any other HIP runtime failure */
+  DAGSCHED_ESCRATCH = -6   /* dagsched_schedule_static: more than DAGSCHED_STATIC_MAX_NODES operations */
 };
 
 /* Per-candidate flags[c]: exactly one value, tested in this order. */
@@ -204,6 +205,21 @@ int dagsched_select(dagsched_t *h, int32_t n_cand, const int32_t *makespan, cons
                     void *hip_stream);
 int dagsched_schedule(dagsched_t *h, const int32_t *placement, const int32_t *rank, int32_t *start, int32_t *end,
                       int32_t *flag, void *hip_stream);
+
+/*
+ * dagsched_schedule for callers that cannot allocate or have no workspace to give: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same results and same asynchrony as
+ * dagsched_schedule, but the per-call scratch (one order-list row, one end-time row, a small output block) lives in
+ * a static device array of the library instead of the handle's workspace: about 257 KiB that every GPU a handle
+ * was made on holds until the process ends.  The call allocates and frees nothing.  Problems with more than
+ * DAGSCHED_STATIC_MAX_NODES operations are refused with DAGSCHED_ESCRATCH (nothing is enqueued).  All calls on
+ * one GPU share that GPU's array, whatever the handle: calls that overlap in time on one GPU (different streams,
+ * different threads) race; calls enqueued on one stream do not.  The array keeps the last call's contents, which
+ * no call reads: every entry a call reads it has written before.
+ */
+#define DAGSCHED_STATIC_MAX_NODES 32768
+int dagsched_schedule_static(dagsched_t *h, const int32_t *placement, const int32_t *rank, int32_t *start,
+                             int32_t *end, int32_t *flag, void *hip_stream);
 
 /*
  * Introspection for benchmarks and tests: which kernel variant the handle selected and its launch

@@ -40,7 +40,19 @@
 
 using namespace dagsched_dev;
 
+// Scratch of dagsched_schedule_static, the entry point for callers that cannot allocate: one order-list row and one
+// end-time row of kStaticMaxNodes int32 each, then the small output block of the one-candidate evaluation.  The
+// array's name is a host-side stand-in only; host code uses the device address that hipGetSymbolAddress returns for
+// the current device (every GPU holds a copy of its own), kept per device in g_scratch.
+constexpr int kStaticMaxNodes = DAGSCHED_STATIC_MAX_NODES;
+constexpr size_t kScratchOut = 2 * sizeof(int32_t) * (size_t)kStaticMaxNodes;
+constexpr size_t kScratchBytes = kScratchOut + 32 + 8 * DAGSCHED_MAX_DEVICES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
 namespace {
+
+constexpr int kMaxGpus = 64;
+unsigned char *g_scratch[kMaxGpus] = {};   // device address of `scratch` on each GPU a handle was made on
 
 thread_local char g_hip_error[256] = "";
 
@@ -738,6 +750,11 @@ int dagsched_create(const dagsched_desc_t *caller_desc, dagsched_t **out) {
   if (!hip_ok(hipGetDeviceCount(&n_dev), "hipGetDeviceCount")) return DAGSCHED_EHIP;
   if (desc->hip_device < 0 || desc->hip_device >= n_dev) return DAGSCHED_EINVAL;
   if (!hip_ok(hipSetDevice(desc->hip_device), "hipSetDevice")) return DAGSCHED_EHIP;
+  if (desc->hip_device < kMaxGpus && !g_scratch[desc->hip_device]) {   // with the handle's device current
+    unsigned char *ptr = nullptr;
+    if (!hip_ok(hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch)), "hipGetSymbolAddress") || !ptr) return DAGSCHED_EHIP;
+    g_scratch[desc->hip_device] = ptr;
+  }
   int lds_max = 0, n_cu = 0;
   if (!hip_ok(hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, desc->hip_device),
               "hipDeviceGetAttribute") ||
@@ -952,6 +969,17 @@ int dagsched_schedule(dagsched_t *h, const int32_t *placement, const int32_t *ra
                          (hipStream_t)hip_stream);
 }
 
+int dagsched_schedule_static(dagsched_t *h, const int32_t *placement, const int32_t *rank, int32_t *start, int32_t *end,
+                             int32_t *flag, void *hip_stream) {
+  if (!h || !placement || !rank || !start || !end || !flag) return DAGSCHED_EINVAL;
+  if (h->N > kStaticMaxNodes) return DAGSCHED_ESCRATCH;
+  unsigned char *ptr = h->device < kMaxGpus ? g_scratch[h->device] : nullptr;
+  if (!ptr) return DAGSCHED_EHIP;                          // (dagsched_create resolves it; a handle implies it is there)
+  // rows of row_stride <= kStaticMaxNodes entries each (N rounded up to 32, and kStaticMaxNodes is a multiple of 32)
+  int32_t *list_row = (int32_t *)ptr, *end_row = list_row + kStaticMaxNodes;
+  return launch_schedule(h, list_row, end_row, ptr + kScratchOut, placement, rank, start, end, flag, (hipStream_t)hip_stream);
+}
+
 int dagsched_get_info(const dagsched_t *h, dagsched_info_t *info) {
   if (!h || !info) return DAGSCHED_EINVAL;
   memset(info, 0, sizeof(*info));
@@ -1002,6 +1030,7 @@ const char *dagsched_strerror(int code) {
     case DAGSCHED_ECYCLE: return "the operator graph is cyclic";
     case DAGSCHED_EOVERFLOW: return "sum(dur) + (N-1)*max(comm) exceeds INT32_MAX";
     case DAGSCHED_ENOMEM: return "out of memory";
+    case DAGSCHED_ESCRATCH: return "the problem has more operations than the static scratch of the allocation-free entry point holds";
     case DAGSCHED_EHIP:
       snprintf(buf, sizeof(buf), "HIP runtime failure (%s)", g_hip_error[0] ? g_hip_error : "no detail recorded");
       return buf;

@@ -13,7 +13,8 @@ import numpy as np
 
 from . import _build
 
-OK, EINVAL, ECYCLE, EOVERFLOW, ENOMEM, EHIP = 0, -1, -2, -3, -4, -5
+OK, EINVAL, ECYCLE, EOVERFLOW, ENOMEM, EHIP, ESCRATCH = 0, -1, -2, -3, -4, -5, -6
+STATIC_MAX_NODES = 32768
 FLAG_OK, FLAG_CYCLIC, FLAG_BAD_PLACEMENT, FLAG_BAD_RANK, FLAG_INTERNAL, FLAG_OVER_MEMORY, FLAG_NO_CHANNEL = 0, 1, 2, 4, 8, 16, 32
 NO_CHANNEL = -1      # off-diagonal comm entry of a machine pair without a channel (eq. (10))
 CAND_MAJOR, CAND_MINOR = 0, 1
@@ -21,7 +22,7 @@ MAX_DEVICES, MAX_NODES = 64, 65535
 
 EXPORTS = ("dagsched_validate", "dagsched_create", "dagsched_evaluate", "dagsched_destroy",
            "dagsched_strerror", "dagsched_get_info", "dagsched_last_fallbacks", "dagsched_time_evaluate", "dagsched_propose",
-           "dagsched_propose_orders", "dagsched_select", "dagsched_schedule")
+           "dagsched_propose_orders", "dagsched_select", "dagsched_schedule", "dagsched_schedule_static")
 
 
 class Desc(ctypes.Structure):
@@ -121,6 +122,8 @@ def load(import_torch_first: bool = True):
     lib.dagsched_select.argtypes = [vp, i32, vp, vp, vp, vp]
     lib.dagsched_schedule.restype = ctypes.c_int
     lib.dagsched_schedule.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+    lib.dagsched_schedule_static.restype = ctypes.c_int
+    lib.dagsched_schedule_static.argtypes = [vp, vp, vp, vp, vp, vp, vp]
     _lib = lib
     return lib
 
@@ -346,8 +349,9 @@ class Evaluator:
                                       s.cuda_stream))
         return out
 
-    def schedule(self, placement, rank, stream=None, out=None):
-        """Start / end times of ONE candidate (device int32 [N] each) -> (start int32 [N], end int32 [N], flag int32 [1])."""
+    def schedule(self, placement, rank, stream=None, out=None, static_scratch: bool = False):
+        """Start / end times of ONE candidate (device int32 [N] each) -> (start int32 [N], end int32 [N], flag int32 [1]).
+        static_scratch: through dagsched_schedule_static, whose scratch is a static device array of the library."""
         import torch
         dev = torch.device("cuda", self.hip_device)
         if out is None:
@@ -355,7 +359,8 @@ class Evaluator:
                    torch.empty(1, dtype=torch.int32, device=dev))
         start, end, flag = out
         s = torch.cuda.current_stream(self.hip_device) if stream is None else stream
-        _check(load().dagsched_schedule(self._h, placement.data_ptr(), rank.data_ptr(), start.data_ptr(), end.data_ptr(), flag.data_ptr(),
+        call = load().dagsched_schedule_static if static_scratch else load().dagsched_schedule
+        _check(call(self._h, placement.data_ptr(), rank.data_ptr(), start.data_ptr(), end.data_ptr(), flag.data_ptr(),
                     s.cuda_stream))
         return start, end, flag
 
