@@ -33,6 +33,7 @@ def build() -> str:
     if proc.returncode != 0:
         raise RuntimeError("oracle build failed:\n" + proc.stdout)
     os.replace(tmp, _LIB)
+    build_coarsen()
     return _LIB
 
 
@@ -165,3 +166,57 @@ def evaluate_workload(w, layout: int = CAND_MAJOR, threads: int = 1):
     if layout == CAND_MAJOR:
         return prob.evaluate(w.placement, w.rank, layout, threads)
     return prob.evaluate(np.ascontiguousarray(w.placement.T), np.ascontiguousarray(w.rank.T), layout, threads)
+
+
+# --------------------------------------------------------------------------- graph coarsening (Sec. IV, Alg. 1)
+
+_CO_SRC = os.path.join(_DIR, "coarsen_oracle.c")
+_CO_LIB = os.path.join(_DIR, "libcoarsen_oracle.so")
+_co_lib = None
+
+
+def build_coarsen() -> str:
+    """gcc -> oracle/libcoarsen_oracle.so (always recompiles)."""
+    tmp = _CO_LIB + ".tmp"
+    proc = subprocess.run(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-Wall", "-Wextra", _CO_SRC, "-o", tmp],
+                          stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if proc.returncode != 0:
+        raise RuntimeError("coarsening oracle build failed:\n" + proc.stdout)
+    os.replace(tmp, _CO_LIB)
+    return _CO_LIB
+
+
+NO_MERGES = -1       # a threshold that no pair passes (sums are never negative)
+NO_LIMIT = 2 ** 62
+
+
+def coarsen(row_ptr, col_idx, dur, mem_delta, mem_req=None, target=1, edge_dur_max=NO_LIMIT, edge_mem_max=NO_LIMIT,
+            nonedge_dur_max=NO_LIMIT, nonedge_mem_max=NO_LIMIT):
+    """Alg. 1 -> dict(n_coarse, node_map [N], row_ptr, col_idx, dur, mem_delta, mem_req, merges_edge, merges_nonedge)."""
+    global _co_lib
+    if _co_lib is None:
+        if not os.path.exists(_CO_LIB) or os.path.getmtime(_CO_LIB) < os.path.getmtime(_CO_SRC):
+            build_coarsen()
+        _co_lib = ctypes.CDLL(_CO_LIB)
+        vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+        _co_lib.coarsen_oracle.restype = ctypes.c_int
+        _co_lib.coarsen_oracle.argtypes = [i32, i32, vp, vp, vp, vp, vp, i32, i64, i64, i64, i64] + [vp] * 9
+    rp, ci = _c(row_ptr, np.int32), _c(col_idx, np.int32)
+    n, e = len(rp) - 1, len(ci)
+    d, m = _c(dur, np.int64), _c(mem_delta, np.int64)
+    r = None if mem_req is None else _c(mem_req, np.int64)
+    assert d.shape == (n,) and m.shape == (n,) and (r is None or r.shape == (n,))
+    n_coarse, me, mn = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
+    node_map = np.empty(n, np.int32)
+    c_rp, c_ci = np.empty(n + 1, np.int32), np.empty(max(e, 1), np.int32)
+    c_d, c_m, c_r = np.empty(n, np.int64), np.empty(n, np.int64), np.empty(n, np.int64)
+    rc = _co_lib.coarsen_oracle(n, e, _ptr(rp), _ptr(ci), _ptr(d), _ptr(m), None if r is None else _ptr(r), int(target),
+                                int(edge_dur_max), int(edge_mem_max), int(nonedge_dur_max), int(nonedge_mem_max),
+                                ctypes.addressof(n_coarse), _ptr(node_map), _ptr(c_rp), _ptr(c_ci), _ptr(c_d), _ptr(c_m),
+                                _ptr(c_r), ctypes.addressof(me), ctypes.addressof(mn))
+    if rc != OK:
+        raise OracleError(rc)
+    k = n_coarse.value
+    return dict(n_coarse=k, node_map=node_map, row_ptr=c_rp[:k + 1].copy(), col_idx=c_ci[:c_rp[k]].copy(),
+                dur=c_d[:k].copy(), mem_delta=c_m[:k].copy(), mem_req=c_r[:k].copy(),
+                merges_edge=me.value, merges_nonedge=mn.value)

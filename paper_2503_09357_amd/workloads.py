@@ -443,6 +443,24 @@ def random_dag(rng: np.random.Generator, n: int, max_fanin: int = 3, window: Opt
     return csr_from_edges(n, src, dst)
 
 
+def random_dag_bounded_degree(rng: np.random.Generator, n: int, max_degree: int = 3, window: int = 12
+                              ) -> Tuple[np.ndarray, np.ndarray]:
+    """Random DAG whose in- and out-degrees are at most max_degree (the shape of the random computational graph of
+    Sec. V-B: 200 operations, maximum in- and out-degree 3), under a random relabelling.  Operation v draws up to
+    max_degree distinct predecessors among the `window` operations before it that still have an output to give."""
+    perm = rng.permutation(n)
+    out_left = np.full(n, max_degree, dtype=np.int64)
+    src: List[int] = []
+    dst: List[int] = []
+    for v in range(1, n):
+        pool = [u for u in range(max(0, v - window), v) if out_left[u] > 0]
+        fan = min(len(pool), int(rng.integers(1, max_degree + 1)))
+        for u in rng.choice(pool, size=fan, replace=False) if fan else []:
+            src.append(int(perm[int(u)])); dst.append(int(perm[v]))
+            out_left[int(u)] -= 1
+    return csr_from_edges(n, src, dst)
+
+
 def random_instance(rng: np.random.Generator, n: int, p: int, n_cand: int, max_fanin: int = 3,
                     max_dur: int = 9, max_comm: int = 5, frac_arbitrary: float = 0.3,
                     frac_bad: float = 0.1, dup_prob: float = 0.05, zero_dur: bool = True) -> Workload:
