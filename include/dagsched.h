@@ -222,6 +222,54 @@ int dagsched_schedule_static(dagsched_t *h, const int32_t *placement, const int3
                              int32_t *end, int32_t *flag, void *hip_stream);
 
 /*
+ * Graph coarsening before the planning (Sec. IV, Alg. 1): merge operations greedily until at most target_nodes are
+ * left, so that the planner works on a graph of manageable size.  Runs on the GPU hip_device (one persistent
+ * workgroup; the merges are inherently sequential, each step is parallel over the graph), synchronously: every
+ * pointer is HOST memory, device memory is allocated and released inside the call.
+ *
+ *   Redundant edges   (i1, i2) in B with some i3 such that (i1, i3) and (i3, i2) are in B (two hops, as the set
+ *                     printed in Sec. IV) are left out while a candidate pair is looked for, never deleted.
+ *   GetCandidateEdge  an edge (i1, i2) of the reduced graph whose head i2 has a single input and whose tail i1 has
+ *                     a single output there, with dur[i1] + dur[i2] <= edge_dur_max and mem_req[i1] + mem_req[i2]
+ *                     <= edge_mem_max; of several the lowest (i1, i2).
+ *   GetCandidateNonEdge  two operations of equal depth (edges on the longest path of B from a source; they cannot
+ *                     reach one another) with sums within nonedge_dur_max / nonedge_mem_max; of several the pair
+ *                     with the least summed duration, then the lowest (i1, i2), i1 < i2.
+ *   MergeNodes        duration, memory adjustment and memory requirement are summed, the edges of both operations
+ *                     go to the new one, which keeps the smaller of the two names.
+ *   Loop              as Alg. 1: edge merges while there is a candidate, then non-edge merges while there is one,
+ *                     again from the top; it ends as soon as target_nodes is reached, or after a pass without a merge.
+ * A negative threshold switches that kind of merge off.  What the paper leaves open (the thresholds, the choice
+ * among several candidates, the rule for non-edges, the loop's exits) is fixed as stated here.
+ *
+ * Inputs: the successor CSR of B (as in dagsched_desc_t; duplicates allowed), dur [N] >= 0 with a sum of at most
+ * INT32_MAX, mem_delta [N], mem_req [N] >= 0 or NULL (all zero).  Outputs, owned by the caller: node_map [N]
+ * (operation -> index of its group; groups are numbered by their smallest member), the coarse graph c_row_ptr
+ * [N + 1] / c_col_idx [E] (the first n_coarse + 1 and n_coarse_edges entries are written; columns ascending, no
+ * duplicates), c_dur, c_mem_delta, c_mem_req [N] (the first n_coarse entries), and *result.
+ * Returns DAGSCHED_OK, DAGSCHED_EINVAL (null pointer, sizes, malformed CSR, negative dur or mem_req, target_nodes
+ * < 1), DAGSCHED_ECYCLE (B is cyclic), DAGSCHED_EOVERFLOW (sum of dur above INT32_MAX), DAGSCHED_ENOMEM, DAGSCHED_EHIP.
+ */
+typedef struct {
+  int32_t target_nodes;     /* N of Alg. 1, >= 1 */
+  int64_t edge_dur_max, edge_mem_max;        /* thresholds of GetCandidateEdge on the sums of a pair    */
+  int64_t nonedge_dur_max, nonedge_mem_max;  /* thresholds of GetCandidateNonEdge (the stricter ones)   */
+} dagsched_coarsen_params_t;
+
+typedef struct {
+  int32_t n_coarse;         /* operations left */
+  int32_t n_coarse_edges;   /* edges of the coarse graph */
+  int32_t merges_edge;      /* merges proposed by GetCandidateEdge */
+  int32_t merges_nonedge;   /* merges proposed by GetCandidateNonEdge */
+} dagsched_coarsen_result_t;
+
+int dagsched_coarsen(int32_t n_nodes, int32_t n_edges, const int32_t *row_ptr, const int32_t *col_idx,
+                     const int32_t *dur, const int64_t *mem_delta, const int64_t *mem_req,
+                     const dagsched_coarsen_params_t *params, int32_t hip_device, int32_t *node_map,
+                     int32_t *c_row_ptr, int32_t *c_col_idx, int32_t *c_dur, int64_t *c_mem_delta,
+                     int64_t *c_mem_req, dagsched_coarsen_result_t *result);
+
+/*
  * Introspection for benchmarks and tests: which kernel variant the handle selected and its launch
  * shape.  Fills the struct and returns DAGSCHED_OK, or DAGSCHED_EINVAL on NULL.
  */

@@ -32,6 +32,7 @@
 
 #include "dagsched.h"
 #include "device_common.h"
+#include "kernel_coarsen.h"
 #include "kernel_general.h"
 #include "kernel_ring.h"
 #include "kernel_search.h"
@@ -978,6 +979,105 @@ int dagsched_schedule_static(dagsched_t *h, const int32_t *placement, const int3
   // rows of row_stride <= kStaticMaxNodes entries each (N rounded up to 32, and kStaticMaxNodes is a multiple of 32)
   int32_t *list_row = (int32_t *)ptr, *end_row = list_row + kStaticMaxNodes;
   return launch_schedule(h, list_row, end_row, ptr + kScratchOut, placement, rank, start, end, flag, (hipStream_t)hip_stream);
+}
+
+int dagsched_coarsen(int32_t n_nodes, int32_t n_edges, const int32_t *row_ptr, const int32_t *col_idx,
+                     const int32_t *dur, const int64_t *mem_delta, const int64_t *mem_req,
+                     const dagsched_coarsen_params_t *params, int32_t hip_device, int32_t *node_map,
+                     int32_t *c_row_ptr, int32_t *c_col_idx, int32_t *c_dur, int64_t *c_mem_delta,
+                     int64_t *c_mem_req, dagsched_coarsen_result_t *result) {
+  const int32_t n = n_nodes, E = n_edges;
+  if (n < 1 || n > DAGSCHED_MAX_NODES || E < 0 || !row_ptr || !dur || !mem_delta || (E > 0 && !col_idx)) return DAGSCHED_EINVAL;
+  if (!params || params->target_nodes < 1 || !node_map || !c_row_ptr || (E > 0 && !c_col_idx) || !c_dur || !c_mem_delta ||
+      !c_mem_req || !result)
+    return DAGSCHED_EINVAL;
+  if (row_ptr[0] != 0 || row_ptr[n] != E) return DAGSCHED_EINVAL;
+  // the graph: CSR shape, no self-loops, acyclic (sources peeled until none is left)
+  std::vector<int32_t> indeg(n, 0), stack;
+  for (int32_t u = 0; u < n; ++u) {
+    if (row_ptr[u + 1] < row_ptr[u]) return DAGSCHED_EINVAL;
+    for (int32_t k = row_ptr[u]; k < row_ptr[u + 1]; ++k) {
+      const int32_t v = col_idx[k];
+      if (v < 0 || v >= n || v == u) return DAGSCHED_EINVAL;
+      ++indeg[v];
+    }
+  }
+  int64_t sum_dur = 0;
+  for (int32_t v = 0; v < n; ++v) {
+    if (dur[v] < 0 || (mem_req && mem_req[v] < 0)) return DAGSCHED_EINVAL;
+    sum_dur += dur[v];
+  }
+  for (int32_t v = 0; v < n; ++v)
+    if (indeg[v] == 0) stack.push_back(v);
+  int32_t peeled = 0;
+  while (!stack.empty()) {
+    const int32_t u = stack.back();
+    stack.pop_back();
+    ++peeled;
+    for (int32_t k = row_ptr[u]; k < row_ptr[u + 1]; ++k)
+      if (--indeg[col_idx[k]] == 0) stack.push_back(col_idx[k]);
+  }
+  if (peeled != n) return DAGSCHED_ECYCLE;
+  if (sum_dur > (int64_t)INT32_MAX) return DAGSCHED_EOVERFLOW;   // a group's duration is a sum of durations
+
+  int n_dev = 0;
+  if (!hip_ok(hipGetDeviceCount(&n_dev), "hipGetDeviceCount")) return DAGSCHED_EHIP;
+  if (hip_device < 0 || hip_device >= n_dev) return DAGSCHED_EINVAL;
+  if (!hip_ok(hipSetDevice(hip_device), "hipSetDevice")) return DAGSCHED_EHIP;
+
+  CoarsenParams p{};
+  p.n = n; p.n_edges = E; p.words = (n + 63) / 64; p.target = params->target_nodes;
+  p.edge_dur_max = params->edge_dur_max; p.edge_mem_max = params->edge_mem_max;
+  p.nonedge_dur_max = params->nonedge_dur_max; p.nonedge_mem_max = params->nonedge_mem_max;
+  std::vector<int64_t> dur64(dur, dur + n), req64(n, 0);
+  if (mem_req) req64.assign(mem_req, mem_req + n);
+  const size_t matrix = (size_t)n * (size_t)p.words;
+  std::vector<void *> owned;
+  auto alloc = [&](auto **dst, size_t count) {
+    if (!dev_alloc(dst, count)) return false;
+    owned.push_back((void *)*dst);
+    return true;
+  };
+  int32_t *d_row_ptr = nullptr, *d_col_idx = nullptr;
+  bool ok = alloc(&d_row_ptr, (size_t)n + 1) && alloc(&d_col_idx, (size_t)E) && alloc(&p.succ, matrix) && alloc(&p.pred, matrix) && alloc(&p.kept, matrix) &&
+            alloc(&p.dur, (size_t)n) && alloc(&p.mem, (size_t)n) && alloc(&p.req, (size_t)n) && alloc(&p.alive, (size_t)n) &&
+            alloc(&p.parent, (size_t)n) && alloc(&p.outdeg, (size_t)n) && alloc(&p.indeg, (size_t)n) && alloc(&p.only, (size_t)n) &&
+            alloc(&p.depth, (size_t)n) && alloc(&p.left, (size_t)n) && alloc(&p.index_of, (size_t)n) && alloc(&p.node_map, (size_t)n) &&
+            alloc(&p.c_row_ptr, (size_t)n + 1) && alloc(&p.c_col_idx, (size_t)E) && alloc(&p.c_dur, (size_t)n) &&
+            alloc(&p.c_mem, (size_t)n) && alloc(&p.c_req, (size_t)n) && alloc(&p.counts, 3);
+  p.row_ptr = d_row_ptr; p.col_idx = d_col_idx;
+  auto h2d = [&](void *dst, const void *src, size_t bytes) {
+    return bytes == 0 || hip_ok(hipMemcpy(dst, src, bytes, hipMemcpyHostToDevice), "hipMemcpy");
+  };
+  ok = ok && h2d(d_row_ptr, row_ptr, sizeof(int32_t) * ((size_t)n + 1)) && h2d(d_col_idx, col_idx, sizeof(int32_t) * (size_t)E) &&
+       h2d(p.dur, dur64.data(), sizeof(int64_t) * (size_t)n) && h2d(p.mem, mem_delta, sizeof(int64_t) * (size_t)n) &&
+       h2d(p.req, req64.data(), sizeof(int64_t) * (size_t)n) &&
+       hip_ok(hipMemset(p.succ, 0, matrix * sizeof(unsigned long long)), "hipMemset") &&
+       hip_ok(hipMemset(p.pred, 0, matrix * sizeof(unsigned long long)), "hipMemset") &&
+       hip_ok(hipMemset(p.kept, 0, matrix * sizeof(unsigned long long)), "hipMemset");
+  int32_t counts[3] = {0, 0, 0};
+  std::vector<int64_t> out_dur(n);
+  if (ok) {
+    hipLaunchKernelGGL(coarsen_kernel, dim3(1), dim3(1024), 0, (hipStream_t)nullptr, p);
+    ok = hip_ok(hipGetLastError(), "kernel launch") && hip_ok(hipDeviceSynchronize(), "hipDeviceSynchronize");
+  }
+  auto d2h = [&](void *dst, const void *src, size_t bytes) {
+    return bytes == 0 || hip_ok(hipMemcpy(dst, src, bytes, hipMemcpyDeviceToHost), "hipMemcpy");
+  };
+  ok = ok && d2h(counts, p.counts, sizeof(counts));
+  const size_t k = ok ? (size_t)counts[0] : 0;
+  int32_t coarse_edges = 0;
+  ok = ok && d2h(node_map, p.node_map, sizeof(int32_t) * (size_t)n) && d2h(c_row_ptr, p.c_row_ptr, sizeof(int32_t) * (k + 1));
+  if (ok) coarse_edges = c_row_ptr[k];
+  ok = ok && d2h(c_col_idx, p.c_col_idx, sizeof(int32_t) * (size_t)coarse_edges) && d2h(out_dur.data(), p.c_dur, sizeof(int64_t) * k) &&
+       d2h(c_mem_delta, p.c_mem, sizeof(int64_t) * k) && d2h(c_mem_req, p.c_req, sizeof(int64_t) * k);
+  const bool oom = !ok && strstr(g_hip_error, "memory") != nullptr;
+  for (void *b : owned) (void)hipFree(b);
+  if (!ok) return oom ? DAGSCHED_ENOMEM : DAGSCHED_EHIP;
+  for (size_t i = 0; i < k; ++i) c_dur[i] = (int32_t)out_dur[i];
+  result->n_coarse = counts[0]; result->n_coarse_edges = coarse_edges;
+  result->merges_edge = counts[1]; result->merges_nonedge = counts[2];
+  return DAGSCHED_OK;
 }
 
 int dagsched_get_info(const dagsched_t *h, dagsched_info_t *info) {

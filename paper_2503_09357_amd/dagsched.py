@@ -22,7 +22,7 @@ MAX_DEVICES, MAX_NODES = 64, 65535
 
 EXPORTS = ("dagsched_validate", "dagsched_create", "dagsched_evaluate", "dagsched_destroy",
            "dagsched_strerror", "dagsched_get_info", "dagsched_last_fallbacks", "dagsched_time_evaluate", "dagsched_propose",
-           "dagsched_propose_orders", "dagsched_select", "dagsched_schedule", "dagsched_schedule_static")
+           "dagsched_propose_orders", "dagsched_select", "dagsched_schedule", "dagsched_schedule_static", "dagsched_coarsen")
 
 
 class Desc(ctypes.Structure):
@@ -78,6 +78,16 @@ class Info(ctypes.Structure):
                 ("reserved", ctypes.c_int8)]
 
 
+class CoarsenParams(ctypes.Structure):
+    _fields_ = [("target_nodes", ctypes.c_int32), ("edge_dur_max", ctypes.c_int64), ("edge_mem_max", ctypes.c_int64),
+                ("nonedge_dur_max", ctypes.c_int64), ("nonedge_mem_max", ctypes.c_int64)]
+
+
+class CoarsenResult(ctypes.Structure):
+    _fields_ = [("n_coarse", ctypes.c_int32), ("n_coarse_edges", ctypes.c_int32), ("merges_edge", ctypes.c_int32),
+                ("merges_nonedge", ctypes.c_int32)]
+
+
 class DagschedError(RuntimeError):
     def __init__(self, code: int, text: str):
         super().__init__("dagsched error %d: %s" % (code, text))
@@ -124,6 +134,9 @@ def load(import_torch_first: bool = True):
     lib.dagsched_schedule.argtypes = [vp, vp, vp, vp, vp, vp, vp]
     lib.dagsched_schedule_static.restype = ctypes.c_int
     lib.dagsched_schedule_static.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+    lib.dagsched_coarsen.restype = ctypes.c_int
+    lib.dagsched_coarsen.argtypes = [i32, i32, vp, vp, vp, vp, vp, ctypes.POINTER(CoarsenParams), i32, vp, vp, vp, vp, vp, vp,
+                                     ctypes.POINTER(CoarsenResult)]
     _lib = lib
     return lib
 
@@ -135,6 +148,35 @@ def strerror(code: int) -> str:
 def _check(code: int):
     if code != OK:
         raise DagschedError(code, strerror(code))
+
+
+NO_MERGES, NO_LIMIT = -1, 2 ** 62     # thresholds of coarsen: that kind of merge off / no bound
+
+
+def coarsen(row_ptr, col_idx, dur, mem_delta, mem_req=None, target=1, edge_dur_max=NO_LIMIT, edge_mem_max=NO_LIMIT,
+            nonedge_dur_max=NO_LIMIT, nonedge_mem_max=NO_LIMIT, hip_device: int = 0) -> dict:
+    """dagsched_coarsen (Sec. IV, Alg. 1) on host arrays -> dict(n_coarse, node_map [N], row_ptr, col_idx, dur,
+    mem_delta, mem_req, merges_edge, merges_nonedge) of the coarse graph."""
+    rp = np.ascontiguousarray(row_ptr, dtype=np.int32)
+    ci = np.ascontiguousarray(col_idx, dtype=np.int32)
+    n, e = len(rp) - 1, len(ci)
+    d = np.ascontiguousarray(dur, dtype=np.int32)
+    m = np.ascontiguousarray(mem_delta, dtype=np.int64)
+    r = None if mem_req is None else np.ascontiguousarray(mem_req, dtype=np.int64)
+    if d.shape != (n,) or m.shape != (n,) or (r is not None and r.shape != (n,)):
+        raise ValueError("dur, mem_delta and mem_req must have one entry per node")
+    params = CoarsenParams(int(target), int(edge_dur_max), int(edge_mem_max), int(nonedge_dur_max), int(nonedge_mem_max))
+    res = CoarsenResult()
+    node_map = np.empty(max(n, 1), np.int32)
+    c_rp, c_ci = np.empty(max(n, 0) + 1, np.int32), np.empty(max(e, 1), np.int32)
+    c_d, c_m, c_r = np.empty(max(n, 1), np.int32), np.empty(max(n, 1), np.int64), np.empty(max(n, 1), np.int64)
+    ptr = lambda a: a.ctypes.data if a is not None and a.size else None
+    _check(load().dagsched_coarsen(n, e, ptr(rp), ptr(ci), ptr(d), ptr(m), ptr(r), ctypes.byref(params), hip_device,
+                                   ptr(node_map), ptr(c_rp), ptr(c_ci), ptr(c_d), ptr(c_m), ptr(c_r), ctypes.byref(res)))
+    k = res.n_coarse
+    return dict(n_coarse=k, node_map=node_map[:n].copy(), row_ptr=c_rp[:k + 1].copy(), col_idx=c_ci[:res.n_coarse_edges].copy(),
+                dur=c_d[:k].copy(), mem_delta=c_m[:k].copy(), mem_req=c_r[:k].copy(), merges_edge=res.merges_edge,
+                merges_nonedge=res.merges_nonedge)
 
 
 class _HostProblem:
