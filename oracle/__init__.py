@@ -51,6 +51,9 @@ def _load():
                                                      i64, i64, vp, vp, vp, vp]
         lib.dagsched_oracle_schedule_mem.restype = ctypes.c_int
         lib.dagsched_oracle_schedule_mem.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        lib.dagsched_oracle_evaluate_contended.restype = ctypes.c_int
+        lib.dagsched_oracle_evaluate_contended.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, i32, i64, vp, vp, vp,
+                                                           i64, i64, vp, vp, vp, vp, vp, vp, vp]
         _lib = lib
     return _lib
 
@@ -140,6 +143,55 @@ class Problem:
             if rc != OK:
                 raise OracleError(rc)
         return makespan, bubble, peak, flags
+
+    def evaluate_contended(self, placement, rank, edge_rank, layout: int = CAND_MAJOR, threads: int = 1):
+        """With channel contention (eqs. (11)-(15)): edge_rank [C, E] (or [E, C]) is the rank of every edge's transfer
+        on its channel.  -> (makespan, bubble, peak_mem, flags) as evaluate."""
+        placement, rank, edge_rank = _c(placement, np.int32), _c(rank, np.int32), _c(edge_rank, np.int32)
+        if layout == CAND_MAJOR:
+            C = placement.shape[0]
+            assert placement.shape == (C, self.N) and rank.shape == (C, self.N) and edge_rank.shape == (C, self.E)
+            peak = np.empty((C, self.P), dtype=np.int64)
+        else:
+            C = placement.shape[1]
+            assert placement.shape == (self.N, C) and rank.shape == (self.N, C) and edge_rank.shape == (self.E, C)
+            peak = np.empty((self.P, C), dtype=np.int64)
+        makespan, bubble, flags = np.empty(C, np.int32), np.empty(C, np.int64), np.empty(C, np.int32)
+        lib = _load()
+        rcs = []
+
+        def run(first, count):
+            rcs.append(lib.dagsched_oracle_evaluate_contended(
+                *self._head(), *self._mem(), layout, C, _ptr(placement), _ptr(rank), _ptr(edge_rank), first, count,
+                _ptr(makespan), _ptr(bubble), _ptr(peak), _ptr(flags), None, None, None))
+
+        threads = max(1, min(int(threads), C if C else 1))
+        bounds = np.linspace(0, C, threads + 1).astype(np.int64)
+        ts = [threading.Thread(target=run, args=(int(bounds[i]), int(bounds[i + 1] - bounds[i]))) for i in range(threads)]
+        for t in ts:
+            t.start()
+        for t in ts:
+            t.join()
+        for rc in rcs:
+            if rc != OK:
+                raise OracleError(rc)
+        return makespan, bubble, peak, flags
+
+    def schedule_contended(self, placement, rank, edge_rank):
+        """One candidate with channel contention -> (flag, makespan, start [N], end [N], transfer_end [E]; -1 for
+        edges inside a machine); the arrays are valid when the flag is 0 or OVER_MEMORY."""
+        placement, rank = _c(placement, np.int32).reshape(1, -1), _c(rank, np.int32).reshape(1, -1)
+        edge_rank = _c(edge_rank, np.int32).reshape(1, -1)
+        assert placement.shape == (1, self.N) and rank.shape == (1, self.N) and edge_rank.shape == (1, self.E)
+        z, b, f = np.empty(1, np.int32), np.empty(1, np.int64), np.empty(1, np.int32)
+        peak = np.empty((1, self.P), np.int64)
+        start, end, t_end = np.zeros(self.N, np.int64), np.zeros(self.N, np.int64), np.zeros(max(self.E, 1), np.int64)
+        rc = _load().dagsched_oracle_evaluate_contended(
+            *self._head(), *self._mem(), CAND_MAJOR, 1, _ptr(placement), _ptr(rank), _ptr(edge_rank), 0, 1,
+            _ptr(z), _ptr(b), _ptr(peak), _ptr(f), _ptr(start), _ptr(end), _ptr(t_end))
+        if rc != OK:
+            raise OracleError(rc)
+        return int(f[0]), int(z[0]), start, end, t_end[:self.E]
 
     def schedule(self, placement, rank):
         """One candidate -> (flag, start, end, m_minus, m_plus); arrays valid when flag == 0."""

@@ -443,6 +443,35 @@ def random_dag(rng: np.random.Generator, n: int, max_fanin: int = 3, window: Opt
     return csr_from_edges(n, src, dst)
 
 
+def fcfs_edge_ranks(row_ptr: np.ndarray, col_idx: np.ndarray, n_devices: int, placement: np.ndarray,
+                    rank: np.ndarray) -> np.ndarray:
+    """Channel orders for the evaluation with contention: [C, E] int32, for every candidate and every DAG edge (in
+    successor-CSR order) the rank of the edge's transfer among the transfers of its channel (the ordered pair of its
+    ends' machines), first come first served: by the producer's rank on its machine, then by edge index.  The
+    producers of one channel share a machine, so this order never contradicts the candidate's own orders.  Edges
+    inside a machine, and edges of candidates with a placement out of range, get 0."""
+    n = len(row_ptr) - 1
+    e = len(col_idx)
+    src = np.repeat(np.arange(n, dtype=np.int64), np.diff(row_ptr))
+    dst = np.asarray(col_idx, dtype=np.int64)
+    out = np.zeros((placement.shape[0], e), dtype=np.int32)
+    edge_no = np.arange(e, dtype=np.int64)
+    for c in range(placement.shape[0]):
+        a, b = placement[c, src].astype(np.int64), placement[c, dst].astype(np.int64)
+        if e == 0 or a.min() < 0 or a.max() >= n_devices or b.min() < 0 or b.max() >= n_devices:
+            continue
+        cross = np.nonzero(a != b)[0]
+        if len(cross) == 0:
+            continue
+        ch = a[cross] * n_devices + b[cross]
+        order = np.lexsort((edge_no[cross], rank[c, src[cross]], ch))
+        ch_sorted = ch[order]
+        first = np.r_[0, np.nonzero(np.diff(ch_sorted))[0] + 1]
+        start_of = np.repeat(first, np.diff(np.r_[first, len(order)]))
+        out[c, cross[order]] = (np.arange(len(order)) - start_of).astype(np.int32)
+    return out
+
+
 def random_dag_bounded_degree(rng: np.random.Generator, n: int, max_degree: int = 3, window: int = 12
                               ) -> Tuple[np.ndarray, np.ndarray]:
     """Random DAG whose in- and out-degrees are at most max_degree (the shape of the random computational graph of
