@@ -129,6 +129,9 @@ typedef struct {
                                      candidates with a kernel of their own; candidates that place differently
                                      are still evaluated, one by one and slowly.  Results never depend on it.
                                      Entries outside [0, P): DAGSCHED_EINVAL                                   */
+  int32_t contention;       /* 1: dagsched_evaluate_contended will be called on this handle; create then also
+                               checks sum(dur) + E * max comm <= INT32_MAX (a path may pay one transfer per edge)
+                               and allocates that call's workspace.  0 otherwise                               */
 } dagsched_desc_t;
 
 /*
@@ -162,6 +165,25 @@ int dagsched_create(const dagsched_desc_t *desc, dagsched_t **out);
 int dagsched_evaluate(dagsched_t *h, int32_t n_cand, const int32_t *placement, const int32_t *rank,
                       int32_t *makespan, int64_t *bubble, int64_t *peak_mem, int32_t *flags,
                       void *hip_stream);
+
+/*
+ * dagsched_evaluate with channel contention (eqs. (11)-(15)): the message of an edge (u, x) of B whose ends sit on
+ * different machines a, b is a transfer that occupies the channel (a, b) for comm[a*P + b] time units; it starts
+ * once u has ended (eq. (13)) and the transfer before it on that channel has ended (eqs. (14)-(15)), and x starts
+ * after it has ended (eqs. (11)-(12)).  The order of the transfers of a channel, i.e. the binaries w of eqs.
+ * (14)-(15), comes with the candidate:
+ *   edge_rank : int32 DEVICE, E * n_cand entries in the handle's layout (candidate-major edge_rank[c*E + k],
+ *               candidate-minor edge_rank[k*C + c]); entry k belongs to the k-th edge of the description's CSR
+ *               (u -> col_idx[k]) and is the rank of its transfer among the transfers of the same channel, which
+ *               must be exactly 0..n-1 on every channel (else DAGSCHED_FLAG_BAD_RANK).  Entries of edges inside a
+ *               machine are not looked at.
+ * Everything else as dagsched_evaluate: same outputs, same flags (DAGSCHED_FLAG_CYCLIC now also for a cycle through
+ * transfers), same asynchrony.  The makespan is taken over the operations (eq. (2)).  Only for handles made with
+ * dagsched_desc_t.contention = 1 (else DAGSCHED_EINVAL).
+ */
+int dagsched_evaluate_contended(dagsched_t *h, int32_t n_cand, const int32_t *placement, const int32_t *rank,
+                                const int32_t *edge_rank, int32_t *makespan, int64_t *bubble, int64_t *peak_mem,
+                                int32_t *flags, void *hip_stream);
 
 /* Release the handle and its device memory.  NULL is a no-op.  Synchronises the device first. */
 void dagsched_destroy(dagsched_t *h);

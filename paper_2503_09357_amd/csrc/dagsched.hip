@@ -33,6 +33,7 @@
 #include "dagsched.h"
 #include "device_common.h"
 #include "kernel_coarsen.h"
+#include "kernel_contended.h"
 #include "kernel_general.h"
 #include "kernel_ring.h"
 #include "kernel_search.h"
@@ -115,7 +116,13 @@ struct dagsched {
   int32_t *ws_cnt = nullptr, *ws_sched_list = nullptr, *ws_sched_end = nullptr;
   unsigned char *ws_sched_out = nullptr;
   // candidate-minor input staging
-  int32_t *ws_tp = nullptr, *ws_tr = nullptr;
+  int32_t *ws_tp = nullptr, *ws_tr = nullptr, *ws_te = nullptr;
+  // evaluation with channel contention: edge tables and one workspace row per resident workgroup
+  bool contention = false;
+  int32_t *d_pred_eid = nullptr, *d_edge_src = nullptr, *d_edge_dst = nullptr;
+  int32_t *wc_list = nullptr, *wc_end = nullptr, *wc_tlist = nullptr, *wc_tend = nullptr, *wc_ccnt = nullptr, *wc_coff = nullptr;
+  int32_t wc_grid = 0;
+  int64_t row_e = 0, row_c = 0;
 };
 
 namespace {
@@ -210,7 +217,8 @@ void free_handle(dagsched *h) {
   void *bufs[] = {h->d_pred_ptr, h->d_pred_idx, h->d_dur, h->d_comm, h->d_mem, h->d_weight, h->d_limit, h->ws_list, h->ws_end, h->d_rec,
                   h->d_comm_scaled, h->d_nparts, h->ws_list16, h->ws_pib, h->ws_cnt, h->ws_sched_list, h->ws_sched_end,
                   h->ws_sched_out, h->d_fb_count, h->d_fb_list, h->ws_tp, h->ws_tr, h->d_no_channel, h->d_edges,
-                  h->d_st_ops, h->d_st_machine, h->d_st_off, h->d_st_base};
+                  h->d_st_ops, h->d_st_machine, h->d_st_off, h->d_st_base, h->ws_te, h->d_pred_eid, h->d_edge_src, h->d_edge_dst,
+                  h->wc_list, h->wc_end, h->wc_tlist, h->wc_tend, h->wc_ccnt, h->wc_coff};
   for (void *b : bufs)
     if (b) (void)hipFree(b);
   delete h;
@@ -727,6 +735,14 @@ int dagsched_create(const dagsched_desc_t *caller_desc, dagsched_t **out) {
   int64_t sum_dur = 0;
   int rc = validate_desc(caller_desc, &pred_ptr, &pred_idx, &sum_dur);
   if (rc != DAGSCHED_OK) return rc;
+  if (caller_desc->contention != 0 && caller_desc->contention != 1) return DAGSCHED_EINVAL;
+  if (caller_desc->contention) {                        // a path may pay one transfer per edge of B
+    int64_t max_comm = 0;
+    for (int a = 0; a < caller_desc->n_devices; ++a)
+      for (int b = 0; b < caller_desc->n_devices; ++b)
+        if (a != b) max_comm = std::max<int64_t>(max_comm, caller_desc->comm[a * caller_desc->n_devices + b]);
+    if (sum_dur + (int64_t)caller_desc->n_edges * max_comm > (int64_t)INT32_MAX) return DAGSCHED_EOVERFLOW;
+  }
   // pairs without a channel (eq. (10)) become a bit matrix for the flag pass; the evaluation itself sees delay 0
   dagsched_desc_t cleaned = *caller_desc;
   const dagsched_desc_t *desc = &cleaned;
@@ -847,6 +863,28 @@ int dagsched_create(const dagsched_desc_t *caller_desc, dagsched_t **out) {
   }
   if (ok && h->layout == DAGSCHED_CAND_MINOR)
     ok = dev_alloc(&h->ws_tp, maxc * (size_t)h->N) && dev_alloc(&h->ws_tr, maxc * (size_t)h->N);
+  if (ok && desc->contention) {
+    // the edges by their index in successor-CSR order (the index edge_rank uses), and that index for every in-edge
+    const int32_t E = h->E;
+    std::vector<int32_t> peid((size_t)std::max(E, 1)), esrc((size_t)std::max(E, 1)), edst((size_t)std::max(E, 1));
+    std::vector<int32_t> fill(pred_ptr.begin(), pred_ptr.end() - 1);
+    for (int32_t u = 0; u < h->N; ++u)
+      for (int32_t k = desc->row_ptr[u]; k < desc->row_ptr[u + 1]; ++k) {
+        const int32_t v = desc->col_idx[k];
+        peid[fill[v]++] = k; esrc[k] = u; edst[k] = v;
+      }
+    h->contention = true;
+    h->wc_grid = (int32_t)std::min<int64_t>(h->max_cand, (int64_t)n_cu * 8);
+    h->row_e = ((int64_t)std::max(E, 1) + 31) / 32 * 32;
+    h->row_c = ((int64_t)h->P * h->P + 1 + 31) / 32 * 32;
+    const size_t g = (size_t)h->wc_grid;
+    ok = upload(&h->d_pred_eid, peid.data(), (size_t)E) && upload(&h->d_edge_src, esrc.data(), (size_t)E) &&
+         upload(&h->d_edge_dst, edst.data(), (size_t)E) &&
+         dev_alloc(&h->wc_list, g * (size_t)h->row_stride) && dev_alloc(&h->wc_end, g * (size_t)h->row_stride) &&
+         dev_alloc(&h->wc_tlist, g * (size_t)h->row_e) && dev_alloc(&h->wc_tend, g * (size_t)h->row_e) &&
+         dev_alloc(&h->wc_ccnt, g * (size_t)h->row_c) && dev_alloc(&h->wc_coff, g * (size_t)h->row_c) &&
+         (h->layout != DAGSCHED_CAND_MINOR || dev_alloc(&h->ws_te, maxc * (size_t)std::max(E, 1)));
+  }
   if (!ok) {
     const bool oom = strstr(g_hip_error, "memory") != nullptr;
     free_handle(h);
@@ -861,6 +899,46 @@ int dagsched_evaluate(dagsched_t *h, int32_t n_cand, const int32_t *placement, c
   int rc = check_evaluate_args(h, n_cand, placement, rank, makespan, bubble, peak_mem, flags);
   if (rc != DAGSCHED_OK || n_cand == 0) return rc;
   return launch_evaluate(h, n_cand, placement, rank, makespan, bubble, peak_mem, flags, (hipStream_t)hip_stream);
+}
+
+int dagsched_evaluate_contended(dagsched_t *h, int32_t n_cand, const int32_t *placement, const int32_t *rank,
+                                const int32_t *edge_rank, int32_t *makespan, int64_t *bubble, int64_t *peak_mem,
+                                int32_t *flags, void *hip_stream) {
+  int rc = check_evaluate_args(h, n_cand, placement, rank, makespan, bubble, peak_mem, flags);
+  if (rc != DAGSCHED_OK) return rc;
+  if (!h->contention || (n_cand > 0 && h->E > 0 && !edge_rank)) return DAGSCHED_EINVAL;
+  if (n_cand == 0) return DAGSCHED_OK;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  const int32_t N = h->N, E = h->E;
+  const int32_t *pl = placement, *rk = rank, *er = edge_rank;
+  if (h->layout == DAGSCHED_CAND_MINOR) {
+    dim3 grid((unsigned)((n_cand + 63) / 64), (unsigned)((N + 63) / 64));
+    hipLaunchKernelGGL(transpose_i32_kernel, grid, dim3(256), 0, stream, placement, h->ws_tp, (int64_t)N, (int64_t)n_cand);
+    hipLaunchKernelGGL(transpose_i32_kernel, grid, dim3(256), 0, stream, rank, h->ws_tr, (int64_t)N, (int64_t)n_cand);
+    pl = h->ws_tp; rk = h->ws_tr;
+    if (E > 0) {
+      dim3 egrid((unsigned)((n_cand + 63) / 64), (unsigned)((E + 63) / 64));
+      hipLaunchKernelGGL(transpose_i32_kernel, egrid, dim3(256), 0, stream, edge_rank, h->ws_te, (int64_t)E, (int64_t)n_cand);
+      er = h->ws_te;
+    }
+  }
+  ContendedParams p;
+  p.N = N; p.E = E; p.P = h->P; p.C = n_cand;
+  p.pred_ptr = h->d_pred_ptr; p.pred_idx = h->d_pred_idx; p.pred_eid = h->d_pred_eid;
+  p.edge_src = h->d_edge_src; p.edge_dst = h->d_edge_dst;
+  p.dur = h->d_dur; p.comm = h->d_comm; p.mem_delta = h->d_mem; p.weight = h->d_weight; p.mem_limit = h->d_limit;
+  p.sum_dur = h->sum_dur;
+  p.placement = pl; p.rank = rk; p.edge_rank = er;
+  p.ws_list = h->wc_list; p.ws_end = h->wc_end; p.ws_tlist = h->wc_tlist; p.ws_tend = h->wc_tend;
+  p.ws_ccnt = h->wc_ccnt; p.ws_coff = h->wc_coff;
+  p.row_n = h->row_stride; p.row_e = h->row_e; p.row_c = h->row_c;
+  p.out = make_out(h, n_cand, makespan, bubble, peak_mem, flags);
+  hipLaunchKernelGGL(relax_contended_kernel, dim3((unsigned)std::min(n_cand, h->wc_grid)), dim3(kContendedThreads), 0, stream, p);
+  if (h->d_no_channel)
+    hipLaunchKernelGGL(channel_flag_kernel, dim3((unsigned)n_cand), dim3(n_cand < 2048 ? 1024 : 256), channel_flag_lds(N), stream, N, E,
+                       h->P, h->d_edges, h->d_no_channel, pl, p.out);
+  if (!hip_ok(hipGetLastError(), "kernel launch")) return DAGSCHED_EHIP;
+  return DAGSCHED_OK;
 }
 
 int dagsched_time_evaluate(dagsched_t *h, int32_t n_cand, const int32_t *placement, const int32_t *rank,

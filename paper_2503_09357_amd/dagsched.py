@@ -20,7 +20,7 @@ NO_CHANNEL = -1      # off-diagonal comm entry of a machine pair without a chann
 CAND_MAJOR, CAND_MINOR = 0, 1
 MAX_DEVICES, MAX_NODES = 64, 65535
 
-EXPORTS = ("dagsched_validate", "dagsched_create", "dagsched_evaluate", "dagsched_destroy",
+EXPORTS = ("dagsched_validate", "dagsched_create", "dagsched_evaluate", "dagsched_evaluate_contended", "dagsched_destroy",
            "dagsched_strerror", "dagsched_get_info", "dagsched_last_fallbacks", "dagsched_time_evaluate", "dagsched_propose",
            "dagsched_propose_orders", "dagsched_select", "dagsched_schedule", "dagsched_schedule_static", "dagsched_coarsen")
 
@@ -31,7 +31,7 @@ class Desc(ctypes.Structure):
                 ("comm", ctypes.c_void_p), ("mem_delta", ctypes.c_void_p),
                 ("max_candidates", ctypes.c_int32), ("layout", ctypes.c_int32), ("hip_device", ctypes.c_int32),
                 ("weight", ctypes.c_void_p), ("mem_limit", ctypes.c_void_p), ("shape", ctypes.c_void_p),
-                ("shared_placement", ctypes.c_void_p)]
+                ("shared_placement", ctypes.c_void_p), ("contention", ctypes.c_int32)]
 
 
 class Shape(ctypes.Structure):
@@ -114,6 +114,8 @@ def load(import_torch_first: bool = True):
     lib.dagsched_create.argtypes = [ctypes.POINTER(Desc), ctypes.POINTER(vp)]
     lib.dagsched_evaluate.restype = ctypes.c_int
     lib.dagsched_evaluate.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp]
+    lib.dagsched_evaluate_contended.restype = ctypes.c_int
+    lib.dagsched_evaluate_contended.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.dagsched_time_evaluate.restype = ctypes.c_int
     lib.dagsched_time_evaluate.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, i32, ctypes.POINTER(ctypes.c_float)]
     lib.dagsched_destroy.restype = None
@@ -183,7 +185,8 @@ class _HostProblem:
     """Keeps the contiguous host arrays alive while a Desc points at them."""
 
     def __init__(self, n_devices, row_ptr, col_idx, dur, comm, mem_delta, max_candidates, layout, hip_device,
-                 n_nodes=None, n_edges=None, weight=None, mem_limit=None, shape=None, shared_placement=None):
+                 n_nodes=None, n_edges=None, weight=None, mem_limit=None, shape=None, shared_placement=None,
+                 contention=False):
         self.row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int32)
         self.col_idx = np.ascontiguousarray(col_idx, dtype=np.int32)
         self.dur = np.ascontiguousarray(dur, dtype=np.int32)
@@ -221,14 +224,16 @@ class _HostProblem:
         if self.shared_placement is not None and self.shared_placement.shape != (d.n_nodes,):
             raise ValueError("shared_placement must have one entry per node")
         d.shared_placement = None if self.shared_placement is None else self.shared_placement.ctypes.data
+        d.contention = 1 if contention else 0
         self.desc = d
 
 
 def validate(n_devices, row_ptr, col_idx, dur, comm, mem_delta, max_candidates=1, layout=CAND_MAJOR,
-             n_nodes=None, n_edges=None, weight=None, mem_limit=None, shape=None, shared_placement=None) -> int:
+             n_nodes=None, n_edges=None, weight=None, mem_limit=None, shape=None, shared_placement=None,
+             contention=False) -> int:
     """Host-only description check; returns the code dagsched_create would return."""
     hp = _HostProblem(n_devices, row_ptr, col_idx, dur, comm, mem_delta, max_candidates, layout, 0, n_nodes, n_edges,
-                      weight, mem_limit, shape, shared_placement)
+                      weight, mem_limit, shape, shared_placement, contention)
     return load(import_torch_first=False).dagsched_validate(ctypes.byref(hp.desc))
 
 
@@ -237,21 +242,23 @@ class Evaluator:
 
     def __init__(self, n_devices, row_ptr, col_idx, dur, comm, mem_delta, max_candidates: int,
                  layout: int = CAND_MAJOR, hip_device: int = 0, weight=None, mem_limit=None, shape=None,
-                 shared_placement=None):
+                 shared_placement=None, contention: bool = False):
         """shared_placement: [N] machine of every operation when (nearly) all candidates will place alike and differ
-        in the orders only; a hint that selects a faster kernel, never changes a result."""
+        in the orders only; a hint that selects a faster kernel, never changes a result.
+        contention: the handle will also be used for evaluate_contended (channel contention, eqs. (11)-(15))."""
         lib = load()
         hp = _HostProblem(n_devices, row_ptr, col_idx, dur, comm, mem_delta, max_candidates, layout, hip_device,
-                          weight=weight, mem_limit=mem_limit, shape=shape, shared_placement=shared_placement)
+                          weight=weight, mem_limit=mem_limit, shape=shape, shared_placement=shared_placement,
+                          contention=contention)
         handle = ctypes.c_void_p()
         _check(lib.dagsched_create(ctypes.byref(hp.desc), ctypes.byref(handle)))
         self._h = handle
-        self.N, self.P = hp.desc.n_nodes, n_devices
+        self.N, self.P, self.E = hp.desc.n_nodes, n_devices, hp.desc.n_edges
         self.layout, self.max_candidates, self.hip_device = layout, max_candidates, hip_device
 
     @classmethod
     def for_workload(cls, w, max_candidates: Optional[int] = None, layout: int = CAND_MAJOR, hip_device: int = 0,
-                     shape=None, shared_placement="auto"):
+                     shape=None, shared_placement="auto", contention: bool = False):
         """shared_placement "auto": pass the hint when the workload has several candidates and all place alike."""
         if isinstance(shared_placement, str):
             pl = np.asarray(w.placement)
@@ -260,7 +267,7 @@ class Evaluator:
         return cls(w.n_devices, w.row_ptr, w.col_idx, w.dur, w.comm, w.mem_delta,
                    w.n_cand if max_candidates is None else max_candidates, layout, hip_device,
                    weight=getattr(w, "weight", None), mem_limit=getattr(w, "mem_limit", None), shape=shape,
-                   shared_placement=shared_placement)
+                   shared_placement=shared_placement, contention=contention)
 
     @classmethod
     def autotuned(cls, make, placement, rank, reps: int = 3, verbose: bool = False):
@@ -351,6 +358,23 @@ class Evaluator:
         s = torch.cuda.current_stream(self.hip_device) if stream is None else stream
         _check(load().dagsched_evaluate(self._h, n_cand, placement.data_ptr(), rank.data_ptr(), z.data_ptr(),
                                         b.data_ptr(), pk.data_ptr(), f.data_ptr(), s.cuda_stream))
+        return out
+
+    def evaluate_contended(self, placement, rank, edge_rank, out: Optional[Tuple] = None, stream=None):
+        """Evaluation with channel contention: edge_rank is a device int32 tensor [C, E] (candidate-major) or [E, C],
+        the rank of every DAG edge's transfer on its channel.  Same outputs as evaluate; asynchronous."""
+        import torch
+        n_cand = self._n_cand(placement, rank)
+        want = (n_cand, self.E) if self.layout == CAND_MAJOR else (self.E, n_cand)
+        if not (edge_rank.is_cuda and edge_rank.dtype == torch.int32 and edge_rank.is_contiguous() and tuple(edge_rank.shape) == want):
+            raise ValueError("edge_rank must be a contiguous int32 device tensor of shape %s" % (want,))
+        if out is None:
+            out = self.alloc_outputs(n_cand)
+        z, b, pk, f = out
+        s = torch.cuda.current_stream(self.hip_device) if stream is None else stream
+        _check(load().dagsched_evaluate_contended(self._h, n_cand, placement.data_ptr(), rank.data_ptr(),
+                                                  edge_rank.data_ptr() if self.E else None, z.data_ptr(), b.data_ptr(),
+                                                  pk.data_ptr(), f.data_ptr(), s.cuda_stream))
         return out
 
     def time_evaluate(self, placement, rank, out, reps: int, stream=None) -> float:
