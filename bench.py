@@ -122,8 +122,12 @@ def main() -> int:
     ms_per_step = 1e3 * wall / args.steps
     cand_per_s = w.n_cand * args.steps / wall
 
-    # kernel time from HIP events recorded on the launch stream (device time, no host gaps)
+    # kernel time from HIP events recorded on the launch stream (device time, no host gaps): the mean over the
+    # launches of one back-to-back run, and the median of single launches
     ms_kernel = ev.time_evaluate(tp, tr, out, reps=max(5, args.steps))
+    singles = sorted(ev.time_evaluate(tp, tr, out, reps=1) for _ in range(max(20, min(args.steps, 50))))
+    ms_kernel_median = singles[len(singles) // 2]
+    n_fallback = ev.last_fallbacks()
     torch.cuda.synchronize()
     got = [t.cpu().numpy() for t in out]
     abytes = algorithmic_bytes(w)
@@ -149,6 +153,8 @@ def main() -> int:
         "node_relax_per_s": cand_per_s * w.n_nodes,
         "edge_relax_per_s": cand_per_s * (w.n_edges + w.n_nodes - w.n_devices),
         "ms_kernel_hip_events": ms_kernel,
+        "ms_kernel_median_single_launch": ms_kernel_median,
+        "candidates_sent_to_int32_kernel": n_fallback,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(args.config, dominant_kernel(ev.info())),
                      "kernel": dominant_kernel(ev.info()),
@@ -199,27 +205,73 @@ def main() -> int:
     del tp, tr, out
 
     if not args.no_other_workloads:
-        # short, untimed-by-the-driver runs of the other workloads (parity for them is in tests/)
+        # short runs of the other workloads, each checked against the oracle in this same run; plus the headline
+        # workload in the candidate-minor layout (the transposes in front of the kernel are part of that time)
+        import oracle
         others = []
-        for cfg in (1, 2, 3, 4, 5):
-            if cfg == args.config:
-                continue
+        for cfg, layout in [(c, 0) for c in (1, 2, 3, 4, 5) if c != args.config] + [(args.config, 1 - args.layout)]:
             w2 = W.gen_config(cfg)
-            ev2 = ds.Evaluator.for_workload(w2)
-            p2, r2 = torch.from_numpy(w2.placement).to(dev), torch.from_numpy(w2.rank).to(dev)
+            pl2, rk2 = (w2.placement, w2.rank) if layout == 0 else (np.ascontiguousarray(w2.placement.T), np.ascontiguousarray(w2.rank.T))
+            ev2 = ds.Evaluator.for_workload(w2, layout=layout)
+            p2, r2 = torch.from_numpy(pl2).to(dev), torch.from_numpy(rk2).to(dev)
             o2 = ev2.alloc_outputs(w2.n_cand)
             for _ in range(5):
                 ev2.evaluate(p2, r2, o2)
             torch.cuda.synchronize()
             ms2 = ev2.time_evaluate(p2, r2, o2, reps=30)
+            singles2 = sorted(ev2.time_evaluate(p2, r2, o2, reps=1) for _ in range(21))
+            got2 = [t.cpu().numpy() for t in o2]
+            want2 = oracle.evaluate_workload(w2, layout, threads=min(16, os.cpu_count() or 1))
+            parity2 = all(bool((a == b).all()) for a, b in zip(got2, want2))
             ab2 = algorithmic_bytes(w2)
-            others.append({"workload": w2.name, "cfg": cfg, "ms_kernel_hip_events": ms2,
+            info2 = ev2.info()
+            others.append({"workload": w2.name, "cfg": cfg, "layout": "candidate-major" if layout == 0 else "candidate-minor",
+                           "ms_kernel_hip_events": ms2, "ms_kernel_median_single_launch": singles2[len(singles2) // 2],
                            "candidates_per_s": w2.n_cand / (ms2 * 1e-3),
                            "node_relax_per_s": w2.n_cand * w2.n_nodes / (ms2 * 1e-3),
-                           "roofline_frac": ab2 / (ms2 * 1e-3) / 1e9 / HBM_PEAK_GBS, "kernel": ev2.info()})
+                           "roofline_frac": ab2 / (ms2 * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                           "traffic": measured_traffic(cfg, dominant_kernel(info2)) if layout == 0 else None,
+                           "candidates_sent_to_int32_kernel": ev2.last_fallbacks(),
+                           "parity_vs_oracle": parity2, "kernel": info2})
             ev2.close()
             del p2, r2, o2, w2
+            if not parity2:
+                result["other_workloads"] = others
+                print("bench.py: GPU results differ from the oracle on workload %d (layout %d)" % (cfg, layout), file=sys.stderr)
+                print(json.dumps(result))
+                return 1
         result["other_workloads"] = others
+        # the steps around the path: evaluation with channel contention (eqs. (14)-(15)) and coarsening (Alg. 1)
+        extras = {}
+        w3 = W.gen_config(args.config, n_cand=512)
+        er = W.fcfs_edge_ranks(w3.row_ptr, w3.col_idx, w3.n_devices, w3.placement, w3.rank)
+        ev3 = ds.Evaluator.for_workload(w3, contention=True)
+        p3, r3, e3 = (torch.from_numpy(a).to(dev) for a in (w3.placement, w3.rank, er))
+        o3 = ev3.evaluate_contended(p3, r3, e3)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(3):
+            ev3.evaluate_contended(p3, r3, e3, o3)
+        torch.cuda.synchronize()
+        ms3 = 1e3 * (time.perf_counter() - t0) / 3
+        want3 = oracle.Problem.of(w3).evaluate_contended(w3.placement, w3.rank, er, threads=min(16, os.cpu_count() or 1))
+        extras["channel_contention"] = {"workload": w3.name, "n_candidates": w3.n_cand, "channel_orders": "first come, first served",
+                                        "ms_per_evaluate": ms3, "candidates_per_s": w3.n_cand / (ms3 * 1e-3),
+                                        "parity_vs_oracle": all(bool((a.cpu().numpy() == b).all()) for a, b in zip(o3, want3))}
+        ev3.close()
+        rng = np.random.default_rng(20250309)
+        rp, ci = W.random_dag_bounded_degree(rng, 200, 3)
+        cd, cm, cr = rng.integers(1, 20, 200), rng.integers(-3, 4, 200), rng.integers(0, 10, 200)
+        kw = dict(target=40, edge_dur_max=200, edge_mem_max=200, nonedge_dur_max=80, nonedge_mem_max=80)
+        ds.coarsen(rp, ci, cd, cm, cr, **kw)
+        t0 = time.perf_counter()
+        got4 = ds.coarsen(rp, ci, cd, cm, cr, **kw)
+        ms4 = 1e3 * (time.perf_counter() - t0)
+        want4 = oracle.coarsen(rp, ci, cd, cm, cr, **kw)
+        extras["coarsening"] = {"graph": "random, 200 operations, in- and out-degree <= 3 (the scale of Sec. V-B)", "n_coarse": int(got4["n_coarse"]),
+                                "ms_per_call_with_allocation_and_copies": ms4,
+                                "parity_vs_oracle": bool(all((got4[k] == want4[k]).all() if hasattr(got4[k], "all") else got4[k] == want4[k] for k in want4))}
+        result["around_the_path"] = extras
     print(json.dumps(result))
     return 0
 

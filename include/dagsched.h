@@ -317,6 +317,14 @@ typedef struct {
 int dagsched_get_info(const dagsched_t *h, dagsched_info_t *info);
 
 /*
+ * Host-only (no GPU is touched): the kernel variant and launch shape dagsched_create would choose for this
+ * description on a GPU with lds_bytes of LDS per workgroup and n_cu compute units (an MI355X has 163840 and 256).
+ * Returns what dagsched_validate returns for the description, or DAGSCHED_EINVAL for a NULL info or sizes below
+ * 1024 bytes / 1 unit.  For capacity planning, and for testing the planning code where no GPU is at hand.
+ */
+int dagsched_plan(const dagsched_desc_t *desc, int32_t lds_bytes, int32_t n_cu, dagsched_info_t *info);
+
+/*
  * How many candidates of the handle's LAST evaluate were handed to the general int32 kernel one by one: those
  * whose end times left the 16-bit range of an optimistic run (variant 4), or that do not use the shared placement
  * (variant 6).  That path is an order of magnitude slower per candidate, so a caller who sees a large count should

@@ -1158,6 +1158,50 @@ int dagsched_coarsen(int32_t n_nodes, int32_t n_edges, const int32_t *row_ptr, c
   return DAGSCHED_OK;
 }
 
+int dagsched_plan(const dagsched_desc_t *caller_desc, int32_t lds_bytes, int32_t n_cu, dagsched_info_t *info) {
+  if (!info || lds_bytes < 1024 || n_cu < 1) return DAGSCHED_EINVAL;
+  std::vector<int32_t> pred_ptr, pred_idx;
+  int64_t sum_dur = 0;
+  const int rc = validate_desc(caller_desc, &pred_ptr, &pred_idx, &sum_dur);
+  if (rc != DAGSCHED_OK) return rc;
+  // what dagsched_create does with the description, without the uploads: missing channels evaluate as delay 0
+  dagsched_desc_t cleaned = *caller_desc;
+  const int P = cleaned.n_devices;
+  std::vector<int32_t> comm_present((size_t)P * P);
+  for (int a = 0; a < P; ++a)
+    for (int b = 0; b < P; ++b) {
+      const int32_t d = caller_desc->comm[a * P + b];
+      comm_present[(size_t)a * P + b] = (a == b || d == DAGSCHED_NO_CHANNEL) ? 0 : d;
+    }
+  cleaned.comm = comm_present.data();
+  dagsched h;
+  h.N = cleaned.n_nodes; h.E = cleaned.n_edges; h.P = P; h.Pseg = next_pow2(P);
+  const bool force_general = cleaned.shape && cleaned.shape->kernel == 1;
+  RingPlan plan;
+  StaticPlan splan;
+  if (!force_general && cleaned.shared_placement && !(cleaned.shape && cleaned.shape->ignore_shared_placement))
+    splan = plan_static(&cleaned, pred_ptr, pred_idx, sum_dur, lds_bytes, n_cu);
+  if (!force_general && !splan.ok) plan = plan_ring(&cleaned, pred_ptr, pred_idx, sum_dur, lds_bytes);
+  if (splan.ok || !plan.ok || !plan.exact) {
+    h.gen_G = kWave / h.Pseg;
+    const int64_t lds_need = (int64_t)h.gen_G * h.N * 4;
+    h.gen_lds_state = lds_need + 1024 <= lds_bytes;
+    h.gen_lds = h.gen_lds_state ? (int32_t)lds_need : 0;
+    h.variant = h.gen_lds_state ? kVariantGeneralLds : kVariantGeneralGlobal;
+  }
+  if (splan.ok) {
+    h.variant = kVariantStatic;
+    h.time_scale = splan.scale; h.st_preds = splan.preds;
+    h.st.G = splan.G; h.st.W = splan.W; h.st.total = splan.total;
+  }
+  if (plan.ok) {
+    h.variant = plan.cell32 ? kVariantRing32 : plan.exact ? kVariantRingExact : kVariantRingOptimistic;
+    h.ring_G = plan.G; h.ring_slots = plan.ring; h.ring_feeders = plan.feeders; h.ring_kind = plan.kind; h.ring_block = plan.block;
+    h.lds = plan.lds; h.time_scale = plan.scale;
+  }
+  return dagsched_get_info(&h, info);
+}
+
 int dagsched_get_info(const dagsched_t *h, dagsched_info_t *info) {
   if (!h || !info) return DAGSCHED_EINVAL;
   memset(info, 0, sizeof(*info));

@@ -21,7 +21,7 @@ CAND_MAJOR, CAND_MINOR = 0, 1
 MAX_DEVICES, MAX_NODES = 64, 65535
 
 EXPORTS = ("dagsched_validate", "dagsched_create", "dagsched_evaluate", "dagsched_evaluate_contended", "dagsched_destroy",
-           "dagsched_strerror", "dagsched_get_info", "dagsched_last_fallbacks", "dagsched_time_evaluate", "dagsched_propose",
+           "dagsched_strerror", "dagsched_get_info", "dagsched_plan", "dagsched_last_fallbacks", "dagsched_time_evaluate", "dagsched_propose",
            "dagsched_propose_orders", "dagsched_select", "dagsched_schedule", "dagsched_schedule_static", "dagsched_coarsen")
 
 
@@ -124,6 +124,8 @@ def load(import_torch_first: bool = True):
     lib.dagsched_strerror.argtypes = [ctypes.c_int]
     lib.dagsched_get_info.restype = ctypes.c_int
     lib.dagsched_get_info.argtypes = [vp, ctypes.POINTER(Info)]
+    lib.dagsched_plan.restype = ctypes.c_int
+    lib.dagsched_plan.argtypes = [ctypes.POINTER(Desc), i32, i32, ctypes.POINTER(Info)]
     lib.dagsched_last_fallbacks.restype = ctypes.c_int
     lib.dagsched_last_fallbacks.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_int32)]
     lib.dagsched_propose.restype = ctypes.c_int
@@ -237,6 +239,23 @@ def validate(n_devices, row_ptr, col_idx, dur, comm, mem_delta, max_candidates=1
     return load(import_torch_first=False).dagsched_validate(ctypes.byref(hp.desc))
 
 
+def _info_dict(i: "Info") -> dict:
+    d = {k: getattr(i, k) for k in ("variant", "cand_per_block", "block_threads", "lds_bytes", "state_bits",
+                                    "ring_slots", "time_scale", "feeders", "preds_per_op", "kernel_kind", "wide_ops")}
+    d["placement_bytes_in_lds"] = i.placement_mode
+    return d
+
+
+def plan(n_devices, row_ptr, col_idx, dur, comm, mem_delta, max_candidates=1, layout=CAND_MAJOR, weight=None,
+         mem_limit=None, shape=None, shared_placement=None, lds_bytes: int = 160 * 1024, n_cu: int = 256) -> dict:
+    """Host-only: the kernel variant and shape dagsched_create would choose (dagsched_plan); raises on a bad description."""
+    hp = _HostProblem(n_devices, row_ptr, col_idx, dur, comm, mem_delta, max_candidates, layout, 0, weight=weight,
+                      mem_limit=mem_limit, shape=shape, shared_placement=shared_placement)
+    i = Info()
+    _check(load(import_torch_first=False).dagsched_plan(ctypes.byref(hp.desc), lds_bytes, n_cu, ctypes.byref(i)))
+    return _info_dict(i)
+
+
 class Evaluator:
     """dagsched_create / dagsched_evaluate / dagsched_destroy around torch device tensors."""
 
@@ -311,10 +330,7 @@ class Evaluator:
     def info(self) -> dict:
         i = Info()
         _check(load().dagsched_get_info(self._h, ctypes.byref(i)))
-        d = {k: getattr(i, k) for k in ("variant", "cand_per_block", "block_threads", "lds_bytes", "state_bits",
-                                        "ring_slots", "time_scale", "feeders", "preds_per_op", "kernel_kind", "wide_ops")}
-        d["placement_bytes_in_lds"] = i.placement_mode
-        return d
+        return _info_dict(i)
 
     def last_fallbacks(self, stream=None) -> int:
         """Candidates of the last evaluate that went to the int32 kernel one by one (synchronises the stream)."""

@@ -143,3 +143,35 @@ def test_bench_refuses_more_than_one_gpu_and_reads_the_committed_counters():
     t = bench.measured_traffic(4)                    # None once the kernel sources changed after the counters were taken
     assert t is None or t > 0
     assert bench.measured_traffic(99) is None
+
+
+def test_plan_of_the_five_workloads():
+    """dagsched_plan (host only): the variant and shape dagsched_create would take on an MI355X.  The pipelines with
+    their shared placement as a hint: the small one stays on the ring kernel, the zero-bubble one takes the
+    shared-placement kernel, the bidirectional one does not fit it; the MoE and the layered graph run optimistically
+    in 16 bits; every shape fits the LDS, and a shape asked for is the shape planned."""
+    from paper_2503_09357_amd import workloads as W
+    full = {1: 1024, 2: 65536, 3: 16384, 4: 4096, 5: 1024}
+    want = {1: 3, 2: 6, 3: 3, 4: 4, 5: 4}
+    for cfg in (1, 2, 3, 4, 5):
+        w = W.gen_config(cfg, n_cand=2)
+        hint = w.placement[0] if cfg <= 3 else None
+        args = (w.n_devices, w.row_ptr, w.col_idx, w.dur, w.comm, w.mem_delta)
+        info = dagsched.plan(*args, max_candidates=full[cfg], shared_placement=hint)
+        assert info["variant"] == want[cfg], (cfg, info)
+        assert 0 < info["lds_bytes"] <= 160 * 1024 and info["block_threads"] % 64 == 0 and info["state_bits"] == 16
+        assert info["cand_per_block"] * (1 if info["variant"] == 6 else w.n_devices) <= 64 * max(1, info["block_threads"] // 128)
+        no_hint = dagsched.plan(*args, max_candidates=full[cfg], shared_placement=hint, shape={"ignore_shared_placement": 1})
+        assert no_hint["variant"] in (3, 4), (cfg, no_hint)
+        forced = dagsched.plan(*args, max_candidates=full[cfg], shape={"kernel": 1})
+        assert forced["variant"] in (1, 2) and forced["state_bits"] == 32
+        if cfg in (1, 2):
+            shaped = dagsched.plan(*args, max_candidates=full[cfg], shape={"feeders": 1, "ring_slots": 4, "placement_mode": 1, "cand_per_block": 2})
+            assert (shaped["feeders"], shaped["ring_slots"], shaped["placement_bytes_in_lds"], shaped["cand_per_block"]) == (1, 4, 1, 2)
+        small_gpu = dagsched.plan(*args, max_candidates=full[cfg], lds_bytes=64 * 1024, n_cu=8)
+        assert small_gpu["lds_bytes"] <= 64 * 1024
+    # a bad description is answered as dagsched_validate answers it
+    w = W.gen_config(1, n_cand=1)
+    with pytest.raises(dagsched.DagschedError) as e:
+        dagsched.plan(w.n_devices, w.row_ptr, w.col_idx, -w.dur, w.comm, w.mem_delta)
+    assert e.value.code == dagsched.EINVAL
