@@ -119,8 +119,8 @@ struct dagsched {
   int32_t *ws_tp = nullptr, *ws_tr = nullptr, *ws_te = nullptr;
   // evaluation with channel contention: edge tables and one workspace row per resident workgroup
   bool contention = false;
-  int32_t *d_pred_eid = nullptr, *d_edge_src = nullptr, *d_edge_dst = nullptr;
-  int32_t *wc_list = nullptr, *wc_end = nullptr, *wc_tlist = nullptr, *wc_tend = nullptr, *wc_ccnt = nullptr, *wc_coff = nullptr;
+  int32_t *d_pred_eid = nullptr, *d_edge_src = nullptr, *d_edge_dst = nullptr, *d_succ_ptr = nullptr;
+  int32_t *wc_list = nullptr, *wc_end = nullptr, *wc_tlist = nullptr, *wc_tend = nullptr, *wc_ccnt = nullptr, *wc_coff = nullptr, *wc_echan = nullptr;
   int32_t wc_grid = 0;
   int64_t row_e = 0, row_c = 0;
 };
@@ -217,8 +217,8 @@ void free_handle(dagsched *h) {
   void *bufs[] = {h->d_pred_ptr, h->d_pred_idx, h->d_dur, h->d_comm, h->d_mem, h->d_weight, h->d_limit, h->ws_list, h->ws_end, h->d_rec,
                   h->d_comm_scaled, h->d_nparts, h->ws_list16, h->ws_pib, h->ws_cnt, h->ws_sched_list, h->ws_sched_end,
                   h->ws_sched_out, h->d_fb_count, h->d_fb_list, h->ws_tp, h->ws_tr, h->d_no_channel, h->d_edges,
-                  h->d_st_ops, h->d_st_machine, h->d_st_off, h->d_st_base, h->ws_te, h->d_pred_eid, h->d_edge_src, h->d_edge_dst,
-                  h->wc_list, h->wc_end, h->wc_tlist, h->wc_tend, h->wc_ccnt, h->wc_coff};
+                  h->d_st_ops, h->d_st_machine, h->d_st_off, h->d_st_base, h->ws_te, h->d_pred_eid, h->d_edge_src, h->d_edge_dst, h->d_succ_ptr,
+                  h->wc_list, h->wc_end, h->wc_tlist, h->wc_tend, h->wc_ccnt, h->wc_coff, h->wc_echan};
   for (void *b : bufs)
     if (b) (void)hipFree(b);
   delete h;
@@ -874,14 +874,17 @@ int dagsched_create(const dagsched_desc_t *caller_desc, dagsched_t **out) {
         peid[fill[v]++] = k; esrc[k] = u; edst[k] = v;
       }
     h->contention = true;
-    h->wc_grid = (int32_t)std::min<int64_t>(h->max_cand, (int64_t)n_cu * 8);
+    // as many workgroups as fit the CUs' wavefront slots (32 per CU) and LDS, each with a workspace row of its own
+    const int per_cu = std::min(std::min(16, 32 / (contended_threads(h->P) / kWave)), (int)(150 * 1024 / (contended_lds(h->P) + 4096)));
+    h->wc_grid = (int32_t)std::min<int64_t>(h->max_cand, (int64_t)n_cu * std::max(1, per_cu));
     h->row_e = ((int64_t)std::max(E, 1) + 31) / 32 * 32;
     h->row_c = ((int64_t)h->P * h->P + 1 + 31) / 32 * 32;
     const size_t g = (size_t)h->wc_grid;
     ok = upload(&h->d_pred_eid, peid.data(), (size_t)E) && upload(&h->d_edge_src, esrc.data(), (size_t)E) &&
-         upload(&h->d_edge_dst, edst.data(), (size_t)E) &&
+         upload(&h->d_edge_dst, edst.data(), (size_t)E) && upload(&h->d_succ_ptr, desc->row_ptr, (size_t)h->N + 1) &&
          dev_alloc(&h->wc_list, g * (size_t)h->row_stride) && dev_alloc(&h->wc_end, g * (size_t)h->row_stride) &&
          dev_alloc(&h->wc_tlist, g * (size_t)h->row_e) && dev_alloc(&h->wc_tend, g * (size_t)h->row_e) &&
+         dev_alloc(&h->wc_echan, g * (size_t)h->row_e) &&
          dev_alloc(&h->wc_ccnt, g * (size_t)h->row_c) && dev_alloc(&h->wc_coff, g * (size_t)h->row_c) &&
          (h->layout != DAGSCHED_CAND_MINOR || dev_alloc(&h->ws_te, maxc * (size_t)std::max(E, 1)));
   }
@@ -925,15 +928,15 @@ int dagsched_evaluate_contended(dagsched_t *h, int32_t n_cand, const int32_t *pl
   ContendedParams p;
   p.N = N; p.E = E; p.P = h->P; p.C = n_cand;
   p.pred_ptr = h->d_pred_ptr; p.pred_idx = h->d_pred_idx; p.pred_eid = h->d_pred_eid;
-  p.edge_src = h->d_edge_src; p.edge_dst = h->d_edge_dst;
+  p.edge_src = h->d_edge_src; p.edge_dst = h->d_edge_dst; p.succ_ptr = h->d_succ_ptr;
   p.dur = h->d_dur; p.comm = h->d_comm; p.mem_delta = h->d_mem; p.weight = h->d_weight; p.mem_limit = h->d_limit;
   p.sum_dur = h->sum_dur;
   p.placement = pl; p.rank = rk; p.edge_rank = er;
   p.ws_list = h->wc_list; p.ws_end = h->wc_end; p.ws_tlist = h->wc_tlist; p.ws_tend = h->wc_tend;
-  p.ws_ccnt = h->wc_ccnt; p.ws_coff = h->wc_coff;
+  p.ws_ccnt = h->wc_ccnt; p.ws_coff = h->wc_coff; p.ws_echan = h->wc_echan;
   p.row_n = h->row_stride; p.row_e = h->row_e; p.row_c = h->row_c;
   p.out = make_out(h, n_cand, makespan, bubble, peak_mem, flags);
-  hipLaunchKernelGGL(relax_contended_kernel, dim3((unsigned)std::min(n_cand, h->wc_grid)), dim3(kContendedThreads), 0, stream, p);
+  hipLaunchKernelGGL(relax_contended_kernel, dim3((unsigned)std::min(n_cand, h->wc_grid)), dim3((unsigned)contended_threads(h->P)), contended_lds(h->P), stream, p);
   if (h->d_no_channel)
     hipLaunchKernelGGL(channel_flag_kernel, dim3((unsigned)n_cand), dim3(n_cand < 2048 ? 1024 : 256), channel_flag_lds(N), stream, N, E,
                        h->P, h->d_edges, h->d_no_channel, pl, p.out);
