@@ -100,6 +100,10 @@ typedef struct {
   int32_t static_waves;     /* relaxing wavefronts per workgroup of the shared-placement kernel (1..8); naming it
                                also makes small handles take that kernel                                     */
   int32_t ignore_shared_placement; /* 1: dagsched_desc_t.shared_placement is not used                        */
+  int32_t window_cells;     /* end-time cells per candidate in the window mode of the 16-bit kernel (for graphs whose
+                               edges are short in the order of the node ids): a power of two from 8 to 32768 to ask
+                               for that many, -1 to forbid the mode, 0 to let the library decide.  Candidates whose
+                               schedule does not fit the window are evaluated by the int32 kernel one by one   */
 } dagsched_shape_t;
 
 /*
@@ -312,7 +316,7 @@ typedef struct {
   int8_t feeders;          /* ring kernel: feeder wavefronts per workgroup */
   int8_t placement_mode;   /* ring kernel: where the placement bytes sit (0 L2, 1 LDS, 2 LDS as four bits per node) */
   int8_t preds_per_op;     /* predecessors read per op: 2 or 4 (ring and shared-placement kernels) */
-  int8_t reserved;
+  int8_t window_log2;      /* ring kernel in window mode: log2 of the end-time cells per candidate, else 0 */
 } dagsched_info_t;
 int dagsched_get_info(const dagsched_t *h, dagsched_info_t *info);
 

@@ -98,6 +98,10 @@ struct dagsched {
   int64_t list_stride = 0, pib_stride = 0;
   uint8_t *ws_pib = nullptr;
   LdsLayout lds{};
+  LdsLayout lds_ingest{};                 // window mode: layout of the ingest launch
+  int32_t ingest_block = 1024;
+  uint32_t win_magic = 0;
+  int32_t *ws_meta = nullptr;             // window mode: what the ingest launch hands to the relaxation, per workgroup
   uint4 *d_rec = nullptr;
   int32_t *d_comm_scaled = nullptr;
   uint64_t *d_no_channel = nullptr;   // [P] bit b of word a: no channel a -> b (eq. (10)); null when every pair has one
@@ -145,6 +149,9 @@ int validate_desc(const dagsched_desc_t *d, std::vector<int32_t> *pred_ptr, std:
     if (sh->preds_per_op != 0 && sh->preds_per_op != 4) return DAGSCHED_EINVAL;
     if (sh->kernel < 0 || sh->kernel > 1 || sh->static_waves < 0 || sh->static_waves > 8) return DAGSCHED_EINVAL;
     if (sh->ignore_shared_placement < 0 || sh->ignore_shared_placement > 1) return DAGSCHED_EINVAL;
+    if (sh->window_cells < -1 || (sh->window_cells > 0 && (sh->window_cells < 8 || sh->window_cells > 32768 ||
+                                                             (sh->window_cells & (sh->window_cells - 1)))))
+      return DAGSCHED_EINVAL;
   }
   if (d->row_ptr[0] != 0 || d->row_ptr[N] != E) return DAGSCHED_EINVAL;
   for (int32_t u = 0; u < N; ++u)
@@ -216,7 +223,7 @@ void free_handle(dagsched *h) {
   if (!h) return;
   void *bufs[] = {h->d_pred_ptr, h->d_pred_idx, h->d_dur, h->d_comm, h->d_mem, h->d_weight, h->d_limit, h->ws_list, h->ws_end, h->d_rec,
                   h->d_comm_scaled, h->d_nparts, h->ws_list16, h->ws_pib, h->ws_cnt, h->ws_sched_list, h->ws_sched_end,
-                  h->ws_sched_out, h->d_fb_count, h->d_fb_list, h->ws_tp, h->ws_tr, h->d_no_channel, h->d_edges,
+                  h->ws_sched_out, h->d_fb_count, h->d_fb_list, h->ws_meta, h->ws_tp, h->ws_tr, h->d_no_channel, h->d_edges,
                   h->d_st_ops, h->d_st_machine, h->d_st_off, h->d_st_base, h->ws_te, h->d_pred_eid, h->d_edge_src, h->d_edge_dst, h->d_succ_ptr,
                   h->wc_list, h->wc_end, h->wc_tlist, h->wc_tend, h->wc_ccnt, h->wc_coff, h->wc_echan};
   for (void *b : bufs)
@@ -226,10 +233,13 @@ void free_handle(dagsched *h) {
 
 // pib_lds: 0 placement bytes in L2, 1 in LDS, 2 in LDS as nibbles (P <= 16)
 // cell_bytes: 2 (16-bit end times) or 4
-LdsLayout ring_layout(int N, int P, int G, int ring, int pib_lds, int cell_bytes, bool wide) {
+// win_log2 > 0: window mode, 2^win_log2 named cells of four bytes per candidate instead of one cell per operation
+LdsLayout ring_layout(int N, int P, int G, int ring, int pib_lds, int cell_bytes, bool wide, int win_log2 = 0) {
   LdsLayout o{};
   uint32_t at = 0;
-  o.s_stride = align_up((uint32_t)cell_bytes * (uint32_t)(N + 2), 4);   // N cells + dummy + trash; the arrays start at LDS offset 0
+  o.s_stride = win_log2 ? 4u << win_log2
+                        : align_up((uint32_t)cell_bytes * (uint32_t)(N + 2), 4);   // N cells + dummy + trash; the arrays start at LDS offset 0
+  o.win_log2 = (uint32_t)win_log2;
   o.cell_bytes = (uint32_t)cell_bytes;
   at += (uint32_t)G * o.s_stride;
   o.pi_stride = pib_lds == 1 ? align_up((uint32_t)(N + 1), 4) : pib_lds == 2 ? align_up((uint32_t)(N + 2) / 2u, 4) : 0u;
@@ -271,10 +281,14 @@ struct RingPlan {
   int rec_plane = 0, id_bits = 16;
   std::vector<uint8_t> nparts;
   std::vector<int32_t> comm_scaled;
+  // window mode: cells per candidate (0: off), the layout and workgroup size of the ingest launch
+  int win_log2 = 0, ingest_block = 1024;
+  uint32_t win_magic = 0;
+  LdsLayout lds_ingest{};
 };
 
 RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_ptr, const std::vector<int32_t> &pred_idx,
-                   int64_t sum_dur, int lds_max) {
+                   int64_t sum_dur, int lds_max, int n_cu) {
   RingPlan plan;
   const int N = d->n_nodes, P = d->n_devices, Pseg = next_pow2(P);
   int64_t g = 0, max_comm = 0;
@@ -421,6 +435,26 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
   plan.cell32 = wide || force_bits == 32 || (force_bits != 16 && !fits16 && 3 * lower >= (int64_t)kNotDone16);
   if (!plan.cell32 && lower >= (int64_t)kNotDone16) return plan;   // 16 bits asked for, and no candidate could stay inside them
   const int cell_bytes = plan.cell32 ? 4 : 2;
+  // Window mode: when every edge is short in the order of the node ids (a layered graph), a candidate needs only a
+  // window of K named cells instead of a cell per operation (see the kernel).  K = eight times the longest edge,
+  // rounded up to a power of two: the operations in flight of a list schedule spread over a few edge lengths, and a
+  // candidate whose schedule does not fit the window is handed to the int32 kernel, never evaluated wrongly.  Taken
+  // when it shrinks the end-time state at least 2.5 times on a problem large enough for that to matter, or when the
+  // caller's shape names K.
+  int win_log2 = 0;
+  {
+    const int want = sh ? sh->window_cells : 0;
+    int64_t span = 0;
+    bool topological = true;
+    for (int v = 0; v < N; ++v)
+      for (int32_t u : op_preds[v]) { topological = topological && u < v; span = std::max<int64_t>(span, v - u); }
+    int K = 0;
+    if (want > 0) K = want;
+    else if (want == 0 && N >= 8192) { K = 1024; while (K < 8 * span) K <<= 1; }
+    const bool fits_names = K >= 8 && K <= 32768 && (int64_t)N + 3 * ((int64_t)N / (K - 3)) + 1 <= 65535;
+    const bool worth = want > 0 || (int64_t)K * 4 * 5 <= (int64_t)(2 * N) * 2;
+    if (K && topological && fits_names && worth && !plan.cell32 && !wide) win_log2 = ilog2(K);
+  }
   const int force_g = sh ? sh->cand_per_block : 0;
   const int force_ring = sh ? sh->ring_slots : 0;
   const int force_feeders = sh ? sh->feeders : 0;
@@ -431,15 +465,21 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
     if (force_g && G != force_g) continue;
     for (int pib_lds : {1, 2, 0}) {
       if (force_pib >= 0 && pib_lds != force_pib) continue;
+      if (win_log2 && pib_lds != 0) continue;             // window mode: the placement bytes stay in the workspace row
       if (pib_lds == 2 && (P > 16 || wide)) continue;     // a nibble per node; not with wide ops (see the kernel: time origin)
       for (int ring : {8, 16, 32, 4}) {
         if (force_ring && ring != force_ring) continue;
         if (pib_lds ? ring > 8 : ring < 8) continue;     // instantiated: LDS with 4 or 8 slots, L2 with 8, 16 or 32
-        LdsLayout o = ring_layout(N, P, G, ring, pib_lds, cell_bytes, wide);
+        LdsLayout o = ring_layout(N, P, G, ring, pib_lds, cell_bytes, wide, win_log2);
         if ((int)o.total > lds_max) continue;
-        if ((uint64_t)G * (o.s_stride >> (plan.cell32 ? 2 : 1)) > 65536u) continue;   // half (quarter) addresses must fit 16 bits
-        const int wgs = std::min(5, lds_max / (int)align_up(o.total, 512));   // beyond ~20 wavefronts the CU is issue-bound
+        if (!win_log2 && (uint64_t)G * (o.s_stride >> (plan.cell32 ? 2 : 1)) > 65536u) continue;   // half (quarter) addresses must fit 16 bits
+        // window mode: the ingest launch builds the lists of the workgroup's G candidates in LDS, 2 N bytes each
+        if (win_log2 && (int)ring_layout(N, P, G, 0, 0, 2, false).total > lds_max) continue;
+        int wgs = std::min(5, lds_max / (int)align_up(o.total, 512));   // beyond ~20 wavefronts the CU is issue-bound
         if (wgs < 1) continue;
+        // window mode relaxes every candidate of a full batch at once when it can: workgroups per CU beyond what the
+        // batch fills count nothing, a deeper ring does (config 5: 3 % for sixteen slots over eight)
+        if (win_log2) wgs = std::min<int64_t>(wgs, std::max<int64_t>(1, ((d->max_candidates + G - 1) / G + n_cu - 1) / n_cu));
         const int64_t score = (int64_t)wgs * G * (ring >= 8 ? 100 : 70) * (pib_lds == 1 ? 100 : pib_lds == 2 ? 99 : 97) *
                                   (G * Pseg < kWave ? 65 : 100) + (ring == 16 ? 2 : 0) - G;
         if (score > best_score) { best_score = score; best_wgs = wgs; plan.G = G; plan.ring = ring; plan.lds = o; }
@@ -454,14 +494,24 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
                : best_wgs <= 2 ? 3
                : (best_wgs * 4 <= 24 ? 2 : 1);
   auto built = [&](int feeders) {
-    return wide        ? ring_kernel_pick<3>(plan.ring, feeders, (int)plan.lds.pib_mode, plan.kind) != nullptr
+    return win_log2    ? ring_kernel_pick<4>(plan.ring, feeders, (int)plan.lds.pib_mode, plan.kind) != nullptr
+         : wide        ? ring_kernel_pick<3>(plan.ring, feeders, (int)plan.lds.pib_mode, plan.kind) != nullptr
          : plan.cell32 ? ring_kernel_pick<2>(plan.ring, feeders, (int)plan.lds.pib_mode, plan.kind) != nullptr
                        : ring_kernel_pick<0>(plan.ring, feeders, (int)plan.lds.pib_mode, plan.kind) != nullptr;
   };
   if (!force_feeders && !built(plan.feeders)) plan.feeders = 2;
   if (best_score < 0 || !built(plan.feeders)) return plan;   // shape not built
   // the nibble kernels start time at 255 (see the kernel), which the 16-bit range must hold as well
-  plan.exact = plan.cell32 || upper + (plan.lds.pib_mode == 2 ? 255 : 0) < (int64_t)kNotDone16;
+  // (a candidate that does not fit the window goes to the int32 kernel like one that leaves the 16-bit range: window
+  // mode always runs with that kernel behind it)
+  plan.exact = !win_log2 && (plan.cell32 || upper + (plan.lds.pib_mode == 2 ? 255 : 0) < (int64_t)kNotDone16);
+  if (win_log2 && best_score >= 0) {
+    plan.win_log2 = win_log2;
+    plan.win_magic = (uint32_t)((1ull << 32) / (uint64_t)((1 << win_log2) - 3)) + 1u;
+    plan.lds_ingest = ring_layout(N, P, plan.G, 0, 0, 2, false);
+    const int ingest_wgs = std::max(1, lds_max / (int)align_up(plan.lds_ingest.total, 512));
+    plan.ingest_block = ingest_wgs == 1 ? 1024 : ingest_wgs == 2 ? 512 : 256;
+  }
   // workgroup size: the wavefronts with a role, plus helpers for the ingest phase when the LDS leaves the CU
   // nearly empty of wavefronts (one workgroup per CU: 1024 threads, two: 512)
   plan.block = ring_threads(plan.feeders);
@@ -480,9 +530,24 @@ using RingKernel = void (*)(RingParams);
   case 0 * 10000 + PIB * 1000 + RING * 10 + F: return relax_ring_kernel<RING, F, HALF, PIB, 0>;    \
   case 1 * 10000 + PIB * 1000 + RING * 10 + F: return relax_ring_kernel<RING, F, HALF, PIB, 1>;    \
   case 2 * 10000 + PIB * 1000 + RING * 10 + F: return relax_ring_kernel<RING, F, HALF, PIB, 2>;
+// window mode: the relaxation launch (PHASE = 2) in the shapes that large layered problems get, and the ingest launch
+#define DAGSCHED_WIN_CASES(RING, F)                                                               \
+  case 0 * 10000 + RING * 10 + F: return relax_ring_kernel<RING, F, 4, 0, 0, 2>;                  \
+  case 1 * 10000 + RING * 10 + F: return relax_ring_kernel<RING, F, 4, 0, 1, 2>;                  \
+  case 2 * 10000 + RING * 10 + F: return relax_ring_kernel<RING, F, 4, 0, 2, 2>;
+RingKernel ring_ingest_kernel(int kind) {
+  return kind == 0 ? relax_ring_kernel<8, 2, 4, 0, 0, 1> : kind == 1 ? relax_ring_kernel<8, 2, 4, 0, 1, 1> : relax_ring_kernel<8, 2, 4, 0, 2, 1>;
+}
 template <int HALF>
 RingKernel ring_kernel_pick(int ring, int feeders, int pib_lds, int kind) {
-  if constexpr (HALF == 2) {                             // 32-bit end times: the shapes that large problems get
+  if constexpr (HALF == 4) {
+    if (pib_lds != 0) return nullptr;
+    switch (kind * 10000 + ring * 10 + feeders) {
+      DAGSCHED_WIN_CASES(8, 1) DAGSCHED_WIN_CASES(8, 2) DAGSCHED_WIN_CASES(8, 3)
+      DAGSCHED_WIN_CASES(16, 2) DAGSCHED_WIN_CASES(16, 3) DAGSCHED_WIN_CASES(16, 4)
+      default: return nullptr;
+    }
+  } else if constexpr (HALF == 2) {                             // 32-bit end times: the shapes that large problems get
     switch (kind * 10000 + pib_lds * 1000 + ring * 10 + feeders) {
       DAGSCHED_RING_CASES(1, 8, 1) DAGSCHED_RING_CASES(1, 8, 2) DAGSCHED_RING_CASES(1, 8, 3)
       DAGSCHED_RING_CASES(2, 8, 2) DAGSCHED_RING_CASES(2, 8, 3)
@@ -513,6 +578,7 @@ RingKernel ring_kernel_for(const dagsched *h) {
   // byte addresses when the workgroup's end-time arrays fit 64 KB, half addresses otherwise
   const bool half = (uint64_t)h->ring_G * h->lds.s_stride > 65536u;
   const int pib_lds = (int)h->lds.pib_mode;
+  if (h->lds.win_log2) return ring_kernel_pick<4>(h->ring_slots, h->ring_feeders, pib_lds, h->ring_kind);
   if (h->lds.wide) return ring_kernel_pick<3>(h->ring_slots, h->ring_feeders, pib_lds, h->ring_kind);
   if (h->lds.cell_bytes == 4) return ring_kernel_pick<2>(h->ring_slots, h->ring_feeders, pib_lds, h->ring_kind);
   return half ? ring_kernel_pick<1>(h->ring_slots, h->ring_feeders, pib_lds, h->ring_kind)
@@ -700,9 +766,16 @@ int launch_evaluate(dagsched *h, int32_t n_cand, const int32_t *placement, const
     p.ws_list = h->ws_list16; p.ws_pib = h->ws_pib; p.pib_stride = h->pib_stride;
     p.fb_count = h->d_fb_count; p.fb_list = h->d_fb_list;
     p.spin_cap = h->spin_cap;
-    p.lds = h->lds;
+    p.win_magic = h->win_magic; p.ws_meta = h->ws_meta;
     p.out = out;
     const unsigned blocks = (unsigned)((n_cand + h->ring_G - 1) / h->ring_G);
+    if (h->lds.win_log2) {                                // window mode: the lists are built by a launch of their own
+      p.lds = h->lds_ingest;
+      p.lds.win_log2 = h->lds.win_log2;
+      hipLaunchKernelGGL(ring_ingest_kernel(h->ring_kind), dim3(blocks), dim3((unsigned)h->ingest_block), (size_t)h->lds_ingest.total,
+                         stream, p);
+    }
+    p.lds = h->lds;
     hipLaunchKernelGGL(ring_kernel_for(h), dim3(blocks), dim3((unsigned)h->ring_block), (size_t)h->lds.total,
                        stream, p);
     if (optimistic) launch_general(h, n_cand, pl, rk, out, h->d_fb_list, h->d_fb_count, stream);
@@ -796,7 +869,7 @@ int dagsched_create(const dagsched_desc_t *caller_desc, dagsched_t **out) {
   const bool force_general = desc->shape && desc->shape->kernel == 1;
   if (!force_general && desc->shared_placement && !(desc->shape && desc->shape->ignore_shared_placement))
     splan = plan_static(desc, pred_ptr, pred_idx, sum_dur, lds_max, n_cu);
-  if (!force_general && !splan.ok) plan = plan_ring(desc, pred_ptr, pred_idx, sum_dur, lds_max);
+  if (!force_general && !splan.ok) plan = plan_ring(desc, pred_ptr, pred_idx, sum_dur, lds_max, n_cu);
   const bool need_general = splan.ok || !plan.ok || !plan.exact;
 
   bool ok = upload(&h->d_mem, desc->mem_delta, (size_t)h->N) &&
@@ -858,6 +931,11 @@ int dagsched_create(const dagsched_desc_t *caller_desc, dagsched_t **out) {
          dev_alloc(&h->ws_list16, maxc * (size_t)h->list_stride) &&
          (plan.lds.pib_mode != 0 || dev_alloc(&h->ws_pib, maxc * (size_t)h->pib_stride));   // only read when the placement is not in LDS
     if (ok && !plan.exact) ok = dev_alloc(&h->d_fb_count, 1) && dev_alloc(&h->d_fb_list, maxc);
+    if (ok && plan.win_log2) {
+      h->lds_ingest = plan.lds_ingest; h->ingest_block = plan.ingest_block; h->win_magic = plan.win_magic;
+      ok = dev_alloc(&h->ws_meta, ((maxc + plan.G - 1) / plan.G) * 4 * (size_t)kWave) &&
+           (h->lds_ingest.total <= 48 * 1024 || allow_large_lds((const void *)ring_ingest_kernel(plan.kind), h->device, (int)h->lds_ingest.total));
+    }
     if (ok && h->lds.total > 48 * 1024)
       ok = allow_large_lds((const void *)ring_kernel_for(h), h->device, (int)h->lds.total);
   }
@@ -1184,7 +1262,7 @@ int dagsched_plan(const dagsched_desc_t *caller_desc, int32_t lds_bytes, int32_t
   StaticPlan splan;
   if (!force_general && cleaned.shared_placement && !(cleaned.shape && cleaned.shape->ignore_shared_placement))
     splan = plan_static(&cleaned, pred_ptr, pred_idx, sum_dur, lds_bytes, n_cu);
-  if (!force_general && !splan.ok) plan = plan_ring(&cleaned, pred_ptr, pred_idx, sum_dur, lds_bytes);
+  if (!force_general && !splan.ok) plan = plan_ring(&cleaned, pred_ptr, pred_idx, sum_dur, lds_bytes, n_cu);
   if (splan.ok || !plan.ok || !plan.exact) {
     h.gen_G = kWave / h.Pseg;
     const int64_t lds_need = (int64_t)h.gen_G * h.N * 4;
@@ -1231,6 +1309,7 @@ int dagsched_get_info(const dagsched_t *h, dagsched_info_t *info) {
     info->preds_per_op = (int8_t)(h->ring_kind == 2 ? 2 : 4);
     info->kernel_kind = (int8_t)h->ring_kind;
     info->wide_ops = (int8_t)h->lds.wide;
+    info->window_log2 = (int8_t)h->lds.win_log2;
   }
   return DAGSCHED_OK;
 }

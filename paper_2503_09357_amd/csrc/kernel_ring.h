@@ -69,6 +69,7 @@ struct LdsLayout {
   uint32_t pib_mode;                                  // where the placement bytes are: 0 L2 workspace, 1 LDS, 2 LDS as nibbles
   uint32_t cell_bytes;                                // 2: 16-bit end times, 4: 32-bit
   uint32_t wide;                                      // 1: wide ops (machines instead of delays, durations below 256 * 65535)
+  uint32_t win_log2;                                  // window mode: log2 of the cells per candidate (0: one cell per operation)
 };
 
 struct RingParams {
@@ -91,6 +92,9 @@ struct RingParams {
   int64_t pib_stride;
   int32_t *fb_count, *fb_list;         // candidates left to the general kernel
   uint32_t spin_cap;                   // bound on relaxer / feeder loop trips
+  uint32_t win_magic;                  // window mode: ceil(2^32 / (cells - 3)), for node -> cell name
+  int32_t *ws_meta;                    // window mode: [workgroups][4][64] what ingest hands to relaxation: operations per
+                                       // lane, start of the lane's list, op parts per lane, flag bits per candidate
   LdsLayout lds;
   OutPtrs out;
 };
@@ -104,7 +108,22 @@ struct RingParams {
 // KIND: 0 general; 1 every operation is a single part (at most four DAG predecessors each): the feeders walk
 // the order lists directly; 2 at most two DAG predecessors each (single parts as well): the second pair of
 // every record and op is the dummy and neither the feeders nor the relaxer look at it.  Chosen by the host.
-template <int RING, int FEEDERS, int HALF, int PIBL, int KIND = 0>
+//
+// HALF = 4, the WINDOW mode, for graphs whose edges are short in the order of the node ids (layered graphs): a
+// candidate then gets K cells instead of one per operation, K a power of two chosen by the host, and operation v
+// uses the cell of its NAME c(v) = (v div (K-3)) * K + 1 + v mod (K-3), slot c mod K; the slots 0, K-2 and K-1 of
+// every period stay free for "nothing yet" (name 0), the trash cell and the dummy.  A cell is a 32-bit word, name
+// in the upper half, 16-bit end time in the lower one, written with an LDS maximum, so that a later name is never
+// replaced by an earlier one.  A reader that finds the name it expects has the end time; an earlier name means
+// "not ended yet"; a later name means that the window has moved past an operation somebody still waits for: that
+// operation's readers never run, the candidate deadlocks, and at the deadlock the later name tells the miss from a
+// cycle: the candidate goes to the int32 kernel like one stopped by the 16-bit range.  Nothing else changes: node
+// ids stay what they are in the lists, the records and the placement bytes; only the feeders turn them into names
+// when they pack an op.  The end-time state shrinks from 2 N bytes to 4 K per candidate, and with it the LDS a
+// workgroup needs while it relaxes; the order lists, which need 2 N bytes of LDS while they are built, are then
+// built by a launch of their own (PHASE = 1: ingest only, hands cnt / off / total / flags over through ws_meta)
+// and the relaxation (PHASE = 2) runs with several workgroups per CU.  PHASE = 0 is the fused kernel.
+template <int RING, int FEEDERS, int HALF, int PIBL, int KIND = 0, int PHASE = 0>
 __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
   // ring_threads(FEEDERS) threads have a role while the schedule is relaxed; the host may launch more (a
   // multiple of 64): the extra wavefronts only help with ingest and then wait at the final barrier.
@@ -114,13 +133,17 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
   static_assert((RING & (RING - 1)) == 0, "RING must be a power of two");
   static_assert(RING >= FEEDERS, "every feeder needs a slot of its own");
   static_assert(KIND >= 0 && KIND <= 2, "general, single parts, two predecessors");
-  static_assert(HALF >= 0 && HALF <= 3, "byte, half or quarter addresses; 3: quarter addresses and delays looked up by the relaxer");
-  constexpr bool kCell32 = HALF >= 2;                       // 32-bit end times
+  static_assert(HALF >= 0 && HALF <= 4, "byte, half or quarter addresses; 3: quarter addresses and delays looked up by the relaxer; 4: window");
+  static_assert(PHASE >= 0 && PHASE <= 2, "fused, ingest only, relaxation only");
+  constexpr bool kWin = HALF == 4;                          // a window of named cells per candidate
+  static_assert(!kWin || PIBL == 0, "window mode keeps the placement bytes in the workspace row");
+  static_assert(kWin || PHASE == 0, "only the window mode is split into two launches");
+  constexpr bool kCell32 = HALF == 2 || HALF == 3;          // 32-bit end times
   constexpr bool kWide = HALF == 3;                         // ops name machines, not delays; durations below 256 * 65535
-  constexpr int kAsh = kCell32 ? 2 : HALF;                  // 16-bit address -> LDS byte address
+  constexpr int kAsh = kCell32 ? 2 : kWin ? 0 : HALF;       // 16-bit address -> LDS byte address
   static_assert(!(kWide && PIBL == 2), "wide ops need the dummy machine, which a nibble cannot name");
   constexpr uint32_t kNotDone = kCell32 ? kNotDone32 : kNotDone16;
-  constexpr int kNodeShift = kCell32 ? 0 : 1 - HALF;        // node -> offset of its cell in the units of the 16-bit addresses
+  constexpr int kNodeShift = (kCell32 || kWin) ? 0 : 1 - HALF;   // node -> offset of its cell in the units of the 16-bit addresses
   constexpr int PR = KIND == 2 ? 2 : 4;                     // DAG predecessors per op
   constexpr uint32_t kOrigin = PIBL == 2 ? 255u : 0u;
   const int tid = threadIdx.x;
@@ -145,15 +168,29 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
   uint8_t *overb = lds + o.o_over;
   uint8_t *commb = (uint8_t *)(lds + o.o_comm);            // [(P+1)][Pseg], diagonal and dummy row zero
 
+  // window mode: names of the dummy node and of the trash cell, cells per candidate
+  const uint32_t win_mask = kWin ? (1u << o.win_log2) - 1u : 0u;
+  const uint32_t win_dummy = win_mask, win_trash = win_mask - 1u;
+  int32_t *const meta = kWin ? p.ws_meta + (int64_t)blockIdx.x * 4 * kWave : nullptr;
+  // window mode: the name of a node's cell (the dummy node N has the dummy's name)
+  auto name_of = [&](uint32_t v) -> uint32_t {
+    return v == (uint32_t)p.N ? win_dummy : v + 3u * __umulhi(v, p.win_magic) + 1u;
+  };
   // ---------------------------------------------------------------- ingest (all wavefronts)
-  if (tid < kWave) { cntw[tid] = 0; totalw[tid] = 0; flagw[tid] = 0; abortw[tid] = 0; peakw[tid] = 0; overb[tid] = 0; }
+  if (tid < kWave) {
+    if (PHASE != 2) { cntw[tid] = 0; totalw[tid] = 0; flagw[tid] = 0; }
+    else { cntw[tid] = meta[tid]; offw[tid] = meta[kWave + tid]; totalw[tid] = (uint32_t)meta[2 * kWave + tid]; flagw[tid] = meta[3 * kWave + tid]; }
+    abortw[tid] = 0; peakw[tid] = 0; overb[tid] = 0;
+  }
+  if (PHASE != 1)
   for (int i = tid; i < RING * kWave; i += kThreads) {     // every slot free, as if ops -RING .. -1 had been taken
     // (a free slot is copied and looked at like an op: some cell of the workgroup, no delay)
-    ringw[4 * i + 0] = ringw[4 * i + 1] = ((uint32_t)(uintptr_t)ldsb >> kAsh) * 0x10001u;
+    ringw[4 * i + 0] = ringw[4 * i + 1] = kWin ? win_dummy * 0x10001u : ((uint32_t)(uintptr_t)ldsb >> kAsh) * 0x10001u;
     ringw[4 * i + 2] = 0;
     ringw[4 * i + 3] = kNotDone16 | ((uint32_t)((i >> 6) - RING) << 16);
   }
-  if (kWide) {                                              // 64 rows of Pseg dwords (any six-bit machine id stays inside)
+  if (PHASE == 1) {
+  } else if (kWide) {                                       // 64 rows of Pseg dwords (any six-bit machine id stays inside)
     uint32_t *commw = (uint32_t *)(lds + o.o_comm);
     for (int i = tid; i < kWave * Pseg; i += kThreads) {
       const int a = i >> p.log_pseg, b = i & (Pseg - 1);
@@ -170,6 +207,7 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
   const int n_teams = G;
   const int tpc = kThreads / n_teams;
   const int team = tid / tpc, tt = tid - team * tpc;        // this thread's team and its place in it
+  if (PHASE != 2) {
   // The order lists are first built in LDS, over the (not yet used) end-time arrays: every entry starts as
   // "unwritten" (0xFFFF, which no list entry equals: the host checks that)
   for (int gg = team; gg < ng; gg += n_teams) {
@@ -324,11 +362,18 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
   }
   __syncthreads();                                          // workgroup scope: the lists are read by this workgroup only
   if (tid < kWave) totalw[tid] += (uint32_t)cntw[tid];      // ops per lane: its operations plus their further parts
+  if (PHASE == 1) {                                         // the relaxation is a launch of its own
+    if (tid < kWave) { meta[tid] = cntw[tid]; meta[kWave + tid] = offw[tid]; meta[2 * kWave + tid] = (int32_t)totalw[tid]; meta[3 * kWave + tid] = flagw[tid]; }
+    return;
+  }
+  }
   // end-time state: every operation "not ended"; the dummy node N has ended at time 0 on a dummy
   // machine P whose delays are all zero; cell N+1 is a trash cell for parts that do not end an operation
   for (int gg = team; gg < ng; gg += n_teams) {
     uint32_t *sw = (uint32_t *)(lds + gg * o.s_stride);
-    if (kCell32) {
+    if (kWin) {                                             // no name anywhere, but the dummy's in its slot, ended at 0
+      for (uint32_t i = (uint32_t)tt; i <= win_mask; i += (uint32_t)tpc) sw[i] = i == win_dummy ? win_dummy << 16 : 0u;
+    } else if (kCell32) {
       for (int i = tt; i < N + 2; i += tpc) sw[i] = i < N ? kNotDone32 : 0u;
     } else {
       for (int i = tt; i < (N + 3) / 2; i += tpc) {
@@ -347,6 +392,8 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
   const bool has_ops = cand_ok && j < P && cntw[ql] > 0;
   // 16-bit address of this candidate's cell 0: LDS addresses (halved when HALF), so that the relaxer uses them as they are
   const uint32_t sbase = ((uint32_t)(uintptr_t)ldsb >> kAsh) + (uint32_t)g * (o.s_stride >> kAsh);
+  // window mode: LDS byte address of the cell of a name (sbase is then the byte address of the candidate's cells)
+  auto win_addr = [&](uint32_t name) -> uint32_t { return sbase + ((name & win_mask) << 2); };
 
   int32_t acc = 0;
   bool stalled = false;
@@ -359,15 +406,23 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
     lds_vi32_t *const abort_p = (lds_vi32_t *)(ldsb + o.o_abort) + g;
     const uint64_t segmask = ((Pseg == kWave) ? ~0ull : ((1ull << Pseg) - 1ull)) << (g * Pseg);
     auto cell = [&](uint32_t a16) -> uint32_t {
+      if (kWin) return *(lds_vu32_t *)(uintptr_t)win_addr(a16);     // name << 16 | end time
       return kCell32 ? *(lds_vu32_t *)(uintptr_t)(a16 << 2) : (uint32_t)*(lds_vu16_t *)(uintptr_t)(a16 << kAsh);
     };
+    // window mode: where a lane that ran nothing (or a part that ends no operation) leaves its value: a dword of its
+    // own.  The cells are written with an LDS maximum, and lanes that aim one at the same address are served one
+    // after the other, unlike plain stores: a shared trash cell cost 40 % of the LDS pipe's time.
+    const uint32_t own_trash = (uint32_t)(uintptr_t)(ldsb + o.o_scr) + (uint32_t)lane * 4u;
     auto set_cell = [&](uint32_t a16, uint32_t v) {
-      if (kCell32) *(lds_vu32_t *)(uintptr_t)(a16 << 2) = v;
+      // (window: the maximum keeps a later name from being replaced by an earlier one)
+      if (kWin) (void)__hip_atomic_fetch_max((DAGSCHED_LDS uint32_t *)(uintptr_t)(a16 == win_trash ? own_trash : win_addr(a16)),
+                                            (a16 << 16) | v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      else if (kCell32) *(lds_vu32_t *)(uintptr_t)(a16 << 2) = v;
       else *(lds_vu16_t *)(uintptr_t)(a16 << kAsh) = (uint16_t)v;
     };
-    const uint32_t dummy = sbase + ((uint32_t)N << kNodeShift);
+    const uint32_t dummy = kWin ? win_dummy : sbase + ((uint32_t)N << kNodeShift);
     // The loop body is branch-free: every trip stores x somewhere (the trash cell unless an op ran).
-    const uint32_t trash = sbase + (((uint32_t)N + 1u) << kNodeShift);
+    const uint32_t trash = kWin ? win_trash : sbase + (((uint32_t)N + 1u) << kNodeShift);
     __builtin_amdgcn_s_setprio(3);                          // the relaxer's trip is the critical path of the workgroup:
                                                             // it goes first wherever it shares a SIMD (measured: 4-5 % on the MoE workload)
     bool idle = true, dead = !has_ops;                      // idle: the registers hold a free slot's content, not an op
@@ -413,6 +468,15 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
           // then never 0xFFFF
           const uint32_t hi = w2 >> 24;
           x += (w3 & 0xFFFFu) + (hi << 16) - hi;
+        } else if (kWin) {
+          // a predecessor has ended when its cell carries its name; the end time is the cell's lower half
+          // (no short-circuit: the trip stays free of branches)
+          bool named = ((e0 >> 16) == (w0 & 0xFFFFu)) & ((e1 >> 16) == (w0 >> 16));
+          if (PR == 4) named = named & ((e2 >> 16) == (w1 & 0xFFFFu)) & ((e3 >> 16) == (w1 >> 16));
+          x = max(max(x_acc, (e0 & 0xFFFFu) + (w2 & 0xFFu)), (e1 & 0xFFFFu) + (PR == 4 ? (w2 >> 8) & 0xFFu : w2 >> 8));
+          if (PR == 4) x = max(max(x, (e2 & 0xFFFFu) + ((w2 >> 16) & 0xFFu)), (e3 & 0xFFFFu) + (w2 >> 24));
+          x += w3 & 0xFFFFu;
+          ran = named && x < kNotDone;                        // (a free slot's "duration" 0xFFFF lifts x over the range)
         } else {
           x = max(max(x_acc, e0 + (w2 & 0xFFu)), e1 + (PR == 4 ? (w2 >> 8) & 0xFFu : w2 >> 8));
           if (PR == 4) x = max(max(x, e2 + ((w2 >> 16) & 0xFFu)), e3 + (w2 >> 24));
@@ -469,7 +533,20 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
         // If one of the held ops has all its predecessors ended, only the 16-bit range stopped it (optimistic
         // mode: the int32 kernel takes the candidate); otherwise every held op waits for an op that can never
         // run, i.e. the combined graph has a cycle.
-        const bool range_stop = deadlock && !idle && max(max(e0, e1), PR == 4 ? max(e2, e3) : 0u) < kNotDone;
+        // (window mode: likewise when every predecessor's cell carries its name; and a cell that carries a LATER name
+        // says that the window moved past a predecessor this op still waits for: the int32 kernel's candidate, too)
+        bool win_stop = false;
+        if (kWin) {
+          const uint32_t n0 = e0 >> 16, n1 = e1 >> 16, i0 = w0 & 0xFFFFu, i1 = w0 >> 16;
+          bool named = n0 == i0 && n1 == i1, later = n0 > i0 || n1 > i1;
+          if (PR == 4) {
+            const uint32_t n2 = e2 >> 16, n3 = e3 >> 16, i2 = w1 & 0xFFFFu, i3 = w1 >> 16;
+            named = named && n2 == i2 && n3 == i3;
+            later = later || n2 > i2 || n3 > i3;
+          }
+          win_stop = named || later;
+        }
+        const bool range_stop = deadlock && !idle && (kWin ? win_stop : max(max(e0, e1), PR == 4 ? max(e2, e3) : 0u) < kNotDone);
         const bool overflow = (__ballot(range_stop) & segmask) != 0;
         if (deadlock) *abort_p = overflow ? 1 : 2;
         stalled = stalled || deadlock;
@@ -506,7 +583,7 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
     lds_vi32_t *const abort_p = (lds_vi32_t *)(ldsb + o.o_abort) + g;
     const uint16_t *list = p.ws_list + (c0 + (cand_ok ? g : 0)) * p.list_stride;
     const uint32_t base2 = sbase | (sbase << 16);
-    const uint32_t trash = sbase + (((uint32_t)N + 1u) << kNodeShift);
+    const uint32_t trash = kWin ? win_trash : sbase + (((uint32_t)N + 1u) << kNodeShift);
     const uint32_t vbits = (uint32_t)p.id_bits, vmask = (1u << vbits) - 1u;
     const uint32_t n_plane = (uint32_t)p.rec_plane;
     const uint32_t lps = (uint32_t)p.log_pseg;
@@ -618,12 +695,14 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
         // (D) pack e2 and publish it
         if (e2.fl & 1u) {
           const bool more = !kSingle && (e2.rec.z >> 31) != 0;
-          const uint32_t dst = more ? trash : sbase + ((e2.rec.w >> 16) << kNodeShift);
+          const uint32_t dst = more ? trash : kWin ? name_of(e2.rec.w >> 16) : sbase + ((e2.rec.w >> 16) << kNodeShift);
           const uint32_t dur = e2.rec.z & 0xFFFFu;
           lds_byte_t *const sp = ring_lane + ((wseq & (uint32_t)(RING - 1)) << 10);
           // node ids below 32768 whenever they are shifted, so shifting both halves at once cannot carry over;
           // the whole slot first with its free mark unchanged, then the last dword
-          const u32x4_t val = {(e2.rec.x << kNodeShift) + base2, (e2.rec.y << kNodeShift) + base2,
+          const u32x4_t val = {kWin ? name_of(e2.rec.x & 0xFFFFu) | (name_of(e2.rec.x >> 16) << 16) : (e2.rec.x << kNodeShift) + base2,
+                               kWin ? (PR == 4 ? name_of(e2.rec.y & 0xFFFFu) | (name_of(e2.rec.y >> 16) << 16) : win_dummy * 0x10001u)
+                                    : (e2.rec.y << kNodeShift) + base2,
                                kWide ? d0 | (d1 << 6) | (d2 << 12) | (d3 << 18) | (((e2.rec.z >> 16) & 0xFFu) << 24)
                                      : d0 | (d1 << 8) | (d2 << 16) | (d3 << 24),
                                ((wseq - (uint32_t)RING) << 16) | kNotDone16};

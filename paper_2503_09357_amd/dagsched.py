@@ -39,7 +39,7 @@ class Shape(ctypes.Structure):
     _fields_ = [("cand_per_block", ctypes.c_int32), ("ring_slots", ctypes.c_int32), ("feeders", ctypes.c_int32),
                 ("placement_mode", ctypes.c_int32), ("block_threads", ctypes.c_int32), ("state_bits", ctypes.c_int32),
                 ("preds_per_op", ctypes.c_int32), ("kernel", ctypes.c_int32), ("static_waves", ctypes.c_int32),
-                ("ignore_shared_placement", ctypes.c_int32)]
+                ("ignore_shared_placement", ctypes.c_int32), ("window_cells", ctypes.c_int32)]
 
 
 SHAPE_FIELDS = tuple(name for name, _ in Shape._fields_)
@@ -75,7 +75,7 @@ class Info(ctypes.Structure):
                 ("ring_slots", ctypes.c_int16), ("kernel_kind", ctypes.c_int8), ("wide_ops", ctypes.c_int8),
                 ("time_scale", ctypes.c_int32),
                 ("feeders", ctypes.c_int8), ("placement_mode", ctypes.c_int8), ("preds_per_op", ctypes.c_int8),
-                ("reserved", ctypes.c_int8)]
+                ("window_log2", ctypes.c_int8)]
 
 
 class CoarsenParams(ctypes.Structure):
@@ -241,7 +241,8 @@ def validate(n_devices, row_ptr, col_idx, dur, comm, mem_delta, max_candidates=1
 
 def _info_dict(i: "Info") -> dict:
     d = {k: getattr(i, k) for k in ("variant", "cand_per_block", "block_threads", "lds_bytes", "state_bits",
-                                    "ring_slots", "time_scale", "feeders", "preds_per_op", "kernel_kind", "wide_ops")}
+                                    "ring_slots", "time_scale", "feeders", "preds_per_op", "kernel_kind", "wide_ops",
+                                    "window_log2")}
     d["placement_bytes_in_lds"] = i.placement_mode
     return d
 

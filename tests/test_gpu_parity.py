@@ -6,6 +6,7 @@ from __future__ import annotations
 
 import os
 import sys
+from dataclasses import replace as dataclasses_replace
 
 import numpy as np
 import pytest
@@ -503,6 +504,78 @@ def test_two_live_handles_on_one_kernel_instantiation(gpu_lib):
                 torch.cuda.synchronize()
                 for name, a, o in zip(("makespan", "bubble", "peak_mem", "flags"), out, want[id(w)]):
                     assert (a.cpu().numpy() == o).all(), (name, w.name, turn)
+
+
+def _layered_workload(rng, n, p, n_cand, span, extra_edges=()):
+    """A DAG whose node ids are a topological order and whose edges reach at most `span` ids back (plus the given
+    extra edges), list-scheduled candidates, some of them then made cyclic or malformed."""
+    src, dst = [], []
+    for v in range(1, n):
+        for u in rng.choice(np.arange(max(0, v - span), v), size=min(v, int(rng.integers(0, 4))), replace=False):
+            src.append(int(u)); dst.append(v)
+    for u, v in extra_edges:
+        src.append(u); dst.append(v)
+    rp, ci = W.csr_from_edges(n, src, dst)
+    pl, rk = W.list_schedules(rp, ci, p, n_cand, int(rng.integers(0, 2 ** 62)))
+    for c in range(0, n_cand, 5):                            # every fifth candidate: arbitrary orders (mostly cyclic)
+        for j in range(p):
+            idx = np.nonzero(pl[c] == j)[0]
+            rk[c, idx] = rng.permutation(len(idx))
+    if n_cand > 8:
+        pl[3, n // 2] = p
+        rk[7, n // 3] = -1
+        rk[8, 0] = rk[8, n - 1] if pl[8, 0] == pl[8, n - 1] else rk[8, 0] + n
+    return W.Workload("layered n=%d p=%d span=%d" % (n, p, span), p, rp, ci, rng.integers(0, 9, n).astype(np.int32),
+                      rng.integers(0, 6, (p, p)).astype(np.int32), rng.integers(-5, 6, n).astype(np.int64), pl, rk)
+
+
+def test_window_of_end_time_cells(gpu_lib):
+    """Graphs whose edges are short in the order of the node ids can be evaluated with a window of named end-time
+    cells per candidate instead of a cell per operation.  The library takes that mode by itself on the layered
+    workload; here it is also forced, with windows that fit, windows far too small (candidates whose schedule does not
+    fit go to the int32 kernel: the results stay the oracle's, the count says how many went), a single long-range edge
+    that no small window can hold, all kernel kinds, several candidates per wavefront, weights and limits."""
+    import torch
+    rng = np.random.default_rng(5150)
+    dev = torch.device("cuda", 0)
+    w5 = W.gen_config(5, n_cand=40)
+    (z, b, pk, f), info = assert_parity(gpu_lib, w5, repeats=2)
+    assert info["window_log2"] == 12 and info["variant"] == 4, info
+    (z, b, pk, f), info = _with_env({"window_cells": -1}, lambda: assert_parity(gpu_lib, w5))
+    assert info["window_log2"] == 0
+    (z, b, pk, f), info = assert_parity(gpu_lib, dataclasses_replace(w5, placement=w5.placement[:9], rank=w5.rank[:9]), layout=1)
+    assert info["window_log2"] == 12
+    seen_fallbacks = 0
+    for n, p, span, cells, extra in ((700, 5, 20, 256, ()), (700, 5, 20, 32, ()), (1500, 16, 60, 1024, ()),
+                                     (1500, 16, 60, 64, ()), (900, 64, 30, 512, ()), (400, 1, 10, 64, ()),
+                                     (1200, 7, 15, 128, ((0, 1199), (3, 900))), (333, 3, 400, 512, ()), (2000, 33, 8, 8, ())):
+        w = _layered_workload(rng, n, p, 45, span, extra)
+        for shape in ({"window_cells": cells}, {"window_cells": cells, "preds_per_op": 4, "ring_slots": 16, "feeders": 3}):
+            _say("%s window %d %s" % (w.name, cells, shape))
+            want = oracle.evaluate_workload(w, threads=8)
+            with gpu_lib.Evaluator.for_workload(w, shape=shape) as ev:
+                info = ev.info()
+                assert info["window_log2"] == int(np.log2(cells)) and info["variant"] == 4, info
+                got = ev.evaluate(torch.from_numpy(w.placement).to(dev), torch.from_numpy(w.rank).to(dev))
+                n_fb = ev.last_fallbacks()
+                for name, a, o in zip(("makespan", "bubble", "peak_mem", "flags"), got, want):
+                    bad = np.nonzero(np.asarray(a.cpu().numpy() != o).reshape(len(o), -1).any(axis=1))[0]
+                    assert len(bad) == 0, "%s differs at %s (%s, %d fallbacks)" % (name, bad[:8], info, n_fb)
+            if cells - 3 >= n:                               # every operation has a cell of its own: nothing can be missed
+                assert n_fb == 0, (w.name, cells, n_fb)
+            if extra:
+                assert n_fb > 0
+            seen_fallbacks += n_fb
+    assert seen_fallbacks > 0
+    # with static memory and limits (the accountant reads the lists of the ingest launch)
+    w = _layered_workload(rng, 800, 6, 60, 25)
+    w = dataclasses_replace(w, weight=rng.integers(0, 20, 800).astype(np.int64), mem_limit=np.array([1500] + [10 ** 9] * 5, dtype=np.int64))
+    (z, b, pk, f), info = _with_env({"window_cells": 256}, lambda: assert_parity(gpu_lib, w))
+    assert info["window_log2"] == 8 and 16 in set(f.tolist())
+    # node ids that are no topological order: the mode is not taken, whatever the shape asks for
+    wr = W.random_instance(rng, 300, 4, 20)
+    (z, b, pk, f), info = _with_env({"window_cells": 128}, lambda: assert_parity(gpu_lib, wr))
+    assert info["window_log2"] == 0
 
 
 def test_large_delays(gpu_lib):
