@@ -422,7 +422,9 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
 
   // shape: most candidates resident per CU first.  Placement bytes in LDS give the fastest feeders but cost
   // N bytes per candidate; in L2 they leave room for more candidates or a deeper ring.  Measured weights: a
-  // four-slot ring counts 0.7 (hot lanes outrun it), placement bytes in L2 count 0.97, and workgroups beyond
+  // four-slot ring counts 0.7 (hot lanes outrun it), placement bytes in L2 count 0.7 (0.85 with two predecessors
+  // per op: half the gathers; a 36-layer MoE graph, N = 6912: four workgroups per CU with them in L2 0.179 us per
+  // candidate, three with them in LDS 0.135), and workgroups beyond
   // five per CU count nothing, half-empty wavefronts count 0.65 (the feeders do the same work for half the
   // candidates); at equal counts, more workgroups of fewer candidates.
   // a shape given with the description wins, field by field
@@ -480,7 +482,7 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
         // window mode relaxes every candidate of a full batch at once when it can: workgroups per CU beyond what the
         // batch fills count nothing, a deeper ring does (config 5: 3 % for sixteen slots over eight)
         if (win_log2) wgs = std::min<int64_t>(wgs, std::max<int64_t>(1, ((d->max_candidates + G - 1) / G + n_cu - 1) / n_cu));
-        const int64_t score = (int64_t)wgs * G * (ring >= 8 ? 100 : 70) * (pib_lds == 1 ? 100 : pib_lds == 2 ? 99 : 97) *
+        const int64_t score = (int64_t)wgs * G * (ring >= 8 ? 100 : 70) * (pib_lds == 1 ? 100 : pib_lds == 2 ? 99 : plan.kind == 2 ? 85 : 70) *
                                   (G * Pseg < kWave ? 65 : 100) + (ring == 16 ? 2 : 0) - G;
         if (score > best_score) { best_score = score; best_wgs = wgs; plan.G = G; plan.ring = ring; plan.lds = o; }
       }
