@@ -5,7 +5,7 @@
  * from scratch in every call of the two candidate functions, so that each step can be checked against the
  * text by eye.  It shares no code with the HIP library and is never called from the product path.
  *
- * What the section defines, and the reading taken where it leaves a choice (the design doc lists the readings):
+ * What the section defines, and the reading taken where it leaves a choice:
  *
  *  - Topologically redundant edges: (i1, i2) in B such that some i3 has (i1, i3) in B and (i3, i2) in B
  *    (two hops, nothing longer).  They are removed only while a candidate is looked for; B' below is B

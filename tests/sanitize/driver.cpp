@@ -70,6 +70,7 @@ int main(int argc, char **argv) {
         sh.feeders = 1 + variant % 4; sh.ring_slots = (variant & 4) ? 8 : 16; sh.placement_mode = variant % 3;
         sh.state_bits = variant >= 10 ? 32 : 0; sh.preds_per_op = variant == 7 ? 4 : 0; sh.static_waves = variant == 6 ? 2 : 0;
         sh.kernel = variant == 11 ? 1 : 0;
+        sh.window_cells = variant == 8 ? 64 : variant == 9 ? -1 : variant == 5 ? 4096 : 0;
         dd.shape = &sh;
       }
       const int rc = dagsched_plan(&dd, 160 * 1024, 256, &info);

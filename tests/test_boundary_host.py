@@ -175,3 +175,46 @@ def test_plan_of_the_five_workloads():
     with pytest.raises(dagsched.DagschedError) as e:
         dagsched.plan(w.n_devices, w.row_ptr, w.col_idx, -w.dur, w.comm, w.mem_delta)
     assert e.value.code == dagsched.EINVAL
+
+
+def test_plan_takes_the_window_of_end_time_cells_only_where_it_is_sound():
+    """Host logic of the window mode: taken by itself on a large graph whose node ids are a topological order with
+    short edges (the layered workload: 4096 cells for edges of at most 499 ids), never when the ids are no
+    topological order, never when the caller forbids it, with the caller's cell count when one is given, and only
+    while every cell name fits 16 bits (N + 3 N / (K - 3) + 1 <= 65535)."""
+    from paper_2503_09357_amd import workloads as W
+    w = W.gen_config(5, n_cand=2)
+    args = (w.n_devices, w.row_ptr, w.col_idx, w.dur, w.comm, w.mem_delta)
+    src, dst = W.edges_from_csr(w.row_ptr, w.col_idx)
+    assert (src < dst).all() and int((dst - src).max()) == 499
+    info = dagsched.plan(*args, max_candidates=1024)
+    assert info["window_log2"] == 12 and info["variant"] == 4 and info["lds_bytes"] < 48 * 1024 and info["placement_bytes_in_lds"] == 0
+    assert dagsched.plan(*args, max_candidates=1024, shape={"window_cells": -1})["window_log2"] == 0
+    assert dagsched.plan(*args, max_candidates=1024, shape={"window_cells": 8192})["window_log2"] == 13
+    # 50000 operations in periods of 13 names of 16 cells: names up to 61540 fit; in periods of 5 of 8 they do not
+    assert dagsched.plan(*args, max_candidates=1024, shape={"window_cells": 16})["window_log2"] == 4
+    assert dagsched.plan(*args, max_candidates=1024, shape={"window_cells": 8})["window_log2"] == 0
+    for bad in (3, 100, 65536, -2):                          # a power of two from 8 to 32768, 0 or -1
+        with pytest.raises(dagsched.DagschedError):
+            dagsched.plan(*args, max_candidates=1024, shape={"window_cells": bad})
+    # 32-bit end times and the window do not go together
+    assert dagsched.plan(*args, max_candidates=1024, shape={"state_bits": 32})["window_log2"] == 0
+    # the same graph with its ids reversed is no topological order: declined, also when asked for
+    n = w.n_nodes
+    rp, ci = W.csr_from_edges(n, n - 1 - dst, n - 1 - src)
+    rev = (w.n_devices, rp, ci, w.dur[::-1].copy(), w.comm, w.mem_delta[::-1].copy())
+    assert dagsched.plan(*rev, max_candidates=1024)["window_log2"] == 0
+    assert dagsched.plan(*rev, max_candidates=1024, shape={"window_cells": 4096})["window_log2"] == 0
+    # a small layered graph: not by itself (nothing to gain), but on request
+    rng = np.random.default_rng(11)
+    s2, d2 = [], []
+    for v in range(1, 600):
+        for u in rng.choice(np.arange(max(0, v - 9), v), size=min(v, 2), replace=False):
+            s2.append(int(u)); d2.append(v)
+    rp, ci = W.csr_from_edges(600, s2, d2)
+    small = (4, rp, ci, np.ones(600, np.int32), np.ones((4, 4), np.int32), np.zeros(600, np.int64))
+    assert dagsched.plan(*small, max_candidates=64)["window_log2"] == 0
+    assert dagsched.plan(*small, max_candidates=64, shape={"window_cells": 128})["window_log2"] == 7
+    # the MoE graph's edges span 1463 ids: eight times that does not pay against 11712 cells, so no window
+    w4 = W.gen_config(4, n_cand=2)
+    assert dagsched.plan(w4.n_devices, w4.row_ptr, w4.col_idx, w4.dur, w4.comm, w4.mem_delta, max_candidates=4096)["window_log2"] == 0
