@@ -511,7 +511,7 @@ def _layered_workload(rng, n, p, n_cand, span, extra_edges=()):
     extra edges), list-scheduled candidates, some of them then made cyclic or malformed."""
     src, dst = [], []
     for v in range(1, n):
-        for u in rng.choice(np.arange(max(0, v - span), v), size=min(v, int(rng.integers(0, 4))), replace=False):
+        for u in rng.choice(np.arange(max(0, v - span), v), size=min(v, span, int(rng.integers(0, 4))), replace=False):
             src.append(int(u)); dst.append(v)
     for u, v in extra_edges:
         src.append(u); dst.append(v)
