@@ -10,6 +10,7 @@ candidates, inputs already resident in HBM.  Prints ONE JSON line.
 from __future__ import annotations
 
 import argparse
+import dataclasses
 import json
 import os
 import sys
@@ -209,8 +210,13 @@ def main() -> int:
         # workload in the candidate-minor layout (the transposes in front of the kernel are part of that time)
         import oracle
         others = []
-        for cfg, layout in [(c, 0) for c in (1, 2, 3, 4, 5) if c != args.config] + [(args.config, 1 - args.layout)]:
+        # (cfg 5 a second time with durations x 37 + 11 and delays x 30: end times that need 32 bits)
+        for cfg, layout, long_times in ([(c, 0, False) for c in (1, 2, 3, 4, 5) if c != args.config] + [(args.config, 1 - args.layout, False)] +
+                                        [(5, 0, True)]):
             w2 = W.gen_config(cfg)
+            if long_times:
+                w2 = dataclasses.replace(w2, name=w2.name + ", end times of 32 bits", dur=(w2.dur * 37 + 11).astype(np.int32),
+                                         comm=(w2.comm * 30).astype(np.int32))
             pl2, rk2 = (w2.placement, w2.rank) if layout == 0 else (np.ascontiguousarray(w2.placement.T), np.ascontiguousarray(w2.rank.T))
             ev2 = ds.Evaluator.for_workload(w2, layout=layout)
             p2, r2 = torch.from_numpy(pl2).to(dev), torch.from_numpy(rk2).to(dev)
@@ -230,7 +236,7 @@ def main() -> int:
                            "candidates_per_s": w2.n_cand / (ms2 * 1e-3),
                            "node_relax_per_s": w2.n_cand * w2.n_nodes / (ms2 * 1e-3),
                            "roofline_frac": ab2 / (ms2 * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                           "traffic": measured_traffic(cfg, dominant_kernel(info2)) if layout == 0 else None,
+                           "traffic": measured_traffic(cfg, dominant_kernel(info2)) if layout == 0 and not long_times else None,
                            "candidates_sent_to_int32_kernel": ev2.last_fallbacks(),
                            "parity_vs_oracle": parity2, "kernel": info2})
             ev2.close()

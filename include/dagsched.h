@@ -100,7 +100,8 @@ typedef struct {
   int32_t static_waves;     /* relaxing wavefronts per workgroup of the shared-placement kernel (1..8); naming it
                                also makes small handles take that kernel                                     */
   int32_t ignore_shared_placement; /* 1: dagsched_desc_t.shared_placement is not used                        */
-  int32_t window_cells;     /* end-time cells per candidate in the window mode of the 16-bit kernel (for graphs whose
+  int32_t window_cells;     /* end-time cells per candidate in the window mode of the ring kernel (16- or 32-bit end
+                               times; for graphs whose
                                edges are short in the order of the node ids): a power of two from 8 to 32768 to ask
                                for that many, -1 to forbid the mode, 0 to let the library decide.  Candidates whose
                                schedule does not fit the window are evaluated by the int32 kernel one by one   */

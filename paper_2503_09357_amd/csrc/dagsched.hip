@@ -237,7 +237,7 @@ void free_handle(dagsched *h) {
 LdsLayout ring_layout(int N, int P, int G, int ring, int pib_lds, int cell_bytes, bool wide, int win_log2 = 0) {
   LdsLayout o{};
   uint32_t at = 0;
-  o.s_stride = win_log2 ? 4u << win_log2
+  o.s_stride = win_log2 ? (cell_bytes == 4 ? 8u : 4u) << win_log2          // window: name and end time, 16 or 32 bits each
                         : align_up((uint32_t)cell_bytes * (uint32_t)(N + 2), 4);   // N cells + dummy + trash; the arrays start at LDS offset 0
   o.win_log2 = (uint32_t)win_log2;
   o.cell_bytes = (uint32_t)cell_bytes;
@@ -247,7 +247,7 @@ LdsLayout ring_layout(int N, int P, int G, int ring, int pib_lds, int cell_bytes
   o.o_pi = at;    at += (uint32_t)G * o.pi_stride;
   at = align_up(at, 16);
   o.o_ring = at;  at += (uint32_t)ring * kWave * 16u;
-  o.o_scr = at;   at += kWave * 4u;
+  o.o_scr = at;   at += kWave * ((win_log2 && cell_bytes == 4) ? 8u : 4u);
   o.o_total = at; at += kWave * 4u;
   at = align_up(at, 8);
   o.o_peak = at;  at += kWave * 8u;
@@ -455,7 +455,7 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
     else if (want == 0 && N >= 8192) { K = 1024; while (K < 8 * span) K <<= 1; }
     const bool fits_names = K >= 8 && K <= 32768 && (int64_t)N + 3 * ((int64_t)N / (K - 3)) + 1 <= 65535;
     const bool worth = want > 0 || (int64_t)K * 4 * 5 <= (int64_t)(2 * N) * 2;
-    if (K && topological && fits_names && worth && !plan.cell32 && !wide) win_log2 = ilog2(K);
+    if (K && topological && fits_names && worth && !wide) win_log2 = ilog2(K);   // (32-bit end times: cells of 64 bits)
   }
   const int force_g = sh ? sh->cand_per_block : 0;
   const int force_ring = sh ? sh->ring_slots : 0;
@@ -480,8 +480,14 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
         int wgs = std::min(5, lds_max / (int)align_up(o.total, 512));   // beyond ~20 wavefronts the CU is issue-bound
         if (wgs < 1) continue;
         // window mode relaxes every candidate of a full batch at once when it can: workgroups per CU beyond what the
-        // batch fills count nothing, a deeper ring does (config 5: 3 % for sixteen slots over eight)
-        if (win_log2) wgs = std::min<int64_t>(wgs, std::max<int64_t>(1, ((d->max_candidates + G - 1) / G + n_cu - 1) / n_cu));
+        // batch fills count nothing, nor do those that leave the number of rounds as it is (four per CU needed: three
+        // resident take two rounds like two); a deeper ring does count (config 5: 3 % for sixteen slots over eight,
+        // 11 % with 32-bit end times)
+        if (win_log2) {
+          const int64_t need = std::max<int64_t>(1, ((d->max_candidates + G - 1) / G + n_cu - 1) / n_cu);
+          const int64_t rounds = (need + wgs - 1) / wgs;
+          wgs = (int)std::min<int64_t>(wgs, (need + rounds - 1) / rounds);
+        }
         const int64_t score = (int64_t)wgs * G * (ring >= 8 ? 100 : 70) * (pib_lds == 1 ? 100 : pib_lds == 2 ? 99 : plan.kind == 2 ? 85 : 70) *
                                   (G * Pseg < kWave ? 65 : 100) + (ring == 16 ? 2 : 0) - G;
         if (score > best_score) { best_score = score; best_wgs = wgs; plan.G = G; plan.ring = ring; plan.lds = o; }
@@ -496,7 +502,8 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
                : best_wgs <= 2 ? 3
                : (best_wgs * 4 <= 24 ? 2 : 1);
   auto built = [&](int feeders) {
-    return win_log2    ? ring_kernel_pick<4>(plan.ring, feeders, (int)plan.lds.pib_mode, plan.kind) != nullptr
+    return win_log2    ? (plan.cell32 ? ring_kernel_pick<5>(plan.ring, feeders, (int)plan.lds.pib_mode, plan.kind) != nullptr
+                                      : ring_kernel_pick<4>(plan.ring, feeders, (int)plan.lds.pib_mode, plan.kind) != nullptr)
          : wide        ? ring_kernel_pick<3>(plan.ring, feeders, (int)plan.lds.pib_mode, plan.kind) != nullptr
          : plan.cell32 ? ring_kernel_pick<2>(plan.ring, feeders, (int)plan.lds.pib_mode, plan.kind) != nullptr
                        : ring_kernel_pick<0>(plan.ring, feeders, (int)plan.lds.pib_mode, plan.kind) != nullptr;
@@ -537,12 +544,22 @@ using RingKernel = void (*)(RingParams);
   case 0 * 10000 + RING * 10 + F: return relax_ring_kernel<RING, F, 4, 0, 0, 2>;                  \
   case 1 * 10000 + RING * 10 + F: return relax_ring_kernel<RING, F, 4, 0, 1, 2>;                  \
   case 2 * 10000 + RING * 10 + F: return relax_ring_kernel<RING, F, 4, 0, 2, 2>;
+#define DAGSCHED_WIN32_CASES(RING, F)                                                             \
+  case 0 * 10000 + RING * 10 + F: return relax_ring_kernel<RING, F, 5, 0, 0, 2>;                  \
+  case 1 * 10000 + RING * 10 + F: return relax_ring_kernel<RING, F, 5, 0, 1, 2>;                  \
+  case 2 * 10000 + RING * 10 + F: return relax_ring_kernel<RING, F, 5, 0, 2, 2>;
 RingKernel ring_ingest_kernel(int kind) {
   return kind == 0 ? relax_ring_kernel<8, 2, 4, 0, 0, 1> : kind == 1 ? relax_ring_kernel<8, 2, 4, 0, 1, 1> : relax_ring_kernel<8, 2, 4, 0, 2, 1>;
 }
 template <int HALF>
 RingKernel ring_kernel_pick(int ring, int feeders, int pib_lds, int kind) {
-  if constexpr (HALF == 4) {
+  if constexpr (HALF == 5) {                                    // window mode with 32-bit end times: fewer shapes
+    if (pib_lds != 0) return nullptr;
+    switch (kind * 10000 + ring * 10 + feeders) {
+      DAGSCHED_WIN32_CASES(8, 2) DAGSCHED_WIN32_CASES(16, 2) DAGSCHED_WIN32_CASES(16, 3)
+      default: return nullptr;
+    }
+  } else if constexpr (HALF == 4) {
     if (pib_lds != 0) return nullptr;
     switch (kind * 10000 + ring * 10 + feeders) {
       DAGSCHED_WIN_CASES(8, 1) DAGSCHED_WIN_CASES(8, 2) DAGSCHED_WIN_CASES(8, 3)
@@ -580,7 +597,9 @@ RingKernel ring_kernel_for(const dagsched *h) {
   // byte addresses when the workgroup's end-time arrays fit 64 KB, half addresses otherwise
   const bool half = (uint64_t)h->ring_G * h->lds.s_stride > 65536u;
   const int pib_lds = (int)h->lds.pib_mode;
-  if (h->lds.win_log2) return ring_kernel_pick<4>(h->ring_slots, h->ring_feeders, pib_lds, h->ring_kind);
+  if (h->lds.win_log2)
+    return h->lds.cell_bytes == 4 ? ring_kernel_pick<5>(h->ring_slots, h->ring_feeders, pib_lds, h->ring_kind)
+                                  : ring_kernel_pick<4>(h->ring_slots, h->ring_feeders, pib_lds, h->ring_kind);
   if (h->lds.wide) return ring_kernel_pick<3>(h->ring_slots, h->ring_feeders, pib_lds, h->ring_kind);
   if (h->lds.cell_bytes == 4) return ring_kernel_pick<2>(h->ring_slots, h->ring_feeders, pib_lds, h->ring_kind);
   return half ? ring_kernel_pick<1>(h->ring_slots, h->ring_feeders, pib_lds, h->ring_kind)
@@ -922,7 +941,7 @@ int dagsched_create(const dagsched_desc_t *caller_desc, dagsched_t **out) {
       ok = allow_large_lds(splan.preds == 2 ? (const void *)relax_static_kernel<2> : (const void *)relax_static_kernel<4>, h->device, (int)s.total);
   }
   if (ok && plan.ok) {
-    h->variant = plan.cell32 ? kVariantRing32 : plan.exact ? kVariantRingExact : kVariantRingOptimistic;
+    h->variant = !plan.exact ? kVariantRingOptimistic : plan.cell32 ? kVariantRing32 : kVariantRingExact;   // (window mode is never exact)
     h->ring_G = plan.G; h->ring_slots = plan.ring; h->ring_feeders = plan.feeders; h->ring_kind = plan.kind; h->ring_block = plan.block; h->lds = plan.lds; h->time_scale = plan.scale;
     h->rec_plane = plan.rec_plane; h->id_bits = plan.id_bits;
     const int64_t cap = ((int64_t)h->N + h->E + 1024) * 64;
@@ -1278,7 +1297,7 @@ int dagsched_plan(const dagsched_desc_t *caller_desc, int32_t lds_bytes, int32_t
     h.st.G = splan.G; h.st.W = splan.W; h.st.total = splan.total;
   }
   if (plan.ok) {
-    h.variant = plan.cell32 ? kVariantRing32 : plan.exact ? kVariantRingExact : kVariantRingOptimistic;
+    h.variant = !plan.exact ? kVariantRingOptimistic : plan.cell32 ? kVariantRing32 : kVariantRingExact;
     h.ring_G = plan.G; h.ring_slots = plan.ring; h.ring_feeders = plan.feeders; h.ring_kind = plan.kind; h.ring_block = plan.block;
     h.lds = plan.lds; h.time_scale = plan.scale;
   }
@@ -1293,7 +1312,7 @@ int dagsched_get_info(const dagsched_t *h, dagsched_info_t *info) {
   info->cand_per_block = ring ? h->ring_G : h->gen_G;
   info->block_threads = ring ? h->ring_block : kWave;
   info->lds_bytes = ring ? (int32_t)h->lds.total : h->gen_lds;
-  info->state_bits = ring && h->variant != kVariantRing32 ? 16 : 32;
+  info->state_bits = ring && h->lds.cell_bytes != 4 ? 16 : 32;
   if (h->variant == kVariantStatic) {
     info->cand_per_block = h->st.G * h->st.W;
     info->block_threads = static_threads(h->st.W);

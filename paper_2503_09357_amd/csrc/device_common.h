@@ -37,6 +37,7 @@ __device__ __forceinline__ void st_agent(int32_t *p, int32_t v) {
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 typedef DAGSCHED_LDS unsigned char lds_byte_t;
 typedef DAGSCHED_LDS volatile uint32_t lds_vu32_t;
+typedef DAGSCHED_LDS volatile uint64_t lds_vu64_t;
 typedef DAGSCHED_LDS volatile uint16_t lds_vu16_t;
 typedef DAGSCHED_LDS volatile int32_t lds_vi32_t;
 typedef DAGSCHED_LDS const uint8_t lds_cu8_t;

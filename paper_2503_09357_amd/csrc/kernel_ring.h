@@ -123,6 +123,8 @@ struct RingParams {
 // workgroup needs while it relaxes; the order lists, which need 2 N bytes of LDS while they are built, are then
 // built by a launch of their own (PHASE = 1: ingest only, hands cnt / off / total / flags over through ws_meta)
 // and the relaxation (PHASE = 2) runs with several workgroups per CU.  PHASE = 0 is the fused kernel.
+// HALF = 5 is the window mode for end times that need 32 bits: a cell is 64 bits, name above and end time below,
+// written with a 64-bit LDS maximum; names, ops and the ingest launch are the same.
 template <int RING, int FEEDERS, int HALF, int PIBL, int KIND = 0, int PHASE = 0>
 __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
   // ring_threads(FEEDERS) threads have a role while the schedule is relaxed; the host may launch more (a
@@ -133,16 +135,17 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
   static_assert((RING & (RING - 1)) == 0, "RING must be a power of two");
   static_assert(RING >= FEEDERS, "every feeder needs a slot of its own");
   static_assert(KIND >= 0 && KIND <= 2, "general, single parts, two predecessors");
-  static_assert(HALF >= 0 && HALF <= 4, "byte, half or quarter addresses; 3: quarter addresses and delays looked up by the relaxer; 4: window");
+  static_assert(HALF >= 0 && HALF <= 5, "byte, half or quarter addresses; 3: quarter addresses and delays looked up by the relaxer; 4, 5: window");
   static_assert(PHASE >= 0 && PHASE <= 2, "fused, ingest only, relaxation only");
-  constexpr bool kWin = HALF == 4;                          // a window of named cells per candidate
+  constexpr bool kWin = HALF == 4 || HALF == 5;             // a window of named cells per candidate
+  constexpr bool kWin32 = HALF == 5;                        // ... of 64 bits: name above, 32-bit end time below
   static_assert(!kWin || PIBL == 0, "window mode keeps the placement bytes in the workspace row");
   static_assert(kWin || PHASE == 0, "only the window mode is split into two launches");
   constexpr bool kCell32 = HALF == 2 || HALF == 3;          // 32-bit end times
   constexpr bool kWide = HALF == 3;                         // ops name machines, not delays; durations below 256 * 65535
   constexpr int kAsh = kCell32 ? 2 : kWin ? 0 : HALF;       // 16-bit address -> LDS byte address
   static_assert(!(kWide && PIBL == 2), "wide ops need the dummy machine, which a nibble cannot name");
-  constexpr uint32_t kNotDone = kCell32 ? kNotDone32 : kNotDone16;
+  constexpr uint32_t kNotDone = (kCell32 || kWin32) ? kNotDone32 : kNotDone16;
   constexpr int kNodeShift = (kCell32 || kWin) ? 0 : 1 - HALF;   // node -> offset of its cell in the units of the 16-bit addresses
   constexpr int PR = KIND == 2 ? 2 : 4;                     // DAG predecessors per op
   constexpr uint32_t kOrigin = PIBL == 2 ? 255u : 0u;
@@ -375,7 +378,11 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
   for (int gg = team; gg < ng; gg += n_teams) {
     uint32_t *sw = (uint32_t *)(lds + gg * o.s_stride);
     if (kWin) {                                             // no name anywhere, but the dummy's in its slot, ended at 0
-      for (uint32_t i = (uint32_t)tt; i <= win_mask; i += (uint32_t)tpc) sw[i] = i == win_dummy ? win_dummy << 16 : 0u;
+      if (kWin32) {
+        for (uint32_t i = (uint32_t)tt; i <= win_mask; i += (uint32_t)tpc) { sw[2 * i] = 0u; sw[2 * i + 1] = i == win_dummy ? win_dummy : 0u; }
+      } else {
+        for (uint32_t i = (uint32_t)tt; i <= win_mask; i += (uint32_t)tpc) sw[i] = i == win_dummy ? win_dummy << 16 : 0u;
+      }
     } else if (kCell32) {
       for (int i = tt; i < N + 2; i += tpc) sw[i] = i < N ? kNotDone32 : 0u;
     } else {
@@ -396,7 +403,7 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
   // 16-bit address of this candidate's cell 0: LDS addresses (halved when HALF), so that the relaxer uses them as they are
   const uint32_t sbase = ((uint32_t)(uintptr_t)ldsb >> kAsh) + (uint32_t)g * (o.s_stride >> kAsh);
   // window mode: LDS byte address of the cell of a name (sbase is then the byte address of the candidate's cells)
-  auto win_addr = [&](uint32_t name) -> uint32_t { return sbase + ((name & win_mask) << 2); };
+  auto win_addr = [&](uint32_t name) -> uint32_t { return sbase + ((name & win_mask) << (kWin32 ? 3 : 2)); };
 
   int32_t acc = 0;
   bool stalled = false;
@@ -415,10 +422,12 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
     // window mode: where a lane that ran nothing (or a part that ends no operation) leaves its value: a dword of its
     // own.  The cells are written with an LDS maximum, and lanes that aim one at the same address are served one
     // after the other, unlike plain stores: a shared trash cell cost 40 % of the LDS pipe's time.
-    const uint32_t own_trash = (uint32_t)(uintptr_t)(ldsb + o.o_scr) + (uint32_t)lane * 4u;
+    const uint32_t own_trash = (uint32_t)(uintptr_t)(ldsb + o.o_scr) + (uint32_t)lane * (kWin32 ? 8u : 4u);
     auto set_cell = [&](uint32_t a16, uint32_t v) {
       // (window: the maximum keeps a later name from being replaced by an earlier one)
-      if (kWin) (void)__hip_atomic_fetch_max((DAGSCHED_LDS uint32_t *)(uintptr_t)(a16 == win_trash ? own_trash : win_addr(a16)),
+      if (kWin32) (void)__hip_atomic_fetch_max((DAGSCHED_LDS uint64_t *)(uintptr_t)(a16 == win_trash ? own_trash : win_addr(a16)),
+                                              ((uint64_t)a16 << 32) | v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      else if (kWin) (void)__hip_atomic_fetch_max((DAGSCHED_LDS uint32_t *)(uintptr_t)(a16 == win_trash ? own_trash : win_addr(a16)),
                                             (a16 << 16) | v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
       else if (kCell32) *(lds_vu32_t *)(uintptr_t)(a16 << 2) = v;
       else *(lds_vu16_t *)(uintptr_t)(a16 << kAsh) = (uint16_t)v;
@@ -435,7 +444,7 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
     uint32_t tm = kNotDone16;
     constexpr uint32_t kSlotMask = (uint32_t)(RING - 1) << 10;
     // where lanes that take nothing write their "slot free" mark (the store adds 12, the place of a slot's last dword)
-    lds_byte_t *const scr_m12 = ldsb + o.o_scr + (uint32_t)lane * 4u - 12u;
+    lds_byte_t *const scr_m12 = ldsb + o.o_scr + (uint32_t)lane * (kWin32 ? 8u : 4u) - 12u;
     // "This lane holds no op": the registers hold the content of a free slot, whose "duration" 0xFFFF can never
     // run; such a lane copies slot t again in every trip until an op is there.
     const uint32_t z0 = dummy | (dummy << 16);
@@ -445,7 +454,15 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
     lds_byte_t *slot_p = ring_lane;                         // ring slot of op t
     u32x4_t r = *(lds_vu32x4_t *)slot_p;                    // ... as read during the previous trip
     // end times of the current op's predecessors, read at the end of the previous trip
-    uint32_t e0 = cell(dummy), e1 = e0, e2 = e0, e3 = e0;
+    // (64-bit window cells: the time in e, the name in n)
+    uint32_t n0 = 0, n1 = 0, n2 = 0, n3 = 0;
+    auto read_cell = [&](uint32_t a16, uint32_t &e, uint32_t &n) {
+      if (kWin32) { const uint64_t c = *(lds_vu64_t *)(uintptr_t)win_addr(a16); e = (uint32_t)c; n = (uint32_t)(c >> 32); }
+      else e = cell(a16);
+    };
+    uint32_t e0, e1, e2, e3;
+    read_cell(dummy, e0, n0);
+    e1 = e2 = e3 = e0; n1 = n2 = n3 = n0;
     // wide ops: the delays of the current op's predecessors, looked up together with the end times
     lds_vu32_t *const commw = (lds_vu32_t *)(ldsb + o.o_comm) + j;
     const uint32_t lps = (uint32_t)p.log_pseg;
@@ -471,6 +488,13 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
           // then never 0xFFFF
           const uint32_t hi = w2 >> 24;
           x += (w3 & 0xFFFFu) + (hi << 16) - hi;
+        } else if (kWin32) {
+          bool named = (n0 == (w0 & 0xFFFFu)) & (n1 == (w0 >> 16));
+          if (PR == 4) named = named & (n2 == (w1 & 0xFFFFu)) & (n3 == (w1 >> 16));
+          x = max(max(x_acc, e0 + (w2 & 0xFFu)), e1 + (PR == 4 ? (w2 >> 8) & 0xFFu : w2 >> 8));
+          if (PR == 4) x = max(max(x, e2 + ((w2 >> 16) & 0xFFu)), e3 + (w2 >> 24));
+          x += w3 & 0xFFFFu;
+          ran = named && !idle;                               // (the library accepts no problem whose times could pass INT32_MAX)
         } else if (kWin) {
           // a predecessor has ended when its cell carries its name; the end time is the cell's lower half
           // (no short-circuit: the trip stays free of branches)
@@ -505,8 +529,8 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
         if (PR == 4) w1 = next ? c1 : w1;
         // The end-time reads of the next trip (LDS accesses keep their program order, so everything below
         // overlaps with their latency).
-        e0 = cell(w0 & 0xFFFFu); e1 = cell(w0 >> 16);
-        if (PR == 4) { e2 = cell(w1 & 0xFFFFu); e3 = cell(w1 >> 16); }
+        read_cell(w0 & 0xFFFFu, e0, n0); read_cell(w0 >> 16, e1, n1);
+        if (PR == 4) { read_cell(w1 & 0xFFFFu, e2, n2); read_cell(w1 >> 16, e3, n3); }
         if (kWide) {
           const uint32_t m = next ? c2 : w2;                // (w2 itself is updated below)
           d0 = commw[(m & 63u) << lps]; d1 = commw[((m >> 6) & 63u) << lps];
@@ -540,12 +564,12 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
         // says that the window moved past a predecessor this op still waits for: the int32 kernel's candidate, too)
         bool win_stop = false;
         if (kWin) {
-          const uint32_t n0 = e0 >> 16, n1 = e1 >> 16, i0 = w0 & 0xFFFFu, i1 = w0 >> 16;
-          bool named = n0 == i0 && n1 == i1, later = n0 > i0 || n1 > i1;
+          const uint32_t m0 = kWin32 ? n0 : e0 >> 16, m1 = kWin32 ? n1 : e1 >> 16, i0 = w0 & 0xFFFFu, i1 = w0 >> 16;
+          bool named = m0 == i0 && m1 == i1, later = m0 > i0 || m1 > i1;
           if (PR == 4) {
-            const uint32_t n2 = e2 >> 16, n3 = e3 >> 16, i2 = w1 & 0xFFFFu, i3 = w1 >> 16;
-            named = named && n2 == i2 && n3 == i3;
-            later = later || n2 > i2 || n3 > i3;
+            const uint32_t m2 = kWin32 ? n2 : e2 >> 16, m3 = kWin32 ? n3 : e3 >> 16, i2 = w1 & 0xFFFFu, i3 = w1 >> 16;
+            named = named && m2 == i2 && m3 == i3;
+            later = later || m2 > i2 || m3 > i3;
           }
           win_stop = named || later;
         }

@@ -180,8 +180,9 @@ def test_plan_of_the_five_workloads():
 def test_plan_takes_the_window_of_end_time_cells_only_where_it_is_sound():
     """Host logic of the window mode: taken by itself on a large graph whose node ids are a topological order with
     short edges (the layered workload: 4096 cells for edges of at most 499 ids), never when the ids are no
-    topological order, never when the caller forbids it, with the caller's cell count when one is given, and only
-    while every cell name fits 16 bits (N + 3 N / (K - 3) + 1 <= 65535)."""
+    topological order, never when the caller forbids it, with the caller's cell count when one is given, only
+    while every cell name fits 16 bits (N + 3 N / (K - 3) + 1 <= 65535), and with 64-bit cells when the end times
+    need 32 bits."""
     from paper_2503_09357_amd import workloads as W
     w = W.gen_config(5, n_cand=2)
     args = (w.n_devices, w.row_ptr, w.col_idx, w.dur, w.comm, w.mem_delta)
@@ -197,8 +198,13 @@ def test_plan_takes_the_window_of_end_time_cells_only_where_it_is_sound():
     for bad in (3, 100, 65536, -2):                          # a power of two from 8 to 32768, 0 or -1
         with pytest.raises(dagsched.DagschedError):
             dagsched.plan(*args, max_candidates=1024, shape={"window_cells": bad})
-    # 32-bit end times and the window do not go together
-    assert dagsched.plan(*args, max_candidates=1024, shape={"state_bits": 32})["window_log2"] == 0
+    # 32-bit end times: the same window with cells of 64 bits (twice the LDS of the 16-bit window, not 200 KB)
+    wide = dagsched.plan(*args, max_candidates=1024, shape={"state_bits": 32})
+    assert wide["window_log2"] == 12 and wide["state_bits"] == 32 and wide["variant"] == 4 and wide["lds_bytes"] < 64 * 1024
+    big = (w.n_devices, w.row_ptr, w.col_idx, (w.dur * 37 + 11).astype(np.int32), (w.comm * 30).astype(np.int32), w.mem_delta)
+    info = dagsched.plan(*big, max_candidates=1024)
+    assert info["window_log2"] == 12 and info["state_bits"] == 32 and info["variant"] == 4
+    assert dagsched.plan(*big, max_candidates=1024, shape={"window_cells": -1})["variant"] in (1, 2)   # else: the int32 kernel
     # the same graph with its ids reversed is no topological order: declined, also when asked for
     n = w.n_nodes
     rp, ci = W.csr_from_edges(n, n - 1 - dst, n - 1 - src)

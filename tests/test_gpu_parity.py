@@ -572,6 +572,19 @@ def test_window_of_end_time_cells(gpu_lib):
     w = dataclasses_replace(w, weight=rng.integers(0, 20, 800).astype(np.int64), mem_limit=np.array([1500] + [10 ** 9] * 5, dtype=np.int64))
     (z, b, pk, f), info = _with_env({"window_cells": 256}, lambda: assert_parity(gpu_lib, w))
     assert info["window_log2"] == 8 and 16 in set(f.tolist())
+    # end times that need 32 bits: cells of 64 bits, same protocol (before: such a problem of this size went to the
+    # int32 kernel, one wavefront per candidate with its state in HBM)
+    w5big = dataclasses_replace(w5, dur=(w5.dur * 37 + 11).astype(np.int32), comm=(w5.comm * 30).astype(np.int32),
+                                placement=w5.placement[:12], rank=w5.rank[:12])
+    (z, b, pk, f), info = assert_parity(gpu_lib, w5big, repeats=2)
+    assert info["window_log2"] == 12 and info["state_bits"] == 32 and info["variant"] == 4 and int(z.max()) > 65535, info
+    for n, p, span, cells in ((900, 7, 25, 256), (900, 7, 25, 16), (1300, 64, 40, 512), (500, 2, 12, 128)):
+        w = _layered_workload(rng, n, p, 45, span)
+        w = dataclasses_replace(w, dur=(w.dur * 211).astype(np.int32))
+        for shape in ({"window_cells": cells, "state_bits": 32}, {"window_cells": cells, "state_bits": 32, "preds_per_op": 4}):
+            _say("%s window %d of 64-bit cells %s" % (w.name, cells, shape))
+            (z, b, pk, f), info = _with_env(shape, lambda: assert_parity(gpu_lib, w, repeats=2))
+            assert info["window_log2"] == int(np.log2(cells)) and info["state_bits"] == 32, info
     # node ids that are no topological order: the mode is not taken, whatever the shape asks for
     wr = W.random_instance(rng, 300, 4, 20)
     (z, b, pk, f), info = _with_env({"window_cells": 128}, lambda: assert_parity(gpu_lib, wr))
