@@ -95,7 +95,8 @@ typedef struct {
   int32_t state_bits;       /* width of the end times kept on chip: 16 (twice the candidates resident; candidates
                                whose end times leave the range are evaluated by the int32 kernel one by one) or 32 */
   int32_t preds_per_op;     /* 4: the kernel kind that reads four predecessors per op and splits operations with
-                               more into parts, also where a leaner kind (single parts, two predecessors) applies */
+                               more into parts, also where a leaner kind (single parts, two predecessors, one)
+                               applies; 2: the two-predecessor kind also where the one-predecessor kind applies   */
   int32_t kernel;           /* 1: the general int32 kernel, whatever else would apply                        */
   int32_t static_waves;     /* relaxing wavefronts per workgroup of the shared-placement kernel (1..8); naming it
                                also makes small handles take that kernel                                     */
@@ -316,7 +317,7 @@ typedef struct {
   int32_t time_scale;      /* common factor of every duration and delay, divided out inside the kernels */
   int8_t feeders;          /* ring kernel: feeder wavefronts per workgroup */
   int8_t placement_mode;   /* ring kernel: where the placement bytes sit (0 L2, 1 LDS, 2 LDS as four bits per node) */
-  int8_t preds_per_op;     /* predecessors read per op: 2 or 4 (ring and shared-placement kernels) */
+  int8_t preds_per_op;     /* predecessors read per op: 1, 2 or 4 (ring and shared-placement kernels) */
   int8_t window_log2;      /* ring kernel in window mode: log2 of the end-time cells per candidate, else 0 */
 } dagsched_info_t;
 int dagsched_get_info(const dagsched_t *h, dagsched_info_t *info);

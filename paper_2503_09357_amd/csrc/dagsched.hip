@@ -146,7 +146,7 @@ int validate_desc(const dagsched_desc_t *d, std::vector<int32_t> *pred_ptr, std:
     if (sh->feeders < 0 || sh->feeders > 4 || sh->placement_mode < -1 || sh->placement_mode > 2) return DAGSCHED_EINVAL;
     if (b < 0 || b > 1024 || b % kWave) return DAGSCHED_EINVAL;
     if (sh->state_bits != 0 && sh->state_bits != 16 && sh->state_bits != 32) return DAGSCHED_EINVAL;
-    if (sh->preds_per_op != 0 && sh->preds_per_op != 4) return DAGSCHED_EINVAL;
+    if (sh->preds_per_op != 0 && sh->preds_per_op != 2 && sh->preds_per_op != 4) return DAGSCHED_EINVAL;
     if (sh->kernel < 0 || sh->kernel > 1 || sh->static_waves < 0 || sh->static_waves > 8) return DAGSCHED_EINVAL;
     if (sh->ignore_shared_placement < 0 || sh->ignore_shared_placement > 1) return DAGSCHED_EINVAL;
     if (sh->window_cells < -1 || (sh->window_cells > 0 && (sh->window_cells < 8 || sh->window_cells > 32768 ||
@@ -328,11 +328,13 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
   plan.scale = (int32_t)g;
 
   constexpr int PR = 4;                                // DAG predecessors per op part
-  // Predecessor lists of the ops.  An edge (u, v) of an operation with more than PR predecessors is left
-  // out when B has another path u -> w1 -> ... -> wk -> v whose intermediate durations sum to at least the
-  // largest channel delay: then s_v >= e_wk >= ... >= e_u + sum D^o_wi >= e_u + delta(u, v) whatever the
-  // candidate, so eqs. (11)-(13) for (u, v) are implied (and a cycle through (u, v) also runs through that
-  // path).  Fewer parts mean fewer relaxer trips on the critical path.  Bounded search: four hops, 256 visits.
+  // Predecessor lists of the ops.  An edge (u, v) is left out when B has another path u -> w1 -> ... -> wk -> v
+  // whose intermediate durations sum to at least the largest channel delay: then s_v >= e_wk >= ... >= e_u +
+  // sum D^o_wi >= e_u + delta(u, v) whatever the candidate, so eqs. (11)-(13) for (u, v) are implied (and a cycle
+  // through (u, v) also runs through that path).  Fewer parts mean fewer relaxer trips on the critical path, and
+  // a pipeline's operations keep a single predecessor each (the forward -> backward edge of a stage is implied by
+  // the path through the next stage), which selects a lighter kind of kernel.  Bounded search: six hops, 512
+  // visits (four hops do for the plain pipelines, six for the bidirectional one with its transfer operations).
   std::vector<std::vector<int32_t>> op_preds(N);
   {
     struct Item { int32_t node, hops; int64_t sum; };
@@ -344,12 +346,12 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
       while (!stack.empty()) {
         const Item it = stack.back();
         stack.pop_back();
-        if (++visits > 256) return false;
+        if (++visits > 512) return false;
         for (int32_t k = d->row_ptr[it.node]; k < d->row_ptr[it.node + 1]; ++k) {
           const int32_t y = d->col_idx[k];
           if (y == v) {
             if (it.hops >= 1 && it.sum >= max_comm) return true;
-          } else if (it.hops + 1 < 4) {
+          } else if (it.hops + 1 < 6) {
             stack.push_back({y, it.hops + 1, it.sum + d->dur[y]});
           }
         }
@@ -359,7 +361,7 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
     for (int v = 0; v < N; ++v) {
       const int deg = pred_ptr[v + 1] - pred_ptr[v];
       for (int k = pred_ptr[v]; k < pred_ptr[v + 1]; ++k)
-        if (deg <= PR || !implied(pred_idx[k], v)) op_preds[v].push_back(pred_idx[k]);
+        if (deg < 2 || !implied(pred_idx[k], v)) op_preds[v].push_back(pred_idx[k]);
     }
   }
   // shared operator records, part i of node v at [i * plane + v]
@@ -376,7 +378,8 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
   // operation is a single part), 0 otherwise (or when the caller's shape asks for four predecessors per op)
   size_t max_deg = 0;
   for (int v = 0; v < N; ++v) max_deg = std::max(max_deg, op_preds[v].size());
-  plan.kind = (d->shape && d->shape->preds_per_op == 4) ? 0 : max_deg <= 2 ? 2 : max_parts == 1 ? 1 : 0;
+  plan.kind = (d->shape && d->shape->preds_per_op == 4) ? 0 : max_deg <= 1 ? 3 : max_deg <= 2 ? 2 : max_parts == 1 ? 1 : 0;
+  if (d->shape && d->shape->preds_per_op == 2 && plan.kind == 3) plan.kind = 2;   // (the caller asks for the two-predecessor kind)
   const int plane = N;
   std::vector<uint4> rec((size_t)max_parts * plane, make_uint4(dummy | (dummy << 16), dummy | (dummy << 16), 0, 0));
   for (int v = 0; v < N; ++v) {
@@ -437,11 +440,20 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
   plan.cell32 = wide || force_bits == 32 || (force_bits != 16 && !fits16 && 3 * lower >= (int64_t)kNotDone16);
   if (!plan.cell32 && lower >= (int64_t)kNotDone16) return plan;   // 16 bits asked for, and no candidate could stay inside them
   const int cell_bytes = plan.cell32 ? 4 : 2;
-  // Window mode: when every edge is short in the order of the node ids (a layered graph), a candidate needs only a
-  // window of K named cells instead of a cell per operation (see the kernel).  K = eight times the longest edge,
-  // rounded up to a power of two: the operations in flight of a list schedule spread over a few edge lengths, and a
-  // candidate whose schedule does not fit the window is handed to the int32 kernel, never evaluated wrongly.  Taken
-  // when it shrinks the end-time state at least 2.5 times on a problem large enough for that to matter, or when the
+  // Window mode: when the operations run roughly in the order of their ids (a layered graph numbered level by
+  // level), a candidate needs only a window of K named cells instead of a cell per operation (see the kernel).
+  // A candidate whose schedule does not fit the window is handed to the int32 kernel, never evaluated wrongly, but
+  // that kernel is some seventy times slower, so K is chosen with a margin: operation x = u + m (K - 3) takes over
+  // the cell of u, and it must lie at least 24 levels of B (edges on the longest path from a source) behind every
+  // reader v of u, for every edge (u, v) and every m.  (The layered workload: margin 29 at 4096 cells, where a
+  // trip-by-trip simulation of 48 list schedules found none that misses; 13 at 2048 cells, where 11 of 48 miss.
+  // The MoE graph, numbered micro-batch by micro-batch: no K has a margin, although its edges are short once the
+  // implied ones are dropped.)  The margin alone does not do: the MoE graph RENUMBERED level by level has a margin
+  // of 53 levels at 1024 cells and 70 % of its list schedules miss there (6 of 4096 at 2048 cells, none at 4096,
+  // where the mode is slower than a cell per operation anyway: 1.29 against 1.11 ms): its levels are narrow (19
+  // operations for 32 machines), so the machines follow the chains of their micro-batches, not the levels.  Hence
+  // the second condition: a level holds at least one operation per machine on average.  Taken when such a K
+  // shrinks the end-time state at least 2.5 times on a problem large enough for that to matter, or when the
   // caller's shape names K.
   int win_log2 = 0;
   {
@@ -451,8 +463,22 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
     for (int v = 0; v < N; ++v)
       for (int32_t u : op_preds[v]) { topological = topological && u < v; span = std::max<int64_t>(span, v - u); }
     int K = 0;
-    if (want > 0) K = want;
-    else if (want == 0 && N >= 8192) { K = 1024; while (K < 8 * span) K <<= 1; }
+    if (want > 0) {
+      K = want;
+    } else if (want == 0 && N >= 8192 && topological) {
+      std::vector<int32_t> lvl(N, 0);                      // (ids are a topological order here)
+      for (int v = 0; v < N; ++v)
+        for (int32_t u : op_preds[v]) lvl[v] = std::max(lvl[v], lvl[u] + 1);
+      const int64_t n_levels = (int64_t)*std::max_element(lvl.begin(), lvl.end()) + 1;
+      for (int k = 1024; k <= 32768 && !K && (int64_t)N >= n_levels * P; k <<= 1) {
+        if ((int64_t)k * 4 * 5 > (int64_t)(2 * N) * 2 || span >= k - 3) continue;
+        int64_t margin = INT64_MAX;
+        for (int v = 0; v < N && margin >= 24; ++v)
+          for (int32_t u : op_preds[v])
+            for (int64_t x = (int64_t)u + (k - 3); x < N; x += k - 3) margin = std::min<int64_t>(margin, (int64_t)lvl[x] - lvl[v]);
+        if (margin >= 24) K = k;
+      }
+    }
     const bool fits_names = K >= 8 && K <= 32768 && (int64_t)N + 3 * ((int64_t)N / (K - 3)) + 1 <= 65535;
     const bool worth = want > 0 || (int64_t)K * 4 * 5 <= (int64_t)(2 * N) * 2;
     if (K && topological && fits_names && worth && !wide) win_log2 = ilog2(K);   // (32-bit end times: cells of 64 bits)
@@ -508,6 +534,8 @@ RingPlan plan_ring(const dagsched_desc_t *d, const std::vector<int32_t> &pred_pt
          : plan.cell32 ? ring_kernel_pick<2>(plan.ring, feeders, (int)plan.lds.pib_mode, plan.kind) != nullptr
                        : ring_kernel_pick<0>(plan.ring, feeders, (int)plan.lds.pib_mode, plan.kind) != nullptr;
   };
+  // the one-predecessor kind exists for the 16-bit cells and the common shapes: else the two-predecessor kind does
+  if (plan.kind == 3 && (win_log2 || wide || plan.cell32 || !built(plan.feeders))) plan.kind = 2;
   if (!force_feeders && !built(plan.feeders)) plan.feeders = 2;
   if (best_score < 0 || !built(plan.feeders)) return plan;   // shape not built
   // the nibble kernels start time at 255 (see the kernel), which the 16-bit range must hold as well
@@ -539,6 +567,9 @@ using RingKernel = void (*)(RingParams);
   case 0 * 10000 + PIB * 1000 + RING * 10 + F: return relax_ring_kernel<RING, F, HALF, PIB, 0>;    \
   case 1 * 10000 + PIB * 1000 + RING * 10 + F: return relax_ring_kernel<RING, F, HALF, PIB, 1>;    \
   case 2 * 10000 + PIB * 1000 + RING * 10 + F: return relax_ring_kernel<RING, F, HALF, PIB, 2>;
+// the one-predecessor kind: 16-bit cells only
+#define DAGSCHED_RING_CASES_ONE(PIB, RING, F)                                                     \
+  case 3 * 10000 + PIB * 1000 + RING * 10 + F: return relax_ring_kernel<RING, F, HALF, PIB, 3>;
 // window mode: the relaxation launch (PHASE = 2) in the shapes that large layered problems get, and the ingest launch
 #define DAGSCHED_WIN_CASES(RING, F)                                                               \
   case 0 * 10000 + RING * 10 + F: return relax_ring_kernel<RING, F, 4, 0, 0, 2>;                  \
@@ -588,11 +619,16 @@ RingKernel ring_kernel_pick(int ring, int feeders, int pib_lds, int kind) {
     DAGSCHED_RING_CASES(0, 8, 1) DAGSCHED_RING_CASES(0, 8, 2) DAGSCHED_RING_CASES(0, 8, 3)
     DAGSCHED_RING_CASES(0, 16, 1) DAGSCHED_RING_CASES(0, 16, 2) DAGSCHED_RING_CASES(0, 16, 3) DAGSCHED_RING_CASES(0, 16, 4)
     DAGSCHED_RING_CASES(0, 32, 1) DAGSCHED_RING_CASES(0, 32, 2) DAGSCHED_RING_CASES(0, 32, 3)
+    DAGSCHED_RING_CASES_ONE(1, 4, 1) DAGSCHED_RING_CASES_ONE(1, 4, 2)
+    DAGSCHED_RING_CASES_ONE(1, 8, 1) DAGSCHED_RING_CASES_ONE(1, 8, 2) DAGSCHED_RING_CASES_ONE(1, 8, 3)
+    DAGSCHED_RING_CASES_ONE(2, 8, 1) DAGSCHED_RING_CASES_ONE(2, 8, 2) DAGSCHED_RING_CASES_ONE(2, 8, 3)
+    DAGSCHED_RING_CASES_ONE(0, 8, 2) DAGSCHED_RING_CASES_ONE(0, 8, 3) DAGSCHED_RING_CASES_ONE(0, 16, 2) DAGSCHED_RING_CASES_ONE(0, 16, 3)
     default: return nullptr;
   }
   }
 }
 #undef DAGSCHED_RING_CASES
+#undef DAGSCHED_RING_CASES_ONE
 RingKernel ring_kernel_for(const dagsched *h) {
   // byte addresses when the workgroup's end-time arrays fit 64 KB, half addresses otherwise
   const bool half = (uint64_t)h->ring_G * h->lds.s_stride > 65536u;
@@ -1327,7 +1363,7 @@ int dagsched_get_info(const dagsched_t *h, dagsched_info_t *info) {
     info->ring_slots = (int16_t)h->ring_slots;
     info->feeders = (int8_t)h->ring_feeders;
     info->placement_mode = (int8_t)h->lds.pib_mode;
-    info->preds_per_op = (int8_t)(h->ring_kind == 2 ? 2 : 4);
+    info->preds_per_op = (int8_t)(h->ring_kind == 3 ? 1 : h->ring_kind == 2 ? 2 : 4);
     info->kernel_kind = (int8_t)h->ring_kind;
     info->wide_ops = (int8_t)h->lds.wide;
     info->window_log2 = (int8_t)h->lds.win_log2;

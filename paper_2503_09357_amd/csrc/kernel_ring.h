@@ -107,7 +107,9 @@ struct RingParams {
 // makes the dummy's placement irrelevant.  The origin is subtracted from the makespan at the end.
 // KIND: 0 general; 1 every operation is a single part (at most four DAG predecessors each): the feeders walk
 // the order lists directly; 2 at most two DAG predecessors each (single parts as well): the second pair of
-// every record and op is the dummy and neither the feeders nor the relaxer look at it.  Chosen by the host.
+// every record and op is the dummy and neither the feeders nor the relaxer look at it; 3 at most one (what is
+// left of a pipeline's DAG once the edges that other paths imply are dropped): one end-time read per trip, one
+// placement byte and one delay per op.  Chosen by the host.
 //
 // HALF = 4, the WINDOW mode, for graphs whose edges are short in the order of the node ids (layered graphs): a
 // candidate then gets K cells instead of one per operation, K a power of two chosen by the host, and operation v
@@ -134,7 +136,8 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
   extern __shared__ __align__(16) unsigned char lds[];
   static_assert((RING & (RING - 1)) == 0, "RING must be a power of two");
   static_assert(RING >= FEEDERS, "every feeder needs a slot of its own");
-  static_assert(KIND >= 0 && KIND <= 2, "general, single parts, two predecessors");
+  static_assert(KIND >= 0 && KIND <= 3, "general, single parts, two predecessors, one predecessor");
+  static_assert(KIND != 3 || HALF <= 1, "the one-predecessor kind is built for the 16-bit cells only");
   static_assert(HALF >= 0 && HALF <= 5, "byte, half or quarter addresses; 3: quarter addresses and delays looked up by the relaxer; 4, 5: window");
   static_assert(PHASE >= 0 && PHASE <= 2, "fused, ingest only, relaxation only");
   constexpr bool kWin = HALF == 4 || HALF == 5;             // a window of named cells per candidate
@@ -147,7 +150,7 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
   static_assert(!(kWide && PIBL == 2), "wide ops need the dummy machine, which a nibble cannot name");
   constexpr uint32_t kNotDone = (kCell32 || kWin32) ? kNotDone32 : kNotDone16;
   constexpr int kNodeShift = (kCell32 || kWin) ? 0 : 1 - HALF;   // node -> offset of its cell in the units of the 16-bit addresses
-  constexpr int PR = KIND == 2 ? 2 : 4;                     // DAG predecessors per op
+  constexpr int PR = KIND == 3 ? 1 : KIND == 2 ? 2 : 4;     // DAG predecessors per op
   constexpr uint32_t kOrigin = PIBL == 2 ? 255u : 0u;
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -471,7 +474,7 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
     // the loop is unrolled 32 times with the deadlock test once per pass (1.22 -> 1.09 ms on the MoE workload against
     // 8 times); "all through" is looked for every 8 trips with two predecessors per op (the pipelines: short lists),
     // else every 16 (1-2 % either way).
-    constexpr int kEndMask = KIND == 2 ? 7 : 15;
+    constexpr int kEndMask = KIND >= 2 ? 7 : 15;
     for (uint32_t it = 0; it < p.spin_cap; it += 32) {
 #pragma unroll
       for (int sub = 0; sub < 32; ++sub) {
@@ -505,7 +508,8 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
           x += w3 & 0xFFFFu;
           ran = named && x < kNotDone;                        // (a free slot's "duration" 0xFFFF lifts x over the range)
         } else {
-          x = max(max(x_acc, e0 + (w2 & 0xFFu)), e1 + (PR == 4 ? (w2 >> 8) & 0xFFu : w2 >> 8));
+          if (PR == 1) x = max(x_acc, e0 + w2);
+          else x = max(max(x_acc, e0 + (w2 & 0xFFu)), e1 + (PR == 4 ? (w2 >> 8) & 0xFFu : w2 >> 8));
           if (PR == 4) x = max(max(x, e2 + ((w2 >> 16) & 0xFFu)), e3 + (w2 >> 24));
           x += w3 & 0xFFFFu;
           // an op, every predecessor ended and no 16-bit overflow (a free slot's "duration" 0xFFFF lifts x over the
@@ -529,7 +533,8 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
         if (PR == 4) w1 = next ? c1 : w1;
         // The end-time reads of the next trip (LDS accesses keep their program order, so everything below
         // overlaps with their latency).
-        read_cell(w0 & 0xFFFFu, e0, n0); read_cell(w0 >> 16, e1, n1);
+        read_cell(w0 & 0xFFFFu, e0, n0);
+        if (PR >= 2) read_cell(w0 >> 16, e1, n1);
         if (PR == 4) { read_cell(w1 & 0xFFFFu, e2, n2); read_cell(w1 >> 16, e3, n3); }
         if (kWide) {
           const uint32_t m = next ? c2 : w2;                // (w2 itself is updated below)
@@ -573,7 +578,7 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
           }
           win_stop = named || later;
         }
-        const bool range_stop = deadlock && !idle && (kWin ? win_stop : max(max(e0, e1), PR == 4 ? max(e2, e3) : 0u) < kNotDone);
+        const bool range_stop = deadlock && !idle && (kWin ? win_stop : max(max(e0, PR >= 2 ? e1 : 0u), PR == 4 ? max(e2, e3) : 0u) < kNotDone);
         const bool overflow = (__ballot(range_stop) & segmask) != 0;
         if (deadlock) *abort_p = overflow ? 1 : 2;
         stalled = stalled || deadlock;
@@ -669,13 +674,14 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
         Entry &e1 = E[(s + kStages - 1) % kStages];   // admitted one trip ago: its record has arrived
         Entry &e2 = E[(s + 1) % kStages];             // the oldest: written in this trip (e1 itself when the depth is two)
         if (kStages == 2) {
-          e1.q0 = pib(e1.rec.x & 0xFFFFu); e1.q1 = pib(e1.rec.x >> 16);
+          e1.q0 = pib(e1.rec.x & 0xFFFFu);
+          if (PR >= 2) e1.q1 = pib(e1.rec.x >> 16);
           if (PR == 4) { e1.q2 = pib(e1.rec.y & 0xFFFFu); e1.q3 = pib(e1.rec.y >> 16); }
         }
         // (A) channel delays of e2
         // (wide ops carry the machines themselves; the dummy node's machine P becomes this lane's own: no delay)
         const uint32_t d0 = kWide ? (e2.q0 == (uint32_t)P ? (uint32_t)j : e2.q0) : commr[e2.q0 << lps];
-        const uint32_t d1 = kWide ? (e2.q1 == (uint32_t)P ? (uint32_t)j : e2.q1) : commr[e2.q1 << lps];
+        const uint32_t d1 = PR < 2 ? 0u : kWide ? (e2.q1 == (uint32_t)P ? (uint32_t)j : e2.q1) : commr[e2.q1 << lps];
         const uint32_t d2 = PR != 4 ? 0u : kWide ? (e2.q2 == (uint32_t)P ? (uint32_t)j : e2.q2) : commr[e2.q2 << lps];
         const uint32_t d3 = PR != 4 ? 0u : kWide ? (e2.q3 == (uint32_t)P ? (uint32_t)j : e2.q3) : commr[e2.q3 << lps];
         // (1) move the cursor past the part admitted in the previous trip and the other feeders' parts
@@ -704,7 +710,7 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
         // (measured: with two predecessors per op a branch around the read for exhausted lanes pays, 3 %; else not, 1 %)
         lds_vu32_t *const mark_p = (lds_vu32_t *)(ring_lane + ((aseq & (uint32_t)(RING - 1)) << 10) + 12);
         const uint32_t mark_free = ((aseq - (uint32_t)RING) << 16) | kNotDone16;
-        if (KIND == 2) {
+        if (KIND >= 2) {
           pending = (k <= klast) && *mark_p == mark_free;
         } else {
           const uint32_t mark = *mark_p;
@@ -716,7 +722,8 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
         // (B) placement bytes of e1's predecessors (its record was requested one trip ago)
         if (kStages == 3) {
           if (!(e1.fl & 1u)) e1.rec.x = e1.rec.y = (uint32_t)N | ((uint32_t)N << 16);   // nothing admitted: the dummy node's byte
-          e1.q0 = pib(e1.rec.x & 0xFFFFu); e1.q1 = pib(e1.rec.x >> 16);
+          e1.q0 = pib(e1.rec.x & 0xFFFFu);
+          if (PR >= 2) e1.q1 = pib(e1.rec.x >> 16);
           if (PR == 4) { e1.q2 = pib(e1.rec.y & 0xFFFFu); e1.q3 = pib(e1.rec.y >> 16); }
         }
         // (D) pack e2 and publish it

@@ -221,6 +221,21 @@ def test_plan_takes_the_window_of_end_time_cells_only_where_it_is_sound():
     small = (4, rp, ci, np.ones(600, np.int32), np.ones((4, 4), np.int32), np.zeros(600, np.int64))
     assert dagsched.plan(*small, max_candidates=64)["window_log2"] == 0
     assert dagsched.plan(*small, max_candidates=64, shape={"window_cells": 128})["window_log2"] == 7
-    # the MoE graph's edges span 1463 ids: eight times that does not pay against 11712 cells, so no window
+    # the MoE graph is numbered micro-batch by micro-batch: an operation 1021 ids on lies in another micro-batch at any
+    # depth, no window has a margin.  Renumbered level by level its edges are short (64 ids once the implied ones are
+    # dropped) and the margin is there, but its levels are narrow (19 operations for 32 machines) and most schedules
+    # would miss a window of 1024 cells: not taken by itself either, only on request
     w4 = W.gen_config(4, n_cand=2)
-    assert dagsched.plan(w4.n_devices, w4.row_ptr, w4.col_idx, w4.dur, w4.comm, w4.mem_delta, max_candidates=4096)["window_log2"] == 0
+    args4 = (w4.n_devices, w4.row_ptr, w4.col_idx, w4.dur, w4.comm, w4.mem_delta)
+    assert dagsched.plan(*args4, max_candidates=4096)["window_log2"] == 0
+    s4, d4 = W.edges_from_csr(w4.row_ptr, w4.col_idx)
+    lvl = np.zeros(w4.n_nodes, np.int64)
+    for u, v in sorted(zip(s4.tolist(), d4.tolist())):
+        lvl[v] = max(lvl[v], lvl[u] + 1)
+    by_level = np.lexsort((np.arange(w4.n_nodes), lvl))
+    new_id = np.empty(w4.n_nodes, np.int64)
+    new_id[by_level] = np.arange(w4.n_nodes)
+    rp, ci = W.csr_from_edges(w4.n_nodes, new_id[s4], new_id[d4])
+    lev4 = (w4.n_devices, rp, ci, w4.dur[by_level].copy(), w4.comm, w4.mem_delta[by_level].copy())
+    assert dagsched.plan(*lev4, max_candidates=4096)["window_log2"] == 0
+    assert dagsched.plan(*lev4, max_candidates=4096, shape={"window_cells": 4096})["window_log2"] == 12

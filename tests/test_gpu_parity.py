@@ -220,6 +220,8 @@ def _with_env(env, fn):
     {"feeders": 1, "ring_slots": 32, "placement_mode": 0},
     {"feeders": 2, "ring_slots": 8, "placement_mode": 1, "preds_per_op": 4},
     {"feeders": 2, "ring_slots": 16, "placement_mode": 0, "preds_per_op": 4},
+    {"feeders": 2, "ring_slots": 8, "placement_mode": 1, "preds_per_op": 2},
+    {"feeders": 3, "ring_slots": 16, "placement_mode": 0, "preds_per_op": 2},
     {"feeders": 2, "ring_slots": 8, "placement_mode": 1, "state_bits": 32},
     {"feeders": 3, "ring_slots": 16, "placement_mode": 0, "state_bits": 32},
     {"feeders": 1, "ring_slots": 8, "placement_mode": 1, "state_bits": 32,
@@ -242,12 +244,19 @@ def test_every_kernel_variant(gpu_lib, env):
             assert info["placement_bytes_in_lds"] == env["placement_mode"]
             if "cand_per_block" in env:
                 assert info["cand_per_block"] == env["cand_per_block"]
-            # the pipeline workloads have at most two DAG predecessors per operation: the two-predecessor
-            # kernels take them (where that shape is built) unless the knob says otherwise
-            two = w.name.startswith(("cfg1", "cfg2")) and env.get("preds_per_op", 2) == 2
-            assert info["preds_per_op"] in ((2, 4) if two else (4,)), (w.name, info)
-            if env.get("preds_per_op", 2) == 4:
-                assert info["kernel_kind"] == 0
+            # the pipeline workloads keep a single DAG predecessor per operation once implied edges are dropped: the
+            # one-predecessor kernels take them (where that shape is built; else, and with 32-bit cells, the
+            # two-predecessor ones) unless the knob says otherwise
+            pipe = w.name.startswith(("cfg1", "cfg2"))
+            if env.get("preds_per_op", 0) == 4:
+                assert info["kernel_kind"] == 0 and info["preds_per_op"] == 4
+            elif pipe and env.get("preds_per_op", 0) == 2:
+                assert info["kernel_kind"] == 2 and info["preds_per_op"] == 2, (w.name, info)
+            elif pipe:
+                assert info["kernel_kind"] in (2, 3) and info["preds_per_op"] in (1, 2), (w.name, info)
+                if info["state_bits"] == 16 and (env["placement_mode"], env["ring_slots"], env["feeders"]) in (
+                        (1, 8, 1), (1, 8, 2), (1, 8, 3), (1, 4, 1), (1, 4, 2), (0, 8, 2), (0, 16, 2)):
+                    assert info["kernel_kind"] == 3, (w.name, info)
             elif w.name.startswith("random n=210"):
                 assert info["kernel_kind"] in (1, 2), (w.name, info)
 
@@ -256,6 +265,7 @@ def test_every_kernel_variant(gpu_lib, env):
     {"feeders": 2, "ring_slots": 8, "placement_mode": 2},
     {"feeders": 1, "ring_slots": 4, "placement_mode": 2},
     {"feeders": 2, "ring_slots": 4, "placement_mode": 2, "preds_per_op": 4},
+    {"feeders": 2, "ring_slots": 8, "placement_mode": 2, "preds_per_op": 2},
     {"feeders": 1, "ring_slots": 8, "placement_mode": 2, "cand_per_block": 1},
 ])
 def test_nibble_placement_kernels(gpu_lib, env):
