@@ -311,7 +311,7 @@ typedef struct {
   int32_t state_bits;      /* width of the per-node end-time state (16 or 32) */
   int16_t ring_slots;      /* ring kernel: slots per lane of the op ring, else 0 */
   int8_t kernel_kind;      /* ring kernel: 0 operations split into parts of four predecessors, 1 every operation a
-                              single part, 2 at most two predecessors per operation */
+                              single part, 2 at most two predecessors per operation, 3 at most one */
   int8_t wide_ops;         /* ring kernel: 1 when ops name machines instead of delays (delays above 255 or durations
                               above 65534 after the common factor is divided out) */
   int32_t time_scale;      /* common factor of every duration and delay, divided out inside the kernels */
