@@ -93,7 +93,7 @@ typedef struct {
                                node in LDS (P <= 16)                                                        */
   int32_t block_threads;    /* workgroup size: a multiple of 64, at least 64 * (2 + feeders), at most 1024  */
   int32_t state_bits;       /* width of the end times kept on chip: 16 (twice the candidates resident; candidates
-                               whose end times leave the range are evaluated by the int32 kernel one by one) or 32 */
+                               whose end times leave the range are evaluated again with 32-bit end times) or 32 */
   int32_t preds_per_op;     /* 4: the kernel kind that reads four predecessors per op and splits operations with
                                more into parts, also where a leaner kind (single parts, two predecessors, one)
                                applies; 2: the two-predecessor kind also where the one-predecessor kind applies   */
@@ -105,7 +105,7 @@ typedef struct {
                                times; for graphs whose
                                edges are short in the order of the node ids): a power of two from 8 to 32768 to ask
                                for that many, -1 to forbid the mode, 0 to let the library decide.  Candidates whose
-                               schedule does not fit the window are evaluated by the int32 kernel one by one   */
+                               schedule does not fit the window are evaluated again with a cell per operation   */
 } dagsched_shape_t;
 
 /*
@@ -303,7 +303,7 @@ int dagsched_coarsen(int32_t n_nodes, int32_t n_edges, const int32_t *row_ptr, c
  */
 typedef struct {
   int32_t variant;         /* 1, 2 general int32 kernel (end times in LDS / in HBM); 3 ring kernel, 16-bit times
-                              proven to fit; 4 the same run optimistically with the int32 kernel behind it;
+                              proven to fit; 4 the same run optimistically (or in window mode) with a second, exact run behind it;
                               5 ring kernel with 32-bit times; 6 shared-placement kernel */
   int32_t cand_per_block;  /* candidates evaluated by one workgroup */
   int32_t block_threads;   /* workgroup size */
@@ -331,10 +331,12 @@ int dagsched_get_info(const dagsched_t *h, dagsched_info_t *info);
 int dagsched_plan(const dagsched_desc_t *desc, int32_t lds_bytes, int32_t n_cu, dagsched_info_t *info);
 
 /*
- * How many candidates of the handle's LAST evaluate were handed to the general int32 kernel one by one: those
- * whose end times left the 16-bit range of an optimistic run (variant 4), or that do not use the shared placement
- * (variant 6).  That path is an order of magnitude slower per candidate, so a caller who sees a large count should
- * ask for 32-bit state (dagsched_shape_t.state_bits) or drop the hint.  Synchronises hip_stream, the stream the
+ * How many candidates of the handle's LAST evaluate needed a second, slower evaluation: those whose end times left
+ * the 16-bit range of an optimistic run or whose schedule did not fit the window (variant 4: they are evaluated
+ * again by the 32-bit form of the ring kernel, where a 32-bit end time per operation fits the GPU's LDS, else by
+ * the general int32 kernel one by one, which is an order of magnitude slower per candidate), or that do not use
+ * the shared placement (variant 6: the general kernel).  A caller who sees a large count should ask for 32-bit
+ * state (dagsched_shape_t.state_bits), forbid the window (window_cells = -1) or drop the hint.  Synchronises hip_stream, the stream the
  * evaluate was enqueued on, and copies one word to the host: not for the asynchronous path.  *count = 0 for
  * variants without such a list.
  */

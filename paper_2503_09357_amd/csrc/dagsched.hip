@@ -98,6 +98,10 @@ struct dagsched {
   int64_t list_stride = 0, pib_stride = 0;
   uint8_t *ws_pib = nullptr;
   LdsLayout lds{};
+  // Fallback of the optimistic 16-bit run and of the window mode: the same problem in the 32-bit form of the ring
+  // kernel (exact), launched over the list of candidates the first run left; fb_G == 0: the general kernel instead
+  int32_t fb_G = 0, fb_slots = 0, fb_feeders = 1, fb_block = 256, fb_kind = 0;
+  LdsLayout fb_lds{};
   LdsLayout lds_ingest{};                 // window mode: layout of the ingest launch
   int32_t ingest_block = 1024;
   uint32_t win_magic = 0;
@@ -822,6 +826,7 @@ int launch_evaluate(dagsched *h, int32_t n_cand, const int32_t *placement, const
     p.placement = pl; p.rank = rk;
     p.ws_list = h->ws_list16; p.ws_pib = h->ws_pib; p.pib_stride = h->pib_stride;
     p.fb_count = h->d_fb_count; p.fb_list = h->d_fb_list;
+    p.cand_list = nullptr; p.cand_count = nullptr;
     p.spin_cap = h->spin_cap;
     p.win_magic = h->win_magic; p.ws_meta = h->ws_meta;
     p.out = out;
@@ -835,7 +840,17 @@ int launch_evaluate(dagsched *h, int32_t n_cand, const int32_t *placement, const
     p.lds = h->lds;
     hipLaunchKernelGGL(ring_kernel_for(h), dim3(blocks), dim3((unsigned)h->ring_block), (size_t)h->lds.total,
                        stream, p);
-    if (optimistic) launch_general(h, n_cand, pl, rk, out, h->d_fb_list, h->d_fb_count, stream);
+    if (optimistic && h->fb_G) {
+      // what the run above left: the same candidates again with 32-bit end times (exact), straight off the list
+      RingParams q = p;
+      q.G = h->fb_G; q.optimistic = 0; q.lds = h->fb_lds;
+      q.cand_list = h->d_fb_list; q.cand_count = h->d_fb_count;
+      const unsigned blocks2 = (unsigned)((n_cand + h->fb_G - 1) / h->fb_G);   // as if every candidate were on the list
+      hipLaunchKernelGGL(ring_kernel_pick<2>(h->fb_slots, h->fb_feeders, (int)h->fb_lds.pib_mode, h->fb_kind), dim3(blocks2),
+                         dim3((unsigned)h->fb_block), (size_t)h->fb_lds.total, stream, q);
+    } else if (optimistic) {
+      launch_general(h, n_cand, pl, rk, out, h->d_fb_list, h->d_fb_count, stream);
+    }
   }
   // the evaluation ran with delay 0 on pairs without a channel; candidates that use one are flagged now
   if (h->d_no_channel)
@@ -988,6 +1003,25 @@ int dagsched_create(const dagsched_desc_t *caller_desc, dagsched_t **out) {
          dev_alloc(&h->ws_list16, maxc * (size_t)h->list_stride) &&
          (plan.lds.pib_mode != 0 || dev_alloc(&h->ws_pib, maxc * (size_t)h->pib_stride));   // only read when the placement is not in LDS
     if (ok && !plan.exact) ok = dev_alloc(&h->d_fb_count, 1) && dev_alloc(&h->d_fb_list, maxc);
+    if (ok && !plan.exact && !plan.lds.wide) {
+      // the candidates a 16-bit or window run leaves behind: 32-bit end times, a cell per operation, where that fits
+      dagsched_shape_t fsh{};
+      fsh.placement_mode = -1;
+      fsh.state_bits = 32;
+      fsh.window_cells = -1;
+      dagsched_desc_t fd = *desc;
+      fd.shape = &fsh;
+      const RingPlan fp = plan_ring(&fd, pred_ptr, pred_idx, sum_dur, lds_max, n_cu);
+      // (same records, part counts and delays: both plans divide by the same common factor and drop the same edges)
+      if (fp.ok && fp.exact && fp.cell32 && !fp.lds.wide && fp.scale == plan.scale && fp.rec_plane == plan.rec_plane &&
+          fp.id_bits == plan.id_bits && fp.rec.size() == plan.rec.size()) {
+        h->fb_G = fp.G; h->fb_slots = fp.ring; h->fb_feeders = fp.feeders; h->fb_block = fp.block; h->fb_lds = fp.lds; h->fb_kind = fp.kind;
+        if (fp.lds.pib_mode == 0 && !h->ws_pib) ok = dev_alloc(&h->ws_pib, maxc * (size_t)h->pib_stride);
+        const void *fk = (const void *)ring_kernel_pick<2>(fp.ring, fp.feeders, (int)fp.lds.pib_mode, fp.kind);
+        if (!fk) h->fb_G = 0;
+        if (ok && fp.lds.total > 48 * 1024) ok = allow_large_lds(fk, h->device, (int)fp.lds.total);
+      }
+    }
     if (ok && plan.win_log2) {
       h->lds_ingest = plan.lds_ingest; h->ingest_block = plan.ingest_block; h->win_magic = plan.win_magic;
       ok = dev_alloc(&h->ws_meta, ((maxc + plan.G - 1) / plan.G) * 4 * (size_t)kWave) &&

@@ -90,7 +90,8 @@ struct RingParams {
   uint16_t *ws_list;                   // [C][list_stride]
   uint8_t *ws_pib;                     // [C][pib_stride] placement as one byte per node; entry N = P (the dummy node's machine)
   int64_t pib_stride;
-  int32_t *fb_count, *fb_list;         // candidates left to the general kernel
+  int32_t *fb_count, *fb_list;         // candidates left to the fallback (the 32-bit form of this kernel, or the general kernel)
+  const int32_t *cand_list, *cand_count;   // not NULL: evaluate the candidates cand_list[0 .. *cand_count) instead of 0 .. C-1
   uint32_t spin_cap;                   // bound on relaxer / feeder loop trips
   uint32_t win_magic;                  // window mode: ceil(2^32 / (cells - 3)), for node -> cell name
   int32_t *ws_meta;                    // window mode: [workgroups][4][64] what ingest hands to relaxation: operations per
@@ -158,7 +159,11 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
   const int N = p.N, P = p.P, Pseg = p.Pseg, G = p.G;
   const int L = G * Pseg;                                   // lanes in use per wavefront
   const int64_t c0 = (int64_t)blockIdx.x * G;
-  const int ng = (int)min((int64_t)G, (int64_t)p.C - c0);
+  // (a launch over a list of candidates is sized for the longest list possible: the workgroups beyond its end leave)
+  const int64_t n_todo = p.cand_list ? (int64_t)*p.cand_count : (int64_t)p.C;
+  if (c0 >= n_todo) return;
+  const int ng = (int)min((int64_t)G, n_todo - c0);
+  auto cid = [&](int gg) -> int64_t { return p.cand_list ? (int64_t)p.cand_list[c0 + gg] : c0 + gg; };
   const LdsLayout &o = p.lds;
   lds_byte_t *const ldsb = (lds_byte_t *)lds;
 
@@ -230,8 +235,8 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
 
   // placement in range (eq. (6)), operations per machine
   for (int gg = team; gg < ng; gg += n_teams) {
-    const int32_t *pl = p.placement + (c0 + gg) * N;
-    uint8_t *pib = PIBL ? lds + o.o_pi + gg * o.pi_stride : p.ws_pib + (c0 + gg) * p.pib_stride;
+    const int32_t *pl = p.placement + cid(gg) * N;
+    uint8_t *pib = PIBL ? lds + o.o_pi + gg * o.pi_stride : p.ws_pib + cid(gg) * p.pib_stride;
     int32_t *cnt_g = cntw + gg * Pseg;
     if (PIBL == 2) { if (tt == 0 && !(N & 1)) pib[N >> 1] = 0; }   // the dummy's nibble: any machine will do
     else if (tt == 0) pib[N] = (uint8_t)P;                  // the dummy node sits on a dummy machine whose delays are all zero
@@ -302,9 +307,9 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
   // no slot left unwritten <=> every (machine, rank) slot hit exactly once
   for (int gg = team; gg < ng; gg += n_teams) {
     if (flagw[gg] & kBitBadPlacement) continue;
-    const int32_t *rk = p.rank + (c0 + gg) * N;
+    const int32_t *rk = p.rank + cid(gg) * N;
     const uint8_t *pib = PIBL ? lds + o.o_pi + gg * o.pi_stride
-                              : p.ws_pib + (c0 + gg) * p.pib_stride;   // written by this workgroup before the barrier above
+                              : p.ws_pib + cid(gg) * p.pib_stride;   // written by this workgroup before the barrier above
     uint16_t *lds_list = (uint16_t *)(lds + gg * o.s_stride);
     const int32_t *cnt_g = cntw + gg * Pseg, *off_g = offw + gg * Pseg;
     int32_t *flag_g = flagw + gg;
@@ -360,7 +365,7 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
   for (int gg = team; gg < ng; gg += n_teams) {
     if (flagw[gg] & kBitBadPlacement) continue;
     const uint32_t *lw = (const uint32_t *)(lds + gg * o.s_stride);
-    uint32_t *gw = (uint32_t *)(p.ws_list + (c0 + gg) * p.list_stride);     // rows are 128-byte aligned
+    uint32_t *gw = (uint32_t *)(p.ws_list + cid(gg) * p.list_stride);       // rows are 128-byte aligned
     bool hole = false;
     for (int i = tt; i < (N + 1) / 2; i += tpc) {
       const uint32_t w = lw[i];
@@ -604,7 +609,7 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
     //             and written to the ring
     // The loop is unrolled by the pipeline depth so that the registers rotate by renaming, not by moves.
     const int f = wave - 1;
-    const uint8_t *const pib_g = p.ws_pib + (c0 + (cand_ok ? g : 0)) * p.pib_stride;   // L2-resident: this workgroup wrote it
+    const uint8_t *const pib_g = p.ws_pib + cid(cand_ok ? g : 0) * p.pib_stride;   // L2-resident: this workgroup wrote it
     lds_cu8_t *const pib_l = (lds_cu8_t *)(ldsb + o.o_pi + g * o.pi_stride);
     auto pib = [&](uint32_t u) -> uint32_t {
       if (PIBL == 2) return ((uint32_t)pib_l[u >> 1] >> ((u & 1u) << 2)) & 0xFu;
@@ -613,7 +618,7 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
     lds_cu8_t *const commr = (lds_cu8_t *)(ldsb + o.o_comm) + j;
     lds_byte_t *const ring_lane = ldsb + o.o_ring + (uint32_t)lane * 16u;
     lds_vi32_t *const abort_p = (lds_vi32_t *)(ldsb + o.o_abort) + g;
-    const uint16_t *list = p.ws_list + (c0 + (cand_ok ? g : 0)) * p.list_stride;
+    const uint16_t *list = p.ws_list + cid(cand_ok ? g : 0) * p.list_stride;
     const uint32_t base2 = sbase | (sbase << 16);
     const uint32_t trash = kWin ? win_trash : sbase + (((uint32_t)N + 1u) << kNodeShift);
     const uint32_t vbits = (uint32_t)p.id_bits, vmask = (1u << vbits) - 1u;
@@ -751,7 +756,7 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
     // ------------------------------------------------------------ accountant
     // Peak of the running memory level of machine j (eqs. (17)-(19)): it depends on the order only,
     // so one wavefront walks the order lists on its own, four operations per trip.
-    const uint16_t *list = p.ws_list + (c0 + (cand_ok ? g : 0)) * p.list_stride;
+    const uint16_t *list = p.ws_list + cid(cand_ok ? g : 0) * p.list_stride;
     const uint32_t vmask = (1u << p.id_bits) - 1u;
     const int k0 = has_ops ? offw[ql] : 0;
     const int kend = has_ops ? k0 + cntw[ql] : 0;
@@ -781,7 +786,7 @@ __global__ __launch_bounds__(1024) void relax_ring_kernel(RingParams p) {
     int32_t z = acc;
     for (int d = 1; d < Pseg; d <<= 1) z = max(z, __shfl_xor(z, d, Pseg));
     if (lane_on && g < ng && j < P) {
-      const int64_t c = c0 + g;
+      const int64_t c = cid(g);
       int bits = flagw[g] | (overb[g] ? kBitOverMemory : 0);
       if (stalled || abortw[g]) {
         if (p.optimistic && !(bits & kBitInternal) && abortw[g] != 2) {
