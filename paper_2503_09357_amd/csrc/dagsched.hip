@@ -101,6 +101,8 @@ struct dagsched {
   // Fallback of the optimistic 16-bit run and of the window mode: the same problem in the 32-bit form of the ring
   // kernel (exact), launched over the list of candidates the first run left; fb_G == 0: the general kernel instead
   int32_t fb_G = 0, fb_slots = 0, fb_feeders = 1, fb_block = 256, fb_kind = 0;
+  bool fb_optimistic = false;             // the fallback is itself a 16-bit run with the general kernel behind it (window mode on
+                                          // a problem too large for 32-bit cells)
   LdsLayout fb_lds{};
   LdsLayout lds_ingest{};                 // window mode: layout of the ingest launch
   int32_t ingest_block = 1024;
@@ -646,6 +648,15 @@ RingKernel ring_kernel_for(const dagsched *h) {
               : ring_kernel_pick<0>(h->ring_slots, h->ring_feeders, pib_lds, h->ring_kind);
 }
 
+// the kernel of the second run over the candidates the first one left (32-bit cells, or 16-bit ones behind a window)
+RingKernel fallback_kernel(const dagsched *h) {
+  const int pib_lds = (int)h->fb_lds.pib_mode;
+  if (h->fb_lds.cell_bytes == 4) return ring_kernel_pick<2>(h->fb_slots, h->fb_feeders, pib_lds, h->fb_kind);
+  const bool half = (uint64_t)h->fb_G * h->fb_lds.s_stride > 65536u;
+  return half ? ring_kernel_pick<1>(h->fb_slots, h->fb_feeders, pib_lds, h->fb_kind)
+              : ring_kernel_pick<0>(h->fb_slots, h->fb_feeders, pib_lds, h->fb_kind);
+}
+
 int static_threads(int relaxers) {                       // relaxers, accountants and as many wavefronts again for ingest
   return std::min(1024, 4 * relaxers * kWave);
 }
@@ -843,11 +854,12 @@ int launch_evaluate(dagsched *h, int32_t n_cand, const int32_t *placement, const
     if (optimistic && h->fb_G) {
       // what the run above left: the same candidates again with 32-bit end times (exact), straight off the list
       RingParams q = p;
-      q.G = h->fb_G; q.optimistic = 0; q.lds = h->fb_lds;
+      q.G = h->fb_G; q.optimistic = h->fb_optimistic ? 1 : 0; q.lds = h->fb_lds;
       q.cand_list = h->d_fb_list; q.cand_count = h->d_fb_count;
+      q.fb_list = h->d_fb_list + h->max_cand; q.fb_count = h->d_fb_count + 1;   // (what this run leaves in its turn)
       const unsigned blocks2 = (unsigned)((n_cand + h->fb_G - 1) / h->fb_G);   // as if every candidate were on the list
-      hipLaunchKernelGGL(ring_kernel_pick<2>(h->fb_slots, h->fb_feeders, (int)h->fb_lds.pib_mode, h->fb_kind), dim3(blocks2),
-                         dim3((unsigned)h->fb_block), (size_t)h->fb_lds.total, stream, q);
+      hipLaunchKernelGGL(fallback_kernel(h), dim3(blocks2), dim3((unsigned)h->fb_block), (size_t)h->fb_lds.total, stream, q);
+      if (h->fb_optimistic) launch_general(h, n_cand, pl, rk, out, h->d_fb_list + h->max_cand, h->d_fb_count + 1, stream);
     } else if (optimistic) {
       launch_general(h, n_cand, pl, rk, out, h->d_fb_list, h->d_fb_count, stream);
     }
@@ -979,7 +991,7 @@ int dagsched_create(const dagsched_desc_t *caller_desc, dagsched_t **out) {
          upload(&h->d_st_machine, splan.machine.data(), splan.machine.size()) &&
          upload(&h->d_st_off, splan.off.data(), splan.off.size()) &&
          (splan.base.empty() || upload(&h->d_st_base, splan.base.data(), splan.base.size())) &&
-         dev_alloc(&h->d_fb_count, 1) && dev_alloc(&h->d_fb_list, maxc);
+         dev_alloc(&h->d_fb_count, 2) && dev_alloc(&h->d_fb_list, maxc);
     StaticParams &s = h->st;
     s.N = h->N; s.P = h->P; s.Pseg = h->Pseg; s.log_pseg = ilog2(h->Pseg); s.G = splan.G; s.W = splan.W;
     s.ops = h->d_st_ops; s.machine = h->d_st_machine; s.off = h->d_st_off; s.mem_delta = h->d_mem;
@@ -1002,7 +1014,7 @@ int dagsched_create(const dagsched_desc_t *caller_desc, dagsched_t **out) {
          (plan.nparts.empty() || upload(&h->d_nparts, plan.nparts.data(), plan.nparts.size())) &&
          dev_alloc(&h->ws_list16, maxc * (size_t)h->list_stride) &&
          (plan.lds.pib_mode != 0 || dev_alloc(&h->ws_pib, maxc * (size_t)h->pib_stride));   // only read when the placement is not in LDS
-    if (ok && !plan.exact) ok = dev_alloc(&h->d_fb_count, 1) && dev_alloc(&h->d_fb_list, maxc);
+    if (ok && !plan.exact) ok = dev_alloc(&h->d_fb_count, 2) && dev_alloc(&h->d_fb_list, 2 * maxc);   // (two lists)
     if (ok && !plan.exact && !plan.lds.wide) {
       // the candidates a 16-bit or window run leaves behind: 32-bit end times, a cell per operation, where that fits
       dagsched_shape_t fsh{};
@@ -1020,6 +1032,21 @@ int dagsched_create(const dagsched_desc_t *caller_desc, dagsched_t **out) {
         const void *fk = (const void *)ring_kernel_pick<2>(fp.ring, fp.feeders, (int)fp.lds.pib_mode, fp.kind);
         if (!fk) h->fb_G = 0;
         if (ok && fp.lds.total > 48 * 1024) ok = allow_large_lds(fk, h->device, (int)fp.lds.total);
+      }
+      if (ok && !h->fb_G && plan.win_log2) {
+        // too large for that: the misses of the window go to the 16-bit kernel with a cell per operation (its own range
+        // stops to a second list and the general kernel)
+        fsh.state_bits = 0;
+        const RingPlan gp = plan_ring(&fd, pred_ptr, pred_idx, sum_dur, lds_max, n_cu);
+        if (gp.ok && !gp.cell32 && !gp.win_log2 && !gp.lds.wide && gp.scale == plan.scale && gp.rec_plane == plan.rec_plane &&
+            gp.id_bits == plan.id_bits && gp.rec.size() == plan.rec.size()) {
+          h->fb_G = gp.G; h->fb_slots = gp.ring; h->fb_feeders = gp.feeders; h->fb_block = gp.block; h->fb_lds = gp.lds; h->fb_kind = gp.kind;
+          h->fb_optimistic = !gp.exact;
+          if (gp.lds.pib_mode == 0 && !h->ws_pib) ok = dev_alloc(&h->ws_pib, maxc * (size_t)h->pib_stride);
+          const void *gk = (const void *)fallback_kernel(h);
+          if (!gk) h->fb_G = 0;
+          if (ok && gk && gp.lds.total > 48 * 1024) ok = allow_large_lds(gk, h->device, (int)gp.lds.total);
+        }
       }
     }
     if (ok && plan.win_log2) {

@@ -23,8 +23,8 @@ __global__ __launch_bounds__(256) void transpose_i32_kernel(const int32_t *__res
 }
 
 // A fill kernel instead of a memset node: safe to record into a captured graph.
-__global__ void reset_counter_kernel(int32_t *counter) {
-  if (threadIdx.x == 0 && blockIdx.x == 0) *counter = 0;
+__global__ void reset_counter_kernel(int32_t *counter) {        // two words: the lists of the first and second fallback
+  if (threadIdx.x == 0 && blockIdx.x == 0) { counter[0] = 0; counter[1] = 0; }
 }
 
 // Missing channels (Sec. III eqs. (9)-(10)), run after the evaluation when the cluster graph lacks some pair: one

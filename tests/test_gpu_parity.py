@@ -555,6 +555,17 @@ def test_window_of_end_time_cells(gpu_lib):
     assert info["window_log2"] == 0
     (z, b, pk, f), info = assert_parity(gpu_lib, dataclasses_replace(w5, placement=w5.placement[:9], rank=w5.rank[:9]), layout=1)
     assert info["window_log2"] == 12
+    # a window far too small for the layered workload: most candidates miss; they are evaluated again by the 16-bit
+    # kernel with a cell per operation (a 32-bit cell per operation does not fit the LDS here), whose own range stops
+    # would go on to the int32 kernel
+    w5few = dataclasses_replace(w5, placement=w5.placement[:12], rank=w5.rank[:12])
+    want5 = oracle.evaluate_workload(w5few, threads=8)
+    for shape in ({"window_cells": 1024}, {"window_cells": 512, "ring_slots": 8}):
+        with gpu_lib.Evaluator.for_workload(w5few, shape=shape) as ev:
+            got = ev.evaluate(torch.from_numpy(w5few.placement).to(dev), torch.from_numpy(w5few.rank).to(dev))
+            assert ev.last_fallbacks() > 0 and ev.info()["window_log2"] == int(np.log2(shape["window_cells"]))
+            for a, o in zip(got, want5):
+                assert np.array_equal(a.cpu().numpy(), o), shape
     seen_fallbacks = 0
     for n, p, span, cells, extra in ((700, 5, 20, 256, ()), (700, 5, 20, 32, ()), (1500, 16, 60, 1024, ()),
                                      (1500, 16, 60, 64, ()), (900, 64, 30, 512, ()), (400, 1, 10, 64, ()),
